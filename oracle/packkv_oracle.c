@@ -1,0 +1,361 @@
+/*
+ * PackKV CPU oracle -- TEST INFRASTRUCTURE, NOT PRODUCT CODE.
+ *
+ * A plain, slow, scalar implementation of what the PackKV decode hot path
+ * computes, written from the paper (arXiv 2512.24449).  It exists only so
+ * that tests, the smoke check and the benchmark's cpu_baseline leg have
+ * something independent to compare the HIP library against.  It shares no
+ * code, header, table or helper with the HIP path and is never linked into
+ * the product library.
+ *
+ * Codec steps follow the paper in its own order:
+ *   Sec. III-B.2 / Sec. IV-A  token-wise quantization with a relative scale
+ *                             (scale = rel * (max - min), error <= scale/2)
+ *   Sec. III-B.3              bit-packing: a pack of k=16 integers along
+ *                             ctx_len shares one minimum and one width
+ *                             ceil(log2(range+1))
+ *   Sec. III-B.4              every 2-D block becomes one contiguous chunk,
+ *                             appended at the end of the buffer, plus an index
+ * The matvecs are the plain definitions (Sec. III-B.3 boxed statement):
+ *   scores = sm_scale * K_hat q      out = p^T V_hat
+ * evaluated in fp64 on the decoded values x_hat = scale*code + min.
+ *
+ * Readings taken where the paper is silent (kept in step with the list in
+ * the design document):
+ *   - one (scale, min) pair per token over ALL kv-heads' values of that token,
+ *     per tensor, stored as fp16; quantization uses the stored fp16 values;
+ *   - fp32 subtract and divide, round-half-to-even, clamp to [0, qmax],
+ *     qmax = round(1/rel); scale == 0 gives code 0;
+ *   - pack metadata is one byte, (width << 4) | min;
+ *   - chunk bytes: 512 header bytes indexed [token_group*128 + channel], then
+ *     the packs in the same order, each 2*width bytes little-endian with the
+ *     code of token i at bits [i*width, (i+1)*width), zero padded to 16 bytes.
+ *
+ * Parity pins live in tests/test_oracle_*.py; the exact byte order inside a
+ * chunk is "parity unpinned" (the paper's format figures are not available):
+ * it is a choice of this build, checked only by an independent bit reader.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define ORC_D 128      /* head_dim                                  */
+#define ORC_N 64       /* tokens per block (truncated block size)   */
+#define ORC_K 16       /* pack size                                 */
+#define ORC_GROUPS (ORC_N / ORC_K)
+#define ORC_PACKS (ORC_GROUPS * ORC_D)
+#define ORC_HEADER ORC_PACKS
+#define ORC_CHUNK_MAX (ORC_HEADER + ORC_PACKS * 8)
+
+/* ---------------------------------------------------------------- fp16 -- */
+
+/* IEEE binary16 -> binary32, exact. */
+float orc_h2f(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    uint32_t exp = (uint32_t)(h >> 10) & 0x1Fu;
+    uint32_t man = (uint32_t)h & 0x3FFu;
+    double v;
+    if (exp == 0)
+        v = ldexp((double)man, -24);                 /* zero / subnormal */
+    else if (exp == 31)
+        v = man ? (double)NAN : (double)INFINITY;
+    else
+        v = ldexp((double)(man + 1024u), (int)exp - 25);
+    return (float)(sign ? -v : v);
+}
+
+/* binary32 -> binary16, round to nearest even, overflow to infinity. */
+uint16_t orc_f2h(float f)
+{
+    uint16_t sign = (uint16_t)(signbit(f) ? 0x8000u : 0u);
+    double a = fabs((double)f);
+    if (isnan(f)) return (uint16_t)(sign | 0x7E00u);
+    if (a == 0.0) return sign;
+    if (isinf(f)) return (uint16_t)(sign | 0x7C00u);
+    int e;
+    (void)frexp(a, &e);                              /* a = m * 2^e, m in [0.5,1) */
+    int ue = e - 1;                                  /* a in [2^ue, 2^(ue+1))     */
+    if (ue < -14) ue = -14;                          /* subnormal spacing 2^-24   */
+    /* spacing of representable values near a is 2^(ue-10) */
+    double scaled = ldexp(a, 10 - ue);               /* exact power-of-two scale  */
+    double r = nearbyint(scaled);                    /* default mode: ties-even   */
+    double v = ldexp(r, ue - 10);
+    if (v >= 65520.0) return (uint16_t)(sign | 0x7C00u);
+    /* re-normalise after rounding may have crossed a power of two */
+    int e2;
+    (void)frexp(v, &e2);
+    int ve = e2 - 1;
+    uint32_t bits;
+    if (v < ldexp(1.0, -14)) {
+        bits = (uint32_t)ldexp(v, 24);               /* subnormal mantissa        */
+    } else {
+        uint32_t man = (uint32_t)(ldexp(v, 10 - ve) - 1024.0);
+        bits = ((uint32_t)(ve + 15) << 10) | man;
+    }
+    return (uint16_t)(sign | bits);
+}
+
+/* ------------------------------------------------- quantization (lossy) -- */
+
+/* Levels of the quantizer for a relative scale: 0 .. round(1/rel).
+ * (Sec. IV-A: actual scale = rel * (max - min).) */
+int orc_qmax(float rel)
+{
+    return (int)lround(1.0 / (double)rel);
+}
+
+/*
+ * Token-wise quantization parameters (Sec. III-B.2, Sec. IV-A).
+ * x is fp16 [B][T][H][D] with explicit token and batch strides in elements.
+ * For every (b, t) the minimum and maximum run over the H*D values of that
+ * token.  scale16 = fp16(rel32 * (max - min)) with the product and the
+ * difference rounded once each in fp32; min16 is the minimum itself
+ * (a zero minimum is stored as +0).
+ */
+void orc_token_params(const uint16_t *x, int B, int T, int H, int D,
+                      int64_t batch_stride, int64_t token_stride, float rel,
+                      uint16_t *scale16, uint16_t *min16)
+{
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t) {
+            const uint16_t *row = x + b * batch_stride + t * token_stride;
+            float mn = orc_h2f(row[0]), mx = mn;
+            uint16_t mn_bits = row[0];
+            for (int i = 1; i < H * D; ++i) {
+                float v = orc_h2f(row[i]);
+                if (v < mn) { mn = v; mn_bits = row[i]; }
+                if (v > mx) mx = v;
+            }
+            if (mn == 0.0f) mn_bits = 0;             /* canonical +0 */
+            float range32 = mx - mn;
+            float s32 = rel * range32;
+            scale16[(int64_t)b * T + t] = orc_f2h(s32);
+            min16[(int64_t)b * T + t] = mn_bits;
+        }
+}
+
+/* One value -> its code (Sec. IV-A; non-negative integers, Sec. III-B.3). */
+static int quantize_one(uint16_t x16, uint16_t scale16, uint16_t min16, int qmax)
+{
+    float s = orc_h2f(scale16);
+    if (s == 0.0f) return 0;
+    float num = orc_h2f(x16) - orc_h2f(min16);       /* fp32 subtract */
+    float ratio = num / s;                           /* fp32 divide   */
+    float r = nearbyintf(ratio);                     /* ties to even  */
+    int q = (int)r;
+    if (q < 0) q = 0;
+    if (q > qmax) q = qmax;
+    return q;
+}
+
+/* Codes for a whole tensor, q is uint8 [B][T][H][D] contiguous. */
+void orc_quantize(const uint16_t *x, int B, int T, int H, int D,
+                  int64_t batch_stride, int64_t token_stride, float rel,
+                  const uint16_t *scale16, const uint16_t *min16, uint8_t *q)
+{
+    int qmax = orc_qmax(rel);
+    for (int b = 0; b < B; ++b)
+        for (int t = 0; t < T; ++t) {
+            const uint16_t *row = x + b * batch_stride + t * token_stride;
+            uint8_t *qrow = q + ((int64_t)b * T + t) * H * D;
+            uint16_t s = scale16[(int64_t)b * T + t], m = min16[(int64_t)b * T + t];
+            for (int i = 0; i < H * D; ++i)
+                qrow[i] = (uint8_t)quantize_one(row[i], s, m, qmax);
+        }
+}
+
+/* Decoded value the consumer sees: x_hat = scale * code + min, in fp64. */
+double orc_xhat(uint8_t code, uint16_t scale16, uint16_t min16)
+{
+    return (double)orc_h2f(scale16) * (double)code + (double)orc_h2f(min16);
+}
+
+void orc_dequant(const uint8_t *q, int B, int T, int H, int D,
+                 const uint16_t *scale16, const uint16_t *min16, double *xhat)
+{
+    for (int64_t bt = 0; bt < (int64_t)B * T; ++bt)
+        for (int i = 0; i < H * D; ++i)
+            xhat[bt * H * D + i] = orc_xhat(q[bt * H * D + i], scale16[bt], min16[bt]);
+}
+
+/* ------------------------------------------------- bit-packing (lossless) -- */
+
+/* Width of a pack whose values span `range` = max - min: ceil(log2(range+1))
+ * (Sec. III-B.3). */
+int orc_width(int range)
+{
+    int w = 0;
+    while ((1 << w) < range + 1) ++w;
+    return w;
+}
+
+/*
+ * Pack one chunk: the 64 x 128 codes of one (batch, kv-head, block).
+ * q points at code (token 0, channel 0); consecutive tokens are `token_stride`
+ * apart.  Writes the chunk bytes (header, payload, zero padding to 16 bytes)
+ * and, when not NULL, the logical per-pack widths and minimums [512].
+ * Returns the chunk size in bytes (a multiple of 16).
+ */
+int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
+                   uint8_t *widths, uint8_t *mins)
+{
+    int pos = ORC_HEADER;
+    for (int g = 0; g < ORC_GROUPS; ++g)
+        for (int d = 0; d < ORC_D; ++d) {
+            int p = g * ORC_D + d;
+            int lo = 255, hi = 0;
+            for (int i = 0; i < ORC_K; ++i) {
+                int v = q[(int64_t)(g * ORC_K + i) * token_stride + d];
+                if (v < lo) lo = v;
+                if (v > hi) hi = v;
+            }
+            int w = orc_width(hi - lo);
+            bytes[p] = (uint8_t)((w << 4) | lo);
+            if (widths) widths[p] = (uint8_t)w;
+            if (mins) mins[p] = (uint8_t)lo;
+            uint64_t bits = 0;
+            for (int i = 0; i < ORC_K; ++i) {
+                uint64_t c = (uint64_t)(q[(int64_t)(g * ORC_K + i) * token_stride + d] - lo);
+                bits |= c << (i * w);
+            }
+            for (int j = 0; j < 2 * w; ++j)
+                bytes[pos++] = (uint8_t)(bits >> (8 * j));
+        }
+    while (pos % 16) bytes[pos++] = 0;
+    return pos;
+}
+
+/*
+ * Compress a whole tensor of T = 64*nblk tokens (Sec. III-B.1 .. III-B.4).
+ * Chunks are appended block by block; inside a block in (batch, kv-head)
+ * order, so chunk index c = (block*B + b)*H + h.  offsets16[c] is the start of
+ * chunk c in 16-byte units, offsets16[nchunks] the end of the arena.
+ * meta[b*T + t] = scale16 | min16 << 16.  q_out (optional) receives the codes,
+ * widths_out / mins_out (optional) the per-pack values [nchunks][512].
+ * Returns the arena size in bytes, or -1 if it would exceed arena_cap.
+ */
+int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
+                     int64_t batch_stride, int64_t token_stride, float rel,
+                     uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
+                     uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
+                     uint8_t *mins_out)
+{
+    if (D != ORC_D || T % ORC_N) return -2;
+    int64_t n = (int64_t)B * T;
+    uint16_t *scale16 = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
+    uint16_t *min16 = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
+    uint8_t *q = q_out ? q_out : (uint8_t *)malloc((size_t)n * H * D);
+    orc_token_params(x, B, T, H, D, batch_stride, token_stride, rel, scale16, min16);
+    orc_quantize(x, B, T, H, D, batch_stride, token_stride, rel, scale16, min16, q);
+    for (int64_t i = 0; i < n; ++i)
+        meta[i] = (uint32_t)scale16[i] | ((uint32_t)min16[i] << 16);
+
+    int nblk = T / ORC_N;
+    int64_t pos = 0, c = 0;
+    uint8_t tmp[ORC_CHUNK_MAX + 16];
+    int64_t rc = 0;
+    for (int blk = 0; blk < nblk && rc == 0; ++blk)
+        for (int b = 0; b < B && rc == 0; ++b)
+            for (int h = 0; h < H; ++h, ++c) {
+                const uint8_t *q0 = q + (((int64_t)b * T + (int64_t)blk * ORC_N) * H + h) * D;
+                int sz = orc_pack_chunk(q0, (int64_t)H * D, tmp,
+                                        widths_out ? widths_out + c * ORC_PACKS : NULL,
+                                        mins_out ? mins_out + c * ORC_PACKS : NULL);
+                if (pos + sz > arena_cap) { rc = -1; break; }
+                memcpy(arena + pos, tmp, (size_t)sz);
+                offsets16[c] = (uint32_t)(pos / 16);
+                pos += sz;
+            }
+    if (rc == 0) offsets16[c] = (uint32_t)(pos / 16);
+    free(scale16);
+    free(min16);
+    if (!q_out) free(q);
+    return rc ? rc : pos;
+}
+
+/* ------------------------------------------------------------- matvecs -- */
+
+/*
+ * scores[b][hq][t] = sm_scale * sum_d q[b][hq][d] * Khat[b][t][hq/G][d]
+ * (attention definition, Sec. III-B.3).  Tokens t < n_packed use the decoded
+ * codes, tokens n_packed <= t < T are the raw fp16 tail (Sec. III-B.1) and
+ * use x itself.  codes/x are [B][T][H][D] contiguous, meta as orc_compress.
+ */
+void orc_k_scores(const uint8_t *codes, const uint16_t *x, const uint32_t *meta,
+                  int B, int T, int n_packed, int H, int Hq, int D,
+                  const uint16_t *qvec, double sm_scale, double *scores)
+{
+    int G = Hq / H;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int h = hq / G;
+            const uint16_t *qv = qvec + ((int64_t)b * Hq + hq) * D;
+            for (int t = 0; t < T; ++t) {
+                int64_t base = (((int64_t)b * T + t) * H + h) * D;
+                uint32_t mt = meta[(int64_t)b * T + t];
+                double acc = 0.0;
+                for (int d = 0; d < D; ++d) {
+                    double kv = t < n_packed
+                        ? orc_xhat(codes[base + d], (uint16_t)(mt & 0xFFFFu), (uint16_t)(mt >> 16))
+                        : (double)orc_h2f(x[base + d]);
+                    acc += (double)orc_h2f(qv[d]) * kv;
+                }
+                scores[((int64_t)b * Hq + hq) * T + t] = sm_scale * acc;
+            }
+        }
+}
+
+/*
+ * out[b][hq][d] = sum_t p[b][hq][t] * Vhat[b][t][hq/G][d], p is fp32 with
+ * leading dimension ldp (Sec. III-B.3 definition; same tail rule as above).
+ */
+void orc_v_out(const uint8_t *codes, const uint16_t *x, const uint32_t *meta,
+               int B, int T, int n_packed, int H, int Hq, int D,
+               const float *p, int64_t ldp, double *out)
+{
+    int G = Hq / H;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int h = hq / G;
+            double *o = out + ((int64_t)b * Hq + hq) * D;
+            for (int d = 0; d < D; ++d) o[d] = 0.0;
+            for (int t = 0; t < T; ++t) {
+                int64_t base = (((int64_t)b * T + t) * H + h) * D;
+                uint32_t mt = meta[(int64_t)b * T + t];
+                double pt = (double)p[((int64_t)b * Hq + hq) * ldp + t];
+                for (int d = 0; d < D; ++d) {
+                    double vv = t < n_packed
+                        ? orc_xhat(codes[base + d], (uint16_t)(mt & 0xFFFFu), (uint16_t)(mt >> 16))
+                        : (double)orc_h2f(x[base + d]);
+                    o[d] += pt * vv;
+                }
+            }
+        }
+}
+
+/* Softmax over the last axis in fp64 (for the end-to-end decode check). */
+void orc_softmax(const double *s, int rows, int T, double *p)
+{
+    for (int r = 0; r < rows; ++r) {
+        const double *sr = s + (int64_t)r * T;
+        double *pr = p + (int64_t)r * T;
+        double mx = sr[0], sum = 0.0;
+        for (int t = 1; t < T; ++t) if (sr[t] > mx) mx = sr[t];
+        for (int t = 0; t < T; ++t) { pr[t] = exp(sr[t] - mx); sum += pr[t]; }
+        for (int t = 0; t < T; ++t) pr[t] /= sum;
+    }
+}
+
+/* Number of OpenMP threads the matvec loops will use (1 without OpenMP). */
+#ifdef _OPENMP
+#include <omp.h>
+int orc_threads(void) { return omp_get_max_threads(); }
+void orc_set_threads(int n) { if (n > 0) omp_set_num_threads(n); }
+#else
+int orc_threads(void) { return 1; }
+void orc_set_threads(int n) { (void)n; }
+#endif

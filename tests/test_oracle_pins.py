@@ -1,0 +1,294 @@
+"""CPU-only pins of the oracle against what the paper and the mathematics fix.
+
+Every test here compares the oracle with something that is not the oracle:
+numpy's IEEE half type, closed forms and printed values from the paper,
+invariants of the quantizer, an independent bit reader, numpy linear algebra
+on special inputs, brute force on tiny inputs.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2512_24449_amd import synth
+from tests import chunk_reader
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _kv(B, T, H, seed, Hq=None):
+    K, V, q = synth.make_kv(B, T, H, Hq or H, seed)
+    return K.numpy(), V.numpy(), q.numpy()
+
+
+# ------------------------------------------------------------------ fp16 --
+
+def test_half_to_float_all_bit_patterns(orc):
+    bits = np.arange(65536, dtype=np.uint32).astype(np.uint16)
+    ref = bits.view(np.float16).astype(np.float32)
+    got = np.array([orc.h2f(int(b)) for b in bits], dtype=np.float32)
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan].view(np.uint32), ref[~nan].view(np.uint32))
+
+
+def test_float_to_half_matches_ieee_rne(orc):
+    rng = np.random.default_rng(1)
+    vals = np.concatenate([
+        rng.standard_normal(20000).astype(np.float32) * np.float32(10.0) ** rng.integers(-9, 5, 20000),
+        np.array([0.0, -0.0, 65504.0, 65519.9, 65520.0, 70000.0, -65520.0, 2.0 ** -24, 2.0 ** -25,
+                  2.0 ** -25 * 1.0001, 2.0 ** -14, 2.0 ** -14 - 2.0 ** -25, 1.0 + 2.0 ** -11,
+                  1.0 + 3 * 2.0 ** -11, 2047.5, 2048.5, 6.1e-5, 5.96e-8], dtype=np.float32),
+    ]).astype(np.float32)
+    with np.errstate(over="ignore"):
+        ref = vals.astype(np.float16).view(np.uint16)
+    got = np.array([orc.f2h(float(v)) for v in vals], dtype=np.uint16)
+    assert np.array_equal(got, ref)
+
+
+# ------------------------------------------------------- quantizer pins --
+
+@pytest.mark.parametrize("rel,H,seed", [(0.1, 1, 0), (0.1, 8, 1), (0.2, 1, 2), (0.2, 32, 3), (1 / 15, 2, 4)])
+def test_error_bound_and_range(orc, rel, H, seed):
+    """|x - x_hat| <= scale/2 = rel/2 * (max - min) (Sec. IV-A); codes in [0, round(1/rel)]."""
+    K, V, _ = _kv(2, 128, H, seed)
+    for x in (K, V):
+        s16, m16 = orc.token_params(x, rel)
+        q = orc.quantize(x, rel, s16, m16)
+        xhat = orc.dequant(q, s16, m16)
+        scale = s16.view(np.float16).astype(np.float64)[:, :, None, None]
+        err = np.abs(x.astype(np.float64) - xhat)
+        # one fp32 ulp of the ratio of slack: the division is rounded once
+        assert (err <= scale * (0.5 + 2.0 ** -20)).all()
+        qmax = round(1 / rel)
+        assert orc.qmax(rel) == qmax
+        assert q.min() >= 0 and q.max() <= qmax
+        # the stored scale is rel*(max-min) rounded to fp16, the min is the min
+        x64 = x.astype(np.float64).reshape(x.shape[0], x.shape[1], -1)
+        rng = x64.max(-1) - x64.min(-1)
+        assert np.allclose(s16.view(np.float16).astype(np.float64), rel * rng, rtol=2.0 ** -10)
+        assert np.array_equal(m16.view(np.float16).astype(np.float64), x64.min(-1))
+        # each token reaches code 0 at its minimum and qmax at its maximum
+        qf = q.reshape(q.shape[0], q.shape[1], -1)
+        assert (np.take_along_axis(qf, x64.argmin(-1)[..., None], -1) == 0).all()
+        assert (np.take_along_axis(qf, x64.argmax(-1)[..., None], -1) == qmax).all()
+
+
+def test_quantizer_rounds_half_to_even_and_clamps(orc):
+    """scale 1, min 0 token: values j + 0.5 must go to the even neighbour."""
+    x = np.zeros((1, 1, 1, 128), np.float16)
+    x[0, 0, 0, :12] = [0, 10, 0.5, 1.5, 2.5, 3.5, 4.5, 0.25, 0.75, 9.5, 8.5, 7.4375]
+    s16, m16 = orc.token_params(x, 0.1)
+    assert s16.view(np.float16)[0, 0] == 1.0 and m16.view(np.float16)[0, 0] == 0.0
+    q = orc.quantize(x, 0.1, s16, m16)[0, 0, 0, :12]
+    assert q.tolist() == [0, 10, 0, 2, 2, 4, 4, 0, 1, 10, 8, 7]
+
+
+def test_degenerate_tokens(orc):
+    """A constant token has scale 0: all codes 0 and x_hat == the constant."""
+    x = np.full((1, 64, 2, 128), 3.25, np.float16)
+    x[0, 5] = 0.0
+    x[0, 6] = -0.0
+    c = orc.compress(x, 0.1)
+    assert (c.codes == 0).all() and (c.scale16 == 0).all()
+    assert np.array_equal(orc.dequant(c.codes, c.scale16, c.min16), x.astype(np.float64))
+    assert c.min16[0, 6] == 0, "a zero minimum is stored as +0"
+    assert (c.widths == 0).all()
+    assert c.arena.size == 2 * 512, "width-0 packs leave only the headers"
+
+
+# ----------------------------------------------------------- pack pins --
+
+def test_width_table(orc):
+    """ceil(log2(range + 1)) (Sec. III-B.3): 0->0, 1->1, 2-3->2, 4-7->3, 8-15->4."""
+    expect = {0: 0, 1: 1, 2: 2, 3: 2, 4: 3, 5: 3, 6: 3, 7: 3}
+    expect.update({r: 4 for r in range(8, 16)})
+    for r, w in expect.items():
+        assert orc.width(r) == w
+        assert w == int(np.ceil(np.log2(r + 1)))
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_pack_chunk_against_independent_reader(orc, seed):
+    rng = np.random.default_rng(seed)
+    q = rng.integers(0, 11, size=(64, 128)).astype(np.uint8)
+    q[:, 3] = 7                 # constant channel: width 0
+    q[16:32, 9] = [0, 1] * 8    # width 1
+    q[:, 40:60] = rng.integers(4, 7, size=(64, 20))
+    buf, widths, mins = orc.pack_chunk(q)
+    codes, w2, m2 = chunk_reader.read_chunk(buf)
+    assert np.array_equal(codes, q)
+    assert np.array_equal(w2, widths) and np.array_equal(m2, mins)
+    # per-pack minimum and minimal width, recomputed from the definition
+    packs = q.reshape(4, 16, 128).astype(np.int64)
+    assert np.array_equal(mins.reshape(4, 128), packs.min(1))
+    rng_ = packs.max(1) - packs.min(1)
+    assert np.array_equal(widths.reshape(4, 128), np.ceil(np.log2(rng_ + 1)).astype(np.int64))
+    # closed-form size: header + 2 bytes per width bit per pack, padded to 16
+    assert buf.size == (512 + 2 * int(widths.sum()) + 15) // 16 * 16
+
+
+@pytest.mark.parametrize("B,T,H,rel,seed", [(1, 128, 1, 0.1, 0), (2, 192, 3, 0.2, 1), (1, 64, 8, 0.1, 2)])
+def test_compress_round_trip_and_size_formula(orc, B, T, H, rel, seed):
+    K, _, _ = _kv(B, T, H, seed)
+    c = orc.compress(K, rel)
+    nchunks = (T // 64) * B * H
+    assert c.offsets16[0] == 0 and int(c.offsets16[nchunks]) * 16 == c.arena.size
+    assert np.array_equal(chunk_reader.read_arena(c.arena, c.offsets16, B, T, H), c.codes)
+    # bits per element = mean width + 8/16 (pack byte) + padding; token meta adds 32/(H*D)
+    sizes = np.diff(c.offsets16.astype(np.int64)) * 16
+    expect = (512 + 2 * c.widths.astype(np.int64).sum(1) + 15) // 16 * 16
+    assert np.array_equal(sizes, expect)
+    pad_bits = (sizes - 512 - 2 * c.widths.astype(np.int64).sum(1)).sum() * 8
+    bits = c.arena.size * 8 / K.size
+    assert np.isclose(bits, c.widths.mean() + 0.5 + pad_bits / K.size)
+
+
+def _fixed_width_tensor(b, g_heads, T=64, seed=0):
+    """Values on an exact grid so that every pack needs exactly b bits."""
+    rng = np.random.default_rng(seed)
+    qmax = 2 ** b - 1
+    codes = rng.integers(0, qmax + 1, size=(1, T, g_heads, 128))
+    t = np.arange(T)[:, None]
+    d = np.arange(128)[None, :]
+    # in every pack one token holds 0 and the next holds qmax; every token holds both
+    codes[0][np.broadcast_to((t % 16 == d % 16)[:, None, :], codes[0].shape)] = 0
+    codes[0][np.broadcast_to((t % 16 == (d + 1) % 16)[:, None, :], codes[0].shape)] = qmax
+    x = (codes - 4).astype(np.float16)
+    return x, codes, 1.0 / qmax
+
+
+def test_fixed_width_special_case_reproduces_printed_ratios(orc):
+    """With every pack at width b, payload + token metadata alone must give the
+    paper's token-wise ratios 16g/(bg+32) (Table of V ratios, Sec. IV-D.2)."""
+    rows = [l.split() for l in open(os.path.join(GOLD, "paper_closed_form_cr.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) == 11
+    for bits, g, printed, _model in rows:
+        b, g, printed = int(bits), int(g), float(printed)
+        x, codes, rel = _fixed_width_tensor(b, g // 128)
+        c = orc.compress(x, rel)
+        assert np.array_equal(c.codes, codes), "grid data quantizes to its own indices"
+        assert (c.widths == b).all()
+        payload = c.arena.size - 512 * c.widths.shape[0]
+        assert payload * 8 == b * x.size
+        token_meta = c.meta.size * 4
+        cr = x.size * 2 / (payload + token_meta)
+        assert np.isclose(cr, 16 * g / (b * g + 32))
+        assert round(cr, 2) == printed, (b, g, cr, printed)
+
+
+def test_paper_arithmetic_examples():
+    """Byte accounting of the cache layout [ctx, heads, dim] in fp16."""
+    rows = {l.split()[0]: float(l.split()[1]) for l in open(os.path.join(GOLD, "paper_arithmetic_examples.txt"))
+            if l.strip() and not l.startswith("#")}
+    hidden, layers, fp16 = 5120, 40, 2
+    assert round(layers * hidden * fp16 * 2 * 50 / 2 ** 20, 2) == rows["kv_generation_rate"]
+    assert round(32768 * hidden * fp16 / (512 * 5e-6) / 1e9) == rows["launch_bound_rate"]
+    w = synth.workload(3)
+    assert round(w.elements * 2 / 1e9, 2) == 3.41
+
+
+# --------------------------------------------------------- matvec pins --
+
+def _grid_kv(B, T, H, rel, seed):
+    """fp16 data lying exactly on each token's quantization grid (lossless case)."""
+    rng = np.random.default_rng(seed)
+    qmax = round(1 / rel)
+    j = rng.integers(0, qmax + 1, size=(B, T, H, 128))
+    flat = j.reshape(B, T, -1)
+    flat[:, :, 0] = 0
+    flat[:, :, 1] = qmax
+    step = 2.0 ** rng.integers(-3, 3, size=(B, T, 1, 1))
+    lo = rng.integers(-8, 8, size=(B, T, 1, 1)) * step
+    return (lo + j * step).astype(np.float16), j
+
+
+@pytest.mark.parametrize("rel", [0.1, 0.2])
+def test_lossless_grid_reduces_to_plain_gemv(orc, rel):
+    B, T, H, Hq = 2, 128, 2, 4
+    x, j = _grid_kv(B, T, H, rel, 5)
+    c = orc.compress(x, rel)
+    assert np.array_equal(c.codes, j)
+    assert np.array_equal(orc.dequant(c.codes, c.scale16, c.min16), x.astype(np.float64))
+    rng = np.random.default_rng(6)
+    q = rng.standard_normal((B, Hq, 128)).astype(np.float16)
+    p = rng.random((B, Hq, T)).astype(np.float32)
+    x64 = x.astype(np.float64)
+    xq = np.repeat(x64, Hq // H, axis=2)                      # query head h reads kv head h // G
+    s_ref = 0.25 * np.einsum("bhd,bthd->bht", q.astype(np.float64), xq)
+    o_ref = np.einsum("bht,bthd->bhd", p.astype(np.float64), xq)
+    assert np.allclose(orc.k_scores(c.codes, x, c.meta, T, q, 0.25), s_ref, rtol=1e-12, atol=1e-12)
+    assert np.allclose(orc.v_out(c.codes, x, c.meta, T, p), o_ref, rtol=1e-12, atol=1e-12)
+
+
+def test_brute_force_from_bytes_with_raw_tail(orc):
+    """Decode the arena with the independent reader, dequantize with numpy,
+    append a raw fp16 tail, and compare numpy matvecs with the oracle's."""
+    B, T, H, Hq, tail = 2, 128, 2, 4, 37
+    K, V, q = _kv(B, T + 64, H, 7, Hq)
+    K, V = K[:, :T + tail], V[:, :T + tail]
+    rng = np.random.default_rng(8)
+    p = rng.random((B, Hq, T + tail)).astype(np.float32)
+    for x, rel in ((K, 0.1), (V, 0.2)):
+        c = orc.compress(np.ascontiguousarray(x[:, :T]), rel)
+        codes = chunk_reader.read_arena(c.arena, c.offsets16, B, T, H)
+        scale = (c.meta & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float64)
+        mn = (c.meta >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
+        xhat = np.concatenate([codes * scale[:, :, None, None] + mn[:, :, None, None],
+                               x[:, T:].astype(np.float64)], axis=1)
+        xq = np.repeat(xhat, Hq // H, axis=2)
+        codes_full = np.zeros(x.shape, np.uint8)
+        codes_full[:, :T] = c.codes
+        meta_full = np.zeros((B, T + tail), np.uint32)
+        meta_full[:, :T] = c.meta
+        s = orc.k_scores(codes_full, x, meta_full, T, q, 0.5)
+        o = orc.v_out(codes_full, x, meta_full, T, p)
+        assert np.allclose(s, 0.5 * np.einsum("bhd,bthd->bht", q.astype(np.float64), xq), rtol=1e-12, atol=1e-12)
+        assert np.allclose(o, np.einsum("bht,bthd->bhd", p.astype(np.float64), xq), rtol=1e-12, atol=1e-12)
+
+
+def test_softmax_matches_torch(orc):
+    rng = np.random.default_rng(9)
+    s = rng.standard_normal((3, 5, 77)) * 4
+    ref = torch.softmax(torch.from_numpy(s), dim=-1).numpy()
+    assert np.allclose(orc.softmax(s), ref, rtol=1e-13, atol=0)
+
+
+def test_permutation_invariance_of_decode_attention(orc):
+    """Att(q, PK, PV) == Att(q, K, V) (boxed statement, Sec. III-B.3): permuting
+    tokens jointly inside blocks before compression leaves the output unchanged
+    up to summation order, because quantization is per token."""
+    B, T, H, Hq = 1, 256, 2, 4
+    K, V, q = _kv(B, T, H, 11, Hq)
+    rng = np.random.default_rng(12)
+    perm = np.concatenate([blk * 64 + rng.permutation(64) for blk in range(T // 64)])
+
+    def attend(K, V):
+        ck, cv = orc.compress(K, 0.1), orc.compress(V, 0.2)
+        s = orc.k_scores(ck.codes, K, ck.meta, T, q, 128 ** -0.5)
+        p = orc.softmax(s)
+        p32 = p.astype(np.float32)
+        return orc.v_out(cv.codes, V, cv.meta, T, p32), s, ck, cv
+
+    o1, s1, ck1, _ = attend(K, V)
+    o2, s2, ck2, _ = attend(np.ascontiguousarray(K[:, perm]), np.ascontiguousarray(V[:, perm]))
+    assert np.array_equal(ck2.codes, ck1.codes[:, perm]), "token-wise codes move with their token"
+    assert np.allclose(s2, s1[:, :, perm], rtol=0, atol=0)
+    assert np.allclose(o1, o2, rtol=1e-6, atol=1e-9)   # p is rounded to fp32 before the V product
+
+
+def test_planted_mistakes_are_caught(orc):
+    """The pins above must be able to see typical slips: check that perturbed
+    variants of the decoded tensor would violate them."""
+    K, _, _ = _kv(1, 64, 1, 13)
+    c = orc.compress(K, 0.1)
+    xhat = orc.dequant(c.codes, c.scale16, c.min16)
+    scale = c.scale16.view(np.float16).astype(np.float64)[:, :, None, None]
+    ok = np.abs(K.astype(np.float64) - xhat) <= scale * (0.5 + 2.0 ** -20)
+    assert ok.all()
+    shifted = xhat + scale                     # off-by-one code
+    assert not (np.abs(K.astype(np.float64) - shifted) <= scale * (0.5 + 2.0 ** -20)).all()
+    trunc = np.floor((K.astype(np.float64) - (xhat - c.codes * scale)) / scale) * scale + (xhat - c.codes * scale)
+    assert not (np.abs(K.astype(np.float64) - trunc) <= scale * (0.5 + 2.0 ** -20)).all()
