@@ -1,0 +1,199 @@
+/*
+ * packkv.h -- C ABI of the PackKV decode hot path for AMD MI355X (gfx950).
+ *
+ * A KV cache that is token-wise quantized and bit-packed in independent
+ * 64-token blocks (PackKV, arXiv 2512.24449, Sec. III), an append-side
+ * compressor, and two fused kernels that stream the packed cache from HBM,
+ * unpack codes in registers and compute q.K^T and p.V without ever writing
+ * decompressed data back (Sec. III-C).
+ *
+ * Conventions for every entry point
+ *   - "device" pointers are HIP device memory of the current device, owned by
+ *     the caller; the library allocates no device memory and keeps only host
+ *     bookkeeping inside kv_cache_t.
+ *   - `hip_stream` is a hipStream_t passed as void* (NULL = default stream).
+ *     Work is enqueued on it and the call returns without synchronizing
+ *     unless stated otherwise.
+ *   - Return value: KV_OK (0) or a negative KV_ERR_* code.  No exceptions, no
+ *     aborts.  kv_strerror() gives a short text.
+ *   - A kv_cache_t is not thread-safe; distinct handles are independent.
+ *   - Inputs must be finite fp16 values; NaN/Inf never cause out-of-bounds
+ *     accesses but produce unspecified codes.
+ *
+ * Cache layout (Sec. II-A): tokens arrive as fp16 [batch][n][n_kv_heads][128].
+ * Packed format (Sec. III-B.3, III-B.4, III-C): one chunk per
+ * (block of 64 tokens, batch, kv-head), chunk index c = (block*B + b)*H + h,
+ * chunks stored back to back in c order in one arena per tensor:
+ *     bytes [0,512)   header, byte [g*128 + d] = (width << 4) | min of the
+ *                     pack holding tokens 16g..16g+15 of channel d
+ *     then            the 512 packs in the same order, 2*width bytes each,
+ *                     little-endian, token i of the group at bits
+ *                     [i*width, (i+1)*width)
+ *     then            zero padding to a multiple of 16 bytes
+ * index[c] (uint32) is the chunk start in 16-byte units, index[n_chunks] the
+ * arena end.  token_meta[b*max_tokens + t] (uint32) = scale_fp16 | min_fp16<<16
+ * (Sec. III-B.2: one scale and minimum per token over all kv-heads).
+ */
+#ifndef PACKKV_H
+#define PACKKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define KV_OK 0
+#define KV_ERR_ARG (-1)          /* null pointer, bad size, misaligned buffer        */
+#define KV_ERR_UNSUPPORTED (-2)  /* head_dim != 128, block != 64, pack != 16, rel... */
+#define KV_ERR_CAPACITY (-3)     /* append beyond max_tokens / arena too small       */
+#define KV_ERR_HIP (-4)          /* a HIP runtime call failed                        */
+
+#define KV_HEAD_DIM 128
+#define KV_BLOCK_TOKENS 64
+#define KV_PACK_SIZE 16
+#define KV_CHUNK_HEADER 512
+#define KV_CHUNK_MAX_BYTES (512 + 512 * 8)
+
+typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library */
+
+/* Parameters of Sec. IV-A: relative quantization scales (K 0.1, V 0.2 are the
+ * paper's defaults), pack size 16, repacking none, block 64. */
+typedef struct {
+    int32_t batch;         /* B >= 1                                              */
+    int32_t n_kv_heads;    /* H_kv >= 1                                           */
+    int32_t n_q_heads;     /* H_q, a multiple of H_kv, H_q / H_kv in {1,2,4,8}    */
+    int32_t head_dim;      /* must be 128                                         */
+    int32_t block_tokens;  /* must be 64                                          */
+    int32_t pack_size;     /* must be 16                                          */
+    int32_t repack;        /* must be 0 (none)                                    */
+    int32_t tail_capacity; /* raw fp16 tail buffer in tokens, must be 64          */
+    float k_rel_scale;     /* in [1/15, 1]                                        */
+    float v_rel_scale;     /* in [1/15, 1]                                        */
+    int64_t max_tokens;    /* per batch element, rounded up to a block internally */
+} kv_config_t;
+
+/* Bytes of each caller-provided device buffer. */
+typedef struct {
+    size_t k_arena, v_arena;           /* packed chunks                           */
+    size_t k_index, v_index;           /* uint32 [max_chunks + 1]                 */
+    size_t k_token_meta, v_token_meta; /* uint32 [B][max_tokens]                  */
+    size_t k_tail, v_tail;             /* fp16 [B][tail_capacity][H_kv][128]      */
+    size_t workspace;                  /* status words, chunk sizes, V partials   */
+} kv_sizes_t;
+
+/* Device buffers, each at least as large as kv_query_sizes said and 256-byte
+ * aligned.  They must stay valid until kv_cache_destroy. */
+typedef struct {
+    void *k_arena, *v_arena;
+    void *k_index, *v_index;
+    void *k_token_meta, *v_token_meta;
+    void *k_tail, *v_tail;
+    void *workspace;
+} kv_buffers_t;
+
+/* Filled by kv_cache_stats. */
+typedef struct {
+    int64_t tokens;        /* cached tokens per batch element (packed + tail)     */
+    int64_t packed_tokens; /* tokens living in chunks                             */
+    int64_t tail_tokens;   /* tokens in the raw fp16 tail                         */
+    int64_t n_chunks;      /* chunks per tensor                                   */
+    int64_t k_bytes;       /* K arena bytes in use (header + payload + padding)   */
+    int64_t v_bytes;
+    int64_t index_bytes;   /* per tensor                                          */
+    int64_t token_meta_bytes; /* per tensor                                       */
+    int32_t overflow;      /* sticky: an append did not fit into an arena         */
+} kv_stats_t;
+
+/*
+ * Buffer sizes for a configuration.  `bits_per_element_budget` sizes the two
+ * arenas: 0 means worst case (every pack 4 bits wide, 4.5 bits per element
+ * with headers); a positive value reserves that many bits per cached element
+ * (it is clamped to the worst case).  Host only.
+ */
+int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_budget, kv_sizes_t *out);
+
+/*
+ * Create an empty cache over caller-owned device buffers.  Enqueues a small
+ * kernel on the default stream that clears the status words and index[0] and
+ * synchronizes with it.  `sizes` are the real sizes of the buffers (arenas may
+ * be larger or smaller than kv_query_sizes proposed; smaller arenas can
+ * overflow, see kv_cache_stats).
+ */
+int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffers, const kv_sizes_t *sizes,
+                    kv_cache_t **out);
+int kv_cache_destroy(kv_cache_t *cache);
+
+/*
+ * Buffering, quantization, bit-packing and appending (Sec. III-B.1-4).
+ * k_new, v_new: device fp16 [B][n_new][H_kv][128].  Tokens go to the raw
+ * tail; whenever the tail holds 64 tokens they are quantized token-wise
+ * (scale = rel*(max-min) over the token's H_kv*128 values, fp16 scale and
+ * minimum), bit-packed in packs of 16 tokens per channel, and appended to the
+ * arenas as one chunk per (batch, kv-head); the tail then empties.  Several
+ * full blocks in one call are compressed straight from k_new/v_new.
+ * Errors: KV_ERR_CAPACITY if tokens + n_new > max_tokens (nothing is done).
+ * An arena that is too small is detected on the device: the block is dropped,
+ * a sticky overflow flag is set and later reads of that block return zeros.
+ */
+int kv_compress_append(kv_cache_t *cache, const void *k_new, const void *v_new, int32_t n_new,
+                       void *hip_stream);
+
+/*
+ * Fused K path (Sec. III-C.1): scores[b][hq][t] = sm_scale * sum_d
+ * q[b][hq][d] * Khat[b][t][hq / G][d] for every cached token t, where Khat is
+ * scale_t*code + min_t for packed tokens and the raw fp16 value for tail
+ * tokens.  q: device fp16 [B][H_q][128]; scores: device fp32 [B][H_q][ld_scores],
+ * ld_scores >= tokens.  fp32 accumulation.  One launch covers all chunks.
+ */
+int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores, int64_t ld_scores,
+                void *hip_stream);
+
+/*
+ * Fused V path (Sec. III-C.2): out[b][hq][d] = sum_t p[b][hq][t] *
+ * Vhat[b][t][hq / G][d].  p: device fp32 [B][H_q][ld_p], ld_p >= tokens;
+ * out: device fp32 [B][H_q][128].  fp32 accumulation in a fixed order (no
+ * floating-point atomics): the result is bitwise reproducible.  Uses the
+ * workspace for per-split partial sums; calls on one cache must not overlap.
+ */
+int kv_v_matvec(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
+
+/* Counters and byte accounting.  Reads device state: synchronizes `hip_stream`. */
+int kv_cache_stats(kv_cache_t *cache, kv_stats_t *out, void *hip_stream);
+
+/*
+ * Adopt externally written buffer contents (a cache restored from a copy of
+ * its arenas, indices, token metadata and tails): afterwards the cache holds
+ * `tokens` tokens per batch element, floor(tokens/64)*64 of them packed.
+ * Host bookkeeping only; the caller is responsible for the buffer contents.
+ */
+int kv_cache_restore(kv_cache_t *cache, int64_t tokens);
+
+/* Cached tokens per batch element (host bookkeeping, no synchronization). */
+int64_t kv_cache_tokens(const kv_cache_t *cache);
+
+const char *kv_strerror(int code);
+
+/* ---- measurement companions (same shapes, uncompressed fp16 cache) ---------
+ * The comparison kernels of Sec. IV-E, hand-written for the same shapes:
+ * plain fp16 matrix-vector products over an uncompressed cache stored as
+ * fp16 [B][H_kv][tokens][128] (head-major, each (b, h) matrix contiguous).
+ */
+int kv_fp16_k_matvec(const void *k_cache, const void *q, float sm_scale, float *scores,
+                     int64_t ld_scores, int32_t batch, int32_t n_kv_heads, int32_t n_q_heads,
+                     int64_t tokens, void *hip_stream);
+/* workspace: device, at least kv_fp16_v_workspace_bytes(...) bytes. */
+int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_p, float *out, int32_t batch,
+                     int32_t n_kv_heads, int32_t n_q_heads, int64_t tokens, void *workspace,
+                     void *hip_stream);
+size_t kv_fp16_v_workspace_bytes(int32_t batch, int32_t n_q_heads);
+/* Streaming-read ceiling: sums `bytes` (multiple of 16) of device memory into
+ * checksum[0] (device uint32, overwritten).  Used to measure achievable HBM
+ * read bandwidth next to the 8 TB/s peak. */
+int kv_stream_read(const void *src, size_t bytes, uint32_t *checksum, void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PACKKV_H */

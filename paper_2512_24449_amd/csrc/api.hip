@@ -1,0 +1,263 @@
+// Host side of the C ABI declared in packkv.h: argument checks, host
+// bookkeeping and kernel launches.  Allocates no device memory.
+#include <algorithm>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <initializer_list>
+#include <new>
+
+#include "common.h"
+
+using namespace packkv;
+
+namespace {
+
+bool aligned256(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
+
+int check_config(const kv_config_t *c) {
+    if (!c) return KV_ERR_ARG;
+    if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_tokens < 1) return KV_ERR_ARG;
+    if (c->head_dim != D || c->block_tokens != N || c->pack_size != PACK || c->repack != 0 ||
+        c->tail_capacity != N)
+        return KV_ERR_UNSUPPORTED;
+    if (c->n_q_heads % c->n_kv_heads) return KV_ERR_ARG;
+    const int g = c->n_q_heads / c->n_kv_heads;
+    if (g != 1 && g != 2 && g != 4 && g != 8) return KV_ERR_UNSUPPORTED;
+    // one pack byte holds a 4-bit minimum: codes must stay below 16
+    for (float rel : {c->k_rel_scale, c->v_rel_scale}) {
+        if (!(rel > 0.0f) || rel > 1.0f) return KV_ERR_ARG;
+        if (lround(1.0 / double(rel)) > 15) return KV_ERR_UNSUPPORTED;
+    }
+    if (int64_t(c->batch) * c->n_kv_heads > 65535) return KV_ERR_UNSUPPORTED;
+    const int64_t max_tokens = (c->max_tokens + N - 1) / N * N;
+    const int64_t max_chunks = max_tokens / N * c->batch * c->n_kv_heads;
+    if (max_chunks > 0x7FFFFFF0) return KV_ERR_UNSUPPORTED;
+    return KV_OK;
+}
+
+size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
+
+}  // namespace
+
+extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_budget, kv_sizes_t *out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!out || bits_per_element_budget < 0.0) return KV_ERR_ARG;
+    const int64_t max_tokens = (cfg->max_tokens + N - 1) / N * N;
+    const int64_t max_chunks = max_tokens / N * cfg->batch * cfg->n_kv_heads;
+    const double worst_bits = double(CHUNK_MAX) * 8.0 / (N * D);
+    double bits = bits_per_element_budget == 0.0 ? worst_bits : bits_per_element_budget;
+    if (bits > worst_bits) bits = worst_bits;
+    // never less than the headers, plus one worst-case chunk of slack per stream for padding
+    double per_chunk = bits * (N * D) / 8.0;
+    if (per_chunk < HEADER + 16) per_chunk = HEADER + 16;
+    size_t arena = size_t(std::ceil(per_chunk * double(max_chunks))) + 16;
+    if (arena > size_t(0xFFFFFFFFull) * 16) return KV_ERR_UNSUPPORTED;  // index is in 16-byte units
+    out->k_arena = out->v_arena = round256(arena);
+    out->k_index = out->v_index = round256(size_t(max_chunks + 1) * 4);
+    out->k_token_meta = out->v_token_meta = round256(size_t(cfg->batch) * max_tokens * 4);
+    out->k_tail = out->v_tail =
+        round256(size_t(cfg->batch) * cfg->tail_capacity * cfg->n_kv_heads * D * 2);
+    out->workspace = round256(WS_VPART + v_partial_bytes(cfg->batch, cfg->n_q_heads));
+    return KV_OK;
+}
+
+extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffers,
+                               const kv_sizes_t *sizes, kv_cache_t **out) {
+    int rc = check_config(cfg);
+    if (rc) return rc;
+    if (!buffers || !sizes || !out) return KV_ERR_ARG;
+    kv_sizes_t need;
+    rc = kv_query_sizes(cfg, 0.0, &need);
+    if (rc) return rc;
+    const void *ptrs[] = {buffers->k_arena, buffers->v_arena, buffers->k_index, buffers->v_index,
+                          buffers->k_token_meta, buffers->v_token_meta, buffers->k_tail,
+                          buffers->v_tail, buffers->workspace};
+    for (const void *p : ptrs)
+        if (!aligned256(p)) return KV_ERR_ARG;
+    // arenas may be any size >= one chunk; everything else must be complete
+    if (sizes->k_arena < CHUNK_MAX || sizes->v_arena < CHUNK_MAX || sizes->k_index < need.k_index ||
+        sizes->v_index < need.v_index || sizes->k_token_meta < need.k_token_meta ||
+        sizes->v_token_meta < need.v_token_meta || sizes->k_tail < need.k_tail ||
+        sizes->v_tail < need.v_tail || sizes->workspace < need.workspace)
+        return KV_ERR_ARG;
+    kv_cache *c = new (std::nothrow) kv_cache;
+    if (!c) return KV_ERR_ARG;
+    c->cfg = *cfg;
+    c->buf = *buffers;
+    c->sizes = *sizes;
+    c->max_tokens = (cfg->max_tokens + N - 1) / N * N;
+    c->max_chunks = c->max_tokens / N * cfg->batch * cfg->n_kv_heads;
+    c->group = cfg->n_q_heads / cfg->n_kv_heads;
+    c->qmax_k = int(lround(1.0 / double(cfg->k_rel_scale)));
+    c->qmax_v = int(lround(1.0 / double(cfg->v_rel_scale)));
+    c->packed_tokens = 0;
+    c->tail_tokens = 0;
+    rc = launch_init(c, nullptr);
+    if (rc == KV_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = KV_ERR_HIP;
+    if (rc) {
+        delete c;
+        return rc;
+    }
+    *out = c;
+    return KV_OK;
+}
+
+extern "C" int kv_cache_destroy(kv_cache_t *cache) {
+    if (!cache) return KV_ERR_ARG;
+    delete cache;
+    return KV_OK;
+}
+
+namespace {
+
+// Compress `n_blocks` full blocks whose tokens start at `src` (batch 0).
+int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t batch_stride,
+                    int n_blocks, hipStream_t s) {
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
+    const int per_round = std::max(1, MAX_NEW_CHUNKS / (B * H));
+    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
+    uint32_t *status = reinterpret_cast<uint32_t *>(ws + WS_STATUS);
+    int done = 0;
+    while (done < n_blocks) {
+        const int nb = std::min(per_round, n_blocks - done);
+        CompressJob job;
+        job.batch_stride = batch_stride;
+        job.token_stride = int64_t(H) * D;
+        job.n_blocks = nb;
+        job.first_token = c->packed_tokens;
+        job.first_chunk = c->packed_tokens / N * B * H;
+        // K
+        job.src = ksrc + int64_t(done) * N * job.token_stride;
+        job.rel = c->cfg.k_rel_scale;
+        job.qmax = c->qmax_k;
+        job.arena = static_cast<uint8_t *>(c->buf.k_arena);
+        job.arena_cap16 = c->sizes.k_arena / 16;
+        job.index = static_cast<uint32_t *>(c->buf.k_index);
+        job.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
+        job.status = status + ST_OVERFLOW_K;
+        int rc = launch_compress(c, job, s);
+        if (rc) return rc;
+        // V
+        job.src = vsrc + int64_t(done) * N * job.token_stride;
+        job.rel = c->cfg.v_rel_scale;
+        job.qmax = c->qmax_v;
+        job.arena = static_cast<uint8_t *>(c->buf.v_arena);
+        job.arena_cap16 = c->sizes.v_arena / 16;
+        job.index = static_cast<uint32_t *>(c->buf.v_index);
+        job.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
+        job.status = status + ST_OVERFLOW_V;
+        rc = launch_compress(c, job, s);
+        if (rc) return rc;
+        c->packed_tokens += int64_t(nb) * N;
+        done += nb;
+    }
+    return KV_OK;
+}
+
+}  // namespace
+
+extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *v_new, int32_t n_new,
+                                  void *hip_stream) {
+    if (!c || n_new < 0) return KV_ERR_ARG;
+    if (n_new == 0) return KV_OK;
+    if (!k_new || !v_new) return KV_ERR_ARG;
+    if ((reinterpret_cast<uintptr_t>(k_new) | reinterpret_cast<uintptr_t>(v_new)) & 15u) return KV_ERR_ARG;
+    if (c->packed_tokens + c->tail_tokens + n_new > c->max_tokens) return KV_ERR_CAPACITY;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
+    (void)B;
+    const int64_t row = int64_t(H) * D;
+    const int64_t src_batch_stride = int64_t(n_new) * row;
+    const __half *ksrc = static_cast<const __half *>(k_new);
+    const __half *vsrc = static_cast<const __half *>(v_new);
+    __half *ktail = static_cast<__half *>(c->buf.k_tail);
+    __half *vtail = static_cast<__half *>(c->buf.v_tail);
+    int64_t pos = 0, remaining = n_new;
+    int rc;
+
+    if (c->tail_tokens > 0 || remaining < N) {
+        const int take = int(std::min<int64_t>(remaining, N - c->tail_tokens));
+        if ((rc = launch_tail_copy(c, ksrc, src_batch_stride, take, ktail, c->tail_tokens, s))) return rc;
+        if ((rc = launch_tail_copy(c, vsrc, src_batch_stride, take, vtail, c->tail_tokens, s))) return rc;
+        c->tail_tokens += take;
+        pos += take;
+        remaining -= take;
+        if (c->tail_tokens == N) {
+            if ((rc = compress_blocks(c, ktail, vtail, int64_t(c->cfg.tail_capacity) * row, 1, s))) return rc;
+            c->tail_tokens = 0;
+        }
+    }
+    const int full = int(remaining / N);
+    if (full > 0) {
+        if ((rc = compress_blocks(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, full, s))) return rc;
+        pos += int64_t(full) * N;
+        remaining -= int64_t(full) * N;
+    }
+    if (remaining > 0) {
+        if ((rc = launch_tail_copy(c, ksrc + pos * row, src_batch_stride, int(remaining), ktail, 0, s))) return rc;
+        if ((rc = launch_tail_copy(c, vsrc + pos * row, src_batch_stride, int(remaining), vtail, 0, s))) return rc;
+        c->tail_tokens = int(remaining);
+    }
+    return KV_OK;
+}
+
+extern "C" int kv_k_matvec(kv_cache_t *c, const void *q, float sm_scale, float *scores,
+                           int64_t ld_scores, void *hip_stream) {
+    if (!c || !q || !scores) return KV_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(q) & 15u) return KV_ERR_ARG;
+    if (ld_scores < c->packed_tokens + c->tail_tokens) return KV_ERR_ARG;
+    return launch_k_matvec(c, static_cast<const __half *>(q), sm_scale, scores, ld_scores,
+                           static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int kv_v_matvec(kv_cache_t *c, const float *p, int64_t ld_p, float *out, void *hip_stream) {
+    if (!c || !p || !out) return KV_ERR_ARG;
+    if (ld_p < c->packed_tokens + c->tail_tokens) return KV_ERR_ARG;
+    return launch_v_matvec(c, p, ld_p, out, static_cast<hipStream_t>(hip_stream));
+}
+
+extern "C" int kv_cache_stats(kv_cache_t *c, kv_stats_t *out, void *hip_stream) {
+    if (!c || !out) return KV_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    KV_HIP_CHECK(hipStreamSynchronize(s));
+    const int64_t n_chunks = c->packed_tokens / N * c->cfg.batch * c->cfg.n_kv_heads;
+    uint32_t kend = 0, vend = 0, status[2] = {0, 0};
+    KV_HIP_CHECK(hipMemcpy(&kend, static_cast<uint32_t *>(c->buf.k_index) + n_chunks, 4, hipMemcpyDeviceToHost));
+    KV_HIP_CHECK(hipMemcpy(&vend, static_cast<uint32_t *>(c->buf.v_index) + n_chunks, 4, hipMemcpyDeviceToHost));
+    KV_HIP_CHECK(hipMemcpy(status, static_cast<uint8_t *>(c->buf.workspace) + WS_STATUS, 8, hipMemcpyDeviceToHost));
+    std::memset(out, 0, sizeof(*out));
+    out->tokens = c->packed_tokens + c->tail_tokens;
+    out->packed_tokens = c->packed_tokens;
+    out->tail_tokens = c->tail_tokens;
+    out->n_chunks = n_chunks;
+    out->k_bytes = int64_t(kend) * 16;
+    out->v_bytes = int64_t(vend) * 16;
+    out->index_bytes = (n_chunks + 1) * 4;
+    out->token_meta_bytes = int64_t(c->cfg.batch) * c->packed_tokens * 4;
+    out->overflow = (status[ST_OVERFLOW_K] || status[ST_OVERFLOW_V]) ? 1 : 0;
+    return KV_OK;
+}
+
+extern "C" int kv_cache_restore(kv_cache_t *c, int64_t tokens) {
+    if (!c || tokens < 0 || tokens > c->max_tokens) return KV_ERR_ARG;
+    c->packed_tokens = tokens / N * N;
+    c->tail_tokens = int(tokens - c->packed_tokens);
+    return KV_OK;
+}
+
+extern "C" int64_t kv_cache_tokens(const kv_cache_t *c) {
+    return c ? c->packed_tokens + c->tail_tokens : KV_ERR_ARG;
+}
+
+extern "C" const char *kv_strerror(int code) {
+    switch (code) {
+        case KV_OK: return "ok";
+        case KV_ERR_ARG: return "invalid argument";
+        case KV_ERR_UNSUPPORTED: return "unsupported configuration";
+        case KV_ERR_CAPACITY: return "cache capacity exceeded";
+        case KV_ERR_HIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}

@@ -1,0 +1,280 @@
+// Append-side compressor: token-wise quantization, bit-packing, appending
+// (PackKV Sec. III-B.1 .. III-B.4).  Cold path: runs once per 64 decode steps.
+//
+//   token_params   one workgroup per (token, batch): min/max over the token's
+//                  H*128 values -> fp16 scale = rel*(max-min), fp16 min
+//   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
+//   scan_offsets   one workgroup: prefix sum of the new chunk sizes -> index
+//   pack_chunks    one workgroup per chunk: quantize again and write header +
+//                  payload at its final place (no staging copy, no atomics, so
+//                  the arena bytes are a pure function of the input)
+#include <algorithm>
+
+#include "common.h"
+
+namespace packkv {
+
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void token_params_kernel(const __half *__restrict__ src,
+                                                           int64_t batch_stride,
+                                                           int64_t token_stride, int row_elems,
+                                                           float rel, uint32_t *__restrict__ meta,
+                                                           int64_t meta_stride,
+                                                           int64_t first_token) {
+    const int t = blockIdx.x, b = blockIdx.y;
+    const __half *row = src + b * batch_stride + t * token_stride;
+    float mn = INFINITY, mx = -INFINITY;
+    for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+        const __half *h = reinterpret_cast<const __half *>(&raw);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            float v = __half2float(h[k]);
+            mn = fminf(mn, v);
+            mx = fmaxf(mx, v);
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        mn = fminf(mn, __shfl_xor(mn, o));
+        mx = fmaxf(mx, __shfl_xor(mx, o));
+    }
+    __shared__ float smn[4], smx[4];
+    if ((threadIdx.x & 63) == 0) {
+        smn[threadIdx.x >> 6] = mn;
+        smx[threadIdx.x >> 6] = mx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        mn = fminf(fminf(smn[0], smn[1]), fminf(smn[2], smn[3]));
+        mx = fmaxf(fmaxf(smx[0], smx[1]), fmaxf(smx[2], smx[3]));
+        mn = mn + 0.0f;  // a zero minimum or maximum is stored as +0
+        mx = mx + 0.0f;
+        float range = mx - mn;
+        float s = rel * range;
+        // The product is rounded to fp32 first and to fp16 second; keep the
+        // compiler from fusing both into one mixed-precision FMA (one rounding).
+        asm volatile("" : "+v"(s));
+        __half s16 = __float2half_rn(s);
+        __half m16 = __float2half_rn(mn);  // exact: mn is an fp16 value
+        uint32_t word = uint32_t(__half_as_ushort(s16)) | (uint32_t(__half_as_ushort(m16)) << 16);
+        meta[b * meta_stride + first_token + t] = word;
+    }
+}
+
+// Quantize the 16 tokens of one pack (channel d of token group g) and derive
+// its minimum, width and code bits.
+struct PackBits {
+    uint64_t bits;
+    int w, m;
+};
+
+__device__ inline PackBits make_pack(const __half *__restrict__ x0, int64_t token_stride,
+                                     const uint32_t *__restrict__ meta_g, int qmax) {
+    int q[PACK];
+    int lo = 255, hi = 0;
+#pragma unroll
+    for (int i = 0; i < PACK; ++i) {
+        uint32_t mt = meta_g[i];
+        float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+        float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+        float x = __half2float(x0[i * token_stride]);
+        int v = 0;
+        if (s != 0.0f) {
+            float ratio = (x - mn) / s;  // IEEE fp32 divide
+            float r = rintf(ratio);      // ties to even
+            v = (int)r;
+            v = v < 0 ? 0 : (v > qmax ? qmax : v);
+        }
+        q[i] = v;
+        lo = min(lo, v);
+        hi = max(hi, v);
+    }
+    PackBits pb;
+    int range = hi - lo;
+    pb.w = range == 0 ? 0 : 32 - __clz(range);
+    pb.m = lo;
+    pb.bits = 0;
+#pragma unroll
+    for (int i = 0; i < PACK; ++i) pb.bits |= uint64_t(q[i] - lo) << (i * pb.w);
+    return pb;
+}
+
+// Exclusive prefix sum over the 256 threads of a workgroup; also returns the total.
+__device__ inline int block_exclusive_scan(int v, int *total) {
+    __shared__ int wave_sum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        int n = __shfl_up(inc, o);
+        if (lane >= o) inc += n;
+    }
+    __syncthreads();  // protects wave_sum against a previous call
+    if (lane == 63) wave_sum[wave] = inc;
+    __syncthreads();
+    int base = 0;
+    for (int k = 0; k < wave; ++k) base += wave_sum[k];
+    *total = wave_sum[0] + wave_sum[1] + wave_sum[2] + wave_sum[3];
+    return base + inc - v;
+}
+
+// One workgroup per new chunk; thread tau owns packs tau and tau + 256.
+template <bool WRITE>
+__global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ src,
+                                                    int64_t batch_stride, int64_t token_stride,
+                                                    int B, int H, int qmax,
+                                                    const uint32_t *__restrict__ meta,
+                                                    int64_t meta_stride, int64_t first_token,
+                                                    int64_t first_chunk,
+                                                    uint32_t *__restrict__ sizes16,
+                                                    const uint32_t *__restrict__ index,
+                                                    uint8_t *__restrict__ arena) {
+    const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
+    const int h = cl % H;
+    const int b = (cl / H) % B;
+    const int blk = cl / (H * B);
+    const int tau = threadIdx.x;
+    const int d = tau & 127;
+
+    uint8_t *dst = nullptr;
+    if (WRITE) {
+        uint32_t o0 = index[first_chunk + cl], o1 = index[first_chunk + cl + 1];
+        if (o1 == o0) return;  // dropped: the arena was full
+        dst = arena + size_t(o0) * 16;
+    }
+
+    PackBits pb[2];
+    int len[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        int g = (tau >> 7) + 2 * k;
+        int64_t tok = int64_t(blk) * N + g * PACK;
+        const __half *x0 = src + b * batch_stride + tok * token_stride + h * D + d;
+        pb[k] = make_pack(x0, token_stride, meta + b * meta_stride + first_token + tok, qmax);
+        len[k] = 2 * pb[k].w;
+    }
+    int total0, total1;
+    int off0 = block_exclusive_scan(len[0], &total0);
+    int off1 = block_exclusive_scan(len[1], &total1) + total0;
+    const int payload = total0 + total1;
+    const int padded = (HEADER + payload + 15) & ~15;
+
+    if (!WRITE) {
+        if (tau == 0) sizes16[cl] = uint32_t(padded >> 4);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        int p = tau + 256 * k;
+        dst[p] = uint8_t((pb[k].w << 4) | pb[k].m);
+        uint16_t *out = reinterpret_cast<uint16_t *>(dst + HEADER + (k ? off1 : off0));
+        for (int j = 0; j < pb[k].w; ++j) out[j] = uint16_t(pb[k].bits >> (16 * j));
+    }
+    if (tau < (padded - HEADER - payload) / 2)
+        reinterpret_cast<uint16_t *>(dst + HEADER + payload)[tau] = 0;
+}
+
+// Single workgroup: index[first+i+1] = index[first] + sum_{j<=i} sizes16[j].
+// If the new chunks do not fit, all of them get size 0 and the flag is set.
+__global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__restrict__ sizes16,
+                                                            int n, uint32_t *__restrict__ index,
+                                                            int64_t first_chunk,
+                                                            uint64_t arena_cap16,
+                                                            uint32_t *__restrict__ status) {
+    __shared__ uint32_t wsum[16];
+    __shared__ uint32_t total_s;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (n + 1023) / 1024;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);
+    uint32_t local = 0;
+    for (int i = lo; i < hi; ++i) local += sizes16[i];
+    uint32_t inc = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t v = __shfl_up(inc, o);
+        if (lane >= o) inc += v;
+    }
+    if (lane == 63) wsum[wave] = inc;
+    __syncthreads();
+    uint32_t base = 0;
+    for (int k = 0; k < wave; ++k) base += wsum[k];
+    if (tid == 1023) total_s = base + inc;
+    __syncthreads();
+    const uint32_t start = index[first_chunk];
+    const bool fits = uint64_t(start) + total_s <= arena_cap16;
+    if (!fits && tid == 0) status[0] = 1;
+    uint32_t run = start + base + inc - local;
+    for (int i = lo; i < hi; ++i) {
+        run += sizes16[i];
+        index[first_chunk + i + 1] = fits ? run : start;
+    }
+}
+
+__global__ void tail_copy_kernel(const uint4 *__restrict__ src, int64_t src_batch_stride16,
+                                 uint4 *__restrict__ dst, int64_t dst_batch_stride16,
+                                 int64_t n16) {
+    const int b = blockIdx.y;
+    for (int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; i < n16;
+         i += int64_t(gridDim.x) * blockDim.x)
+        dst[b * dst_batch_stride16 + i] = src[b * src_batch_stride16 + i];
+}
+
+__global__ void init_kernel(uint32_t *status, uint32_t *k_index, uint32_t *v_index) {
+    if (threadIdx.x < 64) status[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        k_index[0] = 0;
+        v_index[0] = 0;
+    }
+}
+
+// ---------------------------------------------------------------------------
+int launch_init(const kv_cache *c, hipStream_t s) {
+    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
+    hipLaunchKernelGGL(init_kernel, dim3(1), dim3(64), 0, s,
+                       reinterpret_cast<uint32_t *>(ws + WS_STATUS),
+                       static_cast<uint32_t *>(c->buf.k_index),
+                       static_cast<uint32_t *>(c->buf.v_index));
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_tail_copy(const kv_cache *c, const __half *src, int64_t src_batch_stride, int n,
+                     __half *tail, int tail_pos, hipStream_t s) {
+    const int64_t row = int64_t(c->cfg.n_kv_heads) * D;  // elements per token
+    const int64_t n16 = n * row / 8;
+    if (n16 == 0) return KV_OK;
+    const int threads = 256;
+    const int blocks = int(std::min<int64_t>((n16 + threads - 1) / threads, 1024));
+    hipLaunchKernelGGL(tail_copy_kernel, dim3(blocks, c->cfg.batch), dim3(threads), 0, s,
+                       reinterpret_cast<const uint4 *>(src), src_batch_stride / 8,
+                       reinterpret_cast<uint4 *>(tail + int64_t(tail_pos) * row),
+                       int64_t(c->cfg.tail_capacity) * row / 8, n16);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_compress(const kv_cache *c, const CompressJob &job, hipStream_t s) {
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
+    const int n_tokens = job.n_blocks * N;
+    const int n_chunks = job.n_blocks * B * H;
+    if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
+    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
+    uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
+
+    hipLaunchKernelGGL(token_params_kernel, dim3(n_tokens, B), dim3(256), 0, s, job.src,
+                       job.batch_stride, job.token_stride, H * D, job.rel, job.meta,
+                       c->max_tokens, job.first_token);
+    hipLaunchKernelGGL(chunk_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
+                       job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                       job.first_token, job.first_chunk, sizes16, job.index, job.arena);
+    hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
+                       job.index, job.first_chunk, job.arena_cap16, job.status);
+    hipLaunchKernelGGL(chunk_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
+                       job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                       job.first_token, job.first_chunk, sizes16, job.index, job.arena);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+}  // namespace packkv

@@ -1,0 +1,123 @@
+"""Shared machinery of the GPU parity tests: run one cache configuration
+through the C-ABI library and through the CPU oracle on the same seeded inputs
+and compare.
+
+Acceptance (per output vector y, i.e. one query head's scores over the tokens,
+or one query head's 128 outputs):
+    packed bytes, chunk index, token metadata      bit-exact
+    ||y_gpu - y_orc||_2 <= 1e-3 * ||y_orc||_2  and  max|diff| <= 1e-3 * max|y_orc|
+(fp32 accumulation on the GPU against the oracle's fp64).
+"""
+import numpy as np
+import torch
+
+import oracle
+from paper_2512_24449_amd import binding, synth
+
+REL_TOL = 1e-3
+
+
+def assert_close_vectors(got, ref, what, tol=REL_TOL):
+    """got/ref: [..., n]; every vector along the last axis must meet the bar."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    assert got.shape == ref.shape, (what, got.shape, ref.shape)
+    if ref.size == 0:
+        return
+    diff = got - ref
+    l2 = np.linalg.norm(diff, axis=-1)
+    ref_l2 = np.linalg.norm(ref, axis=-1)
+    mx = np.abs(diff).max(axis=-1)
+    ref_mx = np.abs(ref).max(axis=-1)
+    bad = (l2 > tol * ref_l2 + 1e-30) | (mx > tol * ref_mx + 1e-30)
+    assert not bad.any(), "%s: %d vectors off; worst rel l2 %.3e, worst rel max %.3e" % (
+        what, int(bad.sum()), float((l2 / np.maximum(ref_l2, 1e-300)).max()),
+        float((mx / np.maximum(ref_mx, 1e-300)).max()))
+
+
+def oracle_cache(K, V, k_rel=0.1, v_rel=0.2):
+    """Compress the packed prefix of K and V with the oracle.  K, V: numpy fp16 [B, L, H, D]."""
+    L = K.shape[1]
+    n_packed = L // 64 * 64
+    ck = oracle.compress(np.ascontiguousarray(K[:, :n_packed]), k_rel) if n_packed else None
+    cv = oracle.compress(np.ascontiguousarray(V[:, :n_packed]), v_rel) if n_packed else None
+    return n_packed, ck, cv
+
+
+def full_codes(c, shape, n_packed):
+    """Codes and token meta padded out to all L tokens (tail rows unused)."""
+    B, L, H, D = shape
+    codes = np.zeros(shape, np.uint8)
+    meta = np.zeros((B, L), np.uint32)
+    if n_packed:
+        codes[:, :n_packed] = c.codes
+        meta[:, :n_packed] = c.meta
+    return codes, meta
+
+
+def check_packed_state(cache, n_packed, ck, cv, B, H):
+    """Arena bytes, index and token meta of the GPU cache == the oracle's, bit for bit."""
+    st = cache.kv_cache_stats()
+    assert st.overflow == 0
+    assert st.packed_tokens == n_packed
+    if not n_packed:
+        return st
+    n_chunks = n_packed // 64 * B * H
+    assert st.n_chunks == n_chunks
+    max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
+    for name, c, nbytes in (("k", ck, st.k_bytes), ("v", cv, st.v_bytes)):
+        assert nbytes == c.arena.size, (name, nbytes, c.arena.size)
+        index = cache.view(name + "_index", torch.int32)[:n_chunks + 1].cpu().numpy().view(np.uint32)
+        assert np.array_equal(index, c.offsets16), name + " index"
+        arena = cache.tensors[name + "_arena"][:nbytes].cpu().numpy()
+        if not np.array_equal(arena, c.arena):
+            first = int(np.nonzero(arena != c.arena)[0][0])
+            raise AssertionError("%s arena differs first at byte %d of %d" % (name, first, nbytes))
+        meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[:, :n_packed]
+        assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta), name + " token meta"
+    return st
+
+
+def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
+             max_tokens=None):
+    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything."""
+    K, V, q = synth.make_kv(B, L, H, Hq, seed)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
+    cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), device=device)
+    Kd, Vd, qd = K.to(device), V.to(device), q.to(device)
+    pos = 0
+    for n in (pieces or [L]):
+        cache.kv_compress_append(Kd[:, pos:pos + n].contiguous(), Vd[:, pos:pos + n].contiguous())
+        pos += n
+    assert pos == L and cache.tokens == L
+
+    n_packed, ck, cv = oracle_cache(Kn, Vn)
+    if check_bytes:
+        check_packed_state(cache, n_packed, ck, cv, B, H)
+
+    scores = cache.kv_k_matvec(qd, sm_scale)
+    torch.cuda.synchronize()
+    kcodes, kmeta = full_codes(ck, Kn.shape, n_packed)
+    s_ref = oracle.k_scores(kcodes, Kn, kmeta, n_packed, qn, sm_scale)
+    assert_close_vectors(scores.cpu().numpy(), s_ref, "K scores")
+
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    vcodes, vmeta = full_codes(cv, Vn.shape, n_packed)
+    o_ref = oracle.v_out(vcodes, Vn, vmeta, n_packed, p.cpu().numpy())
+    assert_close_vectors(out.cpu().numpy(), o_ref, "V out")
+
+    # end to end against an fp64 softmax of the oracle's own scores
+    p64 = oracle.softmax(s_ref)
+    o_e2e = oracle.v_out(vcodes, Vn, vmeta, n_packed, p64.astype(np.float32))
+    assert_close_vectors(out.cpu().numpy(), o_e2e, "decode step end to end", tol=2e-3)
+
+    # determinism: a second pass gives the same bits
+    scores2 = cache.kv_k_matvec(qd, sm_scale)
+    out2 = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    assert torch.equal(scores, scores2) and torch.equal(out, out2)
+    cache.close()
+    return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)

@@ -1,0 +1,177 @@
+"""GPU parity tests: the HIP path, called through the C ABI, against the CPU
+oracle on the same seeded inputs."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_24449_amd import binding, synth
+from tests import gpu_cases
+from tests.gpu_cases import assert_close_vectors
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("B,H,Hq,L,seed", [
+    (1, 1, 1, 64, 10),        # one chunk
+    (1, 1, 1, 1024, 0),       # benchmark configuration 0
+    (2, 3, 6, 192, 11),       # several heads and batches, G = 2
+    (1, 8, 32, 512, 12),      # GQA with G = 4
+    (1, 2, 16, 256, 13),      # G = 8
+    (3, 5, 5, 320 + 37, 14),  # ragged: 37 tokens stay in the raw tail
+    (1, 4, 4, 17, 15),        # tail only, nothing packed
+])
+def test_append_then_decode_matches_oracle(B, H, Hq, L, seed):
+    gpu_cases.run_case(B, H, Hq, L, seed)
+
+
+def test_benchmark_configuration_1_llama2_7b_4k():
+    w = synth.workload(1)
+    sizes = gpu_cases.run_case(w.batch, w.n_kv_heads, w.n_q_heads, w.tokens, 1)
+    assert sizes["k_bytes"] > 0
+
+
+def test_incremental_appends_equal_bulk_compression():
+    """Token-by-token growth with flushes every 64 tokens gives the same bytes as one call."""
+    gpu_cases.run_case(2, 2, 4, 64 * 3 + 5, 20, pieces=[1, 62, 1, 1, 63, 64, 5])
+    gpu_cases.run_case(1, 3, 3, 200, 21, pieces=[130, 70])
+    gpu_cases.run_case(1, 1, 1, 130, 22, pieces=[1] * 130)
+
+
+def test_decode_kernels_on_oracle_packed_bytes():
+    """Feed the fused kernels a cache written by the oracle (restore path):
+    isolates the decode kernels from the GPU compressor."""
+    B, H, Hq, L = 2, 4, 8, 448
+    K, V, q = synth.make_kv(B, L, H, Hq, 30)
+    n_packed, ck, cv = gpu_cases.oracle_cache(K.numpy(), V.numpy())
+    cache = binding.PackedKVCache(B, H, Hq, L)
+    for name, c in (("k", ck), ("v", cv)):
+        cache.tensors[name + "_arena"][:c.arena.size].copy_(torch.from_numpy(c.arena))
+        cache.view(name + "_index", torch.int32)[:c.offsets16.size].copy_(
+            torch.from_numpy(c.offsets16.view(np.int32)))
+        cache.view(name + "_token_meta", torch.int32).view(B, -1)[:, :L].copy_(
+            torch.from_numpy(c.meta.view(np.int32)))
+    cache.kv_cache_restore(L)
+    qd = q.cuda()
+    scores = cache.kv_k_matvec(qd, 0.125)
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    s_ref = oracle.k_scores(ck.codes, K.numpy(), ck.meta, L, q.numpy(), 0.125)
+    o_ref = oracle.v_out(cv.codes, V.numpy(), cv.meta, L, p.cpu().numpy())
+    assert_close_vectors(scores.cpu().numpy(), s_ref, "K scores on oracle bytes")
+    assert_close_vectors(out.cpu().numpy(), o_ref, "V out on oracle bytes")
+
+
+def _special_case(K, V, Hq, k_rel=0.1, v_rel=0.2):
+    """Compress given fp16 arrays on the GPU, compare bytes and a decode step."""
+    B, L, H, _ = K.shape
+    q = synth.make_kv(B, 64, H, Hq, 99)[2]
+    cache = binding.PackedKVCache(B, H, Hq, L, k_rel_scale=k_rel, v_rel_scale=v_rel)
+    cache.kv_compress_append(torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    n_packed, ck, cv = gpu_cases.oracle_cache(K, V, k_rel, v_rel)
+    st = gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
+    scores = cache.kv_k_matvec(q.cuda(), 1.0)
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    kc, km = gpu_cases.full_codes(ck, K.shape, n_packed)
+    vc, vm = gpu_cases.full_codes(cv, V.shape, n_packed)
+    assert_close_vectors(scores.cpu().numpy(), oracle.k_scores(kc, K, km, n_packed, q.numpy(), 1.0), "K")
+    assert_close_vectors(out.cpu().numpy(), oracle.v_out(vc, V, vm, n_packed, p.cpu().numpy()), "V")
+    return st, ck, cv
+
+
+def test_degenerate_inputs():
+    rng = np.random.default_rng(40)
+    # constant tokens (scale 0, width 0 everywhere): chunks are headers only
+    K = np.full((1, 128, 2, 128), 1.5, np.float16)
+    V = np.zeros((1, 128, 2, 128), np.float16)
+    V[0, 3] = -0.0
+    st, ck, _ = _special_case(K, V, 2)
+    assert st.k_bytes == 4 * 512 and (ck.widths == 0).all()
+    # every pack at the maximum width 4 (rel 1/15, codes 0..15 on an exact grid)
+    codes = rng.integers(0, 16, size=(1, 64, 1, 128))
+    codes[0, 0::2] = np.where(np.arange(128) % 2 == 0, 0, 15)[None, None, :]
+    codes[0, 1::2] = np.where(np.arange(128) % 2 == 0, 15, 0)[None, None, :]
+    x = (codes - 7).astype(np.float16)
+    st, ck, _ = _special_case(x, x.copy(), 1, k_rel=1 / 15, v_rel=1 / 15)
+    assert (ck.widths == 4).all() and st.k_bytes == binding.CHUNK_MAX_BYTES
+    # widths 1 and 3 mixed in, large dynamic range, subnormal and big values
+    K = (rng.standard_normal((2, 64, 2, 128)) * 100).astype(np.float16)
+    K[0, :, 0, :8] = 6.0e-8
+    K[1, 5] = 60000.0
+    K[1, 5, 0, 0] = -60000.0
+    V = (rng.standard_normal((2, 64, 2, 128)) * 1e-3).astype(np.float16)
+    _special_case(K, V, 4)
+
+
+def test_arena_overflow_sets_sticky_flag_and_drops_the_block():
+    B, H, Hq, L = 1, 2, 2, 256
+    K, V, q = synth.make_kv(B, L, H, Hq, 50)
+    cfg = binding.make_config(B, H, Hq, L)
+    cache = binding.PackedKVCache(B, H, Hq, L)
+    # rebuild the handle over a K arena that holds about two blocks only
+    sizes = binding.kv_sizes_t.from_buffer_copy(cache.sizes)
+    sizes.k_arena = 2 * H * 3300
+    bufs = binding.kv_buffers_t()
+    for name in binding._BUFFER_NAMES:
+        setattr(bufs, name, cache.tensors[name].data_ptr())
+    handle = C.c_void_p()
+    assert binding.lib().kv_cache_create(C.byref(cfg), C.byref(bufs), C.byref(sizes), C.byref(handle)) == 0
+    binding.lib().kv_cache_destroy(cache.handle)
+    cache.handle = handle
+    Kd, Vd = K.cuda(), V.cuda()
+    for blk in range(4):
+        cache.kv_compress_append(Kd[:, blk * 64:(blk + 1) * 64].contiguous(),
+                                 Vd[:, blk * 64:(blk + 1) * 64].contiguous())
+    st = cache.kv_cache_stats()
+    assert st.overflow == 1 and st.k_bytes <= sizes.k_arena
+    scores = cache.kv_k_matvec(q.cuda(), 1.0)
+    torch.cuda.synchronize()
+    n_packed, ck, _ = gpu_cases.oracle_cache(K.numpy(), V.numpy())
+    s_ref = oracle.k_scores(ck.codes, K.numpy(), ck.meta, L, q.numpy(), 1.0)
+    kept = st.k_bytes and int(np.searchsorted(ck.offsets16.astype(np.int64) * 16, st.k_bytes, "right") - 1) // (B * H)
+    assert 1 <= kept < 4
+    assert_close_vectors(scores[:, :, :kept * 64].cpu().numpy(), s_ref[:, :, :kept * 64], "kept blocks")
+    assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
+
+
+def test_host_argument_errors():
+    cache = binding.PackedKVCache(1, 2, 2, 128)
+    L = binding.lib()
+    x = torch.zeros(1, 64, 2, 128, dtype=torch.float16, device="cuda")
+    assert L.kv_compress_append(cache.handle, x.data_ptr(), None, 64, None) == -1
+    assert L.kv_compress_append(cache.handle, x.data_ptr(), x.data_ptr(), -1, None) == -1
+    assert L.kv_compress_append(cache.handle, x.data_ptr(), x.data_ptr(), 129, None) == -3
+    cache.kv_compress_append(x, x)
+    q = torch.zeros(1, 2, 128, dtype=torch.float16, device="cuda")
+    s = torch.zeros(1, 2, 32, dtype=torch.float32, device="cuda")
+    assert L.kv_k_matvec(cache.handle, q.data_ptr(), 1.0, s.data_ptr(), 32, None) == -1   # ld < tokens
+    assert L.kv_v_matvec(cache.handle, s.data_ptr(), 32, s.data_ptr(), None) == -1
+    with pytest.raises(binding.PackKVError):
+        cache.kv_compress_append(torch.zeros(1, 65, 2, 128, dtype=torch.float16, device="cuda"),
+                                 torch.zeros(1, 65, 2, 128, dtype=torch.float16, device="cuda"))
+
+
+@pytest.mark.parametrize("B,H,Hq,L", [(1, 2, 2, 1000), (2, 2, 8, 333)])
+def test_fp16_companion_gemv(B, H, Hq, L):
+    """The uncompressed fp16 comparison kernels against numpy fp64."""
+    K, V, q = synth.make_kv(B, L, H, Hq, 60)
+    Kh = K.permute(0, 2, 1, 3).contiguous().cuda()     # head-major [B, H, L, D]
+    Vh = V.permute(0, 2, 1, 3).contiguous().cuda()
+    scores = binding.kv_fp16_k_matvec(Kh, q.cuda(), 0.25, H)
+    p = synth.make_probs(scores)
+    out = binding.kv_fp16_v_matvec(Vh, p)
+    torch.cuda.synchronize()
+    s_ref = oracle.k_scores(None, K.numpy(), None, 0, q.numpy(), 0.25)
+    o_ref = oracle.v_out(None, V.numpy(), None, 0, p.cpu().numpy())
+    assert_close_vectors(scores.cpu().numpy(), s_ref, "fp16 K")
+    assert_close_vectors(out.cpu().numpy(), o_ref, "fp16 V")
+    chk = torch.zeros(1, dtype=torch.int32, device="cuda")
+    binding.kv_stream_read(Kh, chk)
+    torch.cuda.synchronize()
+    ref = np.bitwise_xor.reduce(Kh.cpu().numpy().view(np.uint32).ravel())
+    assert int(chk.cpu().numpy().view(np.uint32)[0]) == int(ref)

@@ -1,0 +1,62 @@
+"""CPU-only checks of the C-ABI boundary: the library loads, exports every
+symbol the header declares, and its host-only entry points behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2512_24449_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "packkv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(kv_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert set(names) == set(binding.EXPORTS)
+    raw = C.CDLL(binding.lib()._name)
+    for n in names:
+        assert hasattr(raw, n), n
+
+
+def test_query_sizes_and_config_checks():
+    cfg = binding.make_config(1, 32, 32, 4096)
+    worst = binding.kv_query_sizes(cfg)
+    n_chunks = 4096 // 64 * 32
+    assert worst.k_arena >= n_chunks * binding.CHUNK_MAX_BYTES
+    assert worst.k_index >= (n_chunks + 1) * 4 and worst.k_token_meta >= 4096 * 4
+    assert worst.k_tail >= 64 * 32 * 128 * 2
+    small = binding.kv_query_sizes(cfg, 3.0)
+    assert small.k_arena < worst.k_arena and small.k_arena >= n_chunks * 64 * 128 * 3 // 8
+    # unsupported / invalid configurations are refused with the documented codes
+    L = binding.lib()
+    out = binding.kv_sizes_t()
+    bad = binding.make_config(1, 32, 32, 4096)
+    bad.head_dim = 64
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05)   # codes would exceed 15
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    bad = binding.make_config(1, 3, 32, 4096)
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
+    bad = binding.make_config(0, 1, 1, 64)
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
+    assert L.kv_query_sizes(None, 0.0, C.byref(out)) == -1
+    assert L.kv_strerror(-3) == b"cache capacity exceeded"
+    assert L.kv_cache_destroy(None) == -1
+    assert L.kv_k_matvec(None, None, 1.0, None, 0, None) == -1
+
+
+def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
+    """No CPU fallback: a missing library with no compiler is an error."""
+    from paper_2512_24449_amd import build
+    monkeypatch.setattr(binding, "_lib", None)
+    monkeypatch.setattr(build, "LIB", str(tmp_path / "missing.so"))
+    monkeypatch.setenv("HIPCC", str(tmp_path / "no-such-hipcc"))
+    with pytest.raises(Exception):
+        binding.lib()
