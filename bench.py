@@ -1,0 +1,377 @@
+#!/usr/bin/env python3
+"""Benchmark of the PackKV decode hot path on one MI355X.
+
+One "step" is one decode step over the whole cache of one layer:
+    kv_compress_append(1 new token)  ->  kv_k_matvec  ->  softmax (torch, outside
+    the library)  ->  kv_v_matvec
+on synthetic, seeded inputs that are resident in HBM before the timed region.
+The headline value is compressed bytes read per step (packed K + packed V)
+divided by the step time.  Beside it: the roofline entry of the dominant
+kernel (HIP events on the launch stream, inside the timed region), the
+uncompressed fp16 GEMV companions at the same shapes, the measured streaming
+read ceiling, and the CPU oracle timed on a bounded sample.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME|INDEX]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0           # MI355X HBM3E, published
+DEFAULT_WORKLOAD = "llama2_30b_32k_b8"
+ROTATE_BYTES = 1.1e9             # working set to rotate over so reads come from HBM, not the 256 MB LLC
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-workloads", action="store_true",
+                    help="skip the short runs of the other benchmark configurations")
+    return ap.parse_args()
+
+
+def _event_pair(torch):
+    return torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+
+class Replicas:
+    """R identical packed caches (rotated so that successive steps do not hit the LLC)."""
+
+    def __init__(self, w, K, V, extra_tokens, binding, torch):
+        B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
+        L = K.shape[1]
+        first = binding.PackedKVCache(B, H, Hq, L + extra_tokens)
+        first.kv_compress_append(K, V)
+        st = first.kv_cache_stats()
+        assert st.overflow == 0
+        self.stats = st
+        step_bytes = st.k_bytes + st.v_bytes
+        R = int(min(max(2, math.ceil(ROTATE_BYTES / max(step_bytes, 1))), 128))
+        bits = max(st.k_bytes, st.v_bytes) * 8.0 / (B * H * 128 * max(st.packed_tokens, 64)) + 0.3
+        self.caches = [first]
+        for _ in range(R - 1):
+            c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, bits_per_element_budget=bits)
+            for name in ("k_arena", "v_arena"):
+                n = st.k_bytes if name[0] == "k" else st.v_bytes
+                c.tensors[name][:n].copy_(first.tensors[name][:n])
+            for name in ("k_index", "v_index", "k_token_meta", "v_token_meta", "k_tail", "v_tail"):
+                n = min(c.tensors[name].numel(), first.tensors[name].numel())
+                c.tensors[name][:n].copy_(first.tensors[name][:n])
+            c.kv_cache_restore(L)
+            self.caches.append(c)
+        torch.cuda.synchronize()
+
+    def __len__(self):
+        return len(self.caches)
+
+
+def algorithmic_bytes(st, w, tokens):
+    """Bytes one launch must move (K path, V path), from the format definition."""
+    B, Hq = w.batch, w.n_q_heads
+    meta = 4 * B * st.packed_tokens
+    index = 4 * (st.n_chunks + 1)
+    tail = 2 * B * st.tail_tokens * w.n_kv_heads * 128
+    k = st.k_bytes + meta + index + tail + 256 * B * Hq + 4 * B * Hq * tokens
+    v = st.v_bytes + meta + index + tail + 4 * B * Hq * tokens + 512 * B * Hq
+    return k, v
+
+
+def run_packed(w, K, V, q, steps, warmup, torch, binding, synth):
+    """Timed decode steps over rotating replicas; returns a dict of measurements."""
+    B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
+    L = K.shape[1]
+    total = steps + warmup
+    reps = Replicas(w, K, V, total + 64, binding, torch)
+    R = len(reps)
+    dev = K.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(1234)
+    k_new = torch.randn(total, B, 1, H, 128, generator=gen, device=dev).to(torch.float16)
+    v_new = torch.randn(total, B, 1, H, 128, generator=gen, device=dev).to(torch.float16)
+    ld = L + total + 64
+    scores = torch.empty(B, Hq, ld, dtype=torch.float32, device=dev)
+    out = torch.empty(B, Hq, 128, dtype=torch.float32, device=dev)
+    sm_scale = 128 ** -0.5
+    k_ev, v_ev = [], []
+
+    def step(i, timed):
+        c = reps.caches[i % R]
+        c.kv_compress_append(k_new[i], v_new[i])
+        n = c.tokens
+        if timed:
+            e0, e1 = _event_pair(torch)
+            e0.record()
+        c.kv_k_matvec(q, sm_scale, scores)
+        if timed:
+            e1.record()
+            k_ev.append((e0, e1))
+        p = torch.softmax(scores[:, :, :n], dim=-1)
+        if timed:
+            e2, e3 = _event_pair(torch)
+            e2.record()
+        c.kv_v_matvec(p, out)
+        if timed:
+            e3.record()
+            v_ev.append((e2, e3))
+
+    for i in range(warmup):
+        step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(warmup, total):
+        step(i, True)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    st = reps.stats
+    k_ms = sum(a.elapsed_time(b) for a, b in k_ev) / len(k_ev)
+    v_ms = sum(a.elapsed_time(b) for a, b in v_ev) / len(v_ev)
+    k_alg, v_alg = algorithmic_bytes(st, w, L)
+    res = dict(ms_per_step=elapsed * 1e3 / steps, k_ms=k_ms, v_ms=v_ms, replicas=R,
+               k_bytes=int(st.k_bytes), v_bytes=int(st.v_bytes),
+               k_alg_bytes=int(k_alg), v_alg_bytes=int(v_alg),
+               k_bits_per_elem=st.k_bytes * 8.0 / (w.batch * w.n_kv_heads * 128 * st.packed_tokens),
+               v_bits_per_elem=st.v_bytes * 8.0 / (w.batch * w.n_kv_heads * 128 * st.packed_tokens))
+    res["value_gbps"] = (st.k_bytes + st.v_bytes) / (res["ms_per_step"] * 1e-3) / 1e9
+    res["k_gbps_compressed"] = st.k_bytes / (k_ms * 1e-3) / 1e9
+    res["v_gbps_compressed"] = st.v_bytes / (v_ms * 1e-3) / 1e9
+    for c in reps.caches:
+        c.close()
+    del reps
+    torch.cuda.empty_cache()
+    return res
+
+
+def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth):
+    """The uncompressed fp16 GEMV companions at the same shapes (head-major cache)."""
+    B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
+    L = K.shape[1]
+    Kh = K.permute(0, 2, 1, 3).contiguous()
+    Vh = V.permute(0, 2, 1, 3).contiguous()
+    nbytes = Kh.numel() * 2
+    R = int(min(max(1, math.ceil(ROTATE_BYTES / (2 * nbytes))), 64))
+    Ks = [Kh] + [Kh.clone() for _ in range(R - 1)]
+    Vs = [Vh] + [Vh.clone() for _ in range(R - 1)]
+    scores = torch.empty(B, Hq, L, dtype=torch.float32, device=K.device)
+    out = torch.empty(B, Hq, 128, dtype=torch.float32, device=K.device)
+    ws = torch.empty(binding.lib().kv_fp16_v_workspace_bytes(B, Hq), dtype=torch.uint8, device=K.device)
+    binding.kv_fp16_k_matvec(Ks[0], q, 128 ** -0.5, H, scores)
+    p = torch.softmax(scores, dim=-1)
+    k_ev, v_ev, mm_ev = [], [], []
+    for i in range(warmup + steps):
+        e0, e1 = _event_pair(torch)
+        e2, e3 = _event_pair(torch)
+        e0.record()
+        binding.kv_fp16_k_matvec(Ks[i % R], q, 128 ** -0.5, H, scores)
+        e1.record()
+        e2.record()
+        binding.kv_fp16_v_matvec(Vs[i % R], p, out, ws)
+        e3.record()
+        if i >= warmup:
+            k_ev.append((e0, e1))
+            v_ev.append((e2, e3))
+    # sanity number: the vendor-library path torch.matmul takes for the same K product
+    qg = q.view(B, H, Hq // H, 128).transpose(2, 3).contiguous()      # [B, H, D, G]
+    for i in range(warmup + min(steps, 10)):
+        e0, e1 = _event_pair(torch)
+        e0.record()
+        torch.matmul(Ks[i % R], qg)
+        e1.record()
+        if i >= warmup:
+            mm_ev.append((e0, e1))
+    torch.cuda.synchronize()
+    avg = lambda ev: sum(a.elapsed_time(b) for a, b in ev) / len(ev)
+    res = dict(k_ms=avg(k_ev), v_ms=avg(v_ev), torch_matmul_k_ms=avg(mm_ev), replicas=R,
+               bytes_per_tensor=int(nbytes))
+    res["k_gbps"] = nbytes / (res["k_ms"] * 1e-3) / 1e9
+    res["v_gbps"] = nbytes / (res["v_ms"] * 1e-3) / 1e9
+    # streaming-read ceiling over >= 2 GB
+    big = Ks[0] if nbytes >= 2e9 else torch.empty(int(2.2e9), dtype=torch.uint8, device=K.device).zero_()
+    chk = torch.zeros(1, dtype=torch.int32, device=K.device)
+    for _ in range(3):
+        binding.kv_stream_read(big, chk)
+    e0, e1 = _event_pair(torch)
+    e0.record()
+    for _ in range(5):
+        binding.kv_stream_read(big, chk)
+    e1.record()
+    torch.cuda.synchronize()
+    res["stream_read_gbps"] = big.numel() * big.element_size() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return res
+
+
+def run_growing(w, steps, torch, binding, synth):
+    """Growing-cache stress: `steps` decode steps, each appending one token; the
+    tail is flushed every 64 tokens.  Times every step end to end."""
+    K, V, q = synth.make_workload(w, device="cuda:0")
+    B, H, Hq, L = w.batch, w.n_kv_heads, w.n_q_heads, w.tokens
+    c = binding.PackedKVCache(B, H, Hq, L + steps + 64)
+    c.kv_compress_append(K, V)
+    gen = torch.Generator(device=K.device)
+    gen.manual_seed(4321)
+    k_new = torch.randn(steps, B, 1, H, 128, generator=gen, device=K.device).to(torch.float16)
+    v_new = torch.randn(steps, B, 1, H, 128, generator=gen, device=K.device).to(torch.float16)
+    scores = torch.empty(B, Hq, L + steps + 64, dtype=torch.float32, device=K.device)
+    out = torch.empty(B, Hq, 128, dtype=torch.float32, device=K.device)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    evs[0].record()
+    for i in range(steps):
+        c.kv_compress_append(k_new[i], v_new[i])
+        c.kv_k_matvec(q, 128 ** -0.5, scores)
+        p = torch.softmax(scores[:, :, :c.tokens], dim=-1)
+        c.kv_v_matvec(p, out)
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    per = sorted(evs[i].elapsed_time(evs[i + 1]) for i in range(steps))
+    st = c.kv_cache_stats()
+    res = dict(steps=steps, tokens_end=int(st.tokens), flushes=int((st.packed_tokens - L) // 64),
+               ms_per_step_mean=wall * 1e3 / steps, ms_per_step_p50=per[len(per) // 2],
+               ms_per_step_p99=per[min(len(per) - 1, int(len(per) * 0.99))],
+               k_bytes=int(st.k_bytes), v_bytes=int(st.v_bytes))
+    res["value_gbps"] = (st.k_bytes + st.v_bytes) / (res["ms_per_step_mean"] * 1e-3) / 1e9
+    c.close()
+    return res
+
+
+def cpu_baseline(w, synth, torch):
+    """The oracle as it stands on the host cores, on a bounded sample of the workload."""
+    import numpy as np
+    import oracle
+    # sized for roughly 10-30 s of host work (compression is single-threaded)
+    L = min(w.tokens // 64 * 64, max(64, (40_000_000 // (w.n_kv_heads * 128)) // 64 * 64))
+    B = 1
+    K, V, q = synth.make_kv(B, L, w.n_kv_heads, w.n_q_heads, 7)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    t0 = time.perf_counter()
+    ck = oracle.compress(Kn, 0.1)
+    cv = oracle.compress(Vn, 0.2)
+    t1 = time.perf_counter()
+    s = oracle.k_scores(ck.codes, Kn, ck.meta, L, qn, 128 ** -0.5)
+    t2 = time.perf_counter()
+    p = oracle.softmax(s).astype(np.float32)
+    t3 = time.perf_counter()
+    oracle.v_out(cv.codes, Vn, cv.meta, L, p)
+    t4 = time.perf_counter()
+    step_s = (t2 - t1) + (t4 - t3)
+    # same unit as the headline: compressed bytes consumed by one decode step / its time
+    return {"value": (ck.arena.size + cv.arena.size) / step_s / 1e9, "unit": "GB/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": "1 batch element x %d tokens x %d kv heads of %s: oracle K and V matvec over the "
+                      "packed cache, %.2f s; oracle compression of the same tokens took %.1f s on one core"
+                      % (L, w.n_kv_heads, w.name, step_s, t1 - t0),
+            "compress_s": t1 - t0, "matvec_s": step_s}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the path shards over (batch, kv-head) "
+              "without exchange; see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2512_24449_amd import binding, synth
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    binding.lib()
+    torch.cuda.set_device(0)
+    w = synth.workload(int(args.workload) if args.workload.isdigit() else args.workload)
+
+    if w.decode_steps:
+        g = run_growing(w, args.steps if args.steps != 40 else w.decode_steps, torch, binding, synth)
+        line = {"metric": "fused K/V decompress-GEMV GB/s (compressed)", "value": round(g["value_gbps"], 2),
+                "unit": "GB/s", "n_gpus": 1, "steps": g["steps"], "warmup": 0,
+                "ms_per_step": round(g["ms_per_step_mean"], 5), "higher_is_better": True, "scaling": "weak",
+                "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+                "config": {"workload": w.name}, "growing_cache": g}
+        print(json.dumps(line))
+        return
+
+    K, V, q = synth.make_workload(w, device="cuda:0")
+    packed = run_packed(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
+    fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
+    del K, V
+    torch.cuda.empty_cache()
+
+    dom = "k" if packed["k_ms"] >= packed["v_ms"] else "v"
+    alg = packed[dom + "_alg_bytes"]
+    achieved = alg / (packed[dom + "_ms"] * 1e-3) / 1e9
+    traffic = None
+    tf = os.path.join(ROOT, "paper_2512_24449_amd", "measured_traffic.json")
+    if os.path.exists(tf):
+        t = json.load(open(tf)).get(w.name, {}).get(dom)
+        if t:
+            traffic = t
+    line = {
+        "metric": "fused K/V decompress-GEMV GB/s (compressed)",
+        "value": round(packed["value_gbps"], 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(packed["ms_per_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": w.name, "batch": w.batch, "n_kv_heads": w.n_kv_heads,
+                   "n_q_heads": w.n_q_heads, "tokens": w.tokens, "k_rel_scale": 0.1, "v_rel_scale": 0.2,
+                   "pack_size": 16, "block_tokens": 64, "replicas": packed["replicas"]},
+        "pct_hbm_peak": round(100.0 * packed["value_gbps"] / HBM_PEAK_GBPS, 2),
+        "roofline": {"bound": "hbm", "kernel": "kv_%s_matvec" % dom, "achieved": round(achieved, 2),
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
+                     "traffic": traffic, "algorithmic_bytes_per_launch": alg,
+                     "avg_launch_ms": round(packed[dom + "_ms"], 5)},
+        "kernels": {
+            "kv_k_matvec": {"ms": round(packed["k_ms"], 5), "compressed_gbps": round(packed["k_gbps_compressed"], 1),
+                            "pct_hbm_peak": round(packed["k_gbps_compressed"] / 80.0, 2),
+                            "bits_per_elem": round(packed["k_bits_per_elem"], 3)},
+            "kv_v_matvec": {"ms": round(packed["v_ms"], 5), "compressed_gbps": round(packed["v_gbps_compressed"], 1),
+                            "pct_hbm_peak": round(packed["v_gbps_compressed"] / 80.0, 2),
+                            "bits_per_elem": round(packed["v_bits_per_elem"], 3)},
+        },
+        "fp16_gemv": {"k_ms": round(fp16["k_ms"], 5), "v_ms": round(fp16["v_ms"], 5),
+                      "k_gbps": round(fp16["k_gbps"], 1), "v_gbps": round(fp16["v_gbps"], 1),
+                      "torch_matmul_k_ms": round(fp16["torch_matmul_k_ms"], 5),
+                      "speedup_k": round(fp16["k_ms"] / packed["k_ms"], 3),
+                      "speedup_v": round(fp16["v_ms"] / packed["v_ms"], 3)},
+        "stream_read_gbps": round(fp16["stream_read_gbps"], 1),
+    }
+    if not args.no_side_workloads:
+        side = {}
+        for idx in (0, 1, 2):
+            sw = synth.workload(idx)
+            if sw.name == w.name:
+                continue
+            Ks, Vs, qs = synth.make_workload(sw, device="cuda:0")
+            sp = run_packed(sw, Ks, Vs, qs, 20, 5, torch, binding, synth)
+            sf = run_fp16(sw, Ks, Vs, qs, 20, 5, torch, binding, synth)
+            side[sw.name] = {"k_ms": round(sp["k_ms"], 5), "v_ms": round(sp["v_ms"], 5),
+                             "fp16_k_ms": round(sf["k_ms"], 5), "fp16_v_ms": round(sf["v_ms"], 5),
+                             "speedup_k": round(sf["k_ms"] / sp["k_ms"], 3),
+                             "speedup_v": round(sf["v_ms"] / sp["v_ms"], 3),
+                             "k_compressed_gbps": round(sp["k_gbps_compressed"], 1),
+                             "v_compressed_gbps": round(sp["v_gbps_compressed"], 1),
+                             "ms_per_step": round(sp["ms_per_step"], 5)}
+            del Ks, Vs
+            torch.cuda.empty_cache()
+        gw = synth.workload(4)
+        g = run_growing(gw, 256, torch, binding, synth)
+        side[gw.name] = g
+        line["other_workloads"] = side
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, synth, torch)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
