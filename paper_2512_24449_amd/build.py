@@ -15,6 +15,7 @@ HIPCC_FLAGS = [
     "-ffp-contract=off",                          # FMAs only where written
     "-fhip-fp32-correctly-rounded-divide-sqrt",   # quantizer needs IEEE divide
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-amdgpu-mfma-vgpr-form",           # MFMA accumulators stay in VGPRs (no AGPR copies)
     "-Wall", "-Wno-unused-function",
 ]
 
@@ -27,7 +28,7 @@ def build(verbose: bool = False) -> str:
     """Compile every HIP source into one shared library; always recompiles."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
+    cmd = [hipcc] + HIPCC_FLAGS + os.environ.get("PACKKV_EXTRA_FLAGS", "").split() + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)

@@ -2,15 +2,20 @@
 // packed K cache once and unpacking in registers.
 //
 // The paper walks a 32-lane warp over K rows and reduces with a warp sum.
-// Here one 64-lane wave owns one chunk (64 tokens x 128 channels): lane l
-// reads header bytes 8l..8l+7, so it owns token group g = l/16 and channels
-// 8*(l%16)..+7, whose payload bytes are contiguous.  It keeps 16 per-token
-// partial sums over its 8 channels; a reduce-scatter inside the 16-lane row
-// then leaves token 16g+i's dot product in lane 16g+i, and the 64 scores are
-// stored with one coalesced 256-byte write.  De-quantization is folded in:
+// Here a 64-lane wave owns whole chunks (64 tokens x 128 channels): lane l
+// owns token group g = l/16 and channels 8*(l%16)..+7 (unpack.h).  It keeps 16
+// per-token partial sums over its 8 channels, fed by mixed-precision FMAs that
+// read the unpacked fp16 code halves directly; a reduce-scatter inside the
+// 16-lane row then leaves token 16g+i's dot product in lane 16g+i and the 64
+// scores leave as one coalesced 256-byte store.  De-quantization is folded in:
 //   score_t = sm_scale * (scale_t * (sum_d q_d code[t,d] + sum_d q_d m[g,d])
 //                         + min_t * sum_d q_d)
-// so the pack minimum costs one FMA per pack and (scale_t, min_t) one per token.
+// so a pack minimum costs one FMA per pack and (scale_t, min_t) one per token.
+// A workgroup of four waves walks a contiguous range of blocks of one
+// (batch, kv-head) stream; the raw fp16 tail is handled by extra workgroups of
+// the same launch (one launch covers everything, Sec. III-B.4).
+#include <algorithm>
+
 #include "unpack.h"
 
 namespace packkv {
@@ -26,103 +31,90 @@ struct KArgs {
     int64_t meta_stride;
     int64_t packed_tokens;
     int B, H;
-    int n_chunks;
-    int n_chunk_groups;     // workgroups that process chunks
+    int n_blocks;           // packed blocks per stream
+    int blocks_per_group;   // blocks walked by one workgroup
+    int groups_per_stream;
+    int n_stream_groups;    // workgroups that process chunks
     int n_tail, tail_cap;
     float sm_scale;
 };
 
 template <int G>
-__device__ inline void k_chunk(const KArgs &a, int c, int lane, uint8_t *lds) {
-    const int h = c % a.H;
-    const int b = (c / a.H) % a.B;
-    const int blk = c / (a.H * a.B);
-    const uint32_t o0 = a.index[c], o1 = a.index[c + 1];
-    const int64_t tok = int64_t(blk) * N + lane;  // this lane's token after the reduction
-
-    float result[G];
-    if (o1 - o0 < uint32_t(HEADER / 16)) {  // dropped block: defined output
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-            a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] = 0.0f;
-        return;
-    }
-    const uint8_t *chunk = a.arena + size_t(o0) * 16;
-    const int payload_bytes = int(o1 - o0) * 16 - HEADER;
-
-    // issue all global loads of the chunk before anything depends on them
-    LaneHeader hd;
-    {
-        uint2 raw = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
-        hd.lo = raw.x;
-        hd.hi = raw.y;
-    }
-    stage_payload(chunk + HEADER, payload_bytes, lds, lane);
-    const uint32_t mt = a.meta[b * a.meta_stride + tok];
-
-    // query slices of this lane's 8 channels, for the G query heads of kv-head h
+__device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
+                                int lane, uint8_t *lds) {
+    const int h = bh % a.H, b = bh / a.H;
     const int ch0 = 8 * (lane & 15);
-    float qf[G][8], qsum[G], msum[G];
+    // query slices of this lane's 8 channels, for the G query heads of kv-head h
+    float qf[G][8], qsum[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         uint4 raw = *reinterpret_cast<const uint4 *>(a.q + (int64_t(b) * a.H * G + h * G + g) * D + ch0);
         const __half *hq = reinterpret_cast<const __half *>(&raw);
-        qsum[g] = 0.0f;
-        msum[g] = 0.0f;
+        float s = 0.0f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             qf[g][j] = __half2float(hq[j]);
-            qsum[g] += qf[g][j];
+            s += qf[g][j];
         }
+        qsum[g] = row_all_reduce16(s);
     }
 
-    const int my_bytes = hd.bytes();
-    int pos = wave_inclusive_scan(my_bytes, lane) - my_bytes;
+    for (int blk = blk_begin + wave; blk < blk_end; blk += 4) {
+        const int c = (blk * a.B + b) * a.H + h;
+        const uint32_t o0 = a.index[c], o1 = a.index[c + 1];
+        const int64_t tok = int64_t(blk) * N + lane;  // this lane's token after the reduction
+        if (o1 - o0 < uint32_t(HEADER / 16)) {        // dropped block: defined output
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] = 0.0f;
+            continue;
+        }
+        const uint8_t *chunk = a.arena + size_t(o0) * 16;
+        const int payload_bytes = int(o1 - o0) * 16 - HEADER;
+        const uint2 hdr = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
+        stage_payload(chunk + HEADER, payload_bytes, lds, lane);
+        const uint32_t mt = a.meta[b * a.meta_stride + tok];
+        LanePacks lp;
+        lp.init(hdr.x, hdr.y);
 
-    float acc[G][16];
+        float acc[G][16], msum[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g)
+        for (int g = 0; g < G; ++g) {
+            msum[g] = 0.0f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
+            for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
+        }
+        wave_lds_fence();
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        const int w = hd.width(j);
-        const float m = float(hd.min(j));
-        uint32_t lo, hi, L, Hh;
-        read_pack(lds, pos, lo, hi);
-        split_pack(lo, hi, w, L, Hh);
-        pos += 2 * w;
+        for (int j = 0; j < 8; ++j) {
+            uint32_t P[8];
+            unpack_pairs(lds, lp.pos(j), lp.width(j), P);
+            const float m = float(lp.min(j));
 #pragma unroll
-        for (int g = 0; g < G; ++g) msum[g] = fmaf(qf[g][j], m, msum[g]);
+            for (int g = 0; g < G; ++g) msum[g] = fmaf(qf[g][j], m, msum[g]);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const float cl = float(__builtin_amdgcn_ubfe(L, i * w, w));
-            const float chh = float(__builtin_amdgcn_ubfe(Hh, i * w, w));
+            for (int k = 0; k < 8; ++k) {
+                // P[k] holds tokens (k, k+8) of the group
+                const int t_lo = k, t_hi = k + 8;
+                const float cl = half_lo(P[k]), chh = half_hi(P[k]);
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                acc[g][i] = fmaf(qf[g][j], cl, acc[g][i]);
-                acc[g][i + 8] = fmaf(qf[g][j], chh, acc[g][i + 8]);
+                for (int g = 0; g < G; ++g) {
+                    acc[g][t_lo] = fmaf(qf[g][j], cl, acc[g][t_lo]);
+                    acc[g][t_hi] = fmaf(qf[g][j], chh, acc[g][t_hi]);
+                }
             }
         }
-    }
-    // the next chunk of this wave must not overwrite LDS before all lanes read it
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
+        wave_lds_fence();  // the next chunk must not overwrite LDS before all lanes read it
 
-    const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+        const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+        const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        float dot = row_reduce_scatter16(acc[g], lane);
-        float ms = row_all_reduce16(msum[g]);
-        float qs = row_all_reduce16(qsum[g]);
-        result[g] = a.sm_scale * fmaf(scale, dot + ms, mn * qs);
-        a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] = result[g];
+        for (int g = 0; g < G; ++g) {
+            const float dot = row_reduce_scatter16(acc[g], lane) * CODE_SCALE;
+            const float ms = row_all_reduce16(msum[g]);
+            a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] =
+                a.sm_scale * fmaf(scale, dot + ms, mn * qsum[g]);
+        }
     }
 }
 
@@ -154,12 +146,17 @@ __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
 template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int unit = blockIdx.x * 4 + wave;
-    if (blockIdx.x < a.n_chunk_groups) {
-        if (unit < a.n_chunks) k_chunk<G>(a, unit, lane, lds_all + wave * PAYLOAD_LDS);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = blockIdx.x;
+    if (grp < a.n_stream_groups) {
+        const int bh = grp / a.groups_per_stream;
+        const int part = grp % a.groups_per_stream;
+        const int blk_begin = part * a.blocks_per_group;
+        const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
+        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all + wave * PAYLOAD_LDS);
     } else {
-        const int bh = (blockIdx.x - a.n_chunk_groups) * 4 + wave;
+        const int bh = (grp - a.n_stream_groups) * 4 + wave;
         if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
     }
 }
@@ -178,13 +175,20 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     a.packed_tokens = c->packed_tokens;
     a.B = c->cfg.batch;
     a.H = c->cfg.n_kv_heads;
-    a.n_chunks = int(c->packed_tokens / N) * a.B * a.H;
-    a.n_chunk_groups = (a.n_chunks + 3) / 4;
+    a.n_blocks = int(c->packed_tokens / N);
+    const int streams = a.B * a.H;
+    // about 4096 workgroups over the chip, never less than one block per wave
+    int64_t want_groups = std::max<int64_t>(1, 4096 / streams);
+    int bpg = int((a.n_blocks + want_groups - 1) / want_groups);
+    bpg = std::max(4, (bpg + 3) / 4 * 4);
+    a.blocks_per_group = bpg;
+    a.groups_per_stream = a.n_blocks > 0 ? (a.n_blocks + bpg - 1) / bpg : 0;
+    a.n_stream_groups = a.groups_per_stream * streams;
     a.n_tail = c->tail_tokens;
     a.tail_cap = c->cfg.tail_capacity;
     a.sm_scale = sm_scale;
-    const int tail_groups = a.n_tail > 0 ? (a.B * a.H + 3) / 4 : 0;
-    const int grid = a.n_chunk_groups + tail_groups;
+    const int tail_groups = a.n_tail > 0 ? (streams + 3) / 4 : 0;
+    const int grid = a.n_stream_groups + tail_groups;
     if (grid == 0) return KV_OK;
     switch (c->group) {
         case 1: hipLaunchKernelGGL(k_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;

@@ -2,18 +2,28 @@
 // cache once and unpacking in registers.
 //
 // The paper gives each thread one pack (a dot-product segment along ctx_len)
-// and combines segments with fp32 atomic adds.  Here a wave owns whole chunks
-// with the same lane-to-pack mapping as the K path (lane l: token group l/16,
-// channels 8*(l%16)..+7), keeps its 8 channel sums in registers across all the
-// chunks it visits, and the context axis is split over workgroups whose partial
-// sums are combined in a fixed order by a second small kernel: no atomics, so
-// the result is bitwise reproducible.  De-quantization is folded in:
-//   out_d = sum_t (p_t scale_t) code[t,d] + sum_g m[g,d] sum_{t in g} p_t scale_t
-//           + sum_t p_t min_t
-// The weights p_t*scale_t of a chunk's 64 tokens are staged in LDS.
+// and combines segments with fp32 atomic adds.  Here the contraction runs
+// along the pack direction, so it maps onto the matrix cores without any
+// transposition: for pack slot jj the wave issues
+//     C_jj[channel row i][column] += A[i][k] * B[k][column]      (16x16x32 fp16 MFMA)
+// where row i is lane%16 (channel 8i+jj), the 32 k-slots are 8 tokens of each
+// of the 4 token groups (lane/16), A holds the unpacked codes exactly as
+// unpack_pairs leaves them (fp16 code * 2^-24) and B holds the weights
+// w_t = p_t * scale_t split into fp16 hi and lo*2^11 parts, one column pair per
+// query head (so fp32-accurate weights cost no extra MFMA and G query heads of
+// a GQA group share one unpack).  Accumulation is fp32 inside the MFMA, in a
+// fixed order: the context axis is split over workgroups whose partial sums
+// are combined by a second small kernel -- no atomics, bitwise reproducible.
+// De-quantization is folded in:
+//   out_d = sum_t w_t code[t,d] + sum_g m[g,d] sum_{t in g} w_t + sum_t p_t min_t
+#include <algorithm>
+
 #include "unpack.h"
 
 namespace packkv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
 
 struct VArgs {
     const uint8_t *arena;
@@ -28,26 +38,40 @@ struct VArgs {
     int blocks_per_split;
 };
 
+constexpr int B_LDS = 4 * 2 * 16 * 16;  // bytes per wave: [token group][half][column][8 fp16]
+
 template <int G>
 __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
-    __shared__ __attribute__((aligned(16))) float wlds_all[4][G][N];
-    __shared__ float red[4][G][D + 1];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * B_LDS];
+    __shared__ float red[4][G][D + 4];
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int split = blockIdx.x;
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
     uint8_t *lds = lds_all + wave * PAYLOAD_LDS;
-    const int row = lane >> 4;
+    uint8_t *blds = blds_all + wave * B_LDS;
+    const int row = lane >> 4, col = lane & 15;
 
-    float acc[G][8];
-    float pm[G];
+    // columns >= 2G of the B operand stay zero for the whole kernel
+    *reinterpret_cast<uint4 *>(blds + lane * 32) = make_uint4(0, 0, 0, 0);
+    *reinterpret_cast<uint4 *>(blds + lane * 32 + 16) = make_uint4(0, 0, 0, 0);
+
+    // where this lane's own token (16*row + col) sits in the B operand
+    const int tm = col & 7;
+    const int bslot = (((row * 2 + (tm >> 2)) * 16) * 8 + 2 * (tm & 3) + (col >> 3)) * 2;
+
+    float4_t acc[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+    float macc[G][8], pm[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         pm[g] = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[g][j] = 0.0f;
+        for (int j = 0; j < 8; ++j) macc[g][j] = 0.0f;
     }
 
     const int blk_begin = split * a.blocks_per_split;
@@ -60,94 +84,75 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
         const int payload_bytes = int(o1 - o0) * 16 - HEADER;
         const int64_t tok = int64_t(blk) * N + lane;
 
-        LaneHeader hd;
-        {
-            uint2 raw = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
-            hd.lo = raw.x;
-            hd.hi = raw.y;
-        }
+        const uint2 hdr = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
         stage_payload(chunk + HEADER, payload_bytes, lds, lane);
         const uint32_t mt = a.meta[b * a.meta_stride + tok];
         const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
         const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+        float wsum[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const float pt = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
-            wlds_all[wave][g][lane] = pt * scale;
+            const float w = pt * scale;
             pm[g] = fmaf(pt, mn, pm[g]);
+            // w = hi + lo with both parts fp16 (lo scaled by 2^11); truncation keeps lo >= 0
+            const _Float16 hi = __builtin_bit_cast(
+                _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
+            const float lo = (w - float(hi)) * 2048.0f;
+            const _Float16 lo16 = __builtin_bit_cast(
+                _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+            *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g) * 16) = hi;
+            *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g + 1) * 16) = lo16;
+            wsum[g] = row_all_reduce16(w);
         }
-        const int my_bytes = hd.bytes();
-        int pos = wave_inclusive_scan(my_bytes, lane) - my_bytes;
+        LanePacks lp;
+        lp.init(hdr.x, hdr.y);
+        wave_lds_fence();
 
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
-        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-
-        // the 16 weights of this lane's token group, and their sum
-        float wv[G][16], wsum[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float4 *src = reinterpret_cast<const float4 *>(&wlds_all[wave][g][row * 16]);
-            wsum[g] = 0.0f;
-#pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                float4 v = src[k];
-                wv[g][4 * k + 0] = v.x;
-                wv[g][4 * k + 1] = v.y;
-                wv[g][4 * k + 2] = v.z;
-                wv[g][4 * k + 3] = v.w;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) wsum[g] += wv[g][i];
-        }
-
+        const half8 b0 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 0) * 16 + col) * 16);
+        const half8 b1 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 1) * 16 + col) * 16);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const int w = hd.width(j);
-            const float m = float(hd.min(j));
-            uint32_t lo, hi, L, Hh;
-            read_pack(lds, pos, lo, hi);
-            split_pack(lo, hi, w, L, Hh);
-            pos += 2 * w;
-            float part[G];
+            uint32_t P[8];
+            unpack_pairs(lds, lp.pos(j), lp.width(j), P);
+            const float m = float(lp.min(j));
 #pragma unroll
-            for (int g = 0; g < G; ++g) part[g] = m * wsum[g];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float cl = float(__builtin_amdgcn_ubfe(L, i * w, w));
-                const float chh = float(__builtin_amdgcn_ubfe(Hh, i * w, w));
-#pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    part[g] = fmaf(wv[g][i], cl, part[g]);
-                    part[g] = fmaf(wv[g][i + 8], chh, part[g]);
-                }
-            }
-#pragma unroll
-            for (int g = 0; g < G; ++g) acc[g][j] += part[g];
+            for (int g = 0; g < G; ++g) macc[g][j] = fmaf(m, wsum[g], macc[g][j]);
+            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+            const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[1], P[2], P[3]});
+            const half8 a1 = __builtin_bit_cast(half8, u32x4{P[4], P[5], P[6], P[7]});
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[j], 0, 0, 0);
+            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[j], 0, 0, 0);
         }
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_fence();  // LDS is rewritten by the next chunk
     }
 
-    // combine the four token-group rows of the wave, then the four waves
+    // ---- combine: MFMA tiles (lane = column `col`, rows 4*row+r), the pack-minimum
+    // term (lane = token group `row`, channels 8*col+j), the four waves ----
+    const int head = col >> 1;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float v = acc[j][r] * ((col & 1) ? CODE_SCALE / 2048.0f : CODE_SCALE);
+            v += dpp_f32<DPP_QUAD_XOR1>(v);  // hi column + lo column
+            if (!(col & 1) && head < G) red[wave][head][8 * (4 * row + r) + j] = v;
+        }
+    }
+    wave_lds_fence();
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            float v = acc[g][j];
+            float v = macc[g][j];
             v += __shfl_xor(v, 16);
             v += __shfl_xor(v, 32);
-            acc[g][j] = v;
+            if (lane < 16) red[wave][g][8 * lane + j] += v;
         }
         float s = pm[g];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-        pm[g] = s;
-        if (lane < 16) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) red[wave][g][8 * lane + j] = acc[g][j];
-        }
-        if (lane == 0) red[wave][g][D] = pm[g];
+        if (lane == 0) red[wave][g][D] = s;
     }
     __syncthreads();
     for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
@@ -186,9 +191,12 @@ __global__ __launch_bounds__(128) void v_reduce_kernel(const float *__restrict__
     out[int64_t(r) * D + d] = acc;
 }
 
+#ifndef V_TARGET_GROUPS
+#define V_TARGET_GROUPS 2048
+#endif
 int v_splits_for(int n_blocks, int streams) {
     // enough workgroups to fill 256 CUs a few times over, at least one block per wave
-    int want = (2048 + streams - 1) / streams;
+    int want = (V_TARGET_GROUPS + streams - 1) / streams;
     int by_blocks = (n_blocks + 3) / 4;
     int s = want < by_blocks ? want : by_blocks;
     if (s > V_SPLITS_MAX) s = V_SPLITS_MAX;
