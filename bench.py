@@ -37,6 +37,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known bytes, for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-side-workloads", action="store_true",
                     help="skip the short runs of the other benchmark configurations")
     return ap.parse_args()
@@ -307,6 +309,13 @@ def main():
     fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     del K, V
     torch.cuda.empty_cache()
+    if args.copy_calibration:
+        src = torch.ones(1 << 30, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     dom = "k" if packed["k_ms"] >= packed["v_ms"] else "v"
     alg = packed[dom + "_alg_bytes"]

@@ -1,0 +1,99 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py
+times: inputs are generated on the device, the whole cache is compressed and
+decoded by the HIP library, and the oracle recomputes complete batch elements
+(every chunk byte, every score, every output of that element)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2512_24449_amd import binding, synth
+from tests.gpu_cases import assert_close_vectors
+
+pytestmark = pytest.mark.gpu
+
+
+def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed):
+    """Oracle over batch element b (all heads, all tokens) against the GPU state and outputs."""
+    B, L, H, _ = K.shape
+    Kb = K[b:b + 1].cpu().numpy()
+    Vb = V[b:b + 1].cpu().numpy()
+    qb = q[b:b + 1].cpu().numpy()
+    st = cache.kv_cache_stats()
+    assert st.overflow == 0 and st.packed_tokens == n_packed
+    n_blk = n_packed // 64
+    max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
+    codes = {}
+    for name, x, rel, nbytes in (("k", Kb, 0.1, st.k_bytes), ("v", Vb, 0.2, st.v_bytes)):
+        c = oracle.compress(np.ascontiguousarray(x[:, :n_packed]), rel)
+        meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[b, :n_packed]
+        assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta[0]), name + " token meta"
+        index = cache.view(name + "_index", torch.int32)[:st.n_chunks + 1].cpu().numpy().view(np.uint32).astype(np.int64)
+        arena = cache.tensors[name + "_arena"][:nbytes].cpu().numpy()
+        off = c.offsets16.astype(np.int64)
+        for blk in range(n_blk):            # chunks (blk, b, 0..H-1) are contiguous on both sides
+            g0, g1 = index[(blk * B + b) * H] * 16, index[(blk * B + b) * H + H] * 16
+            o0, o1 = off[blk * H] * 16, off[blk * H + H] * 16
+            assert g1 - g0 == o1 - o0, (name, blk)
+            assert np.array_equal(arena[g0:g1], c.arena[o0:o1]), "%s arena bytes of block %d" % (name, blk)
+        full = np.zeros(x.shape, np.uint8)
+        full[:, :n_packed] = c.codes
+        fmeta = np.zeros((1, L), np.uint32)
+        fmeta[:, :n_packed] = c.meta
+        codes[name] = (full, fmeta)
+    s_ref = oracle.k_scores(codes["k"][0], Kb, codes["k"][1], n_packed, qb, sm_scale)
+    assert_close_vectors(scores[b:b + 1, :, :L].cpu().numpy(), s_ref, "K scores, batch %d" % b)
+    pb = p[b:b + 1].cpu().numpy()
+    o_ref = oracle.v_out(codes["v"][0], Vb, codes["v"][1], n_packed, pb)
+    assert_close_vectors(out[b:b + 1].cpu().numpy(), o_ref, "V out, batch %d" % b)
+
+
+@pytest.mark.parametrize("index,batch_elements", [(3, [7]), (2, [0, 3])])
+def test_full_size_configuration(index, batch_elements):
+    """Benchmark configurations 3 (8 x 52 heads x 32000 tokens) and 2 (GQA, 4 x 8/32 heads x 32768)."""
+    w = synth.workload(index)
+    K, V, q = synth.make_workload(w, device="cuda:0")
+    L = w.tokens
+    cache = binding.PackedKVCache(w.batch, w.n_kv_heads, w.n_q_heads, L)
+    cache.kv_compress_append(K, V)
+    sm_scale = 128 ** -0.5
+    scores = cache.kv_k_matvec(q, sm_scale)
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    # properties that hold for every element, checked everywhere
+    assert torch.isfinite(scores).all() and torch.isfinite(out).all()
+    st = cache.kv_cache_stats()
+    n_chunks = L // 64 * w.batch * w.n_kv_heads
+    assert st.n_chunks == n_chunks and st.overflow == 0
+    index_t = cache.view("k_index", torch.int32)[:n_chunks + 1].to(torch.int64)
+    sizes = (index_t[1:] - index_t[:-1]) * 16
+    assert int(sizes.min()) >= 512 and int(sizes.max()) <= binding.CHUNK_MAX_BYTES
+    for b in batch_elements:
+        _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64)
+    cache.close()
+
+
+def test_growing_cache_decode_steps():
+    """Benchmark configuration 4 (growing cache): start at 131072 tokens, append one token per
+    decode step with a flush every 64 tokens; compare at a step with a part-filled tail and at the end."""
+    w = synth.workload(4)
+    steps = 130
+    K, V, q = synth.make_kv(w.batch, w.tokens + steps, w.n_kv_heads, w.n_q_heads, 4, device="cuda:0")
+    L0 = w.tokens
+    cache = binding.PackedKVCache(w.batch, w.n_kv_heads, w.n_q_heads, L0 + steps)
+    cache.kv_compress_append(K[:, :L0].contiguous(), V[:, :L0].contiguous())
+    sm_scale = 128 ** -0.5
+    scores = torch.empty(w.batch, w.n_q_heads, L0 + steps, dtype=torch.float32, device="cuda")
+    for i in range(steps):
+        cache.kv_compress_append(K[:, L0 + i:L0 + i + 1].contiguous(), V[:, L0 + i:L0 + i + 1].contiguous())
+        n = L0 + i + 1
+        cache.kv_k_matvec(q, sm_scale, scores)
+        p = torch.softmax(scores[:, :, :n], dim=-1)
+        out = cache.kv_v_matvec(p)
+        if i in (36, steps - 1):
+            torch.cuda.synchronize()
+            assert cache.tokens == n
+            _check_batch_element(cache, K[:, :n], V[:, :n], q, scores, p, out, 0, sm_scale, n // 64 * 64)
+    assert cache.kv_cache_stats().tail_tokens == (L0 + steps) % 64
+    cache.close()
