@@ -41,7 +41,8 @@ struct KArgs {
 
 template <int G>
 __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
-                                int lane, uint8_t *lds) {
+                                int lane, uint8_t *lds0, int lds_base, const uint4 *table) {
+    uint8_t *lds = lds0 + lds_base;
     const int h = bh % a.H, b = bh / a.H;
     const int ch0 = 8 * (lane & 15);
     // query slices of this lane's 8 channels, for the G query heads of kv-head h
@@ -75,7 +76,7 @@ __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_e
         stage_payload(chunk + HEADER, payload_bytes, lds, lane);
         const uint32_t mt = a.meta[b * a.meta_stride + tok];
         LanePacks lp;
-        lp.init(hdr.x, hdr.y);
+        lp.init(hdr.x, hdr.y, lds_base);
 
         float acc[G][16], msum[G];
 #pragma unroll
@@ -88,8 +89,9 @@ __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_e
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint32_t P[8];
-            unpack_pairs(lds, lp.pos(j), lp.width(j), P);
-            const float m = float(lp.min(j));
+            const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
+            expand_pack(raw, P);
+            const float m = __uint_as_float(raw.k.w);
 #pragma unroll
             for (int g = 0; g < G; ++g) msum[g] = fmaf(qf[g][j], m, msum[g]);
 #pragma unroll
@@ -146,6 +148,8 @@ __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
 template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
+    __shared__ uint4 table[256];
+    build_pack_table(table);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x;
@@ -154,7 +158,7 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
         const int part = grp % a.groups_per_stream;
         const int blk_begin = part * a.blocks_per_group;
         const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
-        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all + wave * PAYLOAD_LDS);
+        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * PAYLOAD_LDS, table);
     } else {
         const int bh = (grp - a.n_stream_groups) * 4 + wave;
         if (bh < a.B * a.H) k_tail<G>(a, bh, lane);

@@ -56,45 +56,64 @@ __device__ inline int wave_inclusive_scan(int v) {
     return v;
 }
 
+// Per-header-byte constants, kept in LDS so that a pack's width-dependent
+// values cost one LDS read instead of several vector instructions:
+//   x = pair mask ((1 << w) - 1) * 0x10001, y = w, z = 8 * w, w = float(min)
+constexpr int PACK_TABLE_BYTES = 256 * 16;
+
+// Built once per workgroup (256 threads), followed by a workgroup barrier.
+__device__ inline void build_pack_table(uint4 *table) {
+    const uint32_t hb = threadIdx.x & 255u;
+    uint32_t w = hb >> 4;
+    w = w > 4 ? 4 : w;  // widths above 4 never occur in a valid header; stay in bounds regardless
+    const uint32_t m1 = (1u << w) - 1u;
+    table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w, __float_as_uint(float(hb & 15u)));
+    __syncthreads();
+}
+
 // Per-lane view of a chunk header and of where its eight packs sit in LDS.
 struct LanePacks {
     uint32_t hlo, hhi;  // eight header bytes, pack j in byte j
-    uint32_t plo, phi;  // byte j = w_0 + .. + w_j (inclusive prefix of the widths)
-    int start;          // payload byte offset of pack 0
+    uint32_t plo, phi;  // byte j = 2 * (w_0 + .. + w_j): payload bytes up to and including pack j
+    int start;          // LDS byte address of pack 0
 
-    __device__ inline void init(uint32_t lo, uint32_t hi) {
+    // lds_base: LDS byte address of this wave's payload region
+    __device__ inline void init(uint32_t lo, uint32_t hi, int lds_base) {
         hlo = lo;
         hhi = hi;
-        uint32_t wl = (lo >> 4) & 0x0F0F0F0Fu, wh = (hi >> 4) & 0x0F0F0F0Fu;
+        uint32_t wl = (lo >> 3) & 0x1E1E1E1Eu, wh = (hi >> 3) & 0x1E1E1E1Eu;  // 2 * width per byte
         wl += wl << 8;
         wl += wl << 16;
         wh += wh << 8;
         wh += wh << 16;
-        wh += (wl >> 24) * 0x01010101u;
+        const uint32_t tl = wl >> 24;
+        wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
         plo = wl;
         phi = wh;
-        const int bytes = 2 * int(wh >> 24);
-        start = wave_inclusive_scan(bytes) - bytes;
+        const int bytes = int(wh >> 24);
+        start = wave_inclusive_scan(bytes) - bytes + lds_base;
     }
-    __device__ inline int width(int j) const { return ((j < 4 ? hlo : hhi) >> (8 * (j & 3) + 4)) & 15; }
-    __device__ inline int min(int j) const { return ((j < 4 ? hlo : hhi) >> (8 * (j & 3))) & 15; }
-    // payload byte offset of pack j
+    __device__ inline uint32_t header_byte(int j) const { return ((j < 4 ? hlo : hhi) >> (8 * (j & 3))) & 0xFFu; }
+    // LDS byte address of pack j
     __device__ inline int pos(int j) const {
         if (j == 0) return start;
         const int k = j - 1;
-        return start + 2 * int(((k < 4 ? plo : phi) >> (8 * (k & 3))) & 0xFF);
+        return start + int(((k < 4 ? plo : phi) >> (8 * (k & 3))) & 0xFFu);
     }
 };
 
-// Copy a chunk payload (payload_bytes, padded to 16) from global memory into
-// this wave's LDS region with 16-byte lane accesses.
+// Copy a chunk payload (payload_bytes, a multiple of 16) from global memory
+// into this wave's LDS region with 16-byte lane accesses.  Branch-free: lanes
+// past the end re-read the last 16 bytes of the chunk (header bytes if the
+// payload is empty) into LDS slots nobody decodes.
 __device__ inline void stage_payload(const uint8_t *__restrict__ payload, int payload_bytes,
                                      uint8_t *lds, int lane) {
+    const int last = payload_bytes - 16;  // >= -16: still inside the chunk
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
-        int off = (lane + 64 * k) * 16;
-        if (off < payload_bytes)
-            *reinterpret_cast<uint4 *>(lds + off) = *reinterpret_cast<const uint4 *>(payload + off);
+        const int off = (lane + 64 * k) * 16;
+        const int src = off < last ? off : last;
+        *reinterpret_cast<uint4 *>(lds + off) = *reinterpret_cast<const uint4 *>(payload + src);
     }
 }
 
@@ -106,22 +125,36 @@ __device__ inline void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Unpack the pack of width w at LDS byte `pos` into eight fp16-pair words:
-// P[m] (m = 0..3) = tokens (m, m+8), P[4+m] = tokens (4+m, 12+m); each half is
-// the bit pattern of fp16(code * 2^-24).
-__device__ inline void unpack_pairs(const uint8_t *lds, int pos, int w, uint32_t (&P)[8]) {
-    // aligned dword reads + funnel shifts: packs start on 2-byte boundaries and
-    // misaligned LDS reads, although legal on gfx950, were measured several times slower
-    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds + (pos & ~3));
-    const uint32_t d0 = pp[0], d1 = pp[1], d2 = pp[2];
-    const uint32_t sh = (pos & 2) * 8;
-    const uint32_t A = __builtin_amdgcn_alignbit(d1, d0, sh);    // pack bits [0, 32): tokens 0..7
-    const uint32_t hi_ = __builtin_amdgcn_alignbit(d2, d1, sh);  // pack bits [32, 64)
-    const uint32_t R = w == 4 ? hi_ : __builtin_amdgcn_alignbit(hi_, A, 8 * w);  // bits [8w, 8w+32): tokens 8..15
-    uint32_t M = __builtin_amdgcn_ubfe(0xFFFFFFFFu, 0, w);                       // (1 << w) - 1
-    M |= M << 16;
+// The raw LDS words of one pack and its width-dependent constants.
+struct PackRaw {
+    uint32_t d0, d1, d2;  // aligned dwords covering the pack's 64-bit window
+    uint32_t sh;          // low 5 bits: bit offset of the pack inside d0
+    uint4 k;              // pack table entry
+};
+
+// lds0: start of the workgroup's payload array; pos: byte address inside it
+// (2-byte aligned).  Aligned dword reads plus funnel shifts: misaligned LDS
+// reads, although legal on gfx950, were measured several times slower.
+__device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, int pos, uint32_t hb) {
+    PackRaw r;
+    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
+    r.d0 = pp[0];
+    r.d1 = pp[1];
+    r.d2 = pp[2];
+    r.sh = uint32_t(pos) << 3;
+    r.k = table[hb];
+    return r;
+}
+
+// Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
+// 16-bit half is the bit pattern of fp16(code * 2^-24).
+__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
+    const uint32_t A = __builtin_amdgcn_alignbit(r.d1, r.d0, r.sh);    // pack bits [0, 32): tokens 0..7
+    const uint32_t hi_ = __builtin_amdgcn_alignbit(r.d2, r.d1, r.sh);  // pack bits [32, 64)
+    const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32): tokens 8..15
+    const uint32_t w = r.k.y, M = r.k.x;
     const uint32_t s = 4 * w;
-    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // [A.lo16 | R.lo16]
+    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // tokens 0..3 | 8..11
     uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, 0x05040100u);  // tokens 4..7 | 12..15
 #pragma unroll
     for (int m = 0; m < 4; ++m) {

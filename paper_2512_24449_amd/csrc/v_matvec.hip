@@ -45,6 +45,8 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
     __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * B_LDS];
     __shared__ float red[4][G][D + 4];
+    __shared__ uint4 table[256];
+    build_pack_table(table);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -106,7 +108,7 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
             wsum[g] = row_all_reduce16(w);
         }
         LanePacks lp;
-        lp.init(hdr.x, hdr.y);
+        lp.init(hdr.x, hdr.y, wave * PAYLOAD_LDS);
         wave_lds_fence();
 
         const half8 b0 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 0) * 16 + col) * 16);
@@ -114,8 +116,9 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
             uint32_t P[8];
-            unpack_pairs(lds, lp.pos(j), lp.width(j), P);
-            const float m = float(lp.min(j));
+            const PackRaw raw = fetch_pack(lds_all, table, lp.pos(j), lp.header_byte(j));
+            expand_pack(raw, P);
+            const float m = __uint_as_float(raw.k.w);
 #pragma unroll
             for (int g = 0; g < G; ++g) macc[g][j] = fmaf(m, wsum[g], macc[g][j]);
             typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
