@@ -12,7 +12,9 @@
 //                         + min_t * sum_d q_d)
 // so a pack minimum costs one FMA per pack and (scale_t, min_t) one per token.
 // A workgroup of four waves walks a contiguous range of blocks of one
-// (batch, kv-head) stream; the raw fp16 tail is handled by extra workgroups of
+// (batch, kv-head) stream; every wave double-buffers whole chunks in LDS with
+// direct global->LDS transfers, so the next chunk is in flight while the
+// current one is unpacked; the raw fp16 tail is handled by extra workgroups of
 // the same launch (one launch covers everything, Sec. III-B.4).
 #include <algorithm>
 
@@ -39,10 +41,11 @@ struct KArgs {
     float sm_scale;
 };
 
+// lds0: the workgroup's chunk buffers; this wave owns the two buffers at byte
+// offsets buf_base and buf_base + CHUNK_LDS.
 template <int G>
 __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
-                                int lane, uint8_t *lds0, int lds_base, const uint4 *table) {
-    uint8_t *lds = lds0 + lds_base;
+                                int lane, uint8_t *lds0, int buf_base, const uint4 *table) {
     const int h = bh % a.H, b = bh / a.H;
     const int ch0 = 8 * (lane & 15);
     // query slices of this lane's 8 channels, for the G query heads of kv-head h
@@ -60,63 +63,72 @@ __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_e
         qsum[g] = row_all_reduce16(s);
     }
 
-    for (int blk = blk_begin + wave; blk < blk_end; blk += 4) {
-        const int c = (blk * a.B + b) * a.H + h;
-        const uint32_t o0 = a.index[c], o1 = a.index[c + 1];
-        const int64_t tok = int64_t(blk) * N + lane;  // this lane's token after the reduction
-        if (o1 - o0 < uint32_t(HEADER / 16)) {        // dropped block: defined output
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
+        uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
+        for (int it = 0; it < n_it; ++it) {
+            const int cur = buf_base + (it & 1) * CHUNK_LDS;
+            const int64_t tok = int64_t(first + 4 * it) * N + lane;  // this lane's token after the reduction
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+            wait_chunk_landed();
+            const uint32_t mt = mt_next;
+            // the next chunk streams into the other buffer while this one is unpacked
+            if (it + 1 < n_it) {
+                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
+                                lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
+                mt_next = a.meta[b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane];
+            }
+            if (!valid) {  // block dropped by an arena overflow: defined output
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-                a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] = 0.0f;
-            continue;
-        }
-        const uint8_t *chunk = a.arena + size_t(o0) * 16;
-        const int payload_bytes = int(o1 - o0) * 16 - HEADER;
-        const uint2 hdr = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
-        stage_payload(chunk + HEADER, payload_bytes, lds, lane);
-        const uint32_t mt = a.meta[b * a.meta_stride + tok];
-        LanePacks lp;
-        lp.init(hdr.x, hdr.y, lds_base);
+                for (int g = 0; g < G; ++g)
+                    a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] = 0.0f;
+                continue;
+            }
+            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
+            LanePacks lp;
+            lp.init(hdr.x, hdr.y, cur + HEADER);
 
-        float acc[G][16], msum[G];
+            float acc[G][16], msum[G];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            msum[g] = 0.0f;
+            for (int g = 0; g < G; ++g) {
+                msum[g] = 0.0f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
-        }
-        wave_lds_fence();
+                for (int i = 0; i < 16; ++i) acc[g][i] = 0.0f;
+            }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t P[8];
-            const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-            expand_pack(raw, P);
-            const float m = __uint_as_float(raw.k.w);
+            for (int j = 0; j < 8; ++j) {
+                uint32_t P[8];
+                const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
+                expand_pack(raw, P);
+                const float m = __uint_as_float(raw.k.w);
 #pragma unroll
-            for (int g = 0; g < G; ++g) msum[g] = fmaf(qf[g][j], m, msum[g]);
+                for (int g = 0; g < G; ++g) msum[g] = fmaf(qf[g][j], m, msum[g]);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                // P[k] holds tokens (k, k+8) of the group
-                const int t_lo = k, t_hi = k + 8;
-                const float cl = half_lo(P[k]), chh = half_hi(P[k]);
+                for (int k = 0; k < 8; ++k) {
+                    // P[k] holds tokens (k, k+8) of the group
+                    const float cl = half_lo(P[k]), chh = half_hi(P[k]);
 #pragma unroll
-                for (int g = 0; g < G; ++g) {
-                    acc[g][t_lo] = fmaf(qf[g][j], cl, acc[g][t_lo]);
-                    acc[g][t_hi] = fmaf(qf[g][j], chh, acc[g][t_hi]);
+                    for (int g = 0; g < G; ++g) {
+                        acc[g][k] = fmaf(qf[g][j], cl, acc[g][k]);
+                        acc[g][k + 8] = fmaf(qf[g][j], chh, acc[g][k + 8]);
+                    }
                 }
             }
-        }
-        wave_lds_fence();  // the next chunk must not overwrite LDS before all lanes read it
 
-        const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-        const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float dot = row_reduce_scatter16(acc[g], lane) * CODE_SCALE;
-            const float ms = row_all_reduce16(msum[g]);
-            a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] =
-                a.sm_scale * fmaf(scale, dot + ms, mn * qsum[g]);
+            for (int g = 0; g < G; ++g) {
+                const float dot = row_reduce_scatter16(acc[g], lane) * CODE_SCALE;
+                const float ms = row_all_reduce16(msum[g]);
+                a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok] =
+                    a.sm_scale * fmaf(scale, dot + ms, mn * qsum[g]);
+            }
         }
+        wait_chunk_landed();  // nothing may still be streaming into LDS when the buffers are reused
     }
 }
 
@@ -147,8 +159,8 @@ __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
 
 template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
-    __shared__ uint4 table[256];
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
+    __shared__ uint4 table[PACK_TABLE_ENTRIES];
     build_pack_table(table);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -158,7 +170,7 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
         const int part = grp % a.groups_per_stream;
         const int blk_begin = part * a.blocks_per_group;
         const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
-        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * PAYLOAD_LDS, table);
+        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
     } else {
         const int bh = (grp - a.n_stream_groups) * 4 + wave;
         if (bh < a.B * a.H) k_tail<G>(a, bh, lane);

@@ -21,9 +21,8 @@
 
 namespace packkv {
 
-// LDS bytes reserved per wave for a chunk payload: 512 packs * 8 bytes plus
-// slack for the bytes a pack read may touch past the payload end.
-constexpr int PAYLOAD_LDS = PACKS * 8 + 16;
+// A pack read may touch up to 12 bytes past the end of a chunk buffer.
+constexpr int LDS_TAIL_PAD = 16;
 constexpr float CODE_SCALE = 16777216.0f;  // 2^24: fp16 subnormal unit^-1
 
 // DPP controls (wave64, rows of 16 lanes).
@@ -59,15 +58,18 @@ __device__ inline int wave_inclusive_scan(int v) {
 // Per-header-byte constants, kept in LDS so that a pack's width-dependent
 // values cost one LDS read instead of several vector instructions:
 //   x = pair mask ((1 << w) - 1) * 0x10001, y = w, z = 8 * w, w = float(min)
-constexpr int PACK_TABLE_BYTES = 256 * 16;
+// Valid header bytes are below 0x50 (width <= 4); a corrupt byte would index past
+// the table, which on this hardware reads other LDS contents or zero, never faults.
+constexpr int PACK_TABLE_ENTRIES = 80;
 
-// Built once per workgroup (256 threads), followed by a workgroup barrier.
+// Built once per workgroup, followed by a workgroup barrier.
 __device__ inline void build_pack_table(uint4 *table) {
-    const uint32_t hb = threadIdx.x & 255u;
-    uint32_t w = hb >> 4;
-    w = w > 4 ? 4 : w;  // widths above 4 never occur in a valid header; stay in bounds regardless
-    const uint32_t m1 = (1u << w) - 1u;
-    table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w, __float_as_uint(float(hb & 15u)));
+    const uint32_t hb = threadIdx.x;
+    if (hb < PACK_TABLE_ENTRIES) {
+        const uint32_t w = hb >> 4;
+        const uint32_t m1 = (1u << w) - 1u;
+        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w, __float_as_uint(float(hb & 15u)));
+    }
     __syncthreads();
 }
 
@@ -102,20 +104,53 @@ struct LanePacks {
     }
 };
 
-// Copy a chunk payload (payload_bytes, a multiple of 16) from global memory
-// into this wave's LDS region with 16-byte lane accesses.  Branch-free: lanes
-// past the end re-read the last 16 bytes of the chunk (header bytes if the
-// payload is empty) into LDS slots nobody decodes.
-__device__ inline void stage_payload(const uint8_t *__restrict__ payload, int payload_bytes,
-                                     uint8_t *lds, int lane) {
-    const int last = payload_bytes - 16;  // >= -16: still inside the chunk
+// Chunk offsets of up to 64 blocks of one wave, one block per lane: lane i holds
+// the index words of block first + stride*i of stream (b, h).  Read once per 64
+// blocks; iterations pick their words with v_readlane, so no chunk waits on an
+// index load.
+struct IndexBatch {
+    uint32_t o0, o1;
+    __device__ inline void load(const uint32_t *__restrict__ index, int first, int stride, int end,
+                                int B, int H, int b, int h, int lane) {
+        const int blk = first + stride * lane;
+        const int c = blk < end ? (blk * B + b) * H + h : 0;
+        o0 = index[c];
+        o1 = index[c + 1];
+    }
+    __device__ inline uint32_t start16(int it) const { return __builtin_amdgcn_readlane(o0, it); }
+    __device__ inline uint32_t end16(int it) const { return __builtin_amdgcn_readlane(o1, it); }
+};
+
+// One LDS buffer holds one whole chunk (header + payload).
+constexpr int CHUNK_LDS = CHUNK_MAX;
+
+// Start the transfer of a chunk straight from global memory into an LDS buffer
+// (global_load_lds_dwordx4: lane i's 16 bytes land at buf + 1024k + 16i, no
+// vector registers involved), so that it is in flight while the previous chunk
+// is unpacked.  o0/o1: the chunk's index words; buf: wave-uniform.  A dropped
+// block (size 0) transfers nothing.  Lanes past the chunk end re-read its last
+// 16 bytes into buffer bytes nobody decodes; the fifth slice only uses lanes
+// 0..31 because the buffer is 4608 bytes.
+__device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
+                                       uint8_t *buf, int lane) {
+    const int size = int(o1 - o0) * 16;
+    if (size < HEADER) return;
+    const uint8_t *chunk = arena + size_t(o0) * 16;
+    const int last = size - 16;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        const int off = (lane + 64 * k) * 16;
-        const int src = off < last ? off : last;
-        *reinterpret_cast<uint4 *>(lds + off) = *reinterpret_cast<const uint4 *>(payload + src);
+    for (int k = 0; k < 5; ++k) {
+        if (k * 1024 < size && (k < 4 || lane < 32)) {
+            const int off = k * 1024 + lane * 16;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void *)(chunk + (off < last ? off : last)),
+                (__attribute__((address_space(3))) void *)(buf + k * 1024), 16, 0, 0);
+        }
     }
 }
+
+// All outstanding global->LDS transfers (and other vector memory operations) of
+// this wave have landed.
+__device__ inline void wait_chunk_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // LDS writes of this wave become visible to its own later LDS reads in program
 // order; the fences only stop the compiler from moving accesses across.

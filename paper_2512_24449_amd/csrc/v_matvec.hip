@@ -42,10 +42,13 @@ constexpr int B_LDS = 4 * 2 * 16 * 16;  // bytes per wave: [token group][half][c
 
 template <int G>
 __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * PAYLOAD_LDS];
+    // two chunk buffers per wave; after the main loop the same memory holds the
+    // cross-wave reduction array red[4][G][D + 4]
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * B_LDS];
-    __shared__ float red[4][G][D + 4];
-    __shared__ uint4 table[256];
+    __shared__ uint4 table[PACK_TABLE_ENTRIES];
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
+    float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
     build_pack_table(table);
 
     const int lane = threadIdx.x & 63;
@@ -53,7 +56,7 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     const int split = blockIdx.x;
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
-    uint8_t *lds = lds_all + wave * PAYLOAD_LDS;
+    const int buf_base = wave * 2 * CHUNK_LDS;
     uint8_t *blds = blds_all + wave * B_LDS;
     const int row = lane >> 4, col = lane & 15;
 
@@ -78,57 +81,78 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
 
     const int blk_begin = split * a.blocks_per_split;
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
-    for (int blk = blk_begin + wave; blk < blk_end; blk += 4) {
-        const int c = (blk * a.B + b) * a.H + h;
-        const uint32_t o0 = a.index[c], o1 = a.index[c + 1];
-        if (o1 - o0 < uint32_t(HEADER / 16)) continue;  // dropped block contributes nothing
-        const uint8_t *chunk = a.arena + size_t(o0) * 16;
-        const int payload_bytes = int(o1 - o0) * 16 - HEADER;
-        const int64_t tok = int64_t(blk) * N + lane;
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
+        uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
+        float p_next[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + int64_t(first) * N + lane];
+        for (int it = 0; it < n_it; ++it) {
+            const int cur = buf_base + (it & 1) * CHUNK_LDS;
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+            wait_chunk_landed();
+            const uint32_t mt = mt_next;
+            float pt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) pt[g] = p_next[g];
+            // the next chunk streams into the other buffer while this one is unpacked
+            if (it + 1 < n_it) {
+                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
+                                lds_all + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
+                const int64_t tok = int64_t(first + 4 * (it + 1)) * N + lane;
+                mt_next = a.meta[b * a.meta_stride + tok];
+#pragma unroll
+                for (int g = 0; g < G; ++g) p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
+            }
+            if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
 
-        const uint2 hdr = *reinterpret_cast<const uint2 *>(chunk + lane * 8);
-        stage_payload(chunk + HEADER, payload_bytes, lds, lane);
-        const uint32_t mt = a.meta[b * a.meta_stride + tok];
-        const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-        const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
-        float wsum[G];
+            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+            float wsum[G];
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            const float pt = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
-            const float w = pt * scale;
-            pm[g] = fmaf(pt, mn, pm[g]);
-            // w = hi + lo with both parts fp16 (lo scaled by 2^11); truncation keeps lo >= 0
-            const _Float16 hi = __builtin_bit_cast(
-                _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
-            const float lo = (w - float(hi)) * 2048.0f;
-            const _Float16 lo16 = __builtin_bit_cast(
-                _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
-            *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g) * 16) = hi;
-            *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g + 1) * 16) = lo16;
-            wsum[g] = row_all_reduce16(w);
-        }
-        LanePacks lp;
-        lp.init(hdr.x, hdr.y, wave * PAYLOAD_LDS);
-        wave_lds_fence();
+            for (int g = 0; g < G; ++g) {
+                const float w = pt[g] * scale;
+                pm[g] = fmaf(pt[g], mn, pm[g]);
+                // w = hi + lo with both parts fp16 (lo scaled by 2^11); truncation keeps lo >= 0
+                const _Float16 hi = __builtin_bit_cast(
+                    _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
+                const float lo = (w - float(hi)) * 2048.0f;
+                const _Float16 lo16 = __builtin_bit_cast(
+                    _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+                *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g) * 16) = hi;
+                *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g + 1) * 16) = lo16;
+                wsum[g] = row_all_reduce16(w);
+            }
+            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + cur + lane * 8);
+            LanePacks lp;
+            lp.init(hdr.x, hdr.y, cur + HEADER);
+            wave_lds_fence();
 
-        const half8 b0 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 0) * 16 + col) * 16);
-        const half8 b1 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 1) * 16 + col) * 16);
+            const half8 b0 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 0) * 16 + col) * 16);
+            const half8 b1 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 1) * 16 + col) * 16);
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            uint32_t P[8];
-            const PackRaw raw = fetch_pack(lds_all, table, lp.pos(j), lp.header_byte(j));
-            expand_pack(raw, P);
-            const float m = __uint_as_float(raw.k.w);
+            for (int j = 0; j < 8; ++j) {
+                uint32_t P[8];
+                const PackRaw raw = fetch_pack(lds_all, table, lp.pos(j), lp.header_byte(j));
+                expand_pack(raw, P);
+                const float m = __uint_as_float(raw.k.w);
 #pragma unroll
-            for (int g = 0; g < G; ++g) macc[g][j] = fmaf(m, wsum[g], macc[g][j]);
-            typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-            const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[1], P[2], P[3]});
-            const half8 a1 = __builtin_bit_cast(half8, u32x4{P[4], P[5], P[6], P[7]});
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[j], 0, 0, 0);
-            acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[j], 0, 0, 0);
+                for (int g = 0; g < G; ++g) macc[g][j] = fmaf(m, wsum[g], macc[g][j]);
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[1], P[2], P[3]});
+                const half8 a1 = __builtin_bit_cast(half8, u32x4{P[4], P[5], P[6], P[7]});
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[j], 0, 0, 0);
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[j], 0, 0, 0);
+            }
+            wave_lds_fence();  // the B operand is rewritten by the next chunk
         }
-        wave_lds_fence();  // LDS is rewritten by the next chunk
+        wait_chunk_landed();
     }
+    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
 
     // ---- combine: MFMA tiles (lane = column `col`, rows 4*row+r), the pack-minimum
     // term (lane = token group `row`, channels 8*col+j), the four waves ----
