@@ -38,14 +38,21 @@ struct VArgs {
     int blocks_per_split;
 };
 
-constexpr int B_LDS = 4 * 2 * 16 * 16;  // bytes per wave: [token group][half][column][8 fp16]
+// B operand staging per wave: [token group][half][column < 2G][8 fp16], then 16 zero
+// bytes that the lanes of the unused columns (>= 2G) read instead.
+template <int G>
+struct BLds {
+    static constexpr int COLS = 2 * G;
+    static constexpr int ZERO = 4 * 2 * COLS * 16;
+    static constexpr int BYTES = ZERO + 16;
+};
 
 template <int G>
 __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     // two chunk buffers per wave; after the main loop the same memory holds the
     // cross-wave reduction array red[4][G][D + 4]
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
-    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * B_LDS];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
@@ -57,16 +64,18 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
     const int buf_base = wave * 2 * CHUNK_LDS;
-    uint8_t *blds = blds_all + wave * B_LDS;
+    uint8_t *blds = blds_all + wave * BLds<G>::BYTES;
     const int row = lane >> 4, col = lane & 15;
 
-    // columns >= 2G of the B operand stay zero for the whole kernel
-    *reinterpret_cast<uint4 *>(blds + lane * 32) = make_uint4(0, 0, 0, 0);
-    *reinterpret_cast<uint4 *>(blds + lane * 32 + 16) = make_uint4(0, 0, 0, 0);
+    constexpr int COLS = BLds<G>::COLS;
+    if (lane < 4) reinterpret_cast<uint32_t *>(blds + BLds<G>::ZERO)[lane] = 0;
 
-    // where this lane's own token (16*row + col) sits in the B operand
+    // where this lane's own token (16*row + col) sits in the B operand (column 0)
     const int tm = col & 7;
-    const int bslot = (((row * 2 + (tm >> 2)) * 16) * 8 + 2 * (tm & 3) + (col >> 3)) * 2;
+    const int bslot = (((row * 2 + (tm >> 2)) * COLS) * 8 + 2 * (tm & 3) + (col >> 3)) * 2;
+    // where this lane reads its B operand halves from
+    const int bread0 = col < COLS ? ((row * 2 + 0) * COLS + col) * 16 : BLds<G>::ZERO;
+    const int bread1 = col < COLS ? ((row * 2 + 1) * COLS + col) * 16 : BLds<G>::ZERO;
 
     float4_t acc[8];
 #pragma unroll
@@ -132,12 +141,17 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
             lp.init(hdr.x, hdr.y, cur + HEADER);
             wave_lds_fence();
 
-            const half8 b0 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 0) * 16 + col) * 16);
-            const half8 b1 = *reinterpret_cast<const half8 *>(blds + ((row * 2 + 1) * 16 + col) * 16);
+            const half8 b0 = *reinterpret_cast<const half8 *>(blds + bread0);
+            const half8 b1 = *reinterpret_cast<const half8 *>(blds + bread1);
+            PackRaw raw_next = fetch_pack(lds_all, table, lp.pos(0), lp.header_byte(0));
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 uint32_t P[8];
-                const PackRaw raw = fetch_pack(lds_all, table, lp.pos(j), lp.header_byte(j));
+                const PackRaw raw = raw_next;
+                // LDS reads run exactly one pack ahead of their use (the scheduling barrier keeps
+                // the compiler from hoisting all eight fetches and blowing up register use)
+                if (j < 7) raw_next = fetch_pack(lds_all, table, lp.pos(j + 1), lp.header_byte(j + 1));
+                __builtin_amdgcn_sched_barrier(0);
                 expand_pack(raw, P);
                 const float m = __uint_as_float(raw.k.w);
 #pragma unroll
