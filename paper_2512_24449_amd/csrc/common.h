@@ -30,8 +30,46 @@ constexpr int V_PART_STRIDE = 132;              // floats: 128 outputs, [128] = 
 
 enum { ST_OVERFLOW_K = 0, ST_OVERFLOW_V = 1 };
 
+// Workgroups (of four waves, one chunk per wave at a time) to spread `total_blocks` chunks
+// over: a workgroup's start-up (constant table, query operands, first index and chunk
+// loads) costs about as much as unpacking two chunks, so a wave should see about eight
+// chunks; below that 512 workgroups -- two per compute unit -- measured fastest, and
+// beyond a few thousand there is nothing left to gain.
+inline int64_t target_workgroups(int64_t total_blocks) {
+    const int64_t w = total_blocks / 32;
+    return w < 512 ? 512 : (w > 4096 ? 4096 : w);
+}
+
 inline size_t v_partial_bytes(int batch, int n_q_heads) {
     return size_t(V_SPLITS_MAX) * batch * n_q_heads * V_PART_STRIDE * sizeof(float);
+}
+
+// Sum of the per-split partial rows partial[(s * n_rows + r) * V_PART_STRIDE + 0..128] over
+// s < n_splits, in a fixed order, by a workgroup of 256 threads: eight thread groups take every
+// eighth split with independent 16-byte loads, then the eight sums are added pairwise.
+// Returns column d = threadIdx.x (threads < 128; others return 0) and the sum of column 128.
+__device__ inline float reduce_split_partials(const float *__restrict__ partial, int n_splits,
+                                              int n_rows, int r, float (*lds)[V_PART_STRIDE],
+                                              float *col128) {
+    const int sg = threadIdx.x >> 5, q4 = threadIdx.x & 31;
+    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float last = 0.0f;
+#pragma unroll 4
+    for (int s = sg; s < n_splits; s += 8) {
+        const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
+        const float4 v = *reinterpret_cast<const float4 *>(src + 4 * q4);
+        acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
+        if (q4 == 0) last += src[128];
+    }
+    *reinterpret_cast<float4 *>(&lds[sg][4 * q4]) = acc;
+    if (q4 == 0) lds[sg][128] = last;
+    __syncthreads();
+    const int d = threadIdx.x < 128 ? threadIdx.x : 128;
+    const float v = ((lds[0][d] + lds[1][d]) + (lds[2][d] + lds[3][d])) +
+                    ((lds[4][d] + lds[5][d]) + (lds[6][d] + lds[7][d]));
+    *col128 = ((lds[0][128] + lds[1][128]) + (lds[2][128] + lds[3][128])) +
+              ((lds[4][128] + lds[5][128]) + (lds[6][128] + lds[7][128]));
+    return threadIdx.x < 128 ? v : 0.0f;
 }
 
 }  // namespace packkv

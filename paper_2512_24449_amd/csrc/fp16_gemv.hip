@@ -134,13 +134,13 @@ __global__ __launch_bounds__(256) void fp16_v_kernel(const __half *__restrict__ 
     }
 }
 
-__global__ __launch_bounds__(128) void fp16_v_reduce_kernel(const float *__restrict__ partial,
+__global__ __launch_bounds__(256) void fp16_v_reduce_kernel(const float *__restrict__ partial,
                                                             int n_splits, int n_rows,
                                                             float *__restrict__ out) {
-    const int r = blockIdx.x, d = threadIdx.x;
-    float acc = 0.0f;
-    for (int s = 0; s < n_splits; ++s) acc += partial[(int64_t(s) * n_rows + r) * V_PART_STRIDE + d];
-    out[int64_t(r) * D + d] = acc;
+    __shared__ float lds[8][V_PART_STRIDE];
+    float unused;
+    const float acc = reduce_split_partials(partial, n_splits, n_rows, blockIdx.x, lds, &unused);
+    if (threadIdx.x < D) out[int64_t(blockIdx.x) * D + threadIdx.x] = acc;
 }
 
 // Grid-stride 16-byte reads, xor-folded so the loads cannot be dropped.
@@ -211,8 +211,10 @@ extern "C" int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_
     const int G = n_q_heads / n_kv_heads;
     const int streams = batch * n_kv_heads;
     const int64_t tiles = (tokens + 63) / 64;
-    int n_splits = int(std::min<int64_t>(std::min<int64_t>((2048 + streams - 1) / streams, (tiles + 3) / 4),
-                                         V_SPLITS_MAX));
+    // same split rule as the packed V path
+    int n_splits = int(std::min<int64_t>(
+        std::min<int64_t>((target_workgroups(tiles * streams) + streams - 1) / streams, (tiles + 3) / 4),
+        V_SPLITS_MAX));
     if (n_splits < 1) n_splits = 1;
     int64_t tiles_per_split = (tiles + n_splits - 1) / n_splits;
     n_splits = int((tiles + tiles_per_split - 1) / tiles_per_split);
@@ -230,7 +232,7 @@ extern "C" int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_
         default: return KV_ERR_UNSUPPORTED;
     }
 #undef LAUNCH
-    hipLaunchKernelGGL(fp16_v_reduce_kernel, dim3(batch * n_q_heads), dim3(128), 0, s, partial,
+    hipLaunchKernelGGL(fp16_v_reduce_kernel, dim3(batch * n_q_heads), dim3(256), 0, s, partial,
                        n_splits, batch * n_q_heads, out);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;

@@ -132,6 +132,195 @@ __device__ inline void k_stream(const KArgs &a, int bh, int blk_begin, int blk_e
     }
 }
 
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float float4_u __attribute__((ext_vector_type(4), aligned(4)));
+
+// Matrix-core form of the K walk.  The codes of a pack sit along the token axis
+// inside a lane, the dot product runs along the channel axis across lanes, so the
+// wave first turns the tile with a 0/1 selection product and then contracts it
+// with q:
+//   C1[channel i][column n] = sum_k A1[i][k] S_x[k][n]         (16x16x32 fp16 MFMA)
+//     A1: the unpacked words of pack slot j (row i = lane%16 = channel 8i+j, the
+//         32 k-slots = 8 tokens of each token group lane/16), S_x: selects the
+//         16 k-slots with bit 1 of the in-lane slot equal to x, times 2^10
+//   C2[head][column n] += sum_k Q[head][k] cvt16(C1)[k][n]      (16x16x32 fp16 MFMA)
+//     the fp32 tile C1 of lane (r, n) holds channels 4r..4r+3 of column n, which is
+//     exactly the k-run a B operand lane needs; two pack slots fill its 8 k-values.
+// Every value in C1 is an integer code times 2^-14, so its fp16 conversion is
+// exact.  With the k-slot -> column assignment below, lane n (< 16) ends up with
+// four consecutive tokens of the block, 16*(n>>2) + 4*((n>>1)&1) + 8*(n&1) + {0..3},
+// in the four accumulators, for the heads 4*(lane/16)..+3 in their four registers.
+template <int G>
+__device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
+                                     int lane, uint8_t *lds0, int buf_base, const uint4 *table) {
+    const int h = bh % a.H, b = bh / a.H;
+    const int row = lane >> 4, col = lane & 15;
+    const int64_t head0 = int64_t(b) * a.H * G + h * G;
+
+    // q of this lane's 8 channels as fp16 pairs (pack-minimum term) and its sum per head
+    uint32_t qh[G][4];
+    float qsum[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(a.q + (head0 + g) * D + 8 * col);
+        qh[g][0] = raw.x, qh[g][1] = raw.y, qh[g][2] = raw.z, qh[g][3] = raw.w;
+        float s = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) s += half_lo(qh[g][k]) + half_hi(qh[g][k]);
+        qsum[g] = row_all_reduce16(s);
+    }
+    // Q operands of the second product, one per pair of pack slots (2jp, 2jp+1): row = head
+    // lane%16, k-value e of k-run lane/16 = channel 8*(4*(lane/16) + (e&3)) + 2jp + (e>>2)
+    half8 qA[4];
+    {
+        uint32_t rw[4][4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (col < G) raw = *reinterpret_cast<const uint4 *>(a.q + (head0 + col) * D + 8 * (4 * row + e));
+            rw[e][0] = raw.x, rw[e][1] = raw.y, rw[e][2] = raw.z, rw[e][3] = raw.w;
+        }
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+            const uint32_t w0 = __builtin_amdgcn_perm(rw[1][jp], rw[0][jp], 0x05040100u);
+            const uint32_t w1 = __builtin_amdgcn_perm(rw[3][jp], rw[2][jp], 0x05040100u);
+            const uint32_t w2 = __builtin_amdgcn_perm(rw[1][jp], rw[0][jp], 0x07060302u);
+            const uint32_t w3 = __builtin_amdgcn_perm(rw[3][jp], rw[2][jp], 0x07060302u);
+            qA[jp] = __builtin_bit_cast(half8, u32x4{w0, w1, w2, w3});
+        }
+    }
+    // selection operands: lane (k-run kg = lane/16, column n = lane%16) holds S_x[8kg+e][n];
+    // slot e of run kg goes to column 4kg + 2(e>>2) + (e&1) when ((e>>1)&1) == x
+    half8 sel[2];
+#pragma unroll
+    for (int x = 0; x < 2; ++x) {
+        uint32_t wsel[4] = {0, 0, 0, 0};
+        const int e = ((col >> 1) & 1) * 4 + x * 2 + (col & 1);
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if ((col >> 2) == row && (e >> 1) == k) wsel[k] = 0x6400u << (16 * (e & 1));  // fp16 1024
+        sel[x] = __builtin_bit_cast(half8, u32x4{wsel[0], wsel[1], wsel[2], wsel[3]});
+    }
+    // this lane's four output tokens inside a block, the heads it holds, where its
+    // token group's pack-minimum sums come from
+    const int tok_base = 16 * (col >> 2) + 4 * ((col >> 1) & 1) + 8 * (col & 1);
+    const int src_lane = 16 * (col >> 2);
+    float qs[4];
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        qs[x] = x < G ? qsum[x] : 0.0f;
+        if (G > 4 && row == 1) qs[x] = qsum[(4 + x) % G];
+    }
+    const bool writer = 4 * row < G;
+    constexpr float OUT_SCALE = 16384.0f;  // codes enter as code * 2^-24, selection adds 2^10
+
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
+        const uint32_t *meta = a.meta + b * a.meta_stride + tok_base;
+        uint4 mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first) * N);
+        for (int it = 0; it < n_it; ++it) {
+            const int cur = buf_base + (it & 1) * CHUNK_LDS;
+            const int64_t tok = int64_t(first + 4 * it) * N + tok_base;
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+            wait_chunk_landed();
+            const uint4 mt = mt_next;
+            // the next chunk streams into the other buffer while this one is unpacked
+            if (it + 1 < n_it) {
+                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
+                                lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
+                mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first + 4 * (it + 1)) * N);
+            }
+            if (!valid) {  // block dropped by an arena overflow: defined output
+                if (writer) {
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (4 * row + x < G)
+                            *reinterpret_cast<float4_u *>(a.scores + (head0 + 4 * row + x) * a.ld + tok) =
+                                float4_u{0.0f, 0.0f, 0.0f, 0.0f};
+                }
+                continue;
+            }
+            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
+            LanePacks lp;
+            lp.init(hdr.x, hdr.y, cur + HEADER);
+
+            float4_t acc[4];  // [token offset 0..3] x [head register]
+#pragma unroll
+            for (int t = 0; t < 4; ++t) acc[t] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+            float msum[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) msum[g] = 0.0f;
+            const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp) {
+                float4_t c1[2][4];
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    const int j = 2 * jp + jj;
+                    uint32_t P[8];
+                    const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
+                    expand_pack(raw, P);
+                    const float m = __uint_as_float(raw.k.w);
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        msum[g] = fmaf(jj ? half_hi(qh[g][jp]) : half_lo(qh[g][jp]), m, msum[g]);
+                    // P[t + 2i]: tokens (t + 2i, t + 2i + 8); column token offset t = parity + 2x
+                    const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[2], P[4], P[6]});
+                    const half8 a1 = __builtin_bit_cast(half8, u32x4{P[1], P[3], P[5], P[7]});
+                    c1[jj][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, sel[0], zero, 0, 0, 0);
+                    c1[jj][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, sel[0], zero, 0, 0, 0);
+                    c1[jj][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, sel[1], zero, 0, 0, 0);
+                    c1[jj][3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, sel[1], zero, 0, 0, 0);
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const u32x4 bw = {
+                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][0], c1[0][t][1])),
+                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][2], c1[0][t][3])),
+                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][0], c1[1][t][1])),
+                        __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][2], c1[1][t][3]))};
+                    acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(qA[jp], __builtin_bit_cast(half8, bw),
+                                                                     acc[t], 0, 0, 0);
+                }
+            }
+
+            // pack-minimum term of this lane's token group, per head register
+            float ms[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float v = __shfl(row_all_reduce16(msum[g]), src_lane);
+                if (g < 4) {
+                    if (G <= 4 || row == 0) ms[g] = v;
+                } else if (row == 1) {
+                    ms[g - 4] = v;
+                }
+            }
+            if (writer) {
+                const uint32_t mtw[4] = {mt.x, mt.y, mt.z, mt.w};
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    if (4 * row + x < G) {
+                        float4_u o;
+#pragma unroll
+                        for (int t = 0; t < 4; ++t) {
+                            const float scale = __half2float(__ushort_as_half(uint16_t(mtw[t] & 0xFFFFu)));
+                            const float mn = __half2float(__ushort_as_half(uint16_t(mtw[t] >> 16)));
+                            o[t] = a.sm_scale * fmaf(scale, acc[t][x] * OUT_SCALE + ms[x], mn * qs[x]);
+                        }
+                        *reinterpret_cast<float4_u *>(a.scores + (head0 + 4 * row + x) * a.ld + tok) = o;
+                    }
+                }
+            }
+        }
+        wait_chunk_landed();  // nothing may still be streaming into LDS when the buffers are reused
+    }
+}
+
 // Raw fp16 tail (Sec. III-B.1 buffer): plain dot products, one lane per token.
 template <int G>
 __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
@@ -170,7 +359,13 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
         const int part = grp % a.groups_per_stream;
         const int blk_begin = part * a.blocks_per_group;
         const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
-        k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
+        // one query head per kv-head: plain FMAs cost the same issue slots as the two matrix
+        // products and need fewer registers; with grouped queries the unpack is shared by
+        // the G heads only in the matrix-core form
+        if constexpr (G == 1)
+            k_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
+        else
+            k_stream_mfma<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
     } else {
         const int bh = (grp - a.n_stream_groups) * 4 + wave;
         if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
@@ -193,8 +388,9 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     a.H = c->cfg.n_kv_heads;
     a.n_blocks = int(c->packed_tokens / N);
     const int streams = a.B * a.H;
-    // about 4096 workgroups over the chip, never less than one block per wave
-    int64_t want_groups = std::max<int64_t>(1, 4096 / streams);
+    // never less than one block per wave
+    const int64_t want_groups =
+        std::max<int64_t>(1, target_workgroups(int64_t(a.n_blocks) * streams) / streams);
     int bpg = int((a.n_blocks + want_groups - 1) / want_groups);
     bpg = std::max(4, (bpg + 3) / 4 * 4);
     a.blocks_per_group = bpg;

@@ -204,21 +204,19 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
 }
 
 // Fixed-order combination of the split partial sums, plus the raw fp16 tail.
-__global__ __launch_bounds__(128) void v_reduce_kernel(const float *__restrict__ partial,
+__global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__ partial,
                                                        int n_splits, int n_rows,
                                                        const float *__restrict__ p, int64_t ld,
                                                        int64_t packed_tokens,
                                                        const __half *__restrict__ tail, int n_tail,
                                                        int tail_cap, int H, int G,
                                                        float *__restrict__ out) {
+    __shared__ float lds[8][V_PART_STRIDE];
     const int r = blockIdx.x;  // b*Hq + hq
     const int d = threadIdx.x;
-    float acc = 0.0f, pmin = 0.0f;
-    for (int s = 0; s < n_splits; ++s) {
-        const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
-        acc += src[d];
-        pmin += src[D];
-    }
+    float pmin;
+    float acc = reduce_split_partials(partial, n_splits, n_rows, r, lds, &pmin);
+    if (d >= D) return;
     acc += pmin;
     if (n_tail > 0) {
         const int hq = r % (H * G), b = r / (H * G);
@@ -232,17 +230,13 @@ __global__ __launch_bounds__(128) void v_reduce_kernel(const float *__restrict__
     out[int64_t(r) * D + d] = acc;
 }
 
-#ifndef V_TARGET_GROUPS
-#define V_TARGET_GROUPS 2048
-#endif
 int v_splits_for(int n_blocks, int streams) {
-    // enough workgroups to fill 256 CUs a few times over, at least one block per wave
-    int want = (V_TARGET_GROUPS + streams - 1) / streams;
-    int by_blocks = (n_blocks + 3) / 4;
-    int s = want < by_blocks ? want : by_blocks;
+    const int64_t want = (target_workgroups(int64_t(n_blocks) * streams) + streams - 1) / streams;
+    const int by_blocks = (n_blocks + 3) / 4;  // at least one block per wave
+    int64_t s = want < by_blocks ? want : by_blocks;
     if (s > V_SPLITS_MAX) s = V_SPLITS_MAX;
     if (s < 1) s = 1;
-    return s;
+    return int(s);
 }
 
 int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s) {
@@ -275,7 +269,7 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
             default: return KV_ERR_UNSUPPORTED;
         }
     }
-    hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * G), dim3(128), 0, s, partial, n_splits,
+    hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
                        B * H * G, p, ld_p, c->packed_tokens,
                        static_cast<const __half *>(c->buf.v_tail), c->tail_tokens,
                        c->cfg.tail_capacity, H, G, out);
