@@ -22,6 +22,8 @@ pytestmark = pytest.mark.gpu
     (1, 2, 16, 256, 13),      # G = 8
     (3, 5, 5, 320 + 37, 14),  # ragged: 37 tokens stay in the raw tail
     (1, 4, 4, 17, 15),        # tail only, nothing packed
+    (2, 2, 8, 320 + 21, 16),  # G = 4, ragged, odd score row stride (unaligned 16-byte stores)
+    (1, 3, 6, 7 * 64 + 1, 17),  # G = 2, odd number of blocks per wave
 ])
 def test_append_then_decode_matches_oracle(B, H, Hq, L, seed):
     gpu_cases.run_case(B, H, Hq, L, seed)
@@ -108,8 +110,9 @@ def test_degenerate_inputs():
     _special_case(K, V, 4)
 
 
-def test_arena_overflow_sets_sticky_flag_and_drops_the_block():
-    B, H, Hq, L = 1, 2, 2, 256
+@pytest.mark.parametrize("Hq", [2, 4])
+def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq):
+    B, H, L = 1, 2, 256
     K, V, q = synth.make_kv(B, L, H, Hq, 50)
     cfg = binding.make_config(B, H, Hq, L)
     cache = binding.PackedKVCache(B, H, Hq, L)
