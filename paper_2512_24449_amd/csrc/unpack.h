@@ -177,7 +177,11 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
     r.d1 = pp[1];
     r.d2 = pp[2];
     r.sh = uint32_t(pos) << 3;
+#ifdef EXP_TABLE_SAME
+    r.k = table[0x21 + (hb & 0)];
+#else
     r.k = table[hb];
+#endif
     return r;
 }
 
