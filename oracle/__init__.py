@@ -215,6 +215,23 @@ def v_out(codes, x, meta, n_packed, p):
     return out
 
 
+def attention(kcodes, kx, kmeta, vcodes, vx, vmeta, n_packed, q, sm_scale):
+    """Decode attention from its definition in fp64: out float64 [B, Hq, D]."""
+    kx, vx, q = _u16(kx), _u16(vx), _u16(q)
+    B, T, H, Dd = kx.shape
+    Hq = q.shape[1]
+    assert Hq % H == 0 and vx.shape == kx.shape and T >= 1
+    if kcodes is None:
+        kcodes = vcodes = np.zeros((B, T, H, Dd), np.uint8)
+        kmeta = vmeta = np.zeros((B, T), np.uint32)
+        assert n_packed == 0
+    out = np.empty((B, Hq, Dd), np.float64)
+    lib().orc_attention(_p(np.ascontiguousarray(kcodes)), _p(kx), _p(np.ascontiguousarray(kmeta)),
+                        _p(np.ascontiguousarray(vcodes)), _p(vx), _p(np.ascontiguousarray(vmeta)),
+                        B, T, int(n_packed), H, Hq, Dd, _p(q), C.c_double(sm_scale), _p(out))
+    return out
+
+
 def softmax(s):
     """fp64 softmax over the last axis."""
     s = np.ascontiguousarray(s, dtype=np.float64)

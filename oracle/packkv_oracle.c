@@ -350,6 +350,58 @@ void orc_softmax(const double *s, int rows, int T, double *p)
     }
 }
 
+/*
+ * Whole decode attention of one new query (Att(q, K, V) in the permutation
+ * statement of Sec. III-B.3), written out from its definition in fp64:
+ *   s_t = sm_scale * sum_d q_d Khat[t][d];  p = softmax(s);  out_d = sum_t p_t Vhat[t][d]
+ * per batch element and query head, with the decoded caches for t < n_packed
+ * and the raw fp16 tail after that.  kcodes/kx/kmeta describe K, vcodes/vx/vmeta V
+ * (layouts as orc_k_scores / orc_v_out).  out is [B][Hq][D].
+ */
+void orc_attention(const uint8_t *kcodes, const uint16_t *kx, const uint32_t *kmeta,
+                   const uint8_t *vcodes, const uint16_t *vx, const uint32_t *vmeta,
+                   int B, int T, int n_packed, int H, int Hq, int D,
+                   const uint16_t *qvec, double sm_scale, double *out)
+{
+    int G = Hq / H;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int b = 0; b < B; ++b)
+        for (int hq = 0; hq < Hq; ++hq) {
+            int h = hq / G;
+            const uint16_t *qv = qvec + ((int64_t)b * Hq + hq) * D;
+            double *s = (double *)malloc(sizeof(double) * (size_t)T);
+            double *o = out + ((int64_t)b * Hq + hq) * D;
+            double mx = 0.0, sum = 0.0;
+            for (int t = 0; t < T; ++t) {
+                int64_t base = (((int64_t)b * T + t) * H + h) * D;
+                uint32_t mt = kmeta[(int64_t)b * T + t];
+                double acc = 0.0;
+                for (int d = 0; d < D; ++d) {
+                    double kv = t < n_packed
+                        ? orc_xhat(kcodes[base + d], (uint16_t)(mt & 0xFFFFu), (uint16_t)(mt >> 16))
+                        : (double)orc_h2f(kx[base + d]);
+                    acc += (double)orc_h2f(qv[d]) * kv;
+                }
+                s[t] = sm_scale * acc;
+                if (t == 0 || s[t] > mx) mx = s[t];
+            }
+            for (int t = 0; t < T; ++t) { s[t] = exp(s[t] - mx); sum += s[t]; }
+            for (int d = 0; d < D; ++d) o[d] = 0.0;
+            for (int t = 0; t < T; ++t) {
+                int64_t base = (((int64_t)b * T + t) * H + h) * D;
+                uint32_t mt = vmeta[(int64_t)b * T + t];
+                double pt = s[t] / sum;
+                for (int d = 0; d < D; ++d) {
+                    double vv = t < n_packed
+                        ? orc_xhat(vcodes[base + d], (uint16_t)(mt & 0xFFFFu), (uint16_t)(mt >> 16))
+                        : (double)orc_h2f(vx[base + d]);
+                    o[d] += pt * vv;
+                }
+            }
+            free(s);
+        }
+}
+
 /* Number of OpenMP threads the matvec loops will use (1 without OpenMP). */
 #ifdef _OPENMP
 #include <omp.h>

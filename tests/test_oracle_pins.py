@@ -279,6 +279,72 @@ def test_permutation_invariance_of_decode_attention(orc):
     assert np.allclose(o1, o2, rtol=1e-6, atol=1e-9)   # p is rounded to fp32 before the V product
 
 
+def test_attention_on_lossless_grid_matches_torch_attention(orc):
+    """On data that lies on its own quantization grid the codec is lossless, so the oracle's
+    decode attention must equal a library attention on the original fp16 values."""
+    B, T, H, Hq = 2, 192, 2, 4
+    K, _ = _grid_kv(B, T, H, 0.1, 21)
+    V, _ = _grid_kv(B, T, H, 0.2, 22)
+    q = (np.random.default_rng(23).standard_normal((B, Hq, 128)) * 0.3).astype(np.float16)
+    ck, cv = orc.compress(K, 0.1), orc.compress(V, 0.2)
+    out = orc.attention(ck.codes, K, ck.meta, cv.codes, V, cv.meta, T, q, 128 ** -0.5)
+    Kt = torch.from_numpy(np.repeat(K.astype(np.float64), Hq // H, axis=2)).permute(0, 2, 1, 3)
+    Vt = torch.from_numpy(np.repeat(V.astype(np.float64), Hq // H, axis=2)).permute(0, 2, 1, 3)
+    qt = torch.from_numpy(q.astype(np.float64))[:, :, None, :]
+    ref = torch.nn.functional.scaled_dot_product_attention(qt, Kt, Vt)[:, :, 0].numpy()
+    assert np.allclose(out, ref, rtol=1e-10, atol=1e-12)
+
+
+def test_attention_from_bytes_with_raw_tail_and_closed_forms(orc):
+    """(1) brute force: decode the arenas with the independent reader, numpy softmax attention
+    with a raw tail appended; (2) a zero query weighs all tokens equally: the output is the mean
+    of the decoded V rows; (3) a single cached token returns its own V row."""
+    B, T, H, Hq, tail = 1, 128, 2, 4, 19
+    K, V, q = _kv(B, T + 64, H, 31, Hq)
+    K, V = np.ascontiguousarray(K[:, :T + tail]), np.ascontiguousarray(V[:, :T + tail])
+    full = {}
+    for name, x, rel in (("k", K, 0.1), ("v", V, 0.2)):
+        c = orc.compress(np.ascontiguousarray(x[:, :T]), rel)
+        codes = chunk_reader.read_arena(c.arena, c.offsets16, B, T, H)
+        scale = (c.meta & 0xFFFF).astype(np.uint16).view(np.float16).astype(np.float64)
+        mn = (c.meta >> 16).astype(np.uint16).view(np.float16).astype(np.float64)
+        xhat = np.concatenate([codes * scale[:, :, None, None] + mn[:, :, None, None],
+                               x[:, T:].astype(np.float64)], axis=1)
+        cf = np.zeros(x.shape, np.uint8)
+        cf[:, :T] = c.codes
+        mf = np.zeros((B, T + tail), np.uint32)
+        mf[:, :T] = c.meta
+        full[name] = (cf, mf, np.repeat(xhat, Hq // H, axis=2))
+    sm = 128 ** -0.5
+    out = orc.attention(full["k"][0], K, full["k"][1], full["v"][0], V, full["v"][1], T, q, sm)
+    s = sm * np.einsum("bhd,bthd->bht", q.astype(np.float64), full["k"][2])
+    e = np.exp(s - s.max(axis=-1, keepdims=True))
+    ref = np.einsum("bht,bthd->bhd", e / e.sum(axis=-1, keepdims=True), full["v"][2])
+    assert np.allclose(out, ref, rtol=1e-11, atol=1e-13)
+    out0 = orc.attention(full["k"][0], K, full["k"][1], full["v"][0], V, full["v"][1], T,
+                         np.zeros_like(q), sm)
+    assert np.allclose(out0, full["v"][2].mean(axis=1), rtol=1e-12, atol=1e-13)
+    one = orc.attention(None, K[:, :1], None, None, V[:, :1], None, 0, q, sm)
+    assert np.allclose(one, np.repeat(V[:, 0].astype(np.float64), Hq // H, axis=1), rtol=0, atol=0)
+
+
+def test_attention_equals_the_three_step_path(orc):
+    """Att = V-product(softmax(K-product)) with the separately pinned pieces, and a larger
+    softmax scale concentrates the output on the best-scoring token's decoded V row."""
+    B, T, H, Hq = 1, 128, 1, 2
+    K, V, q = _kv(B, T, H, 41, Hq)
+    ck, cv = orc.compress(K, 0.1), orc.compress(V, 0.2)
+    sm = 0.125
+    out = orc.attention(ck.codes, K, ck.meta, cv.codes, V, cv.meta, T, q, sm)
+    s = orc.k_scores(ck.codes, K, ck.meta, T, q, sm)
+    xv = np.repeat(orc.dequant(cv.codes, cv.scale16, cv.min16), Hq // H, axis=2)
+    assert np.allclose(out, np.einsum("bht,bthd->bhd", orc.softmax(s), xv), rtol=1e-12, atol=1e-14)
+    sharp = orc.attention(ck.codes, K, ck.meta, cv.codes, V, cv.meta, T, q, sm * 1e4)
+    best = s.argmax(axis=-1)                       # [B, Hq]
+    for hq in range(Hq):
+        assert np.allclose(sharp[0, hq], xv[0, best[0, hq], hq], rtol=1e-9, atol=1e-9)
+
+
 def test_planted_mistakes_are_caught(orc):
     """The pins above must be able to see typical slips: check that perturbed
     variants of the decoded tensor would violate them."""
