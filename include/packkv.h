@@ -159,6 +159,21 @@ int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores,
  */
 int kv_v_matvec(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
 
+/*
+ * Fused decode attention (the attention of one new query as defined in
+ * Sec. III-B.3, Att(q, K, V) = softmax(sm_scale * K q)^T V, computed with the
+ * fused decompression of Sec. III-C):
+ *   out[b][hq][:] = sum_t softmax_t(sm_scale * q[b][hq] . Khat[b][t][hq / G]) * Vhat[b][t][hq / G][:]
+ * over all cached tokens (packed blocks and raw tail) in one pass: scores and
+ * probabilities stay on chip.  q: device fp16 [B][H_q][128]; out: device fp32
+ * [B][H_q][128].  Equivalent to kv_k_matvec -> softmax -> kv_v_matvec up to
+ * fp32 rounding.  Fixed-order fp32 accumulation, bitwise reproducible.  Uses the
+ * workspace for per-split partial results; calls on one cache must not overlap.
+ * KV_ERR_ARG on an empty cache.  Blocks dropped by an arena overflow are left
+ * out of the softmax.
+ */
+int kv_decode_attention(kv_cache_t *cache, const void *q, float sm_scale, float *out, void *hip_stream);
+
 /* Counters and byte accounting.  Reads device state: synchronizes `hip_stream`. */
 int kv_cache_stats(kv_cache_t *cache, kv_stats_t *out, void *hip_stream);
 

@@ -218,6 +218,14 @@ extern "C" int kv_v_matvec(kv_cache_t *c, const float *p, int64_t ld_p, float *o
     return launch_v_matvec(c, p, ld_p, out, static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale, float *out,
+                                   void *hip_stream) {
+    if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;
+    if (c->packed_tokens + c->tail_tokens < 1) return KV_ERR_ARG;  // softmax over nothing
+    return launch_decode_attention(c, static_cast<const __half *>(q), sm_scale, out,
+                                   static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int kv_cache_stats(kv_cache_t *c, kv_stats_t *out, void *hip_stream) {
     if (!c || !out) return KV_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);

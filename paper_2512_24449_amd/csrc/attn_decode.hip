@@ -1,0 +1,317 @@
+// Fused decode attention over the packed cache: Att(q, K, V) = softmax(sm_scale * K q)^T V
+// (definition in PackKV Sec. III-B.3) in one pass, with the per-chunk K and V work of
+// Sec. III-C.1 / III-C.2 (k_chunk.h, v_chunk.h) and an online softmax in between, so the
+// fp32 scores and probabilities never travel through HBM.
+//
+// A wave walks blocks of one (batch, kv-head) stream.  Per block it unpacks the K chunk
+// into the 64 scores of the block (lane = token), turns them into weights
+// p_t = 2^(s_t - m_ref) against a wave-uniform reference m_ref per head, and feeds the V
+// chunk of the same block with them.  m_ref is only raised when some score exceeds it by
+// more than 8 (in log2 units): then the exact wave maximum becomes the new reference and
+// all running sums are rescaled once.  Weights therefore stay below 2^8, inside the range
+// the fp16 hi/lo split of the V operand represents, and a reference below the true
+// maximum cancels in the final division.  The wave holds one K and one V chunk buffer:
+// the V chunk streams in while K is unpacked, the next K chunk while V is unpacked.
+//
+// The context axis is split over workgroups.  Each wave ends with (m_ref, l = sum p,
+// o[128]) per head; the four waves of a workgroup and then the splits are merged in a
+// fixed order with the usual 2^(m_i - M) factors by attn_combine_kernel, which also
+// handles the raw fp16 tail.  No floating-point atomics: bitwise reproducible.
+#include <algorithm>
+
+#include "k_chunk.h"
+#include "v_chunk.h"
+
+namespace packkv {
+
+constexpr float LOG2E = 1.4426950408889634f;
+constexpr float RAISE_MARGIN = 8.0f;  // log2 units a score may exceed the reference by
+constexpr int A_L = D;                // partial row: [0..127] outputs, [128] sum of weights,
+constexpr int A_M = D + 1;            // [129] reference exponent (log2 units)
+
+struct AArgs {
+    const uint8_t *k_arena, *v_arena;
+    const uint32_t *k_index, *v_index;
+    const uint32_t *k_meta, *v_meta;  // [B][meta_stride]
+    const __half *q;                  // [B][Hq][128]
+    float *partial;                   // [splits][B*Hq][V_PART_STRIDE]
+    int64_t meta_stride;
+    int B, H;
+    int n_blocks;                     // packed blocks per stream
+    int blocks_per_split;
+    float sm_log2;                    // sm_scale * log2(e)
+};
+
+__device__ inline float wave_all_max(float v) {
+    v = fmaxf(v, dpp_f32<DPP_ROW_ROR8>(v));
+    v = fmaxf(v, __shfl_xor(v, 4));
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR2>(v));
+    v = fmaxf(v, dpp_f32<DPP_QUAD_XOR1>(v));
+    v = fmaxf(v, __shfl_xor(v, 16));
+    v = fmaxf(v, __shfl_xor(v, 32));
+    return v;
+}
+
+__device__ inline float wave_all_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    return v;
+}
+
+// 2^(a - b) with the convention that an empty side (a = -inf) weighs nothing.
+__device__ inline float exp2_diff(float a, float b) { return a == -INFINITY ? 0.0f : exp2f(a - b); }
+
+template <int G>
+__global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
+    // per wave: buffer 0 holds the K chunk, buffer 1 the V chunk of the block in flight; after
+    // the main loop the same memory holds the cross-wave reduction array red[4][G][D + 4]
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
+    __shared__ __attribute__((aligned(16))) float sc_all[G == 1 ? 1 : 4][G][N];  // score transposition
+    __shared__ uint4 table[PACK_TABLE_ENTRIES];
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
+    float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
+    build_pack_table(table);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int split = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int h = bh % a.H, b = bh / a.H;
+    const int row = lane >> 4, col = lane & 15;
+    const int kbuf = wave * 2 * CHUNK_LDS, vbuf = kbuf + CHUNK_LDS;
+    const int64_t head0 = int64_t(b) * a.H * G + h * G;
+
+    KQueryFma kq1;
+    KQueryMfma<G == 1 ? 2 : G> kqg;  // the unused form costs nothing
+    float qsum[G];
+    if constexpr (G == 1) {
+        kq1.load(a.q + head0 * D, lane);
+        qsum[0] = kq1.qsum;
+    } else {
+        kqg.load(a.q + head0 * D, lane);
+#pragma unroll
+        for (int g = 0; g < G; ++g) qsum[g] = kqg.qsum[g];
+    }
+    VLane<G> vl;
+    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
+    VState<G> st;
+    st.clear();
+    float m_ref[G], l_lane[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) m_ref[g] = -INFINITY, l_lane[g] = 0.0f;
+
+    const int blk_begin = split * a.blocks_per_split;
+    const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ik, iv;
+        ik.load(a.k_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        iv.load(a.v_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
+        const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + lane;
+        uint32_t kmt_next = a.k_meta[tok0], vmt_next = a.v_meta[tok0];
+        for (int it = 0; it < n_it; ++it) {
+            // a block dropped by an arena overflow (in either tensor) takes no part
+            const bool valid = ik.end16(it) - ik.start16(it) >= uint32_t(HEADER / 16) &&
+                               iv.end16(it) - iv.start16(it) >= uint32_t(HEADER / 16);
+            wait_chunk_landed();  // K chunk of this block
+            const uint32_t kmt = kmt_next, vmt = vmt_next;
+            chunk_issue_lds(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
+            if (it + 1 < n_it) {
+                const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane;
+                kmt_next = a.k_meta[tok];
+                vmt_next = a.v_meta[tok];
+            }
+
+            float s[G];  // scores of token `lane` in log2 units
+            if (valid) {
+                const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
+                LanePacks lp;
+                lp.init(hdr.x, hdr.y, kbuf + HEADER);
+                float u[G];
+                if constexpr (G == 1) {
+                    u[0] = k_chunk_fma(lds_all, table, lp, kq1, lane);
+                } else {
+                    float4_t acc[4];
+                    float ms_row[G];
+                    k_chunk_mfma<G>(lds_all, table, lp, kqg, acc, ms_row);
+                    // lane (r, n) holds four consecutive tokens of heads 4r..4r+3: through LDS to lane = token
+                    float(*sc)[N] = sc_all[wave];
+                    const int tb = k_mfma_token_base(col);
+#pragma unroll
+                    for (int x = 0; x < 4; ++x)
+                        if (4 * row + x < G)
+                            *reinterpret_cast<float4 *>(&sc[4 * row + x][tb]) =
+                                make_float4(acc[0][x], acc[1][x], acc[2][x], acc[3][x]);
+                    wave_lds_fence();
+#pragma unroll
+                    for (int g = 0; g < G; ++g) u[g] = fmaf(sc[g][lane], K_MFMA_OUT_SCALE, ms_row[g]);
+                    wave_lds_fence();
+                }
+                const float kscale = __half2float(__ushort_as_half(uint16_t(kmt & 0xFFFFu)));
+                const float kmn = __half2float(__ushort_as_half(uint16_t(kmt >> 16)));
+#pragma unroll
+                for (int g = 0; g < G; ++g) s[g] = a.sm_log2 * fmaf(kscale, u[g], kmn * qsum[g]);
+
+                // raise the reference only when a score runs away from it
+                bool raise = false;
+#pragma unroll
+                for (int g = 0; g < G; ++g) raise |= s[g] > m_ref[g] + RAISE_MARGIN;
+                if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+                    float alpha_col = 1.0f;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const float m_new = fmaxf(m_ref[g], wave_all_max(s[g]));
+                        const float alpha = exp2_diff(m_ref[g], m_new);
+                        m_ref[g] = m_new;
+                        l_lane[g] *= alpha;
+                        st.pm[g] *= alpha;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) st.macc[g][j] *= alpha;
+                        if ((col >> 1) == g) alpha_col = alpha;
+                    }
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha_col;
+                }
+            }
+            wait_chunk_landed();  // V chunk of this block
+            if (it + 1 < n_it)
+                chunk_issue_lds(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
+            if (!valid) continue;
+            float pt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                pt[g] = exp2f(s[g] - m_ref[g]);
+                l_lane[g] += pt[g];
+            }
+            v_chunk<G>(lds_all, vbuf, table, vl, vmt, pt, st);
+        }
+        wait_chunk_landed();
+    }
+    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
+
+    v_state_store<G>(st, red[wave], lane);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float l = wave_all_sum(l_lane[g]);
+        if (lane == 0) {
+            red[wave][g][D + 1] = l;
+            red[wave][g][D + 2] = m_ref[g];
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
+        const int g = i / (D + 1), d = i % (D + 1);
+        const float m0 = red[0][g][D + 2], m1 = red[1][g][D + 2], m2 = red[2][g][D + 2], m3 = red[3][g][D + 2];
+        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+        const float f0 = exp2_diff(m0, M), f1 = exp2_diff(m1, M), f2 = exp2_diff(m2, M), f3 = exp2_diff(m3, M);
+        float *dst = a.partial + (int64_t(split) * a.B * a.H * G + head0 + g) * V_PART_STRIDE;
+        if (d < D) {
+            // outputs carry the per-head sum p*min term
+            dst[d] = (f0 * (red[0][g][d] + red[0][g][D]) + f1 * (red[1][g][d] + red[1][g][D])) +
+                     (f2 * (red[2][g][d] + red[2][g][D]) + f3 * (red[3][g][d] + red[3][g][D]));
+        } else {
+            dst[A_L] = (f0 * red[0][g][D + 1] + f1 * red[1][g][D + 1]) +
+                       (f2 * red[2][g][D + 1] + f3 * red[3][g][D + 1]);
+            dst[A_M] = M;
+        }
+    }
+}
+
+// Merges the splits of one (batch, query head) row in a fixed order and adds the raw fp16
+// tail tokens (Sec. III-B.1 buffer), whose scores are plain dot products.
+__global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ partial,
+                                                           int n_splits, int n_rows,
+                                                           const __half *__restrict__ q,
+                                                           const __half *__restrict__ k_tail,
+                                                           const __half *__restrict__ v_tail,
+                                                           int n_tail, int tail_cap, int H, int G,
+                                                           float sm_log2, float *__restrict__ out) {
+    __shared__ float ms[V_SPLITS_MAX];  // split references, then split factors
+    __shared__ float st[N];             // tail scores, then tail weights
+    const int r = blockIdx.x;           // b*Hq + hq
+    const int hq = r % (H * G), b = r / (H * G);
+    const int h = hq / G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    for (int t = wave; t < n_tail; t += 4) {
+        const __half *krow = k_tail + ((int64_t(b) * tail_cap + t) * H + h) * D;
+        const __half2 kk = *reinterpret_cast<const __half2 *>(krow + 2 * lane);
+        const __half2 qq = *reinterpret_cast<const __half2 *>(q + int64_t(r) * D + 2 * lane);
+        float s = __half2float(__low2half(kk)) * __half2float(__low2half(qq));
+        s = fmaf(__half2float(__high2half(kk)), __half2float(__high2half(qq)), s);
+        s = wave_all_sum(s);
+        if (lane == 0) st[t] = sm_log2 * s;
+    }
+    if (int(threadIdx.x) < n_splits)
+        ms[threadIdx.x] = partial[(int64_t(threadIdx.x) * n_rows + r) * V_PART_STRIDE + A_M];
+    __syncthreads();
+    float M = -INFINITY;
+    for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ms[s]);
+    for (int t = 0; t < n_tail; ++t) M = fmaxf(M, st[t]);
+    __syncthreads();
+    if (int(threadIdx.x) < n_splits) ms[threadIdx.x] = exp2_diff(ms[threadIdx.x], M);
+    if (threadIdx.x >= 64 && int(threadIdx.x) - 64 < n_tail) st[threadIdx.x - 64] = exp2f(st[threadIdx.x - 64] - M);
+    __syncthreads();
+    const int d = threadIdx.x;
+    if (d >= D) return;
+    float o = 0.0f, l = 0.0f;
+#pragma unroll 8
+    for (int s = 0; s < n_splits; ++s) {
+        const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
+        o = fmaf(ms[s], src[d], o);
+        l = fmaf(ms[s], src[A_L], l);
+    }
+    for (int t = 0; t < n_tail; ++t) {
+        const float v = __half2float(v_tail[((int64_t(b) * tail_cap + t) * H + h) * D + d]);
+        o = fmaf(st[t], v, o);
+        l += st[t];
+    }
+    out[int64_t(r) * D + d] = l > 0.0f ? o / l : 0.0f;  // every block dropped and no tail: defined output
+}
+
+int v_splits_for(int n_blocks, int streams);
+
+int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, float *out, hipStream_t s) {
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group;
+    const int n_blocks = int(c->packed_tokens / N);
+    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
+    float *partial = reinterpret_cast<float *>(ws + WS_VPART);
+    const float sm_log2 = sm_scale * LOG2E;
+    int n_splits = 0;
+    if (n_blocks > 0) {
+        n_splits = v_splits_for(n_blocks, B * H);
+        AArgs a;
+        a.k_arena = static_cast<const uint8_t *>(c->buf.k_arena);
+        a.v_arena = static_cast<const uint8_t *>(c->buf.v_arena);
+        a.k_index = static_cast<const uint32_t *>(c->buf.k_index);
+        a.v_index = static_cast<const uint32_t *>(c->buf.v_index);
+        a.k_meta = static_cast<const uint32_t *>(c->buf.k_token_meta);
+        a.v_meta = static_cast<const uint32_t *>(c->buf.v_token_meta);
+        a.q = q;
+        a.partial = partial;
+        a.meta_stride = c->max_tokens;
+        a.B = B;
+        a.H = H;
+        a.n_blocks = n_blocks;
+        a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
+        a.sm_log2 = sm_log2;
+        n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
+        dim3 grid(n_splits, B * H);
+        switch (G) {
+            case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), 0, s, a); break;
+            case 2: hipLaunchKernelGGL(attn_kernel<2>, grid, dim3(256), 0, s, a); break;
+            case 4: hipLaunchKernelGGL(attn_kernel<4>, grid, dim3(256), 0, s, a); break;
+            case 8: hipLaunchKernelGGL(attn_kernel<8>, grid, dim3(256), 0, s, a); break;
+            default: return KV_ERR_UNSUPPORTED;
+        }
+    }
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
+                       B * H * G, q, static_cast<const __half *>(c->buf.k_tail),
+                       static_cast<const __half *>(c->buf.v_tail), c->tail_tokens,
+                       c->cfg.tail_capacity, H, G, sm_log2, out);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+}  // namespace packkv

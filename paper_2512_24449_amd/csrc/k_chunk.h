@@ -1,0 +1,178 @@
+// Per-chunk K work shared by the K kernel and the fused decode-attention kernel
+// (PackKV Sec. III-C.1): q . code sums of the 64 tokens of one chunk that sits in
+// an LDS buffer, for the G query heads of its kv-head.  De-quantization is folded
+// by the callers:
+//   score_t = sm_scale * (scale_t * (sum_d q_d code[t,d] + sum_d q_d m[g,d]) + min_t * sum_d q_d)
+//
+// Two forms.  With one query head per kv-head, mixed-precision FMAs read the
+// unpacked fp16 code halves directly and a reduce-scatter inside the 16-lane row
+// leaves token 16g+i in lane 16g+i.  With grouped queries the tile is turned on
+// the matrix cores so that one unpack serves all G heads:
+//   C1[channel i][column n] = sum_k A1[i][k] S_x[k][n]         (16x16x32 fp16 MFMA)
+//     A1: the unpacked words of pack slot j (row i = lane%16 = channel 8i+j, the
+//         32 k-slots = 8 tokens of each token group lane/16), S_x: selects the
+//         16 k-slots with bit 1 of the in-lane slot equal to x, times 2^10
+//   C2[head][column n] += sum_k Q[head][k] cvt16(C1)[k][n]      (16x16x32 fp16 MFMA)
+//     the fp32 tile C1 of lane (r, n) holds channels 4r..4r+3 of column n, which is
+//     exactly the k-run a B operand lane needs; two pack slots fill its 8 k-values.
+// Every value in C1 is an integer code times 2^-14, so its fp16 conversion is
+// exact.  With the k-slot -> column assignment below, lane n (< 16) ends up with
+// four consecutive tokens of the block, 16*(n>>2) + 4*((n>>1)&1) + 8*(n&1) + {0..3},
+// in the four accumulators, for the heads 4*(lane/16)..+3 in their four registers.
+#pragma once
+
+#include "unpack.h"
+
+namespace packkv {
+
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef float float4_u __attribute__((ext_vector_type(4), aligned(4)));
+
+// ---- one query head per kv-head ------------------------------------------------
+struct KQueryFma {
+    float qf[8];  // q of this lane's 8 channels
+    float qsum;   // sum of all 128 q values
+
+    // q_head: the 128 fp16 values of the query head
+    __device__ inline void load(const __half *q_head, int lane) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(q_head + 8 * (lane & 15));
+        const __half *hq = reinterpret_cast<const __half *>(&raw);
+        float s = 0.0f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            qf[j] = __half2float(hq[j]);
+            s += qf[j];
+        }
+        qsum = row_all_reduce16(s);
+    }
+};
+
+// Returns, in lane l, sum_d q_d (code[l, d] + m[l / 16, d]) for token l of the chunk whose
+// header has been parsed into `lp`.
+__device__ inline float k_chunk_fma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
+                                    const KQueryFma &kq, int lane) {
+    float acc[16], msum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        uint32_t P[8];
+        const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
+        expand_pack(raw, P);
+        msum = fmaf(kq.qf[j], __uint_as_float(raw.k.w), msum);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            // P[k] holds tokens (k, k+8) of the group
+            acc[k] = fmaf(kq.qf[j], half_lo(P[k]), acc[k]);
+            acc[k + 8] = fmaf(kq.qf[j], half_hi(P[k]), acc[k + 8]);
+        }
+    }
+    return row_reduce_scatter16(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
+}
+
+// ---- grouped queries -------------------------------------------------------------
+constexpr float K_MFMA_OUT_SCALE = 16384.0f;  // codes enter as code * 2^-24, the selection adds 2^10
+
+// Token offset inside a block of the first of the four consecutive tokens that lane%16 = n
+// holds after k_chunk_mfma.
+__device__ inline int k_mfma_token_base(int n) { return 16 * (n >> 2) + 4 * ((n >> 1) & 1) + 8 * (n & 1); }
+
+template <int G>
+struct KQueryMfma {
+    uint32_t qh[G][4];  // q of this lane's 8 channels as fp16 pairs (pack-minimum term)
+    float qsum[G];      // sum of all 128 q values per head
+    half8 qA[4];        // Q operand per pair of pack slots
+    half8 sel[2];       // selection operands S_0, S_1
+
+    // q_group: the G query heads of the kv-head, [G][128] fp16
+    __device__ inline void load(const __half *q_group, int lane) {
+        const int row = lane >> 4, col = lane & 15;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(q_group + g * D + 8 * col);
+            qh[g][0] = raw.x, qh[g][1] = raw.y, qh[g][2] = raw.z, qh[g][3] = raw.w;
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s += half_lo(qh[g][k]) + half_hi(qh[g][k]);
+            qsum[g] = row_all_reduce16(s);
+        }
+        // row = head lane%16, k-value e of k-run lane/16 = channel 8*(4*(lane/16) + (e&3)) + 2jp + (e>>2)
+        uint32_t rw[4][4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            uint4 raw = make_uint4(0, 0, 0, 0);
+            if (col < G) raw = *reinterpret_cast<const uint4 *>(q_group + col * D + 8 * (4 * row + e));
+            rw[e][0] = raw.x, rw[e][1] = raw.y, rw[e][2] = raw.z, rw[e][3] = raw.w;
+        }
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+            const uint32_t w0 = __builtin_amdgcn_perm(rw[1][jp], rw[0][jp], 0x05040100u);
+            const uint32_t w1 = __builtin_amdgcn_perm(rw[3][jp], rw[2][jp], 0x05040100u);
+            const uint32_t w2 = __builtin_amdgcn_perm(rw[1][jp], rw[0][jp], 0x07060302u);
+            const uint32_t w3 = __builtin_amdgcn_perm(rw[3][jp], rw[2][jp], 0x07060302u);
+            qA[jp] = __builtin_bit_cast(half8, u32x4{w0, w1, w2, w3});
+        }
+        // lane (k-run kg = lane/16, column n = lane%16) holds S_x[8kg+e][n]; slot e of run kg
+        // goes to column 4kg + 2(e>>2) + (e&1) when ((e>>1)&1) == x
+#pragma unroll
+        for (int x = 0; x < 2; ++x) {
+            uint32_t wsel[4] = {0, 0, 0, 0};
+            const int e = ((col >> 1) & 1) * 4 + x * 2 + (col & 1);
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if ((col >> 2) == row && (e >> 1) == k) wsel[k] = 0x6400u << (16 * (e & 1));  // fp16 1024
+            sel[x] = __builtin_bit_cast(half8, u32x4{wsel[0], wsel[1], wsel[2], wsel[3]});
+        }
+    }
+};
+
+// acc[t][x] (lane (r, n)): sum_d q[head 4r+x][d] code[token, d] / K_MFMA_OUT_SCALE for token
+// k_mfma_token_base(n) + t; ms_row[g] (every lane of row r): sum_d q[g][d] m[group r, d].
+template <int G>
+__device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
+                                    const KQueryMfma<G> &kq, float4_t (&acc)[4], float (&ms_row)[G]) {
+    const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+    for (int t = 0; t < 4; ++t) acc[t] = zero;
+    float msum[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) msum[g] = 0.0f;
+#pragma unroll
+    for (int jp = 0; jp < 4; ++jp) {
+        float4_t c1[2][4];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = 2 * jp + jj;
+            uint32_t P[8];
+            const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
+            expand_pack(raw, P);
+            const float m = __uint_as_float(raw.k.w);
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                msum[g] = fmaf(jj ? half_hi(kq.qh[g][jp]) : half_lo(kq.qh[g][jp]), m, msum[g]);
+            // P[t + 2i]: tokens (t + 2i, t + 2i + 8); column token offset t = parity + 2x
+            const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[2], P[4], P[6]});
+            const half8 a1 = __builtin_bit_cast(half8, u32x4{P[1], P[3], P[5], P[7]});
+            c1[jj][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, kq.sel[0], zero, 0, 0, 0);
+            c1[jj][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, kq.sel[0], zero, 0, 0, 0);
+            c1[jj][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, kq.sel[1], zero, 0, 0, 0);
+            c1[jj][3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, kq.sel[1], zero, 0, 0, 0);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const u32x4 bw = {
+                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][0], c1[0][t][1])),
+                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][2], c1[0][t][3])),
+                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][0], c1[1][t][1])),
+                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][2], c1[1][t][3]))};
+            acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kq.qA[jp], __builtin_bit_cast(half8, bw),
+                                                             acc[t], 0, 0, 0);
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) ms_row[g] = row_all_reduce16(msum[g]);
+}
+
+}  // namespace packkv

@@ -18,12 +18,9 @@
 //   out_d = sum_t w_t code[t,d] + sum_g m[g,d] sum_{t in g} w_t + sum_t p_t min_t
 #include <algorithm>
 
-#include "unpack.h"
+#include "v_chunk.h"
 
 namespace packkv {
-
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
-typedef float float4_t __attribute__((ext_vector_type(4)));
 
 struct VArgs {
     const uint8_t *arena;
@@ -36,15 +33,6 @@ struct VArgs {
     int B, H;
     int n_blocks;           // packed blocks per stream
     int blocks_per_split;
-};
-
-// B operand staging per wave: [token group][half][column < 2G][8 fp16], then 16 zero
-// bytes that the lanes of the unused columns (>= 2G) read instead.
-template <int G>
-struct BLds {
-    static constexpr int COLS = 2 * G;
-    static constexpr int ZERO = 4 * 2 * COLS * 16;
-    static constexpr int BYTES = ZERO + 16;
 };
 
 template <int G>
@@ -64,29 +52,10 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
     const int buf_base = wave * 2 * CHUNK_LDS;
-    uint8_t *blds = blds_all + wave * BLds<G>::BYTES;
-    const int row = lane >> 4, col = lane & 15;
-
-    constexpr int COLS = BLds<G>::COLS;
-    if (lane < 4) reinterpret_cast<uint32_t *>(blds + BLds<G>::ZERO)[lane] = 0;
-
-    // where this lane's own token (16*row + col) sits in the B operand (column 0)
-    const int tm = col & 7;
-    const int bslot = (((row * 2 + (tm >> 2)) * COLS) * 8 + 2 * (tm & 3) + (col >> 3)) * 2;
-    // where this lane reads its B operand halves from
-    const int bread0 = col < COLS ? ((row * 2 + 0) * COLS + col) * 16 : BLds<G>::ZERO;
-    const int bread1 = col < COLS ? ((row * 2 + 1) * COLS + col) * 16 : BLds<G>::ZERO;
-
-    float4_t acc[8];
-#pragma unroll
-    for (int j = 0; j < 8; ++j) acc[j] = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
-    float macc[G][8], pm[G];
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-        pm[g] = 0.0f;
-#pragma unroll
-        for (int j = 0; j < 8; ++j) macc[g][j] = 0.0f;
-    }
+    VLane<G> vl;
+    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
+    VState<G> st;
+    st.clear();
 
     const int blk_begin = split * a.blocks_per_split;
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
@@ -118,83 +87,13 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
                 for (int g = 0; g < G; ++g) p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
             }
             if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
-
-            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
-            float wsum[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float w = pt[g] * scale;
-                pm[g] = fmaf(pt[g], mn, pm[g]);
-                // w = hi + lo with both parts fp16 (lo scaled by 2^11); truncation keeps lo >= 0
-                const _Float16 hi = __builtin_bit_cast(
-                    _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
-                const float lo = (w - float(hi)) * 2048.0f;
-                const _Float16 lo16 = __builtin_bit_cast(
-                    _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
-                *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g) * 16) = hi;
-                *reinterpret_cast<_Float16 *>(blds + bslot + (2 * g + 1) * 16) = lo16;
-                wsum[g] = row_all_reduce16(w);
-            }
-            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + cur + lane * 8);
-            LanePacks lp;
-            lp.init(hdr.x, hdr.y, cur + HEADER);
-            wave_lds_fence();
-
-            const half8 b0 = *reinterpret_cast<const half8 *>(blds + bread0);
-            const half8 b1 = *reinterpret_cast<const half8 *>(blds + bread1);
-            PackRaw raw_next = fetch_pack(lds_all, table, lp.pos(0), lp.header_byte(0));
-#pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                uint32_t P[8];
-                const PackRaw raw = raw_next;
-                // LDS reads run exactly one pack ahead of their use (the scheduling barrier keeps
-                // the compiler from hoisting all eight fetches and blowing up register use)
-                if (j < 7) raw_next = fetch_pack(lds_all, table, lp.pos(j + 1), lp.header_byte(j + 1));
-                __builtin_amdgcn_sched_barrier(0);
-                expand_pack(raw, P);
-                const float m = __uint_as_float(raw.k.w);
-#pragma unroll
-                for (int g = 0; g < G; ++g) macc[g][j] = fmaf(m, wsum[g], macc[g][j]);
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[1], P[2], P[3]});
-                const half8 a1 = __builtin_bit_cast(half8, u32x4{P[4], P[5], P[6], P[7]});
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, b0, acc[j], 0, 0, 0);
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, b1, acc[j], 0, 0, 0);
-            }
-            wave_lds_fence();  // the B operand is rewritten by the next chunk
+            v_chunk<G>(lds_all, cur, table, vl, mt, pt, st);
         }
         wait_chunk_landed();
     }
     __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
 
-    // ---- combine: MFMA tiles (lane = column `col`, rows 4*row+r), the pack-minimum
-    // term (lane = token group `row`, channels 8*col+j), the four waves ----
-    const int head = col >> 1;
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float v = acc[j][r] * ((col & 1) ? CODE_SCALE / 2048.0f : CODE_SCALE);
-            v += dpp_f32<DPP_QUAD_XOR1>(v);  // hi column + lo column
-            if (!(col & 1) && head < G) red[wave][head][8 * (4 * row + r) + j] = v;
-        }
-    }
-    wave_lds_fence();
-#pragma unroll
-    for (int g = 0; g < G; ++g) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float v = macc[g][j];
-            v += __shfl_xor(v, 16);
-            v += __shfl_xor(v, 32);
-            if (lane < 16) red[wave][g][8 * lane + j] += v;
-        }
-        float s = pm[g];
-#pragma unroll
-        for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
-        if (lane == 0) red[wave][g][D] = s;
-    }
+    v_state_store<G>(st, red[wave], lane);
     __syncthreads();
     for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
         const int g = i / (D + 1), d = i % (D + 1);

@@ -114,10 +114,17 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     o_e2e = oracle.v_out(vcodes, Vn, vmeta, n_packed, p64.astype(np.float32))
     assert_close_vectors(out.cpu().numpy(), o_e2e, "decode step end to end", tol=2e-3)
 
+    # fused decode attention against the oracle's definition of Att(q, K, V)
+    attn = cache.kv_decode_attention(qd, sm_scale)
+    torch.cuda.synchronize()
+    a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
+    assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
+
     # determinism: a second pass gives the same bits
     scores2 = cache.kv_k_matvec(qd, sm_scale)
     out2 = cache.kv_v_matvec(p)
+    attn2 = cache.kv_decode_attention(qd, sm_scale)
     torch.cuda.synchronize()
-    assert torch.equal(scores, scores2) and torch.equal(out, out2)
+    assert torch.equal(scores, scores2) and torch.equal(out, out2) and torch.equal(attn, attn2)
     cache.close()
     return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)
