@@ -68,10 +68,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
     __shared__ __attribute__((aligned(16))) float sc_all[G == 1 ? 1 : 4][G][N];  // score transposition
-    __shared__ uint4 table[PACK_TABLE_ENTRIES];
+    __shared__ uint4 table[PACK_TABLE_ENTRIES], vtable[PACK_TABLE_ENTRIES];  // K form, V form (lifted codes)
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
     build_pack_table(table);
+    build_pack_table(vtable, CODE_LIFT);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                 pt[g] = exp2f(s[g] - m_ref[g]);
                 l_lane[g] += pt[g];
             }
-            v_chunk<G>(lds_all, vbuf, table, vl, vmt, pt, st);
+            v_chunk<G>(lds_all, vbuf, vtable, vl, vmt, pt, st);
         }
         wait_chunk_landed();
     }

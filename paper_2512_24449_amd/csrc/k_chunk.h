@@ -141,32 +141,31 @@ __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, con
     for (int g = 0; g < G; ++g) msum[g] = 0.0f;
 #pragma unroll
     for (int jp = 0; jp < 4; ++jp) {
-        float4_t c1[2][4];
+        uint32_t P[2][8];
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int j = 2 * jp + jj;
-            uint32_t P[8];
             const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-            expand_pack(raw, P);
+            expand_pack(raw, P[jj]);
             const float m = __uint_as_float(raw.k.w);
 #pragma unroll
             for (int g = 0; g < G; ++g)
                 msum[g] = fmaf(jj ? half_hi(kq.qh[g][jp]) : half_lo(kq.qh[g][jp]), m, msum[g]);
-            // P[t + 2i]: tokens (t + 2i, t + 2i + 8); column token offset t = parity + 2x
-            const half8 a0 = __builtin_bit_cast(half8, u32x4{P[0], P[2], P[4], P[6]});
-            const half8 a1 = __builtin_bit_cast(half8, u32x4{P[1], P[3], P[5], P[7]});
-            c1[jj][0] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, kq.sel[0], zero, 0, 0, 0);
-            c1[jj][1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, kq.sel[0], zero, 0, 0, 0);
-            c1[jj][2] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a0, kq.sel[1], zero, 0, 0, 0);
-            c1[jj][3] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a1, kq.sel[1], zero, 0, 0, 0);
         }
+        // P[jj][t + 2i]: tokens (t + 2i, t + 2i + 8) of pack slot 2jp+jj; column token offset
+        // t = parity + 2x
+        const half8 a00 = __builtin_bit_cast(half8, u32x4{P[0][0], P[0][2], P[0][4], P[0][6]});
+        const half8 a01 = __builtin_bit_cast(half8, u32x4{P[0][1], P[0][3], P[0][5], P[0][7]});
+        const half8 a10 = __builtin_bit_cast(half8, u32x4{P[1][0], P[1][2], P[1][4], P[1][6]});
+        const half8 a11 = __builtin_bit_cast(half8, u32x4{P[1][1], P[1][3], P[1][5], P[1][7]});
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
-            const u32x4 bw = {
-                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][0], c1[0][t][1])),
-                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[0][t][2], c1[0][t][3])),
-                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][0], c1[1][t][1])),
-                __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(c1[1][t][2], c1[1][t][3]))};
+            const float4_t ca = __builtin_amdgcn_mfma_f32_16x16x32_f16((t & 1) ? a01 : a00, kq.sel[t >> 1], zero, 0, 0, 0);
+            const float4_t cb = __builtin_amdgcn_mfma_f32_16x16x32_f16((t & 1) ? a11 : a10, kq.sel[t >> 1], zero, 0, 0, 0);
+            const u32x4 bw = {__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ca[0], ca[1])),
+                              __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(ca[2], ca[3])),
+                              __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(cb[0], cb[1])),
+                              __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(cb[2], cb[3]))};
             acc[t] = __builtin_amdgcn_mfma_f32_16x16x32_f16(kq.qA[jp], __builtin_bit_cast(half8, bw),
                                                              acc[t], 0, 0, 0);
         }

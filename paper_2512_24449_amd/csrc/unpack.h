@@ -24,6 +24,13 @@ namespace packkv {
 // A pack read may touch up to 12 bytes past the end of a chunk buffer.
 constexpr int LDS_TAIL_PAD = 16;
 constexpr float CODE_SCALE = 16777216.0f;  // 2^24: fp16 subnormal unit^-1
+// The matrix cores align the products of one instruction to the largest nominal exponent
+// and keep about 24 bits below it.  A code in the lowest bits of a subnormal leaves up to
+// ten leading zeros in its significand, so products of tokens whose weights differ by 2^8
+// or more were measured to lose bits from 2^-17 on.  The V path therefore places each code
+// six bits higher (still subnormal for codes up to 15): value code * 2^-18.
+constexpr int CODE_LIFT = 6;
+constexpr float CODE_SCALE_LIFTED = 262144.0f;  // 2^18
 
 // DPP controls (wave64, rows of 16 lanes).
 constexpr int DPP_QUAD_XOR1 = 0xB1;  // quad_perm [1,0,3,2]
@@ -62,12 +69,13 @@ __device__ inline int wave_inclusive_scan(int v) {
 // the table, which on this hardware reads other LDS contents or zero, never faults.
 constexpr int PACK_TABLE_ENTRIES = 80;
 
-// Built once per workgroup, followed by a workgroup barrier.
-__device__ inline void build_pack_table(uint4 *table) {
+// Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
+// inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).
+__device__ inline void build_pack_table(uint4 *table, int lift = 0) {
     const uint32_t hb = threadIdx.x;
     if (hb < PACK_TABLE_ENTRIES) {
         const uint32_t w = hb >> 4;
-        const uint32_t m1 = (1u << w) - 1u;
+        const uint32_t m1 = ((1u << w) - 1u) << lift;
         table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w, __float_as_uint(float(hb & 15u)));
     }
     __syncthreads();
@@ -186,7 +194,9 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
 }
 
 // Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
-// 16-bit half is the bit pattern of fp16(code * 2^-24).
+// 16-bit half is the bit pattern of fp16(code * 2^(LIFT-24)); the table must have been
+// built with the same lift.
+template <int LIFT = 0>
 __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
     const uint32_t A = __builtin_amdgcn_alignbit(r.d1, r.d0, r.sh);    // pack bits [0, 32): tokens 0..7
     const uint32_t hi_ = __builtin_amdgcn_alignbit(r.d2, r.d1, r.sh);  // pack bits [32, 64)
@@ -195,6 +205,10 @@ __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
     const uint32_t s = 4 * w;
     uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // tokens 0..3 | 8..11
     uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, 0x05040100u);  // tokens 4..7 | 12..15
+    if (LIFT) {  // rotate left: the codes of both halves move up together, the mask picks them there
+        Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - LIFT);
+        Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - LIFT);
+    }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
         P[m] = Z0 & M;

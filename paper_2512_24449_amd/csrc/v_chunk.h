@@ -75,7 +75,8 @@ struct VState {
 };
 
 // Adds the chunk in the LDS buffer at byte offset `cur` of lds_all: lane l is token l of the
-// block with weight pt[g] for head g and token metadata mt (scale | min << 16).
+// block with weight pt[g] for head g and token metadata mt (scale | min << 16).  `table` must
+// have been built with lift CODE_LIFT.
 template <int G>
 __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *table, const VLane<G> &vl,
                                uint32_t mt, const float (&pt)[G], VState<G> &st) {
@@ -112,7 +113,7 @@ __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *tab
         // the compiler from hoisting all eight fetches and blowing up register use)
         if (j < 7) raw_next = fetch_pack(lds_all, table, lp.pos(j + 1), lp.header_byte(j + 1));
         __builtin_amdgcn_sched_barrier(0);
-        expand_pack(raw, P);
+        expand_pack<CODE_LIFT>(raw, P);
         const float m = __uint_as_float(raw.k.w);
 #pragma unroll
         for (int g = 0; g < G; ++g) st.macc[g][j] = fmaf(m, wsum[g], st.macc[g][j]);
@@ -134,7 +135,7 @@ __device__ inline void v_state_store(const VState<G> &st, float (*red)[D + 4], i
     for (int j = 0; j < 8; ++j) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float v = st.acc[j][r] * ((col & 1) ? CODE_SCALE / 2048.0f : CODE_SCALE);
+            float v = st.acc[j][r] * ((col & 1) ? CODE_SCALE_LIFTED / 2048.0f : CODE_SCALE_LIFTED);
             v += dpp_f32<DPP_QUAD_XOR1>(v);  // hi column + lo column
             if (!(col & 1) && head < G) red[head][8 * (4 * row + r) + j] = v;
         }

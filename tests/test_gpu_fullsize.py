@@ -13,7 +13,7 @@ from tests.gpu_cases import assert_close_vectors
 pytestmark = pytest.mark.gpu
 
 
-def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed):
+def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, attn=None):
     """Oracle over batch element b (all heads, all tokens) against the GPU state and outputs."""
     B, L, H, _ = K.shape
     Kb = K[b:b + 1].cpu().numpy()
@@ -46,6 +46,10 @@ def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed):
     pb = p[b:b + 1].cpu().numpy()
     o_ref = oracle.v_out(codes["v"][0], Vb, codes["v"][1], n_packed, pb)
     assert_close_vectors(out[b:b + 1].cpu().numpy(), o_ref, "V out, batch %d" % b)
+    if attn is not None:
+        a_ref = oracle.attention(codes["k"][0], Kb, codes["k"][1], codes["v"][0], Vb, codes["v"][1],
+                                 n_packed, qb, sm_scale)
+        assert_close_vectors(attn[b:b + 1].cpu().numpy(), a_ref, "fused decode attention, batch %d" % b)
 
 
 @pytest.mark.parametrize("index,batch_elements", [(3, [7]), (2, [0, 3])])
@@ -60,9 +64,13 @@ def test_full_size_configuration(index, batch_elements):
     scores = cache.kv_k_matvec(q, sm_scale)
     p = synth.make_probs(scores)
     out = cache.kv_v_matvec(p)
+    attn = cache.kv_decode_attention(q, sm_scale)
     torch.cuda.synchronize()
     # properties that hold for every element, checked everywhere
-    assert torch.isfinite(scores).all() and torch.isfinite(out).all()
+    assert torch.isfinite(scores).all() and torch.isfinite(out).all() and torch.isfinite(attn).all()
+    # the fused pass and the three-step path agree on every output (p here is a softmax of the scores)
+    assert_close_vectors(attn.cpu().numpy(), out.cpu().numpy().astype(np.float64), "fused vs three-step",
+                         tol=2e-3)
     st = cache.kv_cache_stats()
     n_chunks = L // 64 * w.batch * w.n_kv_heads
     assert st.n_chunks == n_chunks and st.overflow == 0
@@ -70,7 +78,7 @@ def test_full_size_configuration(index, batch_elements):
     sizes = (index_t[1:] - index_t[:-1]) * 16
     assert int(sizes.min()) >= 512 and int(sizes.max()) <= binding.CHUNK_MAX_BYTES
     for b in batch_elements:
-        _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64)
+        _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, attn)
     cache.close()
 
 
@@ -92,8 +100,10 @@ def test_growing_cache_decode_steps():
         p = torch.softmax(scores[:, :, :n], dim=-1)
         out = cache.kv_v_matvec(p)
         if i in (36, steps - 1):
+            attn = cache.kv_decode_attention(q, sm_scale)
             torch.cuda.synchronize()
             assert cache.tokens == n
-            _check_batch_element(cache, K[:, :n], V[:, :n], q, scores, p, out, 0, sm_scale, n // 64 * 64)
+            _check_batch_element(cache, K[:, :n], V[:, :n], q, scores, p, out, 0, sm_scale, n // 64 * 64,
+                                 attn)
     assert cache.kv_cache_stats().tail_tokens == (L0 + steps) % 64
     cache.close()
