@@ -112,7 +112,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     # end to end against an fp64 softmax of the oracle's own scores
     p64 = oracle.softmax(s_ref)
     o_e2e = oracle.v_out(vcodes, Vn, vmeta, n_packed, p64.astype(np.float32))
-    assert_close_vectors(out.cpu().numpy(), o_e2e, "decode step end to end", tol=2e-3)
+    assert_close_vectors(out.cpu().numpy(), o_e2e, "decode step end to end")
 
     # fused decode attention against the oracle's definition of Att(q, K, V)
     attn = cache.kv_decode_attention(qd, sm_scale)
