@@ -229,20 +229,31 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
                                                            const __half *__restrict__ v_tail,
                                                            int n_tail, int tail_cap, int H, int G,
                                                            float sm_log2, float *__restrict__ out) {
+    __shared__ float st[N];             // tail scores (log2 units), then tail weights
     __shared__ float ms[V_SPLITS_MAX];  // split references, then split factors
-    __shared__ float st[N];             // tail scores, then tail weights
     const int r = blockIdx.x;           // b*Hq + hq
     const int hq = r % (H * G), b = r / (H * G);
     const int h = hq / G;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int t = wave; t < n_tail; t += 4) {
-        const __half *krow = k_tail + ((int64_t(b) * tail_cap + t) * H + h) * D;
-        const __half2 kk = *reinterpret_cast<const __half2 *>(krow + 2 * lane);
-        const __half2 qq = *reinterpret_cast<const __half2 *>(q + int64_t(r) * D + 2 * lane);
-        float s = __half2float(__low2half(kk)) * __half2float(__low2half(qq));
-        s = fmaf(__half2float(__high2half(kk)), __half2float(__high2half(qq)), s);
-        s = wave_all_sum(s);
-        if (lane == 0) st[t] = sm_log2 * s;
+    // tail scores: thread (t, seg) takes 32 channels of tail token t, four threads per token
+    {
+        const int t = threadIdx.x >> 2, seg = threadIdx.x & 3;
+        float s = 0.0f;
+        if (t < n_tail) {
+            const __half *krow = k_tail + ((int64_t(b) * tail_cap + t) * H + h) * D + 32 * seg;
+            const __half *qrow = q + int64_t(r) * D + 32 * seg;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const uint4 kr = *reinterpret_cast<const uint4 *>(krow + 8 * c);
+                const uint4 qr = *reinterpret_cast<const uint4 *>(qrow + 8 * c);
+                const __half *kk = reinterpret_cast<const __half *>(&kr);
+                const __half *qq = reinterpret_cast<const __half *>(&qr);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s = fmaf(__half2float(kk[e]), __half2float(qq[e]), s);
+            }
+        }
+        s += dpp_f32<DPP_QUAD_XOR1>(s);
+        s += dpp_f32<DPP_QUAD_XOR2>(s);
+        if (seg == 0 && t < n_tail) st[t] = sm_log2 * s;
     }
     if (int(threadIdx.x) < n_splits)
         ms[threadIdx.x] = partial[(int64_t(threadIdx.x) * n_rows + r) * V_PART_STRIDE + A_M];
@@ -263,8 +274,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         o = fmaf(ms[s], src[d], o);
         l = fmaf(ms[s], src[A_L], l);
     }
+    const __half *vrow = v_tail + (int64_t(b) * tail_cap * H + h) * D + d;
+#pragma unroll 8
     for (int t = 0; t < n_tail; ++t) {
-        const float v = __half2float(v_tail[((int64_t(b) * tail_cap + t) * H + h) * D + d]);
+        const float v = __half2float(vrow[int64_t(t) * H * D]);
         o = fmaf(st[t], v, o);
         l += st[t];
     }

@@ -120,11 +120,10 @@ __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__
     if (n_tail > 0) {
         const int hq = r % (H * G), b = r / (H * G);
         const int h = hq / G;
-        for (int t = 0; t < n_tail; ++t) {
-            const float pt = p[int64_t(r) * ld + packed_tokens + t];
-            const float v = __half2float(tail[((int64_t(b) * tail_cap + t) * H + h) * D + d]);
-            acc = fmaf(pt, v, acc);
-        }
+        const float *prow = p + int64_t(r) * ld + packed_tokens;
+        const __half *vrow = tail + (int64_t(b) * tail_cap * H + h) * D + d;
+#pragma unroll 8
+        for (int t = 0; t < n_tail; ++t) acc = fmaf(prow[t], __half2float(vrow[int64_t(t) * H * D]), acc);
     }
     out[int64_t(r) * D + d] = acc;
 }
