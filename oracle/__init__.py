@@ -181,6 +181,26 @@ def compress(x, rel) -> Compressed:
     return Compressed(arena[:size].copy(), offsets, meta, codes, widths, mins)
 
 
+def v_median_order(v_codes):
+    """V-median repacking order: v_codes uint8 [B, T, H, D] (quantized V) -> uint8 [B, T];
+    entry [b, blk*64 + s] is the in-block index of the token stored at slot s."""
+    v_codes = np.ascontiguousarray(v_codes, dtype=np.uint8)
+    B, T, H, Dd = v_codes.shape
+    assert T % N == 0
+    order = np.empty((B, T), np.uint8)
+    lib().orc_v_median_order(_p(v_codes), B, T, H, Dd, _p(order))
+    return order
+
+
+def apply_order(x, order):
+    """Reorder the tokens of x [B, T, ...] inside their 64-token blocks: out[b, blk*64+s] =
+    x[b, blk*64 + order[b, blk*64+s]].  Plain indexing, no arithmetic of the method."""
+    B, T = order.shape
+    src = (np.arange(T) // N * N)[None, :] + order.astype(np.int64)
+    return np.ascontiguousarray(np.take_along_axis(
+        x[:, :T], src.reshape(B, T, *([1] * (x.ndim - 2))), axis=1))
+
+
 def k_scores(codes, x, meta, n_packed, qvec, sm_scale):
     """scores float64 [B, Hq, T]; codes/x [B, T, H, D], qvec fp16 [B, Hq, D]."""
     x = _u16(x)

@@ -275,6 +275,46 @@ int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
     return rc ? rc : pos;
 }
 
+/*
+ * V-median repacking order (Sec. III-B.3, "Faster Repacking with V Median"):
+ * inside every block of 64 tokens the token vectors (all kv-heads of a token,
+ * quantized V part) are sorted by their median.  Reading of the silent points:
+ * the median of the H*D codes of a token is the lower median (the element of
+ * rank floor((n-1)/2), n = H*D), equal medians keep their arrival order (stable
+ * sort), ascending.  q: quantized V codes [B][T][H][D]; order[b*T + blk*64 + s]
+ * = in-block index (0..63) of the token stored at slot s of block blk.  K and V
+ * are then packed with their tokens in that order (the permutation statement
+ * of Sec. III-B.3 makes any joint order valid).
+ */
+void orc_v_median_order(const uint8_t *q, int B, int T, int H, int D, uint8_t *order)
+{
+    int64_t n = (int64_t)H * D;
+    int64_t rank = (n - 1) / 2;
+    for (int b = 0; b < B; ++b)
+        for (int blk = 0; blk < T / ORC_N; ++blk) {
+            int key[ORC_N];
+            for (int i = 0; i < ORC_N; ++i) {
+                const uint8_t *row = q + ((int64_t)b * T + (int64_t)blk * ORC_N + i) * n;
+                int64_t hist[256];
+                memset(hist, 0, sizeof(hist));
+                for (int64_t e = 0; e < n; ++e) hist[row[e]]++;
+                int64_t seen = 0;
+                int v = 0;
+                for (; v < 256; ++v) {
+                    seen += hist[v];
+                    if (seen > rank) break;
+                }
+                key[i] = v;
+            }
+            /* stable insertion of tokens by key */
+            uint8_t *o = order + (int64_t)b * T + (int64_t)blk * ORC_N;
+            int filled = 0;
+            for (int v = 0; v < 256; ++v)
+                for (int i = 0; i < ORC_N; ++i)
+                    if (key[i] == v) o[filled++] = (uint8_t)i;
+        }
+}
+
 /* ------------------------------------------------------------- matvecs -- */
 
 /*

@@ -345,6 +345,65 @@ def test_attention_equals_the_three_step_path(orc):
         assert np.allclose(sharp[0, hq], xv[0, best[0, hq], hq], rtol=1e-9, atol=1e-9)
 
 
+# ---------------------------------------------------------- repacking pins --
+
+def test_v_median_order_matches_numpy_sort_and_stable_argsort(orc):
+    """The order against a library sort: lower median of each token's quantized V vector
+    (numpy sort, element (n-1)//2), then a stable argsort inside each block."""
+    B, T, H = 2, 192, 3
+    rng = np.random.default_rng(51)
+    # quantized V vectors whose value distribution leans differently from token to token
+    lean = rng.choice([0.25, 0.6, 1.0, 2.0, 5.0], size=(B, T, 1, 1))
+    codes = np.floor(6 * rng.random((B, T, H, 128)) ** lean).clip(0, 5).astype(np.uint8)
+    order = orc.v_median_order(codes)
+    flat = np.sort(codes.reshape(B, T, -1), axis=-1)
+    med = flat[..., (flat.shape[-1] - 1) // 2].astype(np.int64)
+    assert len(np.unique(med)) >= 3
+    for b in range(B):
+        for blk in range(T // 64):
+            ref = np.argsort(med[b, blk * 64:(blk + 1) * 64], kind="stable")
+            assert np.array_equal(order[b, blk * 64:(blk + 1) * 64], ref)
+            assert sorted(order[b, blk * 64:(blk + 1) * 64]) == list(range(64))
+    # an even count picks the lower of the two middle elements
+    two = np.zeros((1, 64, 1, 128), np.uint8)
+    two[0, 5, 0, :64] = 0
+    two[0, 5, 0, 64:] = 3                                # sorted: 64 zeros, 64 threes -> lower median 0
+    two[0, 6, 0, :63] = 0
+    two[0, 6, 0, 63:] = 3                                # 63 zeros, 65 threes -> median 3
+    o = orc.v_median_order(two)
+    assert o[0, -1] == 6 and list(o[0, :63]) == [i for i in range(64) if i != 6]
+
+
+def test_repacked_cache_gives_the_same_attention_and_smaller_packs_on_planted_data(orc):
+    """Att(q, PK, PV) = Att(q, K, V) for the repacking order P; and on data whose tokens come in two
+    interleaved kinds (V mass near the token minimum / near the maximum) sorting by the V median
+    puts like with like, so the packs get narrower (the direction of the paper's repacking table)."""
+    B, T, H, Hq = 1, 256, 2, 4
+    rng = np.random.default_rng(61)
+    K, _, q = _kv(B, T, H, 60, Hq)
+    kind = (np.arange(T) % 2).astype(np.float32)[None, :, None, None]
+    base = rng.random((B, T, H, 128)).astype(np.float32) ** 16         # mass near 0
+    V = np.where(kind > 0, 1.0 - base, base)
+    V[..., 0, 0] = 0.0
+    V[..., 0, 1] = 1.0                                                  # same range for every token
+    V = V.astype(np.float16)
+    cv = orc.compress(V, 0.2)
+    order = orc.v_median_order(cv.codes)
+    Kp, Vp = orc.apply_order(K, order), orc.apply_order(V, order)
+    ckp, cvp = orc.compress(Kp, 0.1), orc.compress(Vp, 0.2)
+    assert np.array_equal(cvp.codes, orc.apply_order(cv.codes, order)), "token-wise codes move with their token"
+    assert cvp.arena.size < 0.8 * cv.arena.size
+    ck = orc.compress(K, 0.1)
+    sm = 128 ** -0.5
+    a0 = orc.attention(ck.codes, K, ck.meta, cv.codes, V, cv.meta, T, q, sm)
+    a1 = orc.attention(ckp.codes, Kp, ckp.meta, cvp.codes, Vp, cvp.meta, T, q, sm)
+    assert np.allclose(a0, a1, rtol=1e-11, atol=1e-13)
+    # scores come out in storage order
+    s0 = orc.k_scores(ck.codes, K, ck.meta, T, q, sm)
+    s1 = orc.k_scores(ckp.codes, Kp, ckp.meta, T, q, sm)
+    assert np.array_equal(s1, orc.apply_order(s0.transpose(0, 2, 1), order).transpose(0, 2, 1))
+
+
 def test_planted_mistakes_are_caught(orc):
     """The pins above must be able to see typical slips: check that perturbed
     variants of the decoded tensor would violate them."""
