@@ -284,6 +284,39 @@ def run_growing(w, steps, torch, binding, synth):
     return res
 
 
+def run_repack(w, torch, binding, synth):
+    """V-median repacking in the compressor: packed size and bulk compression time with and
+    without it, on the workload's synthetic data and on the same data with the V tokens given
+    alternating value distributions (so that their medians differ, as in real caches)."""
+    K, V, q = synth.make_workload(w, device="cuda:0")
+    B, H, Hq, L = w.batch, w.n_kv_heads, w.n_q_heads, w.tokens
+    gen = torch.Generator(device=K.device)
+    gen.manual_seed(99)
+    lean = torch.tensor([0.3, 1.0, 3.0], device=K.device)[torch.randint(0, 3, (B, L, 1, 1), generator=gen,
+                                                                         device=K.device)]
+    V_lean = (torch.rand(V.shape, generator=gen, device=K.device) ** lean).to(torch.float16)
+    res = {}
+    for name, Vx in (("synthetic", V), ("leaning_v", V_lean)):
+        for repack in (0, 1):
+            c = binding.PackedKVCache(B, H, Hq, L, repack=repack)
+            e0, e1 = _event_pair(torch)
+            torch.cuda.synchronize()
+            e0.record()
+            c.kv_compress_append(K, Vx)
+            e1.record()
+            torch.cuda.synchronize()
+            st = c.kv_cache_stats()
+            attn = c.kv_decode_attention(q, 128 ** -0.5)
+            torch.cuda.synchronize()
+            res["%s_repack%d" % (name, repack)] = {
+                "compress_ms": round(e0.elapsed_time(e1), 3),
+                "k_bits_per_elem": round(st.k_bytes * 8.0 / (B * H * 128 * st.packed_tokens), 4),
+                "v_bits_per_elem": round(st.v_bytes * 8.0 / (B * H * 128 * st.packed_tokens), 4),
+                "attn_checksum": round(float(attn.double().abs().sum()), 6)}
+            c.close()
+    return res
+
+
 def cpu_baseline(w, synth, torch):
     """The oracle as it stands on the host cores, on a bounded sample of the workload."""
     import numpy as np
@@ -420,6 +453,8 @@ def main():
         g = run_growing(gw, 256, torch, binding, synth)
         side[gw.name] = g
         line["other_workloads"] = side
+        line["v_median_repacking"] = dict(workload=synth.workload(2).name,
+                                          **run_repack(synth.workload(2), torch, binding, synth))
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, synth, torch)
     print(json.dumps(line))

@@ -58,8 +58,15 @@ extern "C" {
 
 typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library */
 
+#define KV_REPACK_NONE 0
+#define KV_REPACK_V_MEDIAN 1
+
 /* Parameters of Sec. IV-A: relative quantization scales (K 0.1, V 0.2 are the
- * paper's defaults), pack size 16, repacking none, block 64. */
+ * paper's defaults), pack size 16, repacking none, block 64.  KV_REPACK_V_MEDIAN
+ * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
+ * tokens, K and V are packed with their tokens sorted by the lower median of the
+ * token's quantized V vector over all kv-heads (ascending, ties in arrival
+ * order); scores then come out in that storage order (see token_order). */
 typedef struct {
     int32_t batch;         /* B >= 1                                              */
     int32_t n_kv_heads;    /* H_kv >= 1                                           */
@@ -67,7 +74,7 @@ typedef struct {
     int32_t head_dim;      /* must be 128                                         */
     int32_t block_tokens;  /* must be 64                                          */
     int32_t pack_size;     /* must be 16                                          */
-    int32_t repack;        /* must be 0 (none)                                    */
+    int32_t repack;        /* KV_REPACK_NONE or KV_REPACK_V_MEDIAN                */
     int32_t tail_capacity; /* raw fp16 tail buffer in tokens, must be 64          */
     float k_rel_scale;     /* in [1/15, 1]                                        */
     float v_rel_scale;     /* in [1/15, 1]                                        */
@@ -81,6 +88,7 @@ typedef struct {
     size_t k_token_meta, v_token_meta; /* uint32 [B][max_tokens]                  */
     size_t k_tail, v_tail;             /* fp16 [B][tail_capacity][H_kv][128]      */
     size_t workspace;                  /* status words, chunk sizes, V partials   */
+    size_t token_order;                /* uint8 [B][max_tokens]; 0 without repacking */
 } kv_sizes_t;
 
 /* Device buffers, each at least as large as kv_query_sizes said and 256-byte
@@ -91,6 +99,10 @@ typedef struct {
     void *k_token_meta, *v_token_meta;
     void *k_tail, *v_tail;
     void *workspace;
+    /* With repacking: token_order[b][blk*64 + s] = position inside block blk (0..63,
+     * arrival order) of the token stored at slot s; scores[b][hq][blk*64 + s] belongs
+     * to token blk*64 + token_order[b][blk*64 + s].  Unused (may be null) without. */
+    void *token_order;
 } kv_buffers_t;
 
 /* Filled by kv_cache_stats. */

@@ -29,7 +29,8 @@ class kv_config_t(C.Structure):
 
 
 _BUFFER_NAMES = ("k_arena", "v_arena", "k_index", "v_index", "k_token_meta", "v_token_meta",
-                 "k_tail", "v_tail", "workspace")
+                 "k_tail", "v_tail", "workspace", "token_order")
+REPACK_NONE, REPACK_V_MEDIAN = 0, 1
 
 
 class kv_sizes_t(C.Structure):
@@ -107,8 +108,9 @@ def _stream_ptr(stream=None):
     return C.c_void_p(s.cuda_stream)
 
 
-def make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2):
-    return kv_config_t(batch, n_kv_heads, n_q_heads, HEAD_DIM, BLOCK_TOKENS, 16, 0, BLOCK_TOKENS,
+def make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2,
+                repack=REPACK_NONE):
+    return kv_config_t(batch, n_kv_heads, n_q_heads, HEAD_DIM, BLOCK_TOKENS, 16, repack, BLOCK_TOKENS,
                        k_rel_scale, v_rel_scale, max_tokens)
 
 
@@ -122,8 +124,8 @@ class PackedKVCache:
     """Owns the device buffers (torch tensors) and the kv_cache_t handle."""
 
     def __init__(self, batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2,
-                 bits_per_element_budget=0.0, device="cuda:0"):
-        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale, v_rel_scale)
+                 bits_per_element_budget=0.0, device="cuda:0", repack=REPACK_NONE):
+        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale, v_rel_scale, repack)
         self.device = torch.device(device)
         self.sizes = kv_query_sizes(self.cfg, bits_per_element_budget)
         self.tensors = {}
@@ -131,9 +133,9 @@ class PackedKVCache:
         with torch.cuda.device(self.device):
             for name in _BUFFER_NAMES:
                 t = torch.empty(getattr(self.sizes, name), dtype=torch.uint8, device=self.device)
-                assert t.data_ptr() % 256 == 0
+                assert t.numel() == 0 or t.data_ptr() % 256 == 0
                 self.tensors[name] = t
-                setattr(bufs, name, t.data_ptr())
+                setattr(bufs, name, t.data_ptr() if t.numel() else None)
             torch.cuda.synchronize()
             handle = C.c_void_p()
             _check(lib().kv_cache_create(C.byref(self.cfg), C.byref(bufs), C.byref(self.sizes),

@@ -18,7 +18,8 @@ bool aligned256(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 2
 int check_config(const kv_config_t *c) {
     if (!c) return KV_ERR_ARG;
     if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_tokens < 1) return KV_ERR_ARG;
-    if (c->head_dim != D || c->block_tokens != N || c->pack_size != PACK || c->repack != 0 ||
+    if (c->head_dim != D || c->block_tokens != N || c->pack_size != PACK ||
+        (c->repack != KV_REPACK_NONE && c->repack != KV_REPACK_V_MEDIAN) ||
         c->tail_capacity != N)
         return KV_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads) return KV_ERR_ARG;
@@ -60,6 +61,7 @@ extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_bu
     out->k_tail = out->v_tail =
         round256(size_t(cfg->batch) * cfg->tail_capacity * cfg->n_kv_heads * D * 2);
     out->workspace = round256(WS_VPART + v_partial_bytes(cfg->batch, cfg->n_q_heads));
+    out->token_order = cfg->repack ? round256(size_t(cfg->batch) * max_tokens) : 0;
     return KV_OK;
 }
 
@@ -81,6 +83,8 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
         sizes->v_index < need.v_index || sizes->k_token_meta < need.k_token_meta ||
         sizes->v_token_meta < need.v_token_meta || sizes->k_tail < need.k_tail ||
         sizes->v_tail < need.v_tail || sizes->workspace < need.workspace)
+        return KV_ERR_ARG;
+    if (cfg->repack && (!aligned256(buffers->token_order) || sizes->token_order < need.token_order))
         return KV_ERR_ARG;
     kv_cache *c = new (std::nothrow) kv_cache;
     if (!c) return KV_ERR_ARG;
@@ -128,28 +132,34 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         job.n_blocks = nb;
         job.first_token = c->packed_tokens;
         job.first_chunk = c->packed_tokens / N * B * H;
-        // K
-        job.src = ksrc + int64_t(done) * N * job.token_stride;
-        job.rel = c->cfg.k_rel_scale;
-        job.qmax = c->qmax_k;
-        job.arena = static_cast<uint8_t *>(c->buf.k_arena);
-        job.arena_cap16 = c->sizes.k_arena / 16;
-        job.index = static_cast<uint32_t *>(c->buf.k_index);
-        job.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
-        job.status = status + ST_OVERFLOW_K;
-        int rc = launch_compress(c, job, s);
-        if (rc) return rc;
-        // V
-        job.src = vsrc + int64_t(done) * N * job.token_stride;
-        job.rel = c->cfg.v_rel_scale;
-        job.qmax = c->qmax_v;
-        job.arena = static_cast<uint8_t *>(c->buf.v_arena);
-        job.arena_cap16 = c->sizes.v_arena / 16;
-        job.index = static_cast<uint32_t *>(c->buf.v_index);
-        job.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
-        job.status = status + ST_OVERFLOW_V;
-        rc = launch_compress(c, job, s);
-        if (rc) return rc;
+        job.order = nullptr;
+        CompressJob kjob = job, vjob = job;
+        kjob.src = ksrc + int64_t(done) * N * job.token_stride;
+        kjob.rel = c->cfg.k_rel_scale;
+        kjob.qmax = c->qmax_k;
+        kjob.arena = static_cast<uint8_t *>(c->buf.k_arena);
+        kjob.arena_cap16 = c->sizes.k_arena / 16;
+        kjob.index = static_cast<uint32_t *>(c->buf.k_index);
+        kjob.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
+        kjob.status = status + ST_OVERFLOW_K;
+        vjob.src = vsrc + int64_t(done) * N * job.token_stride;
+        vjob.rel = c->cfg.v_rel_scale;
+        vjob.qmax = c->qmax_v;
+        vjob.arena = static_cast<uint8_t *>(c->buf.v_arena);
+        vjob.arena_cap16 = c->sizes.v_arena / 16;
+        vjob.index = static_cast<uint32_t *>(c->buf.v_index);
+        vjob.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
+        vjob.status = status + ST_OVERFLOW_V;
+        int rc;
+        if ((rc = launch_token_params(c, kjob, s))) return rc;
+        if ((rc = launch_token_params(c, vjob, s))) return rc;
+        if (c->cfg.repack == KV_REPACK_V_MEDIAN) {
+            uint8_t *order = static_cast<uint8_t *>(c->buf.token_order);
+            if ((rc = launch_v_median_order(c, vjob, kjob.meta, order, s))) return rc;
+            kjob.order = vjob.order = order;
+        }
+        if ((rc = launch_pack(c, kjob, s))) return rc;
+        if ((rc = launch_pack(c, vjob, s))) return rc;
         c->packed_tokens += int64_t(nb) * N;
         done += nb;
     }

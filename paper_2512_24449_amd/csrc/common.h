@@ -109,9 +109,15 @@ struct CompressJob {
     uint32_t *index;
     uint32_t *meta;
     uint32_t *status;         // status word to set on overflow
+    const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
 };
 
-int launch_compress(const kv_cache *c, const CompressJob &job, hipStream_t s);
+int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s);
+int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s);
+// V-median order of the job's blocks (job describes V); permutes the token metadata of both
+// tensors into storage order and fills `order`.
+int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *k_meta, uint8_t *order,
+                          hipStream_t s);
 int launch_tail_copy(const kv_cache *c, const __half *src, int64_t src_batch_stride, int n,
                      __half *tail, int tail_pos, hipStream_t s);
 int launch_init(const kv_cache *c, hipStream_t s);

@@ -3,6 +3,8 @@
 //
 //   token_params   one workgroup per (token, batch): min/max over the token's
 //                  H*128 values -> fp16 scale = rel*(max-min), fp16 min
+//   v_median_key, block_order   (V-median repacking only) sort key per token,
+//                  order of the 64 tokens of a block, metadata into storage order
 //   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
 //   scan_offsets   one workgroup: prefix sum of the new chunk sizes -> index
 //   pack_chunks    one workgroup per chunk: quantize again and write header +
@@ -69,23 +71,32 @@ struct PackBits {
     int w, m;
 };
 
-__device__ inline PackBits make_pack(const __half *__restrict__ x0, int64_t token_stride,
+// Token-wise quantization of one value (Sec. III-B.2) with the stored fp16 scale and minimum.
+__device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
+    const float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+    int v = 0;
+    if (s != 0.0f) {
+        float ratio = (x - mn) / s;  // IEEE fp32 divide
+        float r = rintf(ratio);      // ties to even
+        v = (int)r;
+        v = v < 0 ? 0 : (v > qmax ? qmax : v);
+    }
+    return v;
+}
+
+// x_blk: channel d of the block's first token; the pack holds storage slots 16g..16g+15 of the
+// block, whose source tokens are order_g[0..15] (or 16g + i without repacking); meta_g: their
+// token metadata, already in storage order.
+__device__ inline PackBits make_pack(const __half *__restrict__ x_blk, int64_t token_stride, int g,
+                                     const uint8_t *__restrict__ order_g,
                                      const uint32_t *__restrict__ meta_g, int qmax) {
     int q[PACK];
     int lo = 255, hi = 0;
 #pragma unroll
     for (int i = 0; i < PACK; ++i) {
-        uint32_t mt = meta_g[i];
-        float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-        float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
-        float x = __half2float(x0[i * token_stride]);
-        int v = 0;
-        if (s != 0.0f) {
-            float ratio = (x - mn) / s;  // IEEE fp32 divide
-            float r = rintf(ratio);      // ties to even
-            v = (int)r;
-            v = v < 0 ? 0 : (v > qmax ? qmax : v);
-        }
+        const int src = order_g ? order_g[i] : g * PACK + i;
+        const int v = quantize_value(__half2float(x_blk[src * token_stride]), meta_g[i], qmax);
         q[i] = v;
         lo = min(lo, v);
         hi = max(hi, v);
@@ -129,7 +140,8 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     int64_t first_chunk,
                                                     uint32_t *__restrict__ sizes16,
                                                     const uint32_t *__restrict__ index,
-                                                    uint8_t *__restrict__ arena) {
+                                                    uint8_t *__restrict__ arena,
+                                                    const uint8_t *__restrict__ order) {
     const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
     const int h = cl % H;
     const int b = (cl / H) % B;
@@ -149,9 +161,11 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         int g = (tau >> 7) + 2 * k;
-        int64_t tok = int64_t(blk) * N + g * PACK;
-        const __half *x0 = src + b * batch_stride + tok * token_stride + h * D + d;
-        pb[k] = make_pack(x0, token_stride, meta + b * meta_stride + first_token + tok, qmax);
+        const int64_t tok = int64_t(blk) * N + g * PACK;  // first storage slot of the pack
+        const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D + d;
+        pb[k] = make_pack(x_blk, token_stride, g,
+                          order ? order + b * meta_stride + first_token + tok : nullptr,
+                          meta + b * meta_stride + first_token + tok, qmax);
         len[k] = 2 * pb[k].w;
     }
     int total0, total1;
@@ -228,6 +242,74 @@ __global__ void init_kernel(uint32_t *status, uint32_t *k_index, uint32_t *v_ind
     }
 }
 
+// V-median repacking, step 1 (Sec. III-B.3): the lower median of the H*128 quantized V codes of
+// one token, written as a sort key.  One workgroup per (token, batch).
+__global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restrict__ src,
+                                                           int64_t batch_stride, int64_t token_stride,
+                                                           int row_elems, int qmax,
+                                                           const uint32_t *__restrict__ meta,
+                                                           int64_t meta_stride, int64_t first_token,
+                                                           uint8_t *__restrict__ keys) {
+    __shared__ int hist[16];
+    const int t = blockIdx.x, b = blockIdx.y;
+    if (threadIdx.x < 16) hist[threadIdx.x] = 0;
+    __syncthreads();
+    const __half *row = src + b * batch_stride + t * token_stride;
+    const uint32_t mt = meta[b * meta_stride + first_token + t];
+    // sixteen 8-bit counters in two words; a thread sees at most 8 * ceil(row_elems / 2048) values
+    uint64_t lo = 0, hi = 0;
+    for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
+        uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+        const __half *hv = reinterpret_cast<const __half *>(&raw);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+            const int v = quantize_value(__half2float(hv[k]), mt, qmax);
+            const uint64_t one = 1ull << (8 * (v & 7));
+            if (v < 8) lo += one; else hi += one;
+        }
+    }
+    for (int bin = 0; bin <= qmax; ++bin) {
+        int c = int(((bin < 8 ? lo : hi) >> (8 * (bin & 7))) & 0xFFu);
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+        if ((threadIdx.x & 63) == 0) atomicAdd(&hist[bin], c);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const int rank = (row_elems - 1) / 2;
+        int seen = 0, v = 0;
+        for (; v < qmax; ++v) {
+            seen += hist[v];
+            if (seen > rank) break;
+        }
+        keys[b * meta_stride + first_token + t] = uint8_t(v);
+    }
+}
+
+// Step 2: one wave per (block, batch) ranks the 64 keys (ascending, equal keys in arrival order),
+// replaces them by the order and moves the token metadata of both tensors into storage order.
+__global__ __launch_bounds__(64) void block_order_kernel(uint8_t *__restrict__ order, int qmax,
+                                                         uint32_t *__restrict__ k_meta,
+                                                         uint32_t *__restrict__ v_meta,
+                                                         int64_t meta_stride, int64_t first_token) {
+    __shared__ uint8_t ord[N];
+    const int lane = threadIdx.x;
+    const int64_t pos = blockIdx.y * meta_stride + first_token + int64_t(blockIdx.x) * N;
+    const int key = order[pos + lane];
+    const uint32_t km = k_meta[pos + lane], vm = v_meta[pos + lane];
+    int rank = 0, base = 0;
+    for (int v = 0; v <= qmax; ++v) {
+        const uint64_t mask = __builtin_amdgcn_ballot_w64(key == v);
+        if (key == v) rank = base + __popcll(mask & ((1ull << lane) - 1ull));
+        base += __popcll(mask);
+    }
+    ord[rank] = uint8_t(lane);
+    k_meta[pos + rank] = km;
+    v_meta[pos + rank] = vm;
+    __syncthreads();
+    order[pos + lane] = ord[lane];
+}
+
 // ---------------------------------------------------------------------------
 int launch_init(const kv_cache *c, hipStream_t s) {
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
@@ -254,25 +336,45 @@ int launch_tail_copy(const kv_cache *c, const __half *src, int64_t src_batch_str
     return KV_OK;
 }
 
-int launch_compress(const kv_cache *c, const CompressJob &job, hipStream_t s) {
+int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
     const int n_tokens = job.n_blocks * N;
+    if (n_tokens <= 0) return KV_ERR_ARG;
+    hipLaunchKernelGGL(token_params_kernel, dim3(n_tokens, B), dim3(256), 0, s, job.src,
+                       job.batch_stride, job.token_stride, H * D, job.rel, job.meta,
+                       c->max_tokens, job.first_token);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *k_meta, uint8_t *order,
+                          hipStream_t s) {
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
+    const int n_tokens = vjob.n_blocks * N;
+    if (n_tokens <= 0 || H * D / 2048 + 1 > 31) return KV_ERR_ARG;  // 8-bit per-thread counters
+    hipLaunchKernelGGL(v_median_key_kernel, dim3(n_tokens, B), dim3(256), 0, s, vjob.src,
+                       vjob.batch_stride, vjob.token_stride, H * D, vjob.qmax, vjob.meta,
+                       c->max_tokens, vjob.first_token, order);
+    hipLaunchKernelGGL(block_order_kernel, dim3(vjob.n_blocks, B), dim3(64), 0, s, order, vjob.qmax,
+                       k_meta, vjob.meta, c->max_tokens, vjob.first_token);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
     const int n_chunks = job.n_blocks * B * H;
     if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
-
-    hipLaunchKernelGGL(token_params_kernel, dim3(n_tokens, B), dim3(256), 0, s, job.src,
-                       job.batch_stride, job.token_stride, H * D, job.rel, job.meta,
-                       c->max_tokens, job.first_token);
     hipLaunchKernelGGL(chunk_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, job.arena);
+                       job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
     hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
                        job.index, job.first_chunk, job.arena_cap16, job.status);
     hipLaunchKernelGGL(chunk_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, job.arena);
+                       job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

@@ -142,6 +142,56 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq):
     assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
 
 
+@pytest.mark.parametrize("B,H,Hq,L,pieces", [
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21]),   # blocks from bulk appends and from tail flushes
+    (1, 52, 52, 128, None),                        # wide token vectors (6656 values per median)
+])
+def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces):
+    """KV_REPACK_V_MEDIAN: order, packed bytes and token metadata bit-exact against the oracle's
+    order applied before its compressor; scores in storage order; attention unchanged."""
+    rng = np.random.default_rng(70 + B)
+    K, V, q = synth.make_kv(B, L, H, Hq, 71)
+    # give the V tokens differently leaning value distributions so that their medians differ
+    lean = torch.from_numpy(rng.choice([0.3, 1.0, 3.0], size=(B, L, 1, 1))).float()
+    V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(72)) ** lean).to(torch.float16)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    n_packed = L // 64 * 64
+    cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN)
+    pos = 0
+    for n in (pieces or [L]):
+        cache.kv_compress_append(K[:, pos:pos + n].contiguous().cuda(), V[:, pos:pos + n].contiguous().cuda())
+        pos += n
+    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), 0.2)
+    order = oracle.v_median_order(cv0.codes)
+    assert len(np.unique(order[:, :64])) == 64 and not np.array_equal(order[0, :64], np.arange(64))
+    Kp = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_packed:]], axis=1)
+    Vp = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_packed:]], axis=1)
+    ck, cv = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), 0.1), oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), 0.2)
+    gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
+    max_tokens = cache.tensors["token_order"].numel() // B
+    got_order = cache.tensors["token_order"].view(B, max_tokens)[:, :n_packed].cpu().numpy()
+    assert np.array_equal(got_order, order)
+
+    sm = 128 ** -0.5
+    kc, km = gpu_cases.full_codes(ck, Kp.shape, n_packed)
+    vc, vm = gpu_cases.full_codes(cv, Vp.shape, n_packed)
+    scores = cache.kv_k_matvec(q.cuda(), sm)
+    assert_close_vectors(scores.cpu().numpy(), oracle.k_scores(kc, Kp, km, n_packed, qn, sm), "K scores, storage order")
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    assert_close_vectors(out.cpu().numpy(), oracle.v_out(vc, Vp, vm, n_packed, p.cpu().numpy()), "V out")
+    attn = cache.kv_decode_attention(q.cuda(), sm)
+    a_perm = oracle.attention(kc, Kp, km, vc, Vp, vm, n_packed, qn, sm)
+    assert_close_vectors(attn.cpu().numpy(), a_perm, "attention over the repacked cache")
+    # and the repacked cache answers like the cache in arrival order (Att(q, PK, PV) = Att(q, K, V))
+    _, ck0, cv0b = gpu_cases.oracle_cache(Kn, Vn)
+    kc0, km0 = gpu_cases.full_codes(ck0, Kn.shape, n_packed)
+    vc0, vm0 = gpu_cases.full_codes(cv0b, Vn.shape, n_packed)
+    a_orig = oracle.attention(kc0, Kn, km0, vc0, Vn, vm0, n_packed, qn, sm)
+    assert_close_vectors(attn.cpu().numpy(), a_orig, "attention, arrival order")
+    cache.close()
+
+
 def test_host_argument_errors():
     cache = binding.PackedKVCache(1, 2, 2, 128)
     L = binding.lib()
