@@ -322,7 +322,7 @@ def cpu_baseline(w, synth, torch):
     import numpy as np
     import oracle
     # sized for roughly 10-30 s of host work (compression is single-threaded)
-    L = min(w.tokens // 64 * 64, max(64, (120_000_000 // (w.n_kv_heads * 128)) // 64 * 64))
+    L = min(w.tokens // 64 * 64, max(64, (200_000_000 // (w.n_kv_heads * 128)) // 64 * 64))
     B = 1
     K, V, q = synth.make_kv(B, L, w.n_kv_heads, w.n_q_heads, 7)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()

@@ -196,6 +196,9 @@ def test_host_argument_errors():
     cache = binding.PackedKVCache(1, 2, 2, 128)
     L = binding.lib()
     x = torch.zeros(1, 64, 2, 128, dtype=torch.float16, device="cuda")
+    q0 = torch.zeros(1, 2, 128, dtype=torch.float16, device="cuda")
+    o0 = torch.zeros(1, 2, 128, dtype=torch.float32, device="cuda")
+    assert L.kv_decode_attention(cache.handle, q0.data_ptr(), 1.0, o0.data_ptr(), None) == -1   # empty cache
     assert L.kv_compress_append(cache.handle, x.data_ptr(), None, 64, None) == -1
     assert L.kv_compress_append(cache.handle, x.data_ptr(), x.data_ptr(), -1, None) == -1
     assert L.kv_compress_append(cache.handle, x.data_ptr(), x.data_ptr(), 129, None) == -3

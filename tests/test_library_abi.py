@@ -47,6 +47,13 @@ def test_query_sizes_and_config_checks():
     bad = binding.make_config(0, 1, 1, 64)
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
     assert L.kv_query_sizes(None, 0.0, C.byref(out)) == -1
+    bad = binding.make_config(1, 32, 32, 4096, repack=2)          # unknown repacking mode
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    # the token order buffer exists only with repacking
+    assert worst.token_order == 0
+    rp = binding.kv_query_sizes(binding.make_config(2, 32, 32, 4096, repack=binding.REPACK_V_MEDIAN))
+    assert rp.token_order >= 2 * 4096 and rp.k_arena == binding.kv_query_sizes(binding.make_config(2, 32, 32, 4096)).k_arena
+    assert L.kv_decode_attention(None, None, 1.0, None, None) == -1
     assert L.kv_strerror(-3) == b"cache capacity exceeded"
     assert L.kv_cache_destroy(None) == -1
     assert L.kv_k_matvec(None, None, 1.0, None, 0, None) == -1
