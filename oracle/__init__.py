@@ -192,6 +192,18 @@ def v_median_order(v_codes):
     return order
 
 
+def greedy_order(k_codes, v_codes):
+    """Greedy repacking order over the joint (K | V) token vectors: uint8 [B, T], layout as
+    v_median_order.  O(N^2 D) per block; oracle only."""
+    k_codes = np.ascontiguousarray(k_codes, dtype=np.uint8)
+    v_codes = np.ascontiguousarray(v_codes, dtype=np.uint8)
+    B, T, H, Dd = v_codes.shape
+    assert k_codes.shape == v_codes.shape and T % N == 0
+    order = np.empty((B, T), np.uint8)
+    lib().orc_greedy_order(_p(k_codes), _p(v_codes), B, T, H, Dd, _p(order))
+    return order
+
+
 def apply_order(x, order):
     """Reorder the tokens of x [B, T, ...] inside their 64-token blocks: out[b, blk*64+s] =
     x[b, blk*64 + order[b, blk*64+s]].  Plain indexing, no arithmetic of the method."""

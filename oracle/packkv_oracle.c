@@ -29,7 +29,10 @@
  *   - pack metadata is one byte, (width << 4) | min;
  *   - chunk bytes: 512 header bytes indexed [token_group*128 + channel], then
  *     the packs in the same order, each 2*width bytes little-endian with the
- *     code of token i at bits [i*width, (i+1)*width), zero padded to 16 bytes.
+ *     code of token i at bits [i*width, (i+1)*width), zero padded to 16 bytes;
+ *   - repacking (V-median and greedy orders): see the comments of
+ *     orc_v_median_order and orc_greedy_order; the median and tie conventions
+ *     are "parity unpinned" readings (any order is a valid cache).
  *
  * Parity pins live in tests/test_oracle_*.py; the exact byte order inside a
  * chunk is "parity unpinned" (the paper's format figures are not available):
@@ -313,6 +316,90 @@ void orc_v_median_order(const uint8_t *q, int B, int T, int H, int D, uint8_t *o
                 for (int i = 0; i < ORC_N; ++i)
                     if (key[i] == v) o[filled++] = (uint8_t)i;
         }
+}
+
+/*
+ * Greedy repacking order (Sec. III-B.3, Algorithm "Greedy Repacking for
+ * Bit-Packing"), oracle only.  Inside every block of 64 tokens the token
+ * vectors x_i are the quantized K codes followed by the quantized V codes of
+ * all kv-heads (one joint order for both tensors).  Packs of 16 are built one
+ * after the other: the seed is the remaining vector closest (Euclidean) to the
+ * centroid of the remaining vectors; then the vector with the least marginal
+ * cost joins until the pack is full.  Reading of the cost: the payload bits of
+ * the pack, 16 * sum_d width(max_d - min_d) over all dimensions d (the per-pack
+ * metadata is the same for every candidate, so it does not change the choice,
+ * and with |P| equal for all candidates the marginal cost is ordered like
+ * sum_d width_d(P + j)).  Ties go to the lowest token index.  Output layout as
+ * orc_v_median_order.
+ */
+void orc_greedy_order(const uint8_t *kq, const uint8_t *vq, int B, int T, int H, int D, uint8_t *order)
+{
+    int64_t n = (int64_t)H * D, dim = 2 * n;
+    uint8_t *lo = (uint8_t *)malloc((size_t)dim), *hi = (uint8_t *)malloc((size_t)dim);
+    double *cen = (double *)malloc(sizeof(double) * (size_t)dim);
+    for (int b = 0; b < B; ++b)
+        for (int blk = 0; blk < T / ORC_N; ++blk) {
+            const uint8_t *k0 = kq + ((int64_t)b * T + (int64_t)blk * ORC_N) * n;
+            const uint8_t *v0 = vq + ((int64_t)b * T + (int64_t)blk * ORC_N) * n;
+            uint8_t *o = order + (int64_t)b * T + (int64_t)blk * ORC_N;
+            int left[ORC_N], n_left = ORC_N, filled = 0;
+            for (int i = 0; i < ORC_N; ++i) left[i] = i;
+            while (n_left > 0) {
+                /* seed: closest to the centroid of the remaining vectors */
+                for (int64_t d = 0; d < dim; ++d) cen[d] = 0.0;
+                for (int r = 0; r < n_left; ++r) {
+                    const uint8_t *xk = k0 + left[r] * n, *xv = v0 + left[r] * n;
+                    for (int64_t d = 0; d < n; ++d) { cen[d] += xk[d]; cen[n + d] += xv[d]; }
+                }
+                for (int64_t d = 0; d < dim; ++d) cen[d] /= n_left;
+                int best = 0;
+                double best_d2 = -1.0;
+                for (int r = 0; r < n_left; ++r) {
+                    const uint8_t *xk = k0 + left[r] * n, *xv = v0 + left[r] * n;
+                    double d2 = 0.0;
+                    for (int64_t d = 0; d < n; ++d) {
+                        double a = xk[d] - cen[d], c = xv[d] - cen[n + d];
+                        d2 += a * a + c * c;
+                    }
+                    if (best_d2 < 0.0 || d2 < best_d2) { best_d2 = d2; best = r; }
+                }
+                int seed = left[best];
+                for (int r = best; r + 1 < n_left; ++r) left[r] = left[r + 1];
+                --n_left;
+                for (int64_t d = 0; d < n; ++d) {
+                    lo[d] = hi[d] = k0[seed * n + d];
+                    lo[n + d] = hi[n + d] = v0[seed * n + d];
+                }
+                o[filled++] = (uint8_t)seed;
+                /* fill the pack: least total width after joining */
+                for (int size = 1; size < ORC_K && n_left > 0; ++size) {
+                    int64_t best_w = -1;
+                    best = 0;
+                    for (int r = 0; r < n_left; ++r) {
+                        const uint8_t *xk = k0 + left[r] * n, *xv = v0 + left[r] * n;
+                        int64_t w = 0;
+                        for (int64_t d = 0; d < dim; ++d) {
+                            int x = d < n ? xk[d] : xv[d - n];
+                            int l = x < lo[d] ? x : lo[d], h = x > hi[d] ? x : hi[d];
+                            w += orc_width(h - l);
+                        }
+                        if (best_w < 0 || w < best_w) { best_w = w; best = r; }
+                    }
+                    int j = left[best];
+                    for (int r = best; r + 1 < n_left; ++r) left[r] = left[r + 1];
+                    --n_left;
+                    for (int64_t d = 0; d < dim; ++d) {
+                        int x = d < n ? k0[j * n + d] : v0[j * n + d - n];
+                        if (x < lo[d]) lo[d] = (uint8_t)x;
+                        if (x > hi[d]) hi[d] = (uint8_t)x;
+                    }
+                    o[filled++] = (uint8_t)j;
+                }
+            }
+        }
+    free(lo);
+    free(hi);
+    free(cen);
 }
 
 /* ------------------------------------------------------------- matvecs -- */

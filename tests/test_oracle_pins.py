@@ -404,6 +404,52 @@ def test_repacked_cache_gives_the_same_attention_and_smaller_packs_on_planted_da
     assert np.array_equal(s1, orc.apply_order(s0.transpose(0, 2, 1), order).transpose(0, 2, 1))
 
 
+def _pack_width_sum(vectors):
+    """Payload cost of one pack: sum over dimensions of the bit width of its value range."""
+    rng_ = vectors.max(axis=0).astype(np.int64) - vectors.min(axis=0)
+    return int(np.ceil(np.log2(rng_ + 1)).sum())
+
+
+def test_greedy_order_choices_are_locally_optimal_and_it_orders_the_three_schemes(orc):
+    """Certificate check of the greedy repacking (not a second implementation): every seed is the
+    remaining vector closest to the centroid of the remaining ones, every later member has the least
+    cost among the vectors that were still available; and on tokens of four interleaved kinds the
+    packed size orders as greedy <= V-median < none (the direction of the paper's repacking table)."""
+    B, T, H = 1, 128, 1
+    rng = np.random.default_rng(81)
+    kind = rng.integers(0, 4, size=(B, T, 1, 1))
+    kc = np.clip(rng.integers(0, 3, size=(B, T, H, 128)) + 2 * kind, 0, 10).astype(np.uint8)
+    vc = np.clip(rng.integers(0, 2, size=(B, T, H, 128)) + kind, 0, 5).astype(np.uint8)
+    order = orc.greedy_order(kc, vc)
+    x = np.concatenate([kc.reshape(B, T, -1), vc.reshape(B, T, -1)], axis=-1).astype(np.int64)
+    for blk in range(T // 64):
+        o = order[0, blk * 64:(blk + 1) * 64].astype(int)
+        assert sorted(o) == list(range(64))
+        xb = x[0, blk * 64:(blk + 1) * 64]
+        remaining = list(range(64))
+        for p0 in range(0, 64, 16):
+            cen = xb[remaining].mean(axis=0)
+            d2 = ((xb[remaining] - cen) ** 2).sum(axis=1)
+            assert d2[remaining.index(o[p0])] <= d2.min() + 1e-9, "seed is closest to the centroid"
+            members = [o[p0]]
+            remaining.remove(o[p0])
+            for s_ in range(1, 16):
+                j = o[p0 + s_]
+                cost_j = _pack_width_sum(xb[members + [j]])
+                assert all(cost_j <= _pack_width_sum(xb[members + [r]]) for r in remaining)
+                members.append(j)
+                remaining.remove(j)
+
+    def packed_bytes(ordr):
+        return sum(orc.pack_chunk(orc.apply_order(c, ordr)[0, blk * 64:(blk + 1) * 64, 0])[0].size
+                   for c in (kc, vc) for blk in range(T // 64))
+
+    none = packed_bytes(np.tile(np.arange(64, dtype=np.uint8), (B, T // 64)))
+    median = packed_bytes(orc.v_median_order(vc))
+    greedy = packed_bytes(order)
+    assert greedy <= median < none, (greedy, median, none)
+
+
 def test_planted_mistakes_are_caught(orc):
     """The pins above must be able to see typical slips: check that perturbed
     variants of the decoded tensor would violate them."""
