@@ -191,7 +191,8 @@ int kv_cache_stats(kv_cache_t *cache, kv_stats_t *out, void *hip_stream);
 
 /*
  * Adopt externally written buffer contents (a cache restored from a copy of
- * its arenas, indices, token metadata and tails): afterwards the cache holds
+ * its arenas, indices, token metadata, tails and, with repacking, token
+ * order): afterwards the cache holds
  * `tokens` tokens per batch element, floor(tokens/64)*64 of them packed.
  * Host bookkeeping only; the caller is responsible for the buffer contents.
  */
