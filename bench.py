@@ -30,6 +30,10 @@ DEFAULT_WORKLOAD = "llama2_30b_32k_b8"
 ROTATE_BYTES = 1.1e9             # working set to rotate over so reads come from HBM, not the 256 MB LLC
 
 
+# wave64 issue slots per 64x128 chunk with one query head per kv-head (profiles/issue_counters_*.txt)
+ISSUE_SLOTS_PER_CHUNK = {"k": 438, "v": 321 + 16}
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -396,6 +400,7 @@ def main():
         t = json.load(open(tf)).get(w.name, {}).get(dom)
         if t:
             traffic = t
+    n_chunks = w.tokens // 64 * w.batch * w.n_kv_heads
     line = {
         "metric": "fused K/V decompress-GEMV GB/s (compressed)",
         "value": round(packed["value_gbps"], 2), "unit": "GB/s", "n_gpus": 1,
@@ -410,6 +415,14 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg,
                      "avg_launch_ms": round(packed[dom + "_ms"], 5)},
+        # the binding resource: vector issue slots.  Wave64 instructions per chunk are
+        # the measured constants of profiles/issue_counters_*.txt (an MFMA counted as 2 slots: about
+        # 8 cycles of the port when mixed with vector work); peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per instruction.
+        "roofline_alu": {"bound": "alu", "kernel": "kv_%s_matvec" % dom,
+                         "achieved": round(n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3) / 1e9, 1),
+                         "peak": 614.4, "unit": "G wave-instructions/s",
+                         "frac": round(n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3) / 614.4e9, 4),
+                         "slots_per_chunk": ISSUE_SLOTS_PER_CHUNK[dom]},
         "kernels": {
             "kv_k_matvec": {"ms": round(packed["k_ms"], 5), "compressed_gbps": round(packed["k_gbps_compressed"], 1),
                             "pct_hbm_peak": round(packed["k_gbps_compressed"] / 80.0, 2),
