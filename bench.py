@@ -357,7 +357,7 @@ def main():
     args = parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over (batch, kv-head) "
-              "without exchange; see DESIGN.md); --gpus %d is not supported" % args.gpus, file=sys.stderr)
+              "without exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2512_24449_amd import binding, synth
@@ -415,7 +415,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
                      "traffic": traffic, "algorithmic_bytes_per_launch": alg,
                      "avg_launch_ms": round(packed[dom + "_ms"], 5)},
-        # the binding resource: vector issue slots.  Wave64 instructions per chunk are
+        # the binding resource of these kernels: vector issue slots.  Wave64 instructions per chunk are
         # the measured constants of profiles/issue_counters_*.txt (an MFMA counted as 2 slots: about
         # 8 cycles of the port when mixed with vector work); peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per instruction.
         "roofline_alu": {"bound": "alu", "kernel": "kv_%s_matvec" % dom,
