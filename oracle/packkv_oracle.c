@@ -20,8 +20,7 @@
  *   scores = sm_scale * K_hat q      out = p^T V_hat
  * evaluated in fp64 on the decoded values x_hat = scale*code + min.
  *
- * Readings taken where the paper is silent (kept in step with the list in
- * the design document):
+ * Readings taken where the paper is silent:
  *   - one (scale, min) pair per token over ALL kv-heads' values of that token,
  *     per tensor, stored as fp16; quantization uses the stored fp16 values;
  *   - fp32 subtract and divide, round-half-to-even, clamp to [0, qmax],
