@@ -106,3 +106,63 @@ def test_growing_cache_decode_steps():
                                  attn)
     assert cache.kv_cache_stats().tail_tokens == (L0 + steps) % 64
     cache.close()
+
+
+def test_packed_arena_beyond_4_gib():
+    """Maximum-size edge: more than 4 GiB of packed bytes per tensor (8 x 52 heads x 294912 tokens,
+    15.7 G elements), so chunk offsets pass 2^32 bytes.  The oracle recomputes sampled blocks one by
+    one: chunk bytes, token metadata, the scores of the block, and the V product restricted to the
+    sampled blocks; the fused attention must agree with the three-step path everywhere."""
+    B, H, Hq, L = 8, 52, 52, 294912
+    K, V, q = synth.make_kv(B, L, H, Hq, 9, device="cuda:0")
+    cache = binding.PackedKVCache(B, H, Hq, L, bits_per_element_budget=3.0)
+    cache.kv_compress_append(K, V)
+    st = cache.kv_cache_stats()
+    n_blk = L // 64
+    assert st.overflow == 0 and st.n_chunks == n_blk * B * H
+    assert st.k_bytes > 2 ** 32 and st.v_bytes > 2 ** 32
+    sm_scale = 128 ** -0.5
+    scores = cache.kv_k_matvec(q, sm_scale)
+    samples = [(0, 0), (n_blk // 2, 3), (n_blk - 1, B - 1), (n_blk - 1, 0)]
+    p = torch.zeros_like(scores)
+    for blk, b in samples:
+        p[b, :, blk * 64:(blk + 1) * 64] = torch.softmax(scores[b, :, blk * 64:(blk + 1) * 64], dim=-1)
+    out = cache.kv_v_matvec(p)
+    del p
+    torch.cuda.synchronize()
+    index = {n: cache.view(n + "_index", torch.int32)[:st.n_chunks + 1] for n in ("k", "v")}
+    max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
+    o_ref = np.zeros((B, Hq, 128))
+    for blk, b in samples:
+        sl = slice(blk * 64, (blk + 1) * 64)
+        Kb, Vb = K[b:b + 1, sl].cpu().numpy(), V[b:b + 1, sl].cpu().numpy()
+        qb = q[b:b + 1].cpu().numpy()
+        c0 = (blk * B + b) * H
+        for name, x, rel in (("k", Kb, 0.1), ("v", Vb, 0.2)):
+            c = oracle.compress(x, rel)
+            lo = int(index[name][c0].item()) & 0xFFFFFFFF
+            hi = int(index[name][c0 + H].item()) & 0xFFFFFFFF
+            assert (hi - lo) * 16 == c.arena.size, (name, blk, b)
+            got = cache.tensors[name + "_arena"][lo * 16:hi * 16].cpu().numpy()
+            assert np.array_equal(got, c.arena), "%s chunk bytes of block %d, batch %d" % (name, blk, b)
+            meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[b, sl]
+            assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta[0])
+            if name == "k":
+                s_ref = oracle.k_scores(c.codes, x, c.meta, 64, qb, sm_scale)
+                assert_close_vectors(scores[b:b + 1, :, sl].cpu().numpy(), s_ref, "scores of block %d" % blk)
+            else:
+                pb = torch.softmax(scores[b:b + 1, :, sl], dim=-1).cpu().numpy()
+                o_ref[b] += oracle.v_out(c.codes, x, c.meta, 64, pb)[0]
+        if (blk, b) == samples[-2]:
+            assert lo * 16 > 2 ** 32, "the sampled chunk lies beyond 4 GiB"
+    touched = sorted({b for _, b in samples})
+    assert_close_vectors(out[touched].cpu().numpy(), o_ref[touched], "V product over the sampled blocks")
+    # whole-cache agreement of the two decode paths
+    del K, V
+    pfull = synth.make_probs(scores)
+    out3 = cache.kv_v_matvec(pfull)
+    attn = cache.kv_decode_attention(q, sm_scale)
+    torch.cuda.synchronize()
+    assert torch.isfinite(attn).all()
+    assert_close_vectors(attn.cpu().numpy(), out3.cpu().numpy().astype(np.float64), "fused vs three-step")
+    cache.close()
