@@ -437,6 +437,8 @@ def main():
                       "speedup_k": round(fp16["k_ms"] / packed["k_ms"], 3),
                       "speedup_v": round(fp16["v_ms"] / packed["v_ms"], 3)},
         "stream_read_gbps": round(fp16["stream_read_gbps"], 1),
+        "pct_of_stream_read": {"kv_k_matvec": round(100.0 * packed["k_gbps_compressed"] / fp16["stream_read_gbps"], 2),
+                               "kv_v_matvec": round(100.0 * packed["v_gbps_compressed"] / fp16["stream_read_gbps"], 2)},
         "fused_decode_attention": {"ms": round(packed["attn_ms"], 5),
                                    "ms_per_step": round(packed["fused_ms_per_step"], 5),
                                    "compressed_gbps": round((packed["k_bytes"] + packed["v_bytes"]) /
