@@ -85,18 +85,15 @@ __device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
     return v;
 }
 
-// x_blk: channel d of the block's first token; the pack holds storage slots 16g..16g+15 of the
-// block, whose source tokens are order_g[0..15] (or 16g + i without repacking); meta_g: their
-// token metadata, already in storage order.
-__device__ inline PackBits make_pack(const __half *__restrict__ x_blk, int64_t token_stride, int g,
-                                     const uint8_t *__restrict__ order_g,
+// tile: the block's 64 x 128 values in LDS, rows already in storage order; the pack holds rows
+// 16g..16g+15 of channel d; meta_g: their token metadata (storage order).
+__device__ inline PackBits make_pack(const __half *tile, int g, int d,
                                      const uint32_t *__restrict__ meta_g, int qmax) {
     int q[PACK];
     int lo = 255, hi = 0;
 #pragma unroll
     for (int i = 0; i < PACK; ++i) {
-        const int src = order_g ? order_g[i] : g * PACK + i;
-        const int v = quantize_value(__half2float(x_blk[src * token_stride]), meta_g[i], qmax);
+        const int v = quantize_value(__half2float(tile[(g * PACK + i) * D + d]), meta_g[i], qmax);
         q[i] = v;
         lo = min(lo, v);
         hi = max(hi, v);
@@ -156,16 +153,28 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
         dst = arena + size_t(o0) * 16;
     }
 
+    // stage the block's 64 x 128 values in LDS with 16-byte loads, rows in storage order
+    __shared__ __attribute__((aligned(16))) __half tile[N * D];
+    {
+        const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D;
+        const uint8_t *ord = order ? order + b * meta_stride + first_token + int64_t(blk) * N : nullptr;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = pass * 16 + (tau >> 4), c8 = (tau & 15) * 8;
+            const int src_row = ord ? ord[row] : row;
+            *reinterpret_cast<uint4 *>(tile + row * D + c8) =
+                *reinterpret_cast<const uint4 *>(x_blk + src_row * token_stride + c8);
+        }
+    }
+    __syncthreads();
+
     PackBits pb[2];
     int len[2];
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         int g = (tau >> 7) + 2 * k;
         const int64_t tok = int64_t(blk) * N + g * PACK;  // first storage slot of the pack
-        const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D + d;
-        pb[k] = make_pack(x_blk, token_stride, g,
-                          order ? order + b * meta_stride + first_token + tok : nullptr,
-                          meta + b * meta_stride + first_token + tok, qmax);
+        pb[k] = make_pack(tile, g, d, meta + b * meta_stride + first_token + tok, qmax);
         len[k] = 2 * pb[k].w;
     }
     int total0, total1;
