@@ -467,6 +467,10 @@ def main():
         gw = synth.workload(4)
         g = run_growing(gw, 256, torch, binding, synth)
         side[gw.name] = g
+        side["timing_note"] = ("per-kernel times are HIP event intervals on the launch stream; for kernels under "
+                               "about 20 us they include host submission latency (the GPU runs ahead of the "
+                               "Python caller), so the two small workloads compare launch paths rather than kernels: "
+                               "profiles/kernel_trace_all_workloads.txt has the kernel durations")
         line["other_workloads"] = side
         line["v_median_repacking"] = dict(workload=synth.workload(2).name,
                                           **run_repack(synth.workload(2), torch, binding, synth))
