@@ -123,7 +123,7 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth):
         if timed:
             e1.record()
             k_ev.append((e0, e1))
-        p = torch.softmax(scores[:, :, :n], dim=-1)
+        p = c.kv_softmax(scores)      # in place
         if timed:
             e2, e3 = _event_pair(torch)
             e2.record()
@@ -264,8 +264,7 @@ def run_growing(w, steps, torch, binding, synth):
     for i in range(steps):
         c.kv_compress_append(k_new[i], v_new[i])
         c.kv_k_matvec(q, 128 ** -0.5, scores)
-        p = torch.softmax(scores[:, :, :c.tokens], dim=-1)
-        c.kv_v_matvec(p, out)
+        c.kv_v_matvec(c.kv_softmax(scores), out)
         evs[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0

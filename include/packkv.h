@@ -172,6 +172,17 @@ int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores,
 int kv_v_matvec(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
 
 /*
+ * Row softmax between the two matvecs (smx in the attention definition of
+ * Sec. III-B.3), in place: scores[b][hq][0..tokens) <- softmax over the cached
+ * tokens, for every (b, hq); entries [tokens, ld_scores) are left alone.
+ * scores: device fp32 [B][H_q][ld_scores] as written by kv_k_matvec.  fp32,
+ * reductions in a fixed order (bitwise reproducible).  Long rows are cut into
+ * segments whose statistics pass through the workspace; calls on one cache
+ * must not overlap.  KV_ERR_ARG on an empty cache or ld_scores < tokens.
+ */
+int kv_softmax(kv_cache_t *cache, float *scores, int64_t ld_scores, void *hip_stream);
+
+/*
  * Fused decode attention (the attention of one new query as defined in
  * Sec. III-B.3, Att(q, K, V) = softmax(sm_scale * K q)^T V, computed with the
  * fused decompression of Sec. III-C):

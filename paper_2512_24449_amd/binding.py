@@ -49,7 +49,7 @@ class kv_stats_t(C.Structure):
 
 
 EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append",
-           "kv_k_matvec", "kv_v_matvec", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
+           "kv_k_matvec", "kv_v_matvec", "kv_softmax", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
            "kv_strerror", "kv_fp16_k_matvec", "kv_fp16_v_matvec", "kv_fp16_v_workspace_bytes",
            "kv_stream_read")
 
@@ -76,6 +76,7 @@ def lib():
         L.kv_k_matvec.argtypes = [vp, vp, f32, vp, i64, vp]
         L.kv_v_matvec.argtypes = [vp, vp, i64, vp, vp]
         L.kv_decode_attention.argtypes = [vp, vp, f32, vp, vp]
+        L.kv_softmax.argtypes = [vp, vp, i64, vp]
         L.kv_cache_stats.argtypes = [vp, C.POINTER(kv_stats_t), vp]
         L.kv_cache_restore.argtypes = [vp, i64]
         L.kv_cache_tokens.argtypes = [vp]
@@ -188,6 +189,14 @@ class PackedKVCache:
         _check(lib().kv_v_matvec(self.handle, p.data_ptr(), p.shape[2], out.data_ptr(),
                                  _stream_ptr(stream)), "kv_v_matvec")
         return out
+
+    def kv_softmax(self, scores: torch.Tensor, stream=None):
+        """In-place softmax over the cached tokens of scores fp32 [B, Hq, ld]; returns scores."""
+        assert scores.dtype == torch.float32 and scores.is_contiguous()
+        assert tuple(scores.shape[:2]) == (self.batch, self.n_q_heads)
+        _check(lib().kv_softmax(self.handle, scores.data_ptr(), scores.shape[2], _stream_ptr(stream)),
+               "kv_softmax")
+        return scores
 
     def kv_decode_attention(self, q: torch.Tensor, sm_scale: float, out: torch.Tensor = None, stream=None):
         """q: fp16 [B, Hq, 128] -> out fp32 [B, Hq, 128] = softmax(sm_scale * q K^T) V over the whole cache."""

@@ -114,6 +114,13 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     o_e2e = oracle.v_out(vcodes, Vn, vmeta, n_packed, p64.astype(np.float32))
     assert_close_vectors(out.cpu().numpy(), o_e2e, "decode step end to end")
 
+    # the whole three-step path inside the library: K product, softmax in place, V product
+    s3 = cache.kv_k_matvec(qd, sm_scale)
+    cache.kv_softmax(s3)
+    out3 = cache.kv_v_matvec(s3)
+    torch.cuda.synchronize()
+    assert_close_vectors(out3.cpu().numpy(), o_e2e, "three-step path with the library softmax")
+
     # fused decode attention against the oracle's definition of Att(q, K, V)
     attn = cache.kv_decode_attention(qd, sm_scale)
     torch.cuda.synchronize()

@@ -192,6 +192,37 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces):
     cache.close()
 
 
+@pytest.mark.parametrize("B,Hq,tokens,ld", [
+    (3, 1, 1, 1), (5, 1, 63, 64), (1, 4, 8192, 8192), (2, 1, 8193, 8200), (1, 1, 20000, 20003),
+    (1, 2, 65536, 65536), (1, 1, 65537, 65540), (1, 1, 200001, 200001), (1, 8, 131072 + 5, 131136),
+    (8, 8, 40000, 40000), (66, 8, 70000, 70000),
+])
+def test_softmax_matches_oracle(B, Hq, tokens, ld):
+    """kv_softmax (register path, long-row path, split path) against the oracle's fp64 softmax;
+    entries past the cached tokens stay untouched."""
+    cache = binding.PackedKVCache(B, 1, Hq, tokens)
+    x = torch.zeros(B, tokens, 1, 128, dtype=torch.float16, device="cuda")
+    cache.kv_compress_append(x, x)
+    assert cache.tokens == tokens
+    gen = torch.Generator(device="cuda").manual_seed(B * 1000 + tokens)
+    s = torch.randn(B, Hq, ld, generator=gen, device="cuda") * 6.0
+    s[0, 0, tokens // 2] = 40.0                   # one dominant score
+    s_host = s.cpu().numpy()
+    d = s.clone()
+    assert cache.kv_softmax(d) is d
+    got = d.cpu().numpy()
+    rows = min(B * Hq, 16)                        # the oracle on a sample of rows
+    ref = oracle.softmax(s_host.reshape(B * Hq, ld)[:rows, :tokens].astype(np.float64))
+    assert_close_vectors(got.reshape(B * Hq, ld)[:rows, :tokens], ref, "softmax", tol=1e-5)
+    assert np.allclose(got[..., :tokens].sum(axis=-1), 1.0, atol=2e-5)
+    assert np.array_equal(got[..., tokens:], s_host[..., tokens:])
+    d2 = s.clone()
+    cache.kv_softmax(d2)
+    assert torch.equal(d, d2), "bitwise reproducible"
+    assert binding.lib().kv_softmax(cache.handle, d.data_ptr(), tokens - 1, None) == -1
+    cache.close()
+
+
 def test_host_argument_errors():
     cache = binding.PackedKVCache(1, 2, 2, 128)
     L = binding.lib()
