@@ -2,8 +2,8 @@
 """Benchmark of the PackKV decode hot path on one MI355X.
 
 One "step" is one decode step over the whole cache of one layer:
-    kv_compress_append(1 new token)  ->  kv_k_matvec  ->  softmax (torch, outside
-    the library)  ->  kv_v_matvec
+    kv_compress_append(1 new token)  ->  kv_k_matvec  ->  kv_softmax (in place)
+    ->  kv_v_matvec
 on synthetic, seeded inputs that are resident in HBM before the timed region.
 The headline value is compressed bytes read per step (packed K + packed V)
 divided by the step time.  Beside it: the roofline entry of the dominant
