@@ -189,8 +189,7 @@ extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *
 
     if (c->tail_tokens > 0 || remaining < N) {
         const int take = int(std::min<int64_t>(remaining, N - c->tail_tokens));
-        if ((rc = launch_tail_copy(c, ksrc, src_batch_stride, take, ktail, c->tail_tokens, s))) return rc;
-        if ((rc = launch_tail_copy(c, vsrc, src_batch_stride, take, vtail, c->tail_tokens, s))) return rc;
+        if ((rc = launch_tail_copy(c, ksrc, vsrc, src_batch_stride, take, c->tail_tokens, s))) return rc;
         c->tail_tokens += take;
         pos += take;
         remaining -= take;
@@ -206,8 +205,8 @@ extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *
         remaining -= int64_t(full) * N;
     }
     if (remaining > 0) {
-        if ((rc = launch_tail_copy(c, ksrc + pos * row, src_batch_stride, int(remaining), ktail, 0, s))) return rc;
-        if ((rc = launch_tail_copy(c, vsrc + pos * row, src_batch_stride, int(remaining), vtail, 0, s))) return rc;
+        if ((rc = launch_tail_copy(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, int(remaining), 0, s)))
+            return rc;
         c->tail_tokens = int(remaining);
     }
     return KV_OK;

@@ -118,8 +118,8 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s);
 // tensors into storage order and fills `order`.
 int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *k_meta, uint8_t *order,
                           hipStream_t s);
-int launch_tail_copy(const kv_cache *c, const __half *src, int64_t src_batch_stride, int n,
-                     __half *tail, int tail_pos, hipStream_t s);
+int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t src_batch_stride,
+                     int n, int tail_pos, hipStream_t s);
 int launch_init(const kv_cache *c, hipStream_t s);
 int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *scores,
                     int64_t ld_scores, hipStream_t s);

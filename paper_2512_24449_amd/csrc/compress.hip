@@ -234,10 +234,13 @@ __global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__re
     }
 }
 
-__global__ void tail_copy_kernel(const uint4 *__restrict__ src, int64_t src_batch_stride16,
-                                 uint4 *__restrict__ dst, int64_t dst_batch_stride16,
-                                 int64_t n16) {
+// New tokens of both tensors into their raw tails: blockIdx.z = 0 copies K, 1 copies V.
+__global__ void tail_copy_kernel(const uint4 *__restrict__ ksrc, const uint4 *__restrict__ vsrc,
+                                 int64_t src_batch_stride16, uint4 *__restrict__ kdst,
+                                 uint4 *__restrict__ vdst, int64_t dst_batch_stride16, int64_t n16) {
     const int b = blockIdx.y;
+    const uint4 *src = blockIdx.z ? vsrc : ksrc;
+    uint4 *dst = blockIdx.z ? vdst : kdst;
     for (int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; i < n16;
          i += int64_t(gridDim.x) * blockDim.x)
         dst[b * dst_batch_stride16 + i] = src[b * src_batch_stride16 + i];
@@ -330,16 +333,18 @@ int launch_init(const kv_cache *c, hipStream_t s) {
     return KV_OK;
 }
 
-int launch_tail_copy(const kv_cache *c, const __half *src, int64_t src_batch_stride, int n,
-                     __half *tail, int tail_pos, hipStream_t s) {
+int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t src_batch_stride,
+                     int n, int tail_pos, hipStream_t s) {
     const int64_t row = int64_t(c->cfg.n_kv_heads) * D;  // elements per token
     const int64_t n16 = n * row / 8;
     if (n16 == 0) return KV_OK;
     const int threads = 256;
     const int blocks = int(std::min<int64_t>((n16 + threads - 1) / threads, 1024));
-    hipLaunchKernelGGL(tail_copy_kernel, dim3(blocks, c->cfg.batch), dim3(threads), 0, s,
-                       reinterpret_cast<const uint4 *>(src), src_batch_stride / 8,
-                       reinterpret_cast<uint4 *>(tail + int64_t(tail_pos) * row),
+    __half *ktail = static_cast<__half *>(c->buf.k_tail), *vtail = static_cast<__half *>(c->buf.v_tail);
+    hipLaunchKernelGGL(tail_copy_kernel, dim3(blocks, c->cfg.batch, 2), dim3(threads), 0, s,
+                       reinterpret_cast<const uint4 *>(ksrc), reinterpret_cast<const uint4 *>(vsrc),
+                       src_batch_stride / 8, reinterpret_cast<uint4 *>(ktail + int64_t(tail_pos) * row),
+                       reinterpret_cast<uint4 *>(vtail + int64_t(tail_pos) * row),
                        int64_t(c->cfg.tail_capacity) * row / 8, n16);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
