@@ -111,23 +111,24 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth):
     out = torch.empty(B, Hq, 128, dtype=torch.float32, device=dev)
     sm_scale = 128 ** -0.5
     k_ev, v_ev = [], []
+    st_raw = torch.cuda.current_stream().cuda_stream   # raw hipStream_t of the launch stream
 
     def step(i, timed):
         c = reps.caches[i % R]
-        c.kv_compress_append(k_new[i], v_new[i])
+        c.kv_compress_append(k_new[i], v_new[i], stream=st_raw)
         n = c.tokens
         if timed:
             e0, e1 = _event_pair(torch)
             e0.record()
-        c.kv_k_matvec(q, sm_scale, scores)
+        c.kv_k_matvec(q, sm_scale, scores, stream=st_raw)
         if timed:
             e1.record()
             k_ev.append((e0, e1))
-        p = c.kv_softmax(scores)      # in place
+        p = c.kv_softmax(scores, stream=st_raw)      # in place
         if timed:
             e2, e3 = _event_pair(torch)
             e2.record()
-        c.kv_v_matvec(p, out)
+        c.kv_v_matvec(p, out, stream=st_raw)
         if timed:
             e3.record()
             v_ev.append((e2, e3))
@@ -147,11 +148,11 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth):
 
     def fused_step(i, timed):
         c = reps.caches[i % R]
-        c.kv_compress_append(k_new[i], v_new[i])
+        c.kv_compress_append(k_new[i], v_new[i], stream=st_raw)
         if timed:
             e0, e1 = _event_pair(torch)
             e0.record()
-        c.kv_decode_attention(q, sm_scale, attn_out)
+        c.kv_decode_attention(q, sm_scale, attn_out, stream=st_raw)
         if timed:
             e1.record()
             a_ev.append((e0, e1))
@@ -202,14 +203,15 @@ def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth):
     binding.kv_fp16_k_matvec(Ks[0], q, 128 ** -0.5, H, scores)
     p = torch.softmax(scores, dim=-1)
     k_ev, v_ev, mm_ev = [], [], []
+    st_raw = torch.cuda.current_stream().cuda_stream
     for i in range(warmup + steps):
         e0, e1 = _event_pair(torch)
         e2, e3 = _event_pair(torch)
         e0.record()
-        binding.kv_fp16_k_matvec(Ks[i % R], q, 128 ** -0.5, H, scores)
+        binding.kv_fp16_k_matvec(Ks[i % R], q, 128 ** -0.5, H, scores, stream=st_raw)
         e1.record()
         e2.record()
-        binding.kv_fp16_v_matvec(Vs[i % R], p, out, ws)
+        binding.kv_fp16_v_matvec(Vs[i % R], p, out, ws, stream=st_raw)
         e3.record()
         if i >= warmup:
             k_ev.append((e0, e1))
@@ -258,13 +260,14 @@ def run_growing(w, steps, torch, binding, synth):
     scores = torch.empty(B, Hq, L + 2 * steps + 64, dtype=torch.float32, device=K.device)
     out = torch.empty(B, Hq, 128, dtype=torch.float32, device=K.device)
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    st_raw = torch.cuda.current_stream().cuda_stream
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     evs[0].record()
     for i in range(steps):
-        c.kv_compress_append(k_new[i], v_new[i])
-        c.kv_k_matvec(q, 128 ** -0.5, scores)
-        c.kv_v_matvec(c.kv_softmax(scores), out)
+        c.kv_compress_append(k_new[i], v_new[i], stream=st_raw)
+        c.kv_k_matvec(q, 128 ** -0.5, scores, stream=st_raw)
+        c.kv_v_matvec(c.kv_softmax(scores, stream=st_raw), out, stream=st_raw)
         evs[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -279,8 +282,8 @@ def run_growing(w, steps, torch, binding, synth):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(steps):
-        c.kv_compress_append(k_new[i], v_new[i])
-        c.kv_decode_attention(q, 128 ** -0.5, out)
+        c.kv_compress_append(k_new[i], v_new[i], stream=st_raw)
+        c.kv_decode_attention(q, 128 ** -0.5, out, stream=st_raw)
     torch.cuda.synchronize()
     res["fused_ms_per_step_mean"] = (time.perf_counter() - t0) * 1e3 / steps
     c.close()

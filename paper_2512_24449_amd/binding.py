@@ -105,6 +105,10 @@ def _check(rc: int, what: str) -> None:
 
 
 def _stream_ptr(stream=None):
+    """stream: None (torch's current stream), a torch stream, or a raw hipStream_t as int
+    (looking up the current stream costs microseconds; hot loops pass the integer)."""
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
     s = stream if stream is not None else torch.cuda.current_stream()
     return C.c_void_p(s.cuda_stream)
 
