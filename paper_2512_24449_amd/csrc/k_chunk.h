@@ -56,20 +56,22 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint4 *table, con
     float acc[16], msum = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
+    // lanes 8..15 of a row take their token halves swapped: the layout row_reduce_scatter16_swapped wants
+    const uint32_t pair_sel = (lane & 8) ? PAIR_HI_LO : PAIR_LO_HI;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
         uint32_t P[8];
         const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-        expand_pack(raw, P);
+        expand_pack(raw, P, pair_sel);
         msum = fmaf(kq.qf[j], __uint_as_float(raw.k.w), msum);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-            // P[k] holds tokens (k, k+8) of the group
+            // P[k] holds tokens (k, k+8) of the group (swapped in the upper half of the row)
             acc[k] = fmaf(kq.qf[j], half_lo(P[k]), acc[k]);
             acc[k + 8] = fmaf(kq.qf[j], half_hi(P[k]), acc[k + 8]);
         }
     }
-    return row_reduce_scatter16(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
+    return row_reduce_scatter16_swapped(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
 }
 
 // ---- grouped queries -------------------------------------------------------------

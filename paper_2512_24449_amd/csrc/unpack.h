@@ -196,15 +196,19 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
 // Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
 // 16-bit half is the bit pattern of fp16(code * 2^(LIFT-24)); the table must have been
 // built with the same lift.
+// pair_sel: byte selector that pairs the two token halves; PAIR_LO_HI puts token m in the
+// low half, PAIR_HI_LO swaps the halves (P[m] = tokens (m+8, m)), at no cost.
+constexpr uint32_t PAIR_LO_HI = 0x05040100u, PAIR_HI_LO = 0x01000504u;
+
 template <int LIFT = 0>
-__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
+__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8], uint32_t pair_sel = PAIR_LO_HI) {
     const uint32_t A = __builtin_amdgcn_alignbit(r.d1, r.d0, r.sh);    // pack bits [0, 32): tokens 0..7
     const uint32_t hi_ = __builtin_amdgcn_alignbit(r.d2, r.d1, r.sh);  // pack bits [32, 64)
     const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32): tokens 8..15
     const uint32_t w = r.k.y, M = r.k.x;
     const uint32_t s = 4 * w;
-    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // tokens 0..3 | 8..11
-    uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, 0x05040100u);  // tokens 4..7 | 12..15
+    uint32_t Z0 = __builtin_amdgcn_perm(R, A, pair_sel);            // tokens 0..3 | 8..11
+    uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, pair_sel);  // tokens 4..7 | 12..15
     if (LIFT) {  // rotate left: the codes of both halves move up together, the mask picks them there
         Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - LIFT);
         Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - LIFT);
@@ -223,17 +227,16 @@ __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
 __device__ inline float half_lo(uint32_t p) { return float(__builtin_bit_cast(_Float16, uint16_t(p & 0xFFFFu))); }
 __device__ inline float half_hi(uint32_t p) { return float(__builtin_bit_cast(_Float16, uint16_t(p >> 16))); }
 
-// Reduce-scatter inside each row of 16 lanes: on entry every lane holds 16
-// partial sums v[0..15]; on return lane i of the row holds the row's sum of v[i].
-__device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
+// Reduce-scatter inside each row of 16 lanes.  On entry every lane holds 16 partial sums; in
+// lanes 0..7 of the row v[i] belongs to index i, in lanes 8..15 the two halves are swapped
+// (v[i] belongs to index i ^ 8) -- the caller gets that for free from the pairing selector of
+// expand_pack, and it saves the first round of selects here.  On return lane i of the row
+// holds the row's sum for index i.
+__device__ inline float row_reduce_scatter16_swapped(float (&v)[16], int lane) {
     float a[8], b[4], c[2];
-    const bool b3 = lane & 8, b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
+    const bool b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        float keep = b3 ? v[k + 8] : v[k];
-        float send = b3 ? v[k] : v[k + 8];
-        a[k] = keep + dpp_f32<DPP_ROW_ROR8>(send);
-    }
+    for (int k = 0; k < 8; ++k) a[k] = v[k] + dpp_f32<DPP_ROW_ROR8>(v[k + 8]);
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float keep = b2 ? a[k + 4] : a[k];
@@ -249,6 +252,17 @@ __device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
     float keep = b0 ? c[1] : c[0];
     float send = b0 ? c[0] : c[1];
     return keep + dpp_f32<DPP_QUAD_XOR1>(send);
+}
+
+// The same for sums in natural order in every lane (v[i] belongs to index i).
+__device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
+    float u[16];
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        u[k] = (lane & 8) ? v[k + 8] : v[k];
+        u[k + 8] = (lane & 8) ? v[k] : v[k + 8];
+    }
+    return row_reduce_scatter16_swapped(u, lane);
 }
 
 // Sum over the 16 lanes of a row, result in every lane of the row.
