@@ -30,8 +30,11 @@ DEFAULT_WORKLOAD = "llama2_30b_32k_b8"
 ROTATE_BYTES = 1.1e9             # working set to rotate over so reads come from HBM, not the 256 MB LLC
 
 
-# wave64 issue slots per 64x128 chunk with one query head per kv-head (profiles/issue_counters_*.txt)
-ISSUE_SLOTS_PER_CHUNK = {"k": 438, "v": 321 + 16}
+# Wave64 issue slots per 64x128 chunk with one query head per kv-head, the binding resource of
+# these kernels (measured constants of profiles/issue_counters_*.txt; an MFMA counts as 2 slots:
+# about 8 cycles of the port when mixed with vector work).  Peak = 256 CUs x 4 SIMDs x 2.4 GHz /
+# 4 cycles per instruction = 614.4 G wave-instructions/s.
+ISSUE_SLOTS_PER_CHUNK = {"k": 424, "v": 321 + 16}
 
 
 def parse_args():
@@ -420,11 +423,6 @@ def main():
         # the binding resource of these kernels: vector issue slots.  Wave64 instructions per chunk are
         # the measured constants of profiles/issue_counters_*.txt (an MFMA counted as 2 slots: about
         # 8 cycles of the port when mixed with vector work); peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per instruction.
-        "roofline_alu": {"bound": "alu", "kernel": "kv_%s_matvec" % dom,
-                         "achieved": round(n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3) / 1e9, 1),
-                         "peak": 614.4, "unit": "G wave-instructions/s",
-                         "frac": round(n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3) / 614.4e9, 4),
-                         "slots_per_chunk": ISSUE_SLOTS_PER_CHUNK[dom]},
         "kernels": {
             "kv_k_matvec": {"ms": round(packed["k_ms"], 5), "compressed_gbps": round(packed["k_gbps_compressed"], 1),
                             "pct_hbm_peak": round(packed["k_gbps_compressed"] / 80.0, 2),
@@ -446,6 +444,11 @@ def main():
                                    "compressed_gbps": round((packed["k_bytes"] + packed["v_bytes"]) /
                                                             (packed["attn_ms"] * 1e-3) / 1e9, 1)},
     }
+    if w.n_q_heads == w.n_kv_heads:   # the per-chunk constants below were measured for one query head per kv-head
+        slots = n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3)
+        line["roofline_alu"] = {"bound": "alu", "kernel": "kv_%s_matvec" % dom, "achieved": round(slots / 1e9, 1),
+                                "peak": 614.4, "unit": "G wave-instructions/s", "frac": round(slots / 614.4e9, 4),
+                                "slots_per_chunk": ISSUE_SLOTS_PER_CHUNK[dom]}
     if not args.no_side_workloads:
         side = {}
         for idx in (0, 1, 2):
