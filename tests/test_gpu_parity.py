@@ -29,6 +29,24 @@ def test_append_then_decode_matches_oracle(B, H, Hq, L, seed):
     gpu_cases.run_case(B, H, Hq, L, seed)
 
 
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        B, H, G = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 4, 8]))
+        L = int(rng.integers(1, 900))
+        cuts = sorted(set(int(c) for c in rng.integers(1, L + 1, size=int(rng.integers(0, 5))) if c < L))
+        pieces = [b - a for a, b in zip([0] + cuts, cuts + [L])]
+        cases.append((B, H, H * G, L, 100 + i, pieces))
+    return cases
+
+
+@pytest.mark.parametrize("B,H,Hq,L,seed,pieces", _random_shapes(12, 2024))
+def test_random_shapes_and_append_patterns(B, H, Hq, L, seed, pieces):
+    """Seeded random batch / head / group sizes, lengths and append partitions."""
+    gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces)
+
+
 def test_benchmark_configuration_1_llama2_7b_4k():
     w = synth.workload(1)
     sizes = gpu_cases.run_case(w.batch, w.n_kv_heads, w.n_q_heads, w.tokens, 1)
