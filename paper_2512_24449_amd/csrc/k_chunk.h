@@ -83,7 +83,7 @@ __device__ inline int k_mfma_token_base(int n) { return 16 * (n >> 2) + 4 * ((n 
 
 template <int G>
 struct KQueryMfma {
-    uint32_t qh[G][4];  // q of this lane's 8 channels as fp16 pairs (pack-minimum term)
+    uint32_t qh[fold_min<G>() ? 1 : G][4];  // q of this lane's 8 channels as fp16 pairs (pack-minimum term)
     float qsum[G];      // sum of all 128 q values per head
     half8 qA[4];        // Q operand per pair of pack slots
     half8 sel[2];       // selection operands S_0, S_1
@@ -94,10 +94,13 @@ struct KQueryMfma {
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const uint4 raw = *reinterpret_cast<const uint4 *>(q_group + g * D + 8 * col);
-            qh[g][0] = raw.x, qh[g][1] = raw.y, qh[g][2] = raw.z, qh[g][3] = raw.w;
+            const uint32_t rq[4] = {raw.x, raw.y, raw.z, raw.w};
             float s = 0.0f;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) s += half_lo(qh[g][k]) + half_hi(qh[g][k]);
+            for (int k = 0; k < 4; ++k) {
+                if (!fold_min<G>()) qh[g][k] = rq[k];
+                s += half_lo(rq[k]) + half_hi(rq[k]);
+            }
             qsum[g] = row_all_reduce16(s);
         }
         // row = head lane%16, k-value e of k-run lane/16 = channel 8*(4*(lane/16) + (e&3)) + 2jp + (e>>2)
@@ -131,7 +134,8 @@ struct KQueryMfma {
 };
 
 // acc[t][x] (lane (r, n)): sum_d q[head 4r+x][d] code[token, d] / K_MFMA_OUT_SCALE for token
-// k_mfma_token_base(n) + t; ms_row[g] (every lane of row r): sum_d q[g][d] m[group r, d].
+// k_mfma_token_base(n) + t; ms_row[g] (every lane of row r): sum_d q[g][d] m[group r, d], or 0
+// when the minimum is folded into the codes (fold_min<G>(), table built with fold).
 template <int G>
 __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
                                     const KQueryMfma<G> &kq, float4_t (&acc)[4], float (&ms_row)[G]) {
@@ -148,11 +152,13 @@ __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, con
         for (int jj = 0; jj < 2; ++jj) {
             const int j = 2 * jp + jj;
             const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-            expand_pack(raw, P[jj]);
-            const float m = __uint_as_float(raw.k.w);
+            expand_pack<0, fold_min<G>()>(raw, P[jj]);
+            if constexpr (!fold_min<G>()) {
+                const float m = __uint_as_float(raw.k.w);
 #pragma unroll
-            for (int g = 0; g < G; ++g)
-                msum[g] = fmaf(jj ? half_hi(kq.qh[g][jp]) : half_lo(kq.qh[g][jp]), m, msum[g]);
+                for (int g = 0; g < G; ++g)
+                    msum[g] = fmaf(jj ? half_hi(kq.qh[g][jp]) : half_lo(kq.qh[g][jp]), m, msum[g]);
+            }
         }
         // P[jj][t + 2i]: tokens (t + 2i, t + 2i + 8) of pack slot 2jp+jj; column token offset
         // t = parity + 2x
@@ -173,7 +179,7 @@ __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, con
         }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) ms_row[g] = row_all_reduce16(msum[g]);
+    for (int g = 0; g < G; ++g) ms_row[g] = fold_min<G>() ? 0.0f : row_all_reduce16(msum[g]);
 }
 
 }  // namespace packkv

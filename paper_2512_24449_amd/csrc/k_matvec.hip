@@ -144,7 +144,7 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
             float ms[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float v = __shfl(ms_row[g], src_lane);
+                const float v = fold_min<G>() ? 0.0f : __shfl(ms_row[g], src_lane);
                 if (g < 4) {
                     if (G <= 4 || row == 0) ms[g] = v;
                 } else if (row == 1) {
@@ -201,7 +201,7 @@ template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    build_pack_table(table);
+    build_pack_table(table, 0, G > 1 && fold_min<G>());
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x;

@@ -69,14 +69,23 @@ __device__ inline int wave_inclusive_scan(int v) {
 // the table, which on this hardware reads other LDS contents or zero, never faults.
 constexpr int PACK_TABLE_ENTRIES = 80;
 
+// With many query heads per kv-head the per-head pack-minimum terms cost more registers and
+// instructions than adding the minimum to the codes themselves (eight integer adds per pack,
+// code + m <= 15 still fits the subnormal): from this group size on the kernels fold it in.
+template <int G>
+constexpr bool fold_min() { return G >= 8; }
+
 // Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
-// inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).
-__device__ inline void build_pack_table(uint4 *table, int lift = 0) {
+// inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).  fold: the last field is
+// the pack minimum as a bit pattern for both halves (to be added to the unpacked words)
+// instead of float(min).
+__device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false) {
     const uint32_t hb = threadIdx.x;
     if (hb < PACK_TABLE_ENTRIES) {
-        const uint32_t w = hb >> 4;
+        const uint32_t w = hb >> 4, m = hb & 15u;
         const uint32_t m1 = ((1u << w) - 1u) << lift;
-        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w, __float_as_uint(float(hb & 15u)));
+        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w,
+                               fold ? (m << lift) * 0x10001u : __float_as_uint(float(m)));
     }
     __syncthreads();
 }
@@ -200,7 +209,7 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
 // low half, PAIR_HI_LO swaps the halves (P[m] = tokens (m+8, m)), at no cost.
 constexpr uint32_t PAIR_LO_HI = 0x05040100u, PAIR_HI_LO = 0x01000504u;
 
-template <int LIFT = 0>
+template <int LIFT = 0, bool FOLD = false>
 __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8], uint32_t pair_sel = PAIR_LO_HI) {
     const uint32_t A = __builtin_amdgcn_alignbit(r.d1, r.d0, r.sh);    // pack bits [0, 32): tokens 0..7
     const uint32_t hi_ = __builtin_amdgcn_alignbit(r.d2, r.d1, r.sh);  // pack bits [32, 64)
@@ -215,8 +224,8 @@ __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8], uint32_t 
     }
 #pragma unroll
     for (int m = 0; m < 4; ++m) {
-        P[m] = Z0 & M;
-        P[4 + m] = Z1 & M;
+        P[m] = (Z0 & M) + (FOLD ? r.k.w : 0u);  // FOLD: code + pack minimum (table built with fold)
+        P[4 + m] = (Z1 & M) + (FOLD ? r.k.w : 0u);
         if (m < 3) {
             Z0 = __builtin_amdgcn_alignbit(Z0, Z0, w);
             Z1 = __builtin_amdgcn_alignbit(Z1, Z1, w);

@@ -59,24 +59,24 @@ struct VLane {
 template <int G>
 struct VState {
     vfloat4 acc[8];
-    float macc[G][8];
+    float macc[fold_min<G>() ? 1 : G][8];  // unused when the minimum is folded into the codes
     float pm[G];
 
     __device__ inline void clear() {
 #pragma unroll
         for (int j = 0; j < 8; ++j) acc[j] = vfloat4{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            pm[g] = 0.0f;
+        for (int g = 0; g < G; ++g) pm[g] = 0.0f;
+#pragma unroll
+        for (int g = 0; g < (fold_min<G>() ? 1 : G); ++g)
 #pragma unroll
             for (int j = 0; j < 8; ++j) macc[g][j] = 0.0f;
-        }
     }
 };
 
 // Adds the chunk in the LDS buffer at byte offset `cur` of lds_all: lane l is token l of the
 // block with weight pt[g] for head g and token metadata mt (scale | min << 16).  `table` must
-// have been built with lift CODE_LIFT.
+// have been built with lift CODE_LIFT and fold = fold_min<G>().
 template <int G>
 __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *table, const VLane<G> &vl,
                                uint32_t mt, const float (&pt)[G], VState<G> &st) {
@@ -95,7 +95,7 @@ __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *tab
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
-        wsum[g] = row_all_reduce16(w);
+        if (!fold_min<G>()) wsum[g] = row_all_reduce16(w);
     }
     const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + cur + (threadIdx.x & 63) * 8);
     LanePacks lp;
@@ -113,10 +113,12 @@ __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *tab
         // the compiler from hoisting all eight fetches and blowing up register use)
         if (j < 7) raw_next = fetch_pack(lds_all, table, lp.pos(j + 1), lp.header_byte(j + 1));
         __builtin_amdgcn_sched_barrier(0);
-        expand_pack<CODE_LIFT>(raw, P);
-        const float m = __uint_as_float(raw.k.w);
+        expand_pack<CODE_LIFT, fold_min<G>()>(raw, P);
+        if constexpr (!fold_min<G>()) {
+            const float m = __uint_as_float(raw.k.w);
 #pragma unroll
-        for (int g = 0; g < G; ++g) st.macc[g][j] = fmaf(m, wsum[g], st.macc[g][j]);
+            for (int g = 0; g < G; ++g) st.macc[g][j] = fmaf(m, wsum[g], st.macc[g][j]);
+        }
         typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
         const vhalf8 a0 = __builtin_bit_cast(vhalf8, u32x4v{P[0], P[1], P[2], P[3]});
         const vhalf8 a1 = __builtin_bit_cast(vhalf8, u32x4v{P[4], P[5], P[6], P[7]});
@@ -143,12 +145,14 @@ __device__ inline void v_state_store(const VState<G> &st, float (*red)[D + 4], i
     wave_lds_fence();
 #pragma unroll
     for (int g = 0; g < G; ++g) {
+        if constexpr (!fold_min<G>()) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            float v = st.macc[g][j];
-            v += __shfl_xor(v, 16);
-            v += __shfl_xor(v, 32);
-            if (lane < 16) red[g][8 * lane + j] += v;
+            for (int j = 0; j < 8; ++j) {
+                float v = st.macc[g][j];
+                v += __shfl_xor(v, 16);
+                v += __shfl_xor(v, 32);
+                if (lane < 16) red[g][8 * lane + j] += v;
+            }
         }
         float s = st.pm[g];
 #pragma unroll

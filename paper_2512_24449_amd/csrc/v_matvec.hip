@@ -44,7 +44,7 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
-    build_pack_table(table, CODE_LIFT);
+    build_pack_table(table, CODE_LIFT, fold_min<G>());
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
