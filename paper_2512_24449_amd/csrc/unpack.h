@@ -73,7 +73,7 @@ constexpr int PACK_TABLE_ENTRIES = 80;
 // instructions than adding the minimum to the codes themselves (eight integer adds per pack,
 // code + m <= 15 still fits the subnormal): from this group size on the kernels fold it in.
 template <int G>
-constexpr bool fold_min() { return G >= 8; }
+constexpr bool fold_min() { return G >= 4; }
 
 // Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
 // inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).  fold: the last field is
