@@ -67,7 +67,6 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     // the main loop the same memory holds the cross-wave reduction array red[4][G][D + 4]
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
-    __shared__ __attribute__((aligned(16))) float sc_all[G == 1 ? 1 : 4][G][N];  // score transposition
     __shared__ uint4 table[PACK_TABLE_ENTRIES], vtable[PACK_TABLE_ENTRIES];  // K form, V form (lifted codes)
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
@@ -91,8 +90,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
         qsum[0] = kq1.qsum;
     } else {
         kqg.load(a.q + head0 * D, lane);
+        // the sum over all 128 channels is the same in every lane: scalar registers
 #pragma unroll
-        for (int g = 0; g < G; ++g) qsum[g] = kqg.qsum[g];
+        for (int g = 0; g < G; ++g)
+            qsum[g] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(kqg.qsum[g])));
     }
     VLane<G> vl;
     vl.init(blds_all + wave * BLds<G>::BYTES, lane);
@@ -138,7 +139,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                     float ms_row[G];
                     k_chunk_mfma<G>(lds_all, table, lp, kqg, acc, ms_row);
                     // lane (r, n) holds four consecutive tokens of heads 4r..4r+3: through LDS to lane = token
-                    float(*sc)[N] = sc_all[wave];
+                    // the B operand staging of the V phase is idle now and exactly G * 64 floats large
+                    static_assert(BLds<G>::ZERO == int(sizeof(float)) * G * N, "score tile must fit the B staging");
+                    float(*sc)[N] = reinterpret_cast<float(*)[N]>(vl.blds);
                     const int tb = k_mfma_token_base(col);
 #pragma unroll
                     for (int x = 0; x < 4; ++x)
@@ -163,7 +166,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                     float alpha_col = 1.0f;
 #pragma unroll
                     for (int g = 0; g < G; ++g) {
-                        const float m_new = fmaxf(m_ref[g], wave_all_max(s[g]));
+                        // the same value in every lane: keep it in a scalar register
+                        const float m_new = __int_as_float(__builtin_amdgcn_readfirstlane(
+                            __float_as_int(fmaxf(m_ref[g], wave_all_max(s[g])))));
                         const float alpha = exp2_diff(m_ref[g], m_new);
                         m_ref[g] = m_new;
                         l_lane[g] *= alpha;
