@@ -81,9 +81,9 @@ constexpr float K_MFMA_OUT_SCALE = 16384.0f;  // codes enter as code * 2^-24, th
 // holds after k_chunk_mfma.
 __device__ inline int k_mfma_token_base(int n) { return 16 * (n >> 2) + 4 * ((n >> 1) & 1) + 8 * (n & 1); }
 
-template <int G>
+template <int G, bool FOLD = fold_min<G>()>
 struct KQueryMfma {
-    uint32_t qh[fold_min<G>() ? 1 : G][4];  // q of this lane's 8 channels as fp16 pairs (pack-minimum term)
+    uint32_t qh[FOLD ? 1 : G][4];  // q of this lane's 8 channels as fp16 pairs (pack-minimum term)
     float qsum[G];      // sum of all 128 q values per head
     half8 qA[4];        // Q operand per pair of pack slots
     half8 sel[2];       // selection operands S_0, S_1
@@ -98,7 +98,7 @@ struct KQueryMfma {
             float s = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) {
-                if (!fold_min<G>()) qh[g][k] = rq[k];
+                if (!FOLD) qh[g][k] = rq[k];
                 s += half_lo(rq[k]) + half_hi(rq[k]);
             }
             qsum[g] = row_all_reduce16(s);
@@ -135,10 +135,10 @@ struct KQueryMfma {
 
 // acc[t][x] (lane (r, n)): sum_d q[head 4r+x][d] code[token, d] / K_MFMA_OUT_SCALE for token
 // k_mfma_token_base(n) + t; ms_row[g] (every lane of row r): sum_d q[g][d] m[group r, d], or 0
-// when the minimum is folded into the codes (fold_min<G>(), table built with fold).
-template <int G>
+// when the minimum is folded into the codes (FOLD, table built with fold).
+template <int G, bool FOLD = fold_min<G>()>
 __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
-                                    const KQueryMfma<G> &kq, float4_t (&acc)[4], float (&ms_row)[G]) {
+                                    const KQueryMfma<G, FOLD> &kq, float4_t (&acc)[4], float (&ms_row)[G]) {
     const float4_t zero = float4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
     for (int t = 0; t < 4; ++t) acc[t] = zero;
@@ -152,8 +152,8 @@ __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, con
         for (int jj = 0; jj < 2; ++jj) {
             const int j = 2 * jp + jj;
             const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-            expand_pack<0, fold_min<G>()>(raw, P[jj]);
-            if constexpr (!fold_min<G>()) {
+            expand_pack<0, FOLD>(raw, P[jj]);
+            if constexpr (!FOLD) {
                 const float m = __uint_as_float(raw.k.w);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
@@ -179,7 +179,7 @@ __device__ inline void k_chunk_mfma(const uint8_t *lds0, const uint4 *table, con
         }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g) ms_row[g] = fold_min<G>() ? 0.0f : row_all_reduce16(msum[g]);
+    for (int g = 0; g < G; ++g) ms_row[g] = FOLD ? 0.0f : row_all_reduce16(msum[g]);
 }
 
 }  // namespace packkv

@@ -20,6 +20,11 @@
 
 namespace packkv {
 
+// In the K kernel alone, folding the pack minimum into the codes pays from eight heads on
+// (at four it costs 4 % here, while it wins in the V and fused kernels).
+template <int G>
+constexpr bool K_FOLD = G >= 8;
+
 struct KArgs {
     const uint8_t *arena;
     const uint32_t *index;
@@ -90,7 +95,7 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
     const int h = bh % a.H, b = bh / a.H;
     const int row = lane >> 4, col = lane & 15;
     const int64_t head0 = int64_t(b) * a.H * G + h * G;
-    KQueryMfma<G> kq;
+    KQueryMfma<G, K_FOLD<G>> kq;
     kq.load(a.q + head0 * D, lane);
     // this lane's four output tokens inside a block, the heads it holds, where its
     // token group's pack-minimum sums come from
@@ -138,13 +143,13 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
             lp.init(hdr.x, hdr.y, cur + HEADER);
             float4_t acc[4];  // [token offset 0..3] x [head register]
             float ms_row[G];
-            k_chunk_mfma<G>(lds0, table, lp, kq, acc, ms_row);
+            k_chunk_mfma<G, K_FOLD<G>>(lds0, table, lp, kq, acc, ms_row);
 
             // pack-minimum term of this lane's token group, per head register
             float ms[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float v = fold_min<G>() ? 0.0f : __shfl(ms_row[g], src_lane);
+                const float v = K_FOLD<G> ? 0.0f : __shfl(ms_row[g], src_lane);
                 if (g < 4) {
                     if (G <= 4 || row == 0) ms[g] = v;
                 } else if (row == 1) {
@@ -201,7 +206,7 @@ template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    build_pack_table(table, 0, G > 1 && fold_min<G>());
+    build_pack_table(table, 0, G > 1 && K_FOLD<G>);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x;
