@@ -4,8 +4,8 @@
 // by the callers:
 //   score_t = sm_scale * (scale_t * (sum_d q_d code[t,d] + sum_d q_d m[g,d]) + min_t * sum_d q_d)
 //
-// Two forms.  With one query head per kv-head, mixed-precision FMAs read the
-// unpacked fp16 code halves directly and a reduce-scatter inside the 16-lane row
+// Two forms.  With one query head per kv-head, two-element fp16 dot products read
+// unpacked channel pairs directly and a reduce-scatter inside the 16-lane row
 // leaves token 16g+i in lane 16g+i.  With grouped queries the tile is turned on
 // the matrix cores so that one unpack serves all G heads:
 //   C1[channel i][column n] = sum_k A1[i][k] S_x[k][n]         (16x16x32 fp16 MFMA)
@@ -31,47 +31,78 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float float4_u __attribute__((ext_vector_type(4), aligned(4)));
 
 // ---- one query head per kv-head ------------------------------------------------
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
 struct KQueryFma {
-    float qf[8];  // q of this lane's 8 channels
-    float qsum;   // sum of all 128 q values
+    uint32_t qp[4];  // q of this lane's 8 channels as fp16 pairs (channels 2k, 2k+1 in word k)
+    float qf[8];     // the same as fp32 (pack-minimum term)
+    float qsum;      // sum of all 128 q values
 
     // q_head: the 128 fp16 values of the query head
     __device__ inline void load(const __half *q_head, int lane) {
         const uint4 raw = *reinterpret_cast<const uint4 *>(q_head + 8 * (lane & 15));
-        const __half *hq = reinterpret_cast<const __half *>(&raw);
+        qp[0] = raw.x, qp[1] = raw.y, qp[2] = raw.z, qp[3] = raw.w;
         float s = 0.0f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            qf[j] = __half2float(hq[j]);
-            s += qf[j];
+        for (int k = 0; k < 4; ++k) {
+            qf[2 * k] = half_lo(qp[k]);
+            qf[2 * k + 1] = half_hi(qp[k]);
+            s += qf[2 * k] + qf[2 * k + 1];
         }
         qsum = row_all_reduce16(s);
     }
 };
 
+// The four 16-bit fields of a pack, each in the low half of a word (the high half is
+// don't-care): F[f] holds the codes of tokens 4f..4f+3, w bits each, from bit 0 up.
+__device__ inline void pack_fields(const PackRaw &r, uint32_t (&F)[4]) {
+    const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32)
+    const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
+    const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32)
+    const uint32_t s = r.k.y & 31u;  // 4w: table built in the paired form
+    F[0] = A, F[1] = A >> s, F[2] = R, F[3] = R >> s;
+}
+
 // Returns, in lane l, sum_d q_d (code[l, d] + m[l / 16, d]) for token l of the chunk whose
-// header has been parsed into `lp`.
+// header has been parsed into `lp`; `table` in the paired form.
+//
+// Two packs (channels 2jp, 2jp+1 of the lane) are unpacked side by side, one in each
+// 16-bit half of a word: a packed 16-bit shift moves each half by its own pack's width, so
+// every unpacked word is the pair (channel 2jp, channel 2jp+1) of one token, which a
+// two-element fp16 dot product with fp32 accumulation contracts against the matching q pair
+// in one instruction.  The codes stay fp16 subnormal bit patterns (code * 2^-24); the
+// products are exact.
 __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
                                     const KQueryFma &kq, int lane) {
     float acc[16], msum = 0.0f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) acc[i] = 0.0f;
-    // lanes 8..15 of a row take their token halves swapped: the layout row_reduce_scatter16_swapped wants
-    const uint32_t pair_sel = (lane & 8) ? PAIR_HI_LO : PAIR_LO_HI;
+    for (int jp = 0; jp < 4; ++jp) {
+        const PackRaw ra = fetch_pack(lds0, table, lp.pos(2 * jp), lp.header_byte(2 * jp));
+        const PackRaw rb = fetch_pack(lds0, table, lp.pos(2 * jp + 1), lp.header_byte(2 * jp + 1));
+        uint32_t Fa[4], Fb[4];
+        pack_fields(ra, Fa);
+        pack_fields(rb, Fb);
+        const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(rb.k.y, ra.k.y, 0x0c050c01u));
+        const uint32_t masks = __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x05040100u);
+        const half2_t q2 = __builtin_bit_cast(half2_t, kq.qp[jp]);
+        msum = fmaf(kq.qf[2 * jp], __uint_as_float(ra.k.w), msum);
+        msum = fmaf(kq.qf[2 * jp + 1], __uint_as_float(rb.k.w), msum);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-        uint32_t P[8];
-        const PackRaw raw = fetch_pack(lds0, table, lp.pos(j), lp.header_byte(j));
-        expand_pack(raw, P, pair_sel);
-        msum = fmaf(kq.qf[j], __uint_as_float(raw.k.w), msum);
+        for (int f = 0; f < 4; ++f) {
+            u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            // P[k] holds tokens (k, k+8) of the group (swapped in the upper half of the row)
-            acc[k] = fmaf(kq.qf[j], half_lo(P[k]), acc[k]);
-            acc[k + 8] = fmaf(kq.qf[j], half_hi(P[k]), acc[k + 8]);
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t P = __builtin_bit_cast(uint32_t, Z) & masks;  // token 4f+m, both channels
+                if (jp == 0)  // three-address form with a literal zero: no accumulator to clear first
+                    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(acc[4 * f + m]) : "v"(P), "v"(kq.qp[0]));
+                else
+                    acc[4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P), q2, acc[4 * f + m], false);
+                if (m < 3) Z = Z >> widths;
+            }
         }
     }
-    return row_reduce_scatter16_swapped(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
+    return row_reduce_scatter16(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
 }
 
 // ---- grouped queries -------------------------------------------------------------

@@ -206,7 +206,7 @@ template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    build_pack_table(table, 0, G > 1 && K_FOLD<G>);
+    build_pack_table(table, 0, G > 1 && K_FOLD<G>, G == 1);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x;

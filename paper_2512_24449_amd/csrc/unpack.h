@@ -78,13 +78,14 @@ constexpr bool fold_min() { return G >= 4; }
 // Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
 // inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).  fold: the last field is
 // the pack minimum as a bit pattern for both halves (to be added to the unpacked words)
-// instead of float(min).
-__device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false) {
+// instead of float(min).  paired: the width field is 4w in its low byte (a shift amount as it
+// stands) and w in the next byte, the form the pairwise unpack of the single-head K path reads.
+__device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false, bool paired = false) {
     const uint32_t hb = threadIdx.x;
     if (hb < PACK_TABLE_ENTRIES) {
         const uint32_t w = hb >> 4, m = hb & 15u;
         const uint32_t m1 = ((1u << w) - 1u) << lift;
-        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w,
+        table[hb] = make_uint4(m1 | (m1 << 16), paired ? (4 * w) | (w << 8) : w, 8 * w,
                                fold ? (m << lift) * 0x10001u : __float_as_uint(float(m)));
     }
     __syncthreads();
@@ -180,12 +181,12 @@ __device__ inline void wave_lds_fence() {
 // The raw LDS words of one pack and its width-dependent constants.
 struct PackRaw {
     uint32_t d0, d1, d2;  // aligned dwords covering the pack's 64-bit window
-    uint32_t sh;          // low 5 bits: bit offset of the pack inside d0
+    uint32_t sh;          // low 2 bits: byte offset of the pack inside d0
     uint4 k;              // pack table entry
 };
 
 // lds0: start of the workgroup's payload array; pos: byte address inside it
-// (2-byte aligned).  Aligned dword reads plus funnel shifts: misaligned LDS
+// (2-byte aligned).  Aligned dword reads plus byte funnel shifts: misaligned LDS
 // reads, although legal on gfx950, were measured several times slower.
 __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, int pos, uint32_t hb) {
     PackRaw r;
@@ -193,7 +194,7 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
     r.d0 = pp[0];
     r.d1 = pp[1];
     r.d2 = pp[2];
-    r.sh = uint32_t(pos) << 3;
+    r.sh = uint32_t(pos);
 #ifdef EXP_TABLE_SAME
     r.k = table[0x21 + (hb & 0)];
 #else
@@ -205,19 +206,15 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
 // Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
 // 16-bit half is the bit pattern of fp16(code * 2^(LIFT-24)); the table must have been
 // built with the same lift.
-// pair_sel: byte selector that pairs the two token halves; PAIR_LO_HI puts token m in the
-// low half, PAIR_HI_LO swaps the halves (P[m] = tokens (m+8, m)), at no cost.
-constexpr uint32_t PAIR_LO_HI = 0x05040100u, PAIR_HI_LO = 0x01000504u;
-
 template <int LIFT = 0, bool FOLD = false>
-__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8], uint32_t pair_sel = PAIR_LO_HI) {
-    const uint32_t A = __builtin_amdgcn_alignbit(r.d1, r.d0, r.sh);    // pack bits [0, 32): tokens 0..7
-    const uint32_t hi_ = __builtin_amdgcn_alignbit(r.d2, r.d1, r.sh);  // pack bits [32, 64)
+__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
+    const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32): tokens 0..7
+    const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
     const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32): tokens 8..15
     const uint32_t w = r.k.y, M = r.k.x;
     const uint32_t s = 4 * w;
-    uint32_t Z0 = __builtin_amdgcn_perm(R, A, pair_sel);            // tokens 0..3 | 8..11
-    uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, pair_sel);  // tokens 4..7 | 12..15
+    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // tokens 0..3 | 8..11
+    uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, 0x05040100u);  // tokens 4..7 | 12..15
     if (LIFT) {  // rotate left: the codes of both halves move up together, the mask picks them there
         Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - LIFT);
         Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - LIFT);
@@ -236,16 +233,36 @@ __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8], uint32_t 
 __device__ inline float half_lo(uint32_t p) { return float(__builtin_bit_cast(_Float16, uint16_t(p & 0xFFFFu))); }
 __device__ inline float half_hi(uint32_t p) { return float(__builtin_bit_cast(_Float16, uint16_t(p >> 16))); }
 
-// Reduce-scatter inside each row of 16 lanes.  On entry every lane holds 16 partial sums; in
-// lanes 0..7 of the row v[i] belongs to index i, in lanes 8..15 the two halves are swapped
-// (v[i] belongs to index i ^ 8) -- the caller gets that for free from the pairing selector of
-// expand_pack, and it saves the first round of selects here.  On return lane i of the row
-// holds the row's sum for index i.
-__device__ inline float row_reduce_scatter16_swapped(float (&v)[16], int lane) {
+// Reduce-scatter inside each row of 16 lanes.  On entry every lane holds 16 partial sums
+// (v[i] belongs to index i); on return lane i of the row holds the row's sum for index i.  The first
+// round adds the partner lane's value (eight lanes away) with the write restricted to one
+// half of the row per instruction: lanes 0..7 take index k, lanes 8..15 index k+8 -- two adds
+// per output and no selects.  The leading s_nop covers the two wait states between a vector
+// write and a DPP read of the same register, which the compiler does not track into inline
+// assembly.
+__device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
     float a[8], b[4], c[2];
     const bool b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
-#pragma unroll
-    for (int k = 0; k < 8; ++k) a[k] = v[k] + dpp_f32<DPP_ROW_ROR8>(v[k + 8]);
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %4, %12, %12 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %5, %13, %13 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %6, %14, %14 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %7, %15, %15 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %16, %16 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %1, %17, %17 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %2, %18, %18 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %3, %19, %19 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %4, %20, %20 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %5, %21, %21 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %6, %22, %22 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %7, %23, %23 row_ror:8 row_mask:0xf bank_mask:0xc"
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(a[4]), "=&v"(a[5]), "=&v"(a[6]), "=&v"(a[7])
+        : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]),
+          "v"(v[8]), "v"(v[9]), "v"(v[10]), "v"(v[11]), "v"(v[12]), "v"(v[13]), "v"(v[14]), "v"(v[15]));
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         float keep = b2 ? a[k + 4] : a[k];
@@ -261,17 +278,6 @@ __device__ inline float row_reduce_scatter16_swapped(float (&v)[16], int lane) {
     float keep = b0 ? c[1] : c[0];
     float send = b0 ? c[0] : c[1];
     return keep + dpp_f32<DPP_QUAD_XOR1>(send);
-}
-
-// The same for sums in natural order in every lane (v[i] belongs to index i).
-__device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
-    float u[16];
-#pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        u[k] = (lane & 8) ? v[k + 8] : v[k];
-        u[k + 8] = (lane & 8) ? v[k] : v[k + 8];
-    }
-    return row_reduce_scatter16_swapped(u, lane);
 }
 
 // Sum over the 16 lanes of a row, result in every lane of the row.
