@@ -55,13 +55,14 @@ struct KQueryFma {
 };
 
 // The four 16-bit fields of a pack, each in the low half of a word (the high half is
-// don't-care): F[f] holds the codes of tokens 4f..4f+3, w bits each, from bit 0 up.
+// don't-care): F[f] holds the codes of tokens 4f..4f+3, w bits each, from bit 0 up.  The odd
+// fields come out of a bit-field extract with nothing above their 4w bits.
 __device__ inline void pack_fields(const PackRaw &r, uint32_t (&F)[4]) {
     const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32)
     const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
     const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32)
-    const uint32_t s = r.k.y & 31u;  // 4w: table built in the paired form
-    F[0] = A, F[1] = A >> s, F[2] = R, F[3] = R >> s;
+    const uint32_t s = r.k.y;  // low five bits, all the extract reads: 4w (table built in the paired form)
+    F[0] = A, F[1] = __builtin_amdgcn_ubfe(A, s, s), F[2] = R, F[3] = __builtin_amdgcn_ubfe(R, s, s);
 }
 
 // Returns, in lane l, sum_d q_d (code[l, d] + m[l / 16, d]) for token l of the chunk whose
@@ -93,7 +94,8 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint4 *table, con
             u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
-                const uint32_t P = __builtin_bit_cast(uint32_t, Z) & masks;  // token 4f+m, both channels
+                // token 4f+m, both channels; the last code of a clean field needs no mask
+                const uint32_t P = __builtin_bit_cast(uint32_t, Z) & ((f & 1) && m == 3 ? ~0u : masks);
                 if (jp == 0)  // three-address form with a literal zero: no accumulator to clear first
                     asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(acc[4 * f + m]) : "v"(P), "v"(kq.qp[0]));
                 else
