@@ -237,12 +237,13 @@ __device__ inline float half_hi(uint32_t p) { return float(__builtin_bit_cast(_F
 // (v[i] belongs to index i); on return lane i of the row holds the row's sum for index i.  The first
 // round adds the partner lane's value (eight lanes away) with the write restricted to one
 // half of the row per instruction: lanes 0..7 take index k, lanes 8..15 index k+8 -- two adds
-// per output and no selects.  The leading s_nop covers the two wait states between a vector
+// per output and no selects; the second round does the same with the lane four away.  The
+// leading s_nop covers the two wait states between a vector
 // write and a DPP read of the same register, which the compiler does not track into inline
 // assembly.
 __device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
     float a[8], b[4], c[2];
-    const bool b2 = lane & 4, b1 = lane & 2, b0 = lane & 1;
+    const bool b1 = lane & 2, b0 = lane & 1;
     asm("s_nop 1\n\t"
         "v_add_f32_dpp %0, %8, %8 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
         "v_add_f32_dpp %1, %9, %9 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
@@ -263,12 +264,19 @@ __device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
         : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3]), "=&v"(a[4]), "=&v"(a[5]), "=&v"(a[6]), "=&v"(a[7])
         : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]),
           "v"(v[8]), "v"(v[9]), "v"(v[10]), "v"(v[11]), "v"(v[12]), "v"(v[13]), "v"(v[14]), "v"(v[15]));
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-        float keep = b2 ? a[k + 4] : a[k];
-        float send = b2 ? a[k] : a[k + 4];
-        b[k] = keep + __shfl_xor(send, 4);
-    }
+    // second round, partner four lanes away: lanes 0..3 and 8..11 of the row (banks 0, 2) take
+    // index k from the lane four above (rotate right by 12), the others index k+4 from four below
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_ror:4 row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_ror:4 row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_ror:4 row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_ror:4 row_mask:0xf bank_mask:0xa"
+        : "=&v"(b[0]), "=&v"(b[1]), "=&v"(b[2]), "=&v"(b[3])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]), "v"(a[4]), "v"(a[5]), "v"(a[6]), "v"(a[7]));
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         float keep = b1 ? b[k + 2] : b[k];
