@@ -70,7 +70,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     __shared__ uint4 table[PACK_TABLE_ENTRIES], vtable[PACK_TABLE_ENTRIES];  // K form, V form (lifted codes)
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
-    build_pack_table(table, 0, G > 1 && fold_min<G>(), G == 1);
+    if constexpr (G == 1)
+        build_pair_table(reinterpret_cast<uint2 *>(table));
+    else
+        build_pack_table(table, 0, fold_min<G>());
     build_pack_table(vtable, CODE_LIFT, fold_min<G>());
 
     const int lane = threadIdx.x & 63;
@@ -133,7 +136,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                 lp.init(hdr.x, hdr.y, kbuf + HEADER);
                 float u[G];
                 if constexpr (G == 1) {
-                    u[0] = k_chunk_fma(lds_all, table, lp, kq1, lane);
+                    u[0] = k_chunk_fma(lds_all, reinterpret_cast<const uint2 *>(table), lp, kq1, lane);
                 } else {
                     float4_t acc[4];
                     float ms_row[G];

@@ -36,7 +36,6 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
 struct KQueryFma {
     uint32_t qp[4];  // q of this lane's 8 channels as fp16 pairs (channels 2k, 2k+1 in word k)
-    float qf[8];     // the same as fp32 (pack-minimum term)
     float qsum;      // sum of all 128 q values
 
     // q_head: the 128 fp16 values of the query head
@@ -45,11 +44,7 @@ struct KQueryFma {
         qp[0] = raw.x, qp[1] = raw.y, qp[2] = raw.z, qp[3] = raw.w;
         float s = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            qf[2 * k] = half_lo(qp[k]);
-            qf[2 * k + 1] = half_hi(qp[k]);
-            s += qf[2 * k] + qf[2 * k + 1];
-        }
+        for (int k = 0; k < 4; ++k) s += half_lo(qp[k]) + half_hi(qp[k]);
         qsum = row_all_reduce16(s);
     }
 };
@@ -57,16 +52,16 @@ struct KQueryFma {
 // The four 16-bit fields of a pack, each in the low half of a word (the high half is
 // don't-care): F[f] holds the codes of tokens 4f..4f+3, w bits each, from bit 0 up.  The odd
 // fields come out of a bit-field extract with nothing above their 4w bits.
-__device__ inline void pack_fields(const PackRaw &r, uint32_t (&F)[4]) {
+__device__ inline void pack_fields(const PackRawPair &r, uint32_t (&F)[4]) {
     const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32)
     const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
-    const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32)
-    const uint32_t s = r.k.y;  // low five bits, all the extract reads: 4w (table built in the paired form)
+    const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> (r.k.y & 63u));  // bits [8w, 8w+32)
+    const uint32_t s = r.k.x;  // low five bits, all the extract reads: 4w
     F[0] = A, F[1] = __builtin_amdgcn_ubfe(A, s, s), F[2] = R, F[3] = __builtin_amdgcn_ubfe(R, s, s);
 }
 
 // Returns, in lane l, sum_d q_d (code[l, d] + m[l / 16, d]) for token l of the chunk whose
-// header has been parsed into `lp`; `table` in the paired form.
+// header has been parsed into `lp`; `table`: the pair table.
 //
 // Two packs (channels 2jp, 2jp+1 of the lane) are unpacked side by side, one in each
 // 16-bit half of a word: a packed 16-bit shift moves each half by its own pack's width, so
@@ -74,21 +69,21 @@ __device__ inline void pack_fields(const PackRaw &r, uint32_t (&F)[4]) {
 // two-element fp16 dot product with fp32 accumulation contracts against the matching q pair
 // in one instruction.  The codes stay fp16 subnormal bit patterns (code * 2^-24); the
 // products are exact.
-__device__ inline float k_chunk_fma(const uint8_t *lds0, const uint4 *table, const LanePacks &lp,
+__device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, const LanePacks &lp,
                                     const KQueryFma &kq, int lane) {
     float acc[16], msum = 0.0f;
 #pragma unroll
     for (int jp = 0; jp < 4; ++jp) {
-        const PackRaw ra = fetch_pack(lds0, table, lp.pos(2 * jp), lp.header_byte(2 * jp));
-        const PackRaw rb = fetch_pack(lds0, table, lp.pos(2 * jp + 1), lp.header_byte(2 * jp + 1));
+        const PackRawPair ra = fetch_pack_pair(lds0, table, lp.pos(2 * jp), lp.header_byte(2 * jp));
+        const PackRawPair rb = fetch_pack_pair(lds0, table, lp.pos(2 * jp + 1), lp.header_byte(2 * jp + 1));
         uint32_t Fa[4], Fb[4];
         pack_fields(ra, Fa);
         pack_fields(rb, Fb);
-        const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(rb.k.y, ra.k.y, 0x0c050c01u));
-        const uint32_t masks = __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x05040100u);
+        const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x0c050c01u));
+        const uint32_t masks = __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x07060302u);
         const half2_t q2 = __builtin_bit_cast(half2_t, kq.qp[jp]);
-        msum = fmaf(kq.qf[2 * jp], __uint_as_float(ra.k.w), msum);
-        msum = fmaf(kq.qf[2 * jp + 1], __uint_as_float(rb.k.w), msum);
+        msum = fmaf(half_lo(kq.qp[jp]), half_hi(ra.k.y), msum);
+        msum = fmaf(half_hi(kq.qp[jp]), half_hi(rb.k.y), msum);
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));

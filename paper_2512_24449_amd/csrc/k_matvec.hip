@@ -47,7 +47,7 @@ struct KArgs {
 // lds0: the workgroup's chunk buffers; this wave owns the two buffers at byte
 // offsets buf_base and buf_base + CHUNK_LDS.  One query head per kv-head.
 __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
-                                    int lane, uint8_t *lds0, int buf_base, const uint4 *table) {
+                                    int lane, uint8_t *lds0, int buf_base, const uint2 *table) {
     const int h = bh % a.H, b = bh / a.H;
     const int64_t head = int64_t(b) * a.H + h;
     KQueryFma kq;
@@ -206,7 +206,10 @@ template <int G>
 __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    build_pack_table(table, 0, G > 1 && K_FOLD<G>, G == 1);
+    if constexpr (G == 1)
+        build_pair_table(reinterpret_cast<uint2 *>(table));
+    else
+        build_pack_table(table, 0, K_FOLD<G>);
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int grp = blockIdx.x;
@@ -219,7 +222,8 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
         // products and need fewer registers; with grouped queries the unpack is shared by
         // the G heads only in the matrix-core form
         if constexpr (G == 1)
-            k_stream_fma(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
+            k_stream_fma(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS,
+                         reinterpret_cast<const uint2 *>(table));
         else
             k_stream_mfma<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
     } else {

@@ -78,15 +78,30 @@ constexpr bool fold_min() { return G >= 4; }
 // Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
 // inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).  fold: the last field is
 // the pack minimum as a bit pattern for both halves (to be added to the unpacked words)
-// instead of float(min).  paired: the width field is 4w in its low byte (a shift amount as it
-// stands) and w in the next byte, the form the pairwise unpack of the single-head K path reads.
-__device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false, bool paired = false) {
+// instead of float(min).
+__device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false) {
     const uint32_t hb = threadIdx.x;
     if (hb < PACK_TABLE_ENTRIES) {
         const uint32_t w = hb >> 4, m = hb & 15u;
         const uint32_t m1 = ((1u << w) - 1u) << lift;
-        table[hb] = make_uint4(m1 | (m1 << 16), paired ? (4 * w) | (w << 8) : w, 8 * w,
+        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w,
                                fold ? (m << lift) * 0x10001u : __float_as_uint(float(m)));
+    }
+    __syncthreads();
+}
+
+// Pack table of the single-head K path, which unpacks two packs side by side: eight bytes
+// per entry (half the LDS traffic and bank conflicts of the 16-byte form), every field placed
+// where its consumer reads it without a shift:
+//   x: 4w in bits 0..4 (a bit-field offset/width as it stands), w in byte 1, the w-bit code
+//      mask in the high half
+//   y: 8w in bits 0..5 (a 64-bit shift amount as it stands), fp16(pack minimum) in the high half
+__device__ inline void build_pair_table(uint2 *table) {
+    const uint32_t hb = threadIdx.x;
+    if (hb < PACK_TABLE_ENTRIES) {
+        const uint32_t w = hb >> 4, m = hb & 15u;
+        const uint32_t m16 = __half_as_ushort(__float2half(float(m)));
+        table[hb] = make_uint2((4 * w) | (w << 8) | (((1u << w) - 1u) << 16), (8 * w) | (m16 << 16));
     }
     __syncthreads();
 }
@@ -200,6 +215,23 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
 #else
     r.k = table[hb];
 #endif
+    return r;
+}
+
+// The same with an entry of the pair table.
+struct PackRawPair {
+    uint32_t d0, d1, d2, sh;
+    uint2 k;
+};
+
+__device__ inline PackRawPair fetch_pack_pair(const uint8_t *lds0, const uint2 *table, int pos, uint32_t hb) {
+    PackRawPair r;
+    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
+    r.d0 = pp[0];
+    r.d1 = pp[1];
+    r.d2 = pp[2];
+    r.sh = uint32_t(pos);
+    r.k = table[hb];
     return r;
 }
 
