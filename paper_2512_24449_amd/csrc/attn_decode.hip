@@ -121,7 +121,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
             const bool valid = ik.end16(it) - ik.start16(it) >= uint32_t(HEADER / 16) &&
                                iv.end16(it) - iv.start16(it) >= uint32_t(HEADER / 16);
             wait_chunk_landed();  // K chunk of this block
-            const uint32_t kmt = kmt_next, vmt = vmt_next;
+            uint32_t kmt = kmt_next, vmt = vmt_next;
+            consume_here(kmt), consume_here(vmt);
             chunk_issue_lds(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             if (it + 1 < n_it) {
                 const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane;

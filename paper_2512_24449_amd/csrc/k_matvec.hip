@@ -57,18 +57,27 @@ __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int b
         IndexBatch ib;
         ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
+        vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
+        vmem_order_fence();
         uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
         for (int it = 0; it < n_it; ++it) {
             const int cur = buf_base + (it & 1) * CHUNK_LDS;
             const int64_t tok = int64_t(first + 4 * it) * N + lane;  // this lane's token after the reduction
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
-            wait_chunk_landed();
-            const uint32_t mt = mt_next;
+            // issued after this chunk's transfers, and allowed to stay in flight: the metadata
+            // load and, from the second iteration on, the previous iteration's score store
+            if (it == 0)
+                wait_chunk_landed_except<1>();
+            else
+                wait_chunk_landed_except<2>();
+            uint32_t mt = mt_next;
+            consume_here(mt);
             // the next chunk streams into the other buffer while this one is unpacked
             if (it + 1 < n_it) {
                 chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
                                 lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
+                vmem_order_fence();
                 mt_next = a.meta[b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane];
             }
             if (!valid) {  // block dropped by an arena overflow: defined output
@@ -121,7 +130,8 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
             const int64_t tok = int64_t(first + 4 * it) * N + tok_base;
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
             wait_chunk_landed();
-            const uint4 mt = mt_next;
+            uint4 mt = mt_next;
+            consume_here(mt.x), consume_here(mt.y), consume_here(mt.z), consume_here(mt.w);
             // the next chunk streams into the other buffer while this one is unpacked
             if (it + 1 < n_it) {
                 chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
@@ -218,9 +228,9 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
         const int part = grp % a.groups_per_stream;
         const int blk_begin = part * a.blocks_per_group;
         const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
-        // one query head per kv-head: plain FMAs cost the same issue slots as the two matrix
-        // products and need fewer registers; with grouped queries the unpack is shared by
-        // the G heads only in the matrix-core form
+        // one query head per kv-head: pairwise dot products cost fewer issue slots than the two
+        // matrix products and need fewer registers; with grouped queries the unpack is shared
+        // by the G heads only in the matrix-core form
         if constexpr (G == 1)
             k_stream_fma(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS,
                          reinterpret_cast<const uint2 *>(table));

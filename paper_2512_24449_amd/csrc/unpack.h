@@ -164,26 +164,54 @@ constexpr int CHUNK_LDS = CHUNK_MAX;
 // block (size 0) transfers nothing.  Lanes past the chunk end re-read its last
 // 16 bytes into buffer bytes nobody decodes; the fifth slice only uses lanes
 // 0..31 because the buffer is 4608 bytes.
+//
+// The instruction is issued from inline assembly on purpose.  Issued through the
+// compiler's builtin, every later LDS read of the wave -- also of the OTHER buffer --
+// is preceded by a compiler-inserted wait for all outstanding transfers (it cannot tell the
+// buffers apart), which serializes transfer and unpack inside a wave.  Here the waits
+// are explicit (wait_chunk_landed*), counted by the callers.  M0 carries the LDS base;
+// the s_nop is the wait state between writing M0 and the transfer that reads it.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"  // M0 is a reserved register; naming it as clobbered is the point
 __device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
                                        uint8_t *buf, int lane) {
     const int size = int(o1 - o0) * 16;
     if (size < HEADER) return;
     const uint8_t *chunk = arena + size_t(o0) * 16;
     const int last = size - 16;
+    const uint32_t lds = uint32_t(uintptr_t((__attribute__((address_space(3))) void *)buf));
 #pragma unroll
     for (int k = 0; k < 5; ++k) {
         if (k * 1024 < size && (k < 4 || lane < 32)) {
             const int off = k * 1024 + lane * 16;
-            __builtin_amdgcn_global_load_lds(
-                (const __attribute__((address_space(1))) void *)(chunk + (off < last ? off : last)),
-                (__attribute__((address_space(3))) void *)(buf + k * 1024), 16, 0, 0);
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                         :
+                         : "s"(lds + k * 1024), "v"(off < last ? off : last), "s"(chunk)
+                         : "memory", "m0");
         }
     }
 }
+#pragma clang diagnostic pop
 
 // All outstanding global->LDS transfers (and other vector memory operations) of
 // this wave have landed.
 __device__ inline void wait_chunk_landed() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// The same while the LATER newest vector memory operations of this wave (issued after the
+// chunk's transfers: a metadata load, a result store) may stay in flight; the counter retires
+// in issue order.  Callers keep the issue order fixed with vmem_order_fence().
+template <int LATER>
+__device__ inline void wait_chunk_landed_except() {
+    static_assert(LATER >= 0 && LATER < 8, "");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LATER) : "memory");
+}
+// Compiler-only fence: memory operations are not moved across it.
+__device__ inline void vmem_order_fence() { asm volatile("" ::: "memory"); }
+// Makes a value that was loaded ahead count as used here, so that the compiler's own wait
+// for that load sits at this point (right after an explicit wait, where it costs nothing) and
+// not later, behind the next chunk's transfers, which it would then wait for as well.
+__device__ inline void consume_here(uint32_t &x) { asm volatile("" : "+v"(x)); }
+__device__ inline void consume_here(float &x) { asm volatile("" : "+v"(x)); }
 
 // LDS writes of this wave become visible to its own later LDS reads in program
 // order; the fences only stop the compiler from moving accesses across.

@@ -73,10 +73,14 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
             const int cur = buf_base + (it & 1) * CHUNK_LDS;
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
             wait_chunk_landed();
-            const uint32_t mt = mt_next;
+            uint32_t mt = mt_next;
+            consume_here(mt);
             float pt[G];
 #pragma unroll
-            for (int g = 0; g < G; ++g) pt[g] = p_next[g];
+            for (int g = 0; g < G; ++g) {
+                pt[g] = p_next[g];
+                consume_here(pt[g]);
+            }
             // the next chunk streams into the other buffer while this one is unpacked
             if (it + 1 < n_it) {
                 chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
