@@ -36,6 +36,7 @@ constexpr float CODE_SCALE_LIFTED = 262144.0f;  // 2^18
 constexpr int DPP_QUAD_XOR1 = 0xB1;  // quad_perm [1,0,3,2]
 constexpr int DPP_QUAD_XOR2 = 0x4E;  // quad_perm [2,3,0,1]
 constexpr int DPP_ROW_ROR8 = 0x128;  // lane i <- lane i^8 of its row
+constexpr int DPP_ROW_ROR4 = 0x124;  // lane i <- lane (i-4) mod 16 of its row
 constexpr int DPP_ROW_SHR1 = 0x111, DPP_ROW_SHR2 = 0x112, DPP_ROW_SHR4 = 0x114, DPP_ROW_SHR8 = 0x118;
 constexpr int DPP_ROW_BCAST15 = 0x142, DPP_ROW_BCAST31 = 0x143;
 
@@ -351,7 +352,7 @@ __device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
 // Sum over the 16 lanes of a row, result in every lane of the row.
 __device__ inline float row_all_reduce16(float v) {
     v += dpp_f32<DPP_ROW_ROR8>(v);
-    v += __shfl_xor(v, 4);
+    v += dpp_f32<DPP_ROW_ROR4>(v);  // lanes i, i+4, i+8, i+12: the set is closed under the rotation
     v += dpp_f32<DPP_QUAD_XOR2>(v);
     v += dpp_f32<DPP_QUAD_XOR1>(v);
     return v;
