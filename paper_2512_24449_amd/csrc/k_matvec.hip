@@ -82,6 +82,7 @@ __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int b
             }
             if (!valid) {  // block dropped by an arena overflow: defined output
                 a.scores[head * a.ld + tok] = 0.0f;
+                wait_chunk_landed();  // rare path: keep the next wait's count independent of it
                 continue;
             }
             const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
@@ -122,20 +123,29 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
         IndexBatch ib;
         ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
+        vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
+        vmem_order_fence();
         const uint32_t *meta = a.meta + b * a.meta_stride + tok_base;
         uint4 mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first) * N);
         for (int it = 0; it < n_it; ++it) {
             const int cur = buf_base + (it & 1) * CHUNK_LDS;
             const int64_t tok = int64_t(first + 4 * it) * N + tok_base;
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
-            wait_chunk_landed();
+            // issued after this chunk's transfers, and allowed to stay in flight: the metadata
+            // load and, from the second iteration on, the previous iteration's score stores (one
+            // instruction per head register, also for a dropped block)
+            if (it == 0)
+                wait_chunk_landed_except<1>();
+            else
+                wait_chunk_landed_except<1 + (G < 4 ? G : 4)>();
             uint4 mt = mt_next;
             consume_here(mt.x), consume_here(mt.y), consume_here(mt.z), consume_here(mt.w);
             // the next chunk streams into the other buffer while this one is unpacked
             if (it + 1 < n_it) {
                 chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
                                 lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
+                vmem_order_fence();
                 mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first + 4 * (it + 1)) * N);
             }
             if (!valid) {  // block dropped by an arena overflow: defined output
@@ -146,6 +156,7 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
                             *reinterpret_cast<float4_u *>(a.scores + (head0 + 4 * row + x) * a.ld + tok) =
                                 float4_u{0.0f, 0.0f, 0.0f, 0.0f};
                 }
+                wait_chunk_landed();  // rare path: keep the next wait's count independent of it
                 continue;
             }
             const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
