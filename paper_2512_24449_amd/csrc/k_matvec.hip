@@ -81,8 +81,7 @@ __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int b
                 mt_next = a.meta[b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane];
             }
             if (!valid) {  // block dropped by an arena overflow: defined output
-                a.scores[head * a.ld + tok] = 0.0f;
-                wait_chunk_landed();  // rare path: keep the next wait's count independent of it
+                a.scores[head * a.ld + tok] = 0.0f;  // one store, as on the regular path: the count holds
                 continue;
             }
             const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
