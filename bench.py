@@ -470,7 +470,7 @@ def main():
             del Ks, Vs
             torch.cuda.empty_cache()
         gw = synth.workload(4)
-        g = run_growing(gw, 256, torch, binding, synth)
+        g = run_growing(gw, gw.decode_steps, torch, binding, synth)
         side[gw.name] = g
         side["timing_note"] = ("per-kernel times are HIP event intervals on the launch stream; for kernels under "
                                "about 20 us they include host submission latency (the GPU runs ahead of the "
