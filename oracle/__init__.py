@@ -56,7 +56,9 @@ def lib():
         _lib.orc_xhat.restype = C.c_double
         _lib.orc_xhat.argtypes = [C.c_uint8, C.c_uint16, C.c_uint16]
         _lib.orc_pack_chunk.restype = C.c_int
+        _lib.orc_pack_chunk_k.restype = C.c_int
         _lib.orc_compress.restype = C.c_int64
+        _lib.orc_compress_k.restype = C.c_int64
         _lib.orc_threads.restype = C.c_int
     return _lib
 
@@ -130,14 +132,16 @@ def dequant(q, scale16, min16):
     return out
 
 
-def pack_chunk(q_chunk):
-    """q_chunk: uint8 [64, 128] -> (bytes uint8 [size], widths [512], mins [512])."""
+def pack_chunk(q_chunk, pack_size=K):
+    """q_chunk: uint8 [64, 128] -> (bytes uint8 [size], widths [packs], mins [packs]), packs =
+    (64 / pack_size) * 128."""
     q_chunk = np.ascontiguousarray(q_chunk, dtype=np.uint8)
-    assert q_chunk.shape == (N, D)
-    buf = np.zeros(CHUNK_MAX + 16, np.uint8)
-    w = np.empty(PACKS, np.uint8)
-    m = np.empty(PACKS, np.uint8)
-    size = lib().orc_pack_chunk(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m))
+    assert q_chunk.shape == (N, D) and pack_size in (8, 16)
+    packs = N // pack_size * D
+    buf = np.zeros(packs + N * D // 2 + 16, np.uint8)
+    w = np.empty(packs, np.uint8)
+    m = np.empty(packs, np.uint8)
+    size = lib().orc_pack_chunk_k(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), pack_size)
     return buf[:size].copy(), w, m
 
 
@@ -149,8 +153,8 @@ class Compressed:
         self.offsets16 = offsets16  # uint32 [nchunks + 1], 16-byte units
         self.meta = meta            # uint32 [B, T]: scale16 | min16 << 16
         self.codes = codes          # uint8 [B, T, H, D]
-        self.widths = widths        # uint8 [nchunks, 512]
-        self.mins = mins            # uint8 [nchunks, 512]
+        self.widths = widths        # uint8 [nchunks, packs]
+        self.mins = mins            # uint8 [nchunks, packs]
 
     @property
     def scale16(self):
@@ -161,22 +165,23 @@ class Compressed:
         return (self.meta >> 16).astype(np.uint16)
 
 
-def compress(x, rel) -> Compressed:
-    """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed."""
+def compress(x, rel, pack_size=K) -> Compressed:
+    """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed (packs of pack_size tokens)."""
     x = _u16(x)
     B, T, H, Dd = x.shape
-    assert Dd == D and T % N == 0
+    assert Dd == D and T % N == 0 and pack_size in (8, 16)
+    packs = N // pack_size * D
     nchunks = (T // N) * B * H
-    cap = nchunks * CHUNK_MAX
+    cap = nchunks * (packs + N * D // 2)
     arena = np.zeros(cap, np.uint8)
     offsets = np.zeros(nchunks + 1, np.uint32)
     meta = np.empty((B, T), np.uint32)
     codes = np.empty((B, T, H, Dd), np.uint8)
-    widths = np.empty((nchunks, PACKS), np.uint8)
-    mins = np.empty((nchunks, PACKS), np.uint8)
-    size = lib().orc_compress(_p(x), B, T, H, Dd, C.c_int64(T * H * Dd), C.c_int64(H * Dd),
-                              C.c_float(rel), _p(arena), C.c_int64(cap), _p(offsets), _p(meta),
-                              _p(codes), _p(widths), _p(mins))
+    widths = np.empty((nchunks, packs), np.uint8)
+    mins = np.empty((nchunks, packs), np.uint8)
+    size = lib().orc_compress_k(_p(x), B, T, H, Dd, C.c_int64(T * H * Dd), C.c_int64(H * Dd),
+                                C.c_float(rel), _p(arena), C.c_int64(cap), _p(offsets), _p(meta),
+                                _p(codes), _p(widths), _p(mins), pack_size)
     assert size >= 0, size
     return Compressed(arena[:size].copy(), offsets, meta, codes, widths, mins)
 

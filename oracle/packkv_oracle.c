@@ -11,9 +11,10 @@
  * Codec steps follow the paper in its own order:
  *   Sec. III-B.2 / Sec. IV-A  token-wise quantization with a relative scale
  *                             (scale = rel * (max - min), error <= scale/2)
- *   Sec. III-B.3              bit-packing: a pack of k=16 integers along
- *                             ctx_len shares one minimum and one width
- *                             ceil(log2(range+1))
+ *   Sec. III-B.3              bit-packing: a pack of k integers along
+ *                             ctx_len (k = 16 by default, k = 8 as the second
+ *                             point of the pack-size study, Sec. IV-B) shares
+ *                             one minimum and one width ceil(log2(range+1))
  *   Sec. III-B.4              every 2-D block becomes one contiguous chunk,
  *                             appended at the end of the buffer, plus an index
  * The matvecs are the plain definitions (Sec. III-B.3 boxed statement):
@@ -26,9 +27,10 @@
  *   - fp32 subtract and divide, round-half-to-even, clamp to [0, qmax],
  *     qmax = round(1/rel); scale == 0 gives code 0;
  *   - pack metadata is one byte, (width << 4) | min;
- *   - chunk bytes: 512 header bytes indexed [token_group*128 + channel], then
- *     the packs in the same order, each 2*width bytes little-endian with the
- *     code of token i at bits [i*width, (i+1)*width), zero padded to 16 bytes;
+ *   - chunk bytes: (64/k)*128 header bytes indexed [token_group*128 + channel]
+ *     (512 for k = 16, 1024 for k = 8), then the packs in the same order, each
+ *     k*width/8 bytes little-endian with the code of token i at bits
+ *     [i*width, (i+1)*width), zero padded to 16 bytes;
  *   - repacking (V-median and greedy orders): see the comments of
  *     orc_v_median_order and orc_greedy_order; the median and tie conventions
  *     are "parity unpinned" readings (any order is a valid cache).
@@ -44,11 +46,13 @@
 
 #define ORC_D 128      /* head_dim                                  */
 #define ORC_N 64       /* tokens per block (truncated block size)   */
-#define ORC_K 16       /* pack size                                 */
+#define ORC_K 16       /* default pack size                         */
 #define ORC_GROUPS (ORC_N / ORC_K)
 #define ORC_PACKS (ORC_GROUPS * ORC_D)
 #define ORC_HEADER ORC_PACKS
 #define ORC_CHUNK_MAX (ORC_HEADER + ORC_PACKS * 8)
+/* any pack size k in {8, 16}: 64/k * 128 header bytes + 64*128*4/8 payload bytes */
+#define ORC_CHUNK_MAX_ANY (2 * ORC_PACKS + ORC_N * ORC_D / 2)
 
 /* ---------------------------------------------------------------- fp16 -- */
 
@@ -194,22 +198,23 @@ int orc_width(int range)
 }
 
 /*
- * Pack one chunk: the 64 x 128 codes of one (batch, kv-head, block).
- * q points at code (token 0, channel 0); consecutive tokens are `token_stride`
- * apart.  Writes the chunk bytes (header, payload, zero padding to 16 bytes)
- * and, when not NULL, the logical per-pack widths and minimums [512].
- * Returns the chunk size in bytes (a multiple of 16).
+ * Pack one chunk: the 64 x 128 codes of one (batch, kv-head, block), packs of k
+ * tokens (k = 8 or 16).  q points at code (token 0, channel 0); consecutive
+ * tokens are `token_stride` apart.  Writes the chunk bytes (header, payload,
+ * zero padding to 16 bytes) and, when not NULL, the logical per-pack widths and
+ * minimums [(64/k)*128].  Returns the chunk size in bytes (a multiple of 16).
  */
-int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
-                   uint8_t *widths, uint8_t *mins)
+int orc_pack_chunk_k(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
+                     uint8_t *widths, uint8_t *mins, int k)
 {
-    int pos = ORC_HEADER;
-    for (int g = 0; g < ORC_GROUPS; ++g)
+    int groups = ORC_N / k;
+    int pos = groups * ORC_D;
+    for (int g = 0; g < groups; ++g)
         for (int d = 0; d < ORC_D; ++d) {
             int p = g * ORC_D + d;
             int lo = 255, hi = 0;
-            for (int i = 0; i < ORC_K; ++i) {
-                int v = q[(int64_t)(g * ORC_K + i) * token_stride + d];
+            for (int i = 0; i < k; ++i) {
+                int v = q[(int64_t)(g * k + i) * token_stride + d];
                 if (v < lo) lo = v;
                 if (v > hi) hi = v;
             }
@@ -218,15 +223,21 @@ int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
             if (widths) widths[p] = (uint8_t)w;
             if (mins) mins[p] = (uint8_t)lo;
             uint64_t bits = 0;
-            for (int i = 0; i < ORC_K; ++i) {
-                uint64_t c = (uint64_t)(q[(int64_t)(g * ORC_K + i) * token_stride + d] - lo);
+            for (int i = 0; i < k; ++i) {
+                uint64_t c = (uint64_t)(q[(int64_t)(g * k + i) * token_stride + d] - lo);
                 bits |= c << (i * w);
             }
-            for (int j = 0; j < 2 * w; ++j)
+            for (int j = 0; j < k * w / 8; ++j)
                 bytes[pos++] = (uint8_t)(bits >> (8 * j));
         }
     while (pos % 16) bytes[pos++] = 0;
     return pos;
+}
+
+int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
+                   uint8_t *widths, uint8_t *mins)
+{
+    return orc_pack_chunk_k(q, token_stride, bytes, widths, mins, ORC_K);
 }
 
 /*
@@ -235,16 +246,17 @@ int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
  * order, so chunk index c = (block*B + b)*H + h.  offsets16[c] is the start of
  * chunk c in 16-byte units, offsets16[nchunks] the end of the arena.
  * meta[b*T + t] = scale16 | min16 << 16.  q_out (optional) receives the codes,
- * widths_out / mins_out (optional) the per-pack values [nchunks][512].
+ * widths_out / mins_out (optional) the per-pack values [nchunks][(64/k)*128].
  * Returns the arena size in bytes, or -1 if it would exceed arena_cap.
  */
-int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
-                     int64_t batch_stride, int64_t token_stride, float rel,
-                     uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
-                     uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
-                     uint8_t *mins_out)
+int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
+                       int64_t batch_stride, int64_t token_stride, float rel,
+                       uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
+                       uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
+                       uint8_t *mins_out, int k)
 {
-    if (D != ORC_D || T % ORC_N) return -2;
+    if (D != ORC_D || T % ORC_N || (k != 8 && k != 16)) return -2;
+    int packs = ORC_N / k * ORC_D;
     int64_t n = (int64_t)B * T;
     uint16_t *scale16 = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
     uint16_t *min16 = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
@@ -256,15 +268,15 @@ int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
 
     int nblk = T / ORC_N;
     int64_t pos = 0, c = 0;
-    uint8_t tmp[ORC_CHUNK_MAX + 16];
+    uint8_t tmp[ORC_CHUNK_MAX_ANY + 16];
     int64_t rc = 0;
     for (int blk = 0; blk < nblk && rc == 0; ++blk)
         for (int b = 0; b < B && rc == 0; ++b)
             for (int h = 0; h < H; ++h, ++c) {
                 const uint8_t *q0 = q + (((int64_t)b * T + (int64_t)blk * ORC_N) * H + h) * D;
-                int sz = orc_pack_chunk(q0, (int64_t)H * D, tmp,
-                                        widths_out ? widths_out + c * ORC_PACKS : NULL,
-                                        mins_out ? mins_out + c * ORC_PACKS : NULL);
+                int sz = orc_pack_chunk_k(q0, (int64_t)H * D, tmp,
+                                          widths_out ? widths_out + c * packs : NULL,
+                                          mins_out ? mins_out + c * packs : NULL, k);
                 if (pos + sz > arena_cap) { rc = -1; break; }
                 memcpy(arena + pos, tmp, (size_t)sz);
                 offsets16[c] = (uint32_t)(pos / 16);
@@ -275,6 +287,16 @@ int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
     free(min16);
     if (!q_out) free(q);
     return rc ? rc : pos;
+}
+
+int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
+                     int64_t batch_stride, int64_t token_stride, float rel,
+                     uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
+                     uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
+                     uint8_t *mins_out)
+{
+    return orc_compress_k(x, B, T, H, D, batch_stride, token_stride, rel, arena, arena_cap,
+                          offsets16, meta, q_out, widths_out, mins_out, ORC_K);
 }
 
 /*

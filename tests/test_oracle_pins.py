@@ -109,40 +109,61 @@ def test_width_table(orc):
         assert w == int(np.ceil(np.log2(r + 1)))
 
 
+@pytest.mark.parametrize("k", [16, 8])
 @pytest.mark.parametrize("seed", [0, 1, 2])
-def test_pack_chunk_against_independent_reader(orc, seed):
+def test_pack_chunk_against_independent_reader(orc, seed, k):
     rng = np.random.default_rng(seed)
     q = rng.integers(0, 11, size=(64, 128)).astype(np.uint8)
     q[:, 3] = 7                 # constant channel: width 0
     q[16:32, 9] = [0, 1] * 8    # width 1
     q[:, 40:60] = rng.integers(4, 7, size=(64, 20))
-    buf, widths, mins = orc.pack_chunk(q)
-    codes, w2, m2 = chunk_reader.read_chunk(buf)
+    buf, widths, mins = orc.pack_chunk(q, k)
+    codes, w2, m2 = chunk_reader.read_chunk(buf, k)
     assert np.array_equal(codes, q)
     assert np.array_equal(w2, widths) and np.array_equal(m2, mins)
     # per-pack minimum and minimal width, recomputed from the definition
-    packs = q.reshape(4, 16, 128).astype(np.int64)
-    assert np.array_equal(mins.reshape(4, 128), packs.min(1))
+    packs = q.reshape(64 // k, k, 128).astype(np.int64)
+    assert np.array_equal(mins.reshape(64 // k, 128), packs.min(1))
     rng_ = packs.max(1) - packs.min(1)
-    assert np.array_equal(widths.reshape(4, 128), np.ceil(np.log2(rng_ + 1)).astype(np.int64))
-    # closed-form size: header + 2 bytes per width bit per pack, padded to 16
-    assert buf.size == (512 + 2 * int(widths.sum()) + 15) // 16 * 16
+    assert np.array_equal(widths.reshape(64 // k, 128), np.ceil(np.log2(rng_ + 1)).astype(np.int64))
+    # closed-form size: header + k/8 bytes per width bit per pack, padded to 16
+    assert buf.size == (64 // k * 128 + k // 8 * int(widths.sum()) + 15) // 16 * 16
 
 
+def test_pack_size_8_against_pack_size_16(orc):
+    """A pack of 16 is the union of two packs of 8: its minimum is the smaller of theirs and
+    its range covers both, so its width is never below either's; on a constant-per-half
+    channel the two halves need no bits while the pack of 16 does."""
+    rng = np.random.default_rng(5)
+    q = rng.integers(0, 11, size=(64, 128)).astype(np.uint8)
+    q[0:8, 17], q[8:16, 17] = 2, 9
+    _, w16, m16 = orc.pack_chunk(q, 16)
+    _, w8, m8 = orc.pack_chunk(q, 8)
+    w16, m16 = w16.reshape(4, 128), m16.reshape(4, 128)
+    w8, m8 = w8.reshape(4, 2, 128), m8.reshape(4, 2, 128)
+    assert np.array_equal(m16, m8.min(1))
+    assert (w16 >= w8.max(1)).all()
+    assert w8[0, 0, 17] == 0 and w8[0, 1, 17] == 0 and w16[0, 17] == 3
+
+
+@pytest.mark.parametrize("k", [16, 8])
 @pytest.mark.parametrize("B,T,H,rel,seed", [(1, 128, 1, 0.1, 0), (2, 192, 3, 0.2, 1), (1, 64, 8, 0.1, 2)])
-def test_compress_round_trip_and_size_formula(orc, B, T, H, rel, seed):
+def test_compress_round_trip_and_size_formula(orc, B, T, H, rel, seed, k):
     K, _, _ = _kv(B, T, H, seed)
-    c = orc.compress(K, rel)
+    c = orc.compress(K, rel, k)
     nchunks = (T // 64) * B * H
+    header, per_bit = 64 // k * 128, k // 8
     assert c.offsets16[0] == 0 and int(c.offsets16[nchunks]) * 16 == c.arena.size
-    assert np.array_equal(chunk_reader.read_arena(c.arena, c.offsets16, B, T, H), c.codes)
-    # bits per element = mean width + 8/16 (pack byte) + padding; token meta adds 32/(H*D)
+    assert np.array_equal(chunk_reader.read_arena(c.arena, c.offsets16, B, T, H, k), c.codes)
+    # the codes themselves do not depend on the pack size
+    assert np.array_equal(c.codes, orc.compress(K, rel).codes)
+    # bits per element = mean width + 8/k (pack byte) + padding; token meta adds 32/(H*D)
     sizes = np.diff(c.offsets16.astype(np.int64)) * 16
-    expect = (512 + 2 * c.widths.astype(np.int64).sum(1) + 15) // 16 * 16
+    expect = (header + per_bit * c.widths.astype(np.int64).sum(1) + 15) // 16 * 16
     assert np.array_equal(sizes, expect)
-    pad_bits = (sizes - 512 - 2 * c.widths.astype(np.int64).sum(1)).sum() * 8
+    pad_bits = (sizes - header - per_bit * c.widths.astype(np.int64).sum(1)).sum() * 8
     bits = c.arena.size * 8 / K.size
-    assert np.isclose(bits, c.widths.mean() + 0.5 + pad_bits / K.size)
+    assert np.isclose(bits, c.widths.mean() + 8 / k + pad_bits / K.size)
 
 
 def _fixed_width_tensor(b, g_heads, T=64, seed=0):
