@@ -46,15 +46,17 @@ extern "C" {
 
 #define KV_OK 0
 #define KV_ERR_ARG (-1)          /* null pointer, bad size, misaligned buffer        */
-#define KV_ERR_UNSUPPORTED (-2)  /* head_dim != 128, block != 64, pack != 16, rel... */
+#define KV_ERR_UNSUPPORTED (-2)  /* head_dim != 128, block != 64, pack size, rel...  */
 #define KV_ERR_CAPACITY (-3)     /* append beyond max_tokens / arena too small       */
 #define KV_ERR_HIP (-4)          /* a HIP runtime call failed                        */
 
 #define KV_HEAD_DIM 128
 #define KV_BLOCK_TOKENS 64
-#define KV_PACK_SIZE 16
-#define KV_CHUNK_HEADER 512
-#define KV_CHUNK_MAX_BYTES (512 + 512 * 8)
+#define KV_PACK_SIZE 16                      /* default pack size                      */
+#define KV_CHUNK_HEADER 512                  /* header bytes of a chunk, packs of 16   */
+#define KV_CHUNK_MAX_BYTES (512 + 512 * 8)   /* largest chunk, packs of 16             */
+#define KV_CHUNK_HEADER_PACK8 1024           /* the same with packs of 8 tokens        */
+#define KV_CHUNK_MAX_BYTES_PACK8 (1024 + 1024 * 4)
 
 typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library */
 
@@ -62,7 +64,11 @@ typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library 
 #define KV_REPACK_V_MEDIAN 1
 
 /* Parameters of Sec. IV-A: relative quantization scales (K 0.1, V 0.2 are the
- * paper's defaults), pack size 16, repacking none, block 64.  KV_REPACK_V_MEDIAN
+ * paper's defaults), pack size 16, repacking none, block 64.  Pack size 8 (the
+ * other good point of the pack-size study, Sec. IV-B): a chunk then has 1024
+ * header bytes, indexed [token_group * 128 + channel] with token groups of 8,
+ * and packs of `width` bytes; kv_decode_attention is not available with it
+ * (KV_ERR_UNSUPPORTED), the three-step path is.  KV_REPACK_V_MEDIAN
  * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
  * tokens, K and V are packed with their tokens sorted by the lower median of the
  * token's quantized V vector over all kv-heads (ascending, ties in arrival
@@ -73,7 +79,7 @@ typedef struct {
     int32_t n_q_heads;     /* H_q, a multiple of H_kv, H_q / H_kv in {1,2,4,8}    */
     int32_t head_dim;      /* must be 128                                         */
     int32_t block_tokens;  /* must be 64                                          */
-    int32_t pack_size;     /* must be 16                                          */
+    int32_t pack_size;     /* 16 or 8                                             */
     int32_t repack;        /* KV_REPACK_NONE or KV_REPACK_V_MEDIAN                */
     int32_t tail_capacity; /* raw fp16 tail buffer in tokens, must be 64          */
     float k_rel_scale;     /* in [1/15, 1]                                        */

@@ -14,7 +14,7 @@ import torch
 
 from . import build as _build
 
-KV_OK = 0
+KV_OK, KV_ERR_ARG, KV_ERR_UNSUPPORTED, KV_ERR_CAPACITY, KV_ERR_HIP = 0, -1, -2, -3, -4
 HEAD_DIM = 128
 BLOCK_TOKENS = 64
 CHUNK_MAX_BYTES = 512 + 512 * 8
@@ -96,12 +96,16 @@ def lib():
 
 
 class PackKVError(RuntimeError):
-    pass
+    """A library call returned an error code (kept in .code)."""
+
+    def __init__(self, message, code=None):
+        super().__init__(message)
+        self.code = code
 
 
 def _check(rc: int, what: str) -> None:
     if rc != KV_OK:
-        raise PackKVError("%s: %s (%d)" % (what, lib().kv_strerror(rc).decode(), rc))
+        raise PackKVError("%s: %s (%d)" % (what, lib().kv_strerror(rc).decode(), rc), rc)
 
 
 def _stream_ptr(stream=None):
@@ -114,8 +118,8 @@ def _stream_ptr(stream=None):
 
 
 def make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2,
-                repack=REPACK_NONE):
-    return kv_config_t(batch, n_kv_heads, n_q_heads, HEAD_DIM, BLOCK_TOKENS, 16, repack, BLOCK_TOKENS,
+                repack=REPACK_NONE, pack_size=16):
+    return kv_config_t(batch, n_kv_heads, n_q_heads, HEAD_DIM, BLOCK_TOKENS, pack_size, repack, BLOCK_TOKENS,
                        k_rel_scale, v_rel_scale, max_tokens)
 
 
@@ -129,8 +133,9 @@ class PackedKVCache:
     """Owns the device buffers (torch tensors) and the kv_cache_t handle."""
 
     def __init__(self, batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2,
-                 bits_per_element_budget=0.0, device="cuda:0", repack=REPACK_NONE):
-        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale, v_rel_scale, repack)
+                 bits_per_element_budget=0.0, device="cuda:0", repack=REPACK_NONE, pack_size=16):
+        self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale, v_rel_scale, repack,
+                               pack_size)
         self.device = torch.device(device)
         self.sizes = kv_query_sizes(self.cfg, bits_per_element_budget)
         self.tensors = {}

@@ -18,7 +18,7 @@ bool aligned256(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 2
 int check_config(const kv_config_t *c) {
     if (!c) return KV_ERR_ARG;
     if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_tokens < 1) return KV_ERR_ARG;
-    if (c->head_dim != D || c->block_tokens != N || c->pack_size != PACK ||
+    if (c->head_dim != D || c->block_tokens != N || (c->pack_size != PACK && c->pack_size != 8) ||
         (c->repack != KV_REPACK_NONE && c->repack != KV_REPACK_V_MEDIAN) ||
         c->tail_capacity != N)
         return KV_ERR_UNSUPPORTED;
@@ -47,12 +47,13 @@ extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_bu
     if (!out || bits_per_element_budget < 0.0) return KV_ERR_ARG;
     const int64_t max_tokens = (cfg->max_tokens + N - 1) / N * N;
     const int64_t max_chunks = max_tokens / N * cfg->batch * cfg->n_kv_heads;
-    const double worst_bits = double(CHUNK_MAX) * 8.0 / (N * D);
+    const int header = chunk_header_bytes(cfg->pack_size);
+    const double worst_bits = double(chunk_max_bytes(cfg->pack_size)) * 8.0 / (N * D);
     double bits = bits_per_element_budget == 0.0 ? worst_bits : bits_per_element_budget;
     if (bits > worst_bits) bits = worst_bits;
     // never less than the headers, plus one worst-case chunk of slack per stream for padding
     double per_chunk = bits * (N * D) / 8.0;
-    if (per_chunk < HEADER + 16) per_chunk = HEADER + 16;
+    if (per_chunk < header + 16) per_chunk = header + 16;
     size_t arena = size_t(std::ceil(per_chunk * double(max_chunks))) + 16;
     if (arena > size_t(0xFFFFFFFFull) * 16) return KV_ERR_UNSUPPORTED;  // index is in 16-byte units
     out->k_arena = out->v_arena = round256(arena);
@@ -79,7 +80,8 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
     for (const void *p : ptrs)
         if (!aligned256(p)) return KV_ERR_ARG;
     // arenas may be any size >= one chunk; everything else must be complete
-    if (sizes->k_arena < CHUNK_MAX || sizes->v_arena < CHUNK_MAX || sizes->k_index < need.k_index ||
+    const size_t chunk_max = size_t(chunk_max_bytes(cfg->pack_size));
+    if (sizes->k_arena < chunk_max || sizes->v_arena < chunk_max || sizes->k_index < need.k_index ||
         sizes->v_index < need.v_index || sizes->k_token_meta < need.k_token_meta ||
         sizes->v_token_meta < need.v_token_meta || sizes->k_tail < need.k_tail ||
         sizes->v_tail < need.v_tail || sizes->workspace < need.workspace)
@@ -231,6 +233,7 @@ extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale,
                                    void *hip_stream) {
     if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;
     if (c->packed_tokens + c->tail_tokens < 1) return KV_ERR_ARG;  // softmax over nothing
+    if (c->cfg.pack_size == 8) return KV_ERR_UNSUPPORTED;          // three-step path only
     return launch_decode_attention(c, static_cast<const __half *>(q), sm_scale, out,
                                    static_cast<hipStream_t>(hip_stream));
 }

@@ -17,6 +17,11 @@ constexpr int GROUPS = N / PACK;       // 4 token groups per block
 constexpr int PACKS = GROUPS * D;      // 512 packs per chunk
 constexpr int HEADER = KV_CHUNK_HEADER;
 constexpr int CHUNK_MAX = KV_CHUNK_MAX_BYTES;
+// packs of 8 tokens: 8 token groups, twice the header bytes
+constexpr int HEADER8 = KV_CHUNK_HEADER_PACK8;
+constexpr int CHUNK8_MAX = KV_CHUNK_MAX_BYTES_PACK8;
+inline int chunk_header_bytes(int pack_size) { return pack_size == 8 ? HEADER8 : HEADER; }
+inline int chunk_max_bytes(int pack_size) { return pack_size == 8 ? CHUNK8_MAX : CHUNK_MAX; }
 
 // Workspace layout (bytes).
 constexpr size_t WS_STATUS = 0;                 // uint32 status[64]

@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256) void token_params_kernel(const __half *__restr
     }
 }
 
-// Quantize the 16 tokens of one pack (channel d of token group g) and derive
+// Quantize the PK tokens of one pack (channel d of token group g) and derive
 // its minimum, width and code bits.
 struct PackBits {
     uint64_t bits;
@@ -86,14 +86,15 @@ __device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
 }
 
 // tile: the block's 64 x 128 values in LDS, rows already in storage order; the pack holds rows
-// 16g..16g+15 of channel d; meta_g: their token metadata (storage order).
+// PK*g..PK*g+PK-1 of channel d; meta_g: their token metadata (storage order).
+template <int PK>
 __device__ inline PackBits make_pack(const __half *tile, int g, int d,
                                      const uint32_t *__restrict__ meta_g, int qmax) {
-    int q[PACK];
+    int q[PK];
     int lo = 255, hi = 0;
 #pragma unroll
-    for (int i = 0; i < PACK; ++i) {
-        const int v = quantize_value(__half2float(tile[(g * PACK + i) * D + d]), meta_g[i], qmax);
+    for (int i = 0; i < PK; ++i) {
+        const int v = quantize_value(__half2float(tile[(g * PK + i) * D + d]), meta_g[i], qmax);
         q[i] = v;
         lo = min(lo, v);
         hi = max(hi, v);
@@ -104,7 +105,7 @@ __device__ inline PackBits make_pack(const __half *tile, int g, int d,
     pb.m = lo;
     pb.bits = 0;
 #pragma unroll
-    for (int i = 0; i < PACK; ++i) pb.bits |= uint64_t(q[i] - lo) << (i * pb.w);
+    for (int i = 0; i < PK; ++i) pb.bits |= uint64_t(q[i] - lo) << (i * pb.w);
     return pb;
 }
 
@@ -127,8 +128,10 @@ __device__ inline int block_exclusive_scan(int v, int *total) {
     return base + inc - v;
 }
 
-// One workgroup per new chunk; thread tau owns packs tau and tau + 256.
-template <bool WRITE>
+// One workgroup per new chunk; packs of PK tokens (16, or 8: Sec. IV-B): the chunk has
+// 64/PK token groups of 128 packs, thread tau owns packs tau + 256k (token group (tau >> 7) + 2k,
+// channel tau & 127).  A pack takes PK*w/8 payload bytes.
+template <bool WRITE, int PK>
 __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ src,
                                                     int64_t batch_stride, int64_t token_stride,
                                                     int B, int H, int qmax,
@@ -139,6 +142,8 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     const uint32_t *__restrict__ index,
                                                     uint8_t *__restrict__ arena,
                                                     const uint8_t *__restrict__ order) {
+    constexpr int HDR = N / PK * D;        // header bytes: one per pack
+    constexpr int PER = N / PK * D / 256;  // packs per thread
     const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
     const int h = cl % H;
     const int b = (cl / H) % B;
@@ -168,34 +173,36 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
     }
     __syncthreads();
 
-    PackBits pb[2];
-    int len[2];
+    PackBits pb[PER];
+    int off[PER];
+    int payload = 0;
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        int g = (tau >> 7) + 2 * k;
-        const int64_t tok = int64_t(blk) * N + g * PACK;  // first storage slot of the pack
-        pb[k] = make_pack(tile, g, d, meta + b * meta_stride + first_token + tok, qmax);
-        len[k] = 2 * pb[k].w;
+    for (int k = 0; k < PER; ++k) {
+        const int g = (tau >> 7) + 2 * k;
+        const int64_t tok = int64_t(blk) * N + g * PK;  // first storage slot of the pack
+        pb[k] = make_pack<PK>(tile, g, d, meta + b * meta_stride + first_token + tok, qmax);
+        int total;
+        off[k] = payload + block_exclusive_scan(PK / 8 * pb[k].w, &total);
+        payload += total;
     }
-    int total0, total1;
-    int off0 = block_exclusive_scan(len[0], &total0);
-    int off1 = block_exclusive_scan(len[1], &total1) + total0;
-    const int payload = total0 + total1;
-    const int padded = (HEADER + payload + 15) & ~15;
+    const int padded = (HDR + payload + 15) & ~15;
 
     if (!WRITE) {
         if (tau == 0) sizes16[cl] = uint32_t(padded >> 4);
         return;
     }
 #pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        int p = tau + 256 * k;
-        dst[p] = uint8_t((pb[k].w << 4) | pb[k].m);
-        uint16_t *out = reinterpret_cast<uint16_t *>(dst + HEADER + (k ? off1 : off0));
-        for (int j = 0; j < pb[k].w; ++j) out[j] = uint16_t(pb[k].bits >> (16 * j));
+    for (int k = 0; k < PER; ++k) {
+        dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
+        if constexpr (PK == 16) {
+            uint16_t *out = reinterpret_cast<uint16_t *>(dst + HDR + off[k]);
+            for (int j = 0; j < pb[k].w; ++j) out[j] = uint16_t(pb[k].bits >> (16 * j));
+        } else {
+            uint8_t *out = dst + HDR + off[k];
+            for (int j = 0; j < pb[k].w; ++j) out[j] = uint8_t(pb[k].bits >> (8 * j));
+        }
     }
-    if (tau < (padded - HEADER - payload) / 2)
-        reinterpret_cast<uint16_t *>(dst + HEADER + payload)[tau] = 0;
+    if (tau < padded - HDR - payload) dst[HDR + payload + tau] = 0;
 }
 
 // Single workgroup: index[first+i+1] = index[first] + sum_{j<=i} sizes16[j].
@@ -381,12 +388,14 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
-    hipLaunchKernelGGL(chunk_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
+    auto sizes_kernel = c->cfg.pack_size == 8 ? chunk_kernel<false, 8> : chunk_kernel<false, 16>;
+    auto write_kernel = c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>;
+    hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                        job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
     hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
                        job.index, job.first_chunk, job.arena_cap16, job.status);
-    hipLaunchKernelGGL(chunk_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
+    hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                        job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
     KV_HIP_CHECK(hipGetLastError());

@@ -17,6 +17,7 @@
 #include <algorithm>
 
 #include "k_chunk.h"
+#include "pack8.h"
 
 namespace packkv {
 
@@ -197,6 +198,72 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
     }
 }
 
+// Packs of 8 tokens (Sec. IV-B), any group size: every chunk is decoded as two halves of 32
+// tokens (pack8.h).  After the two reductions lane (r, i) holds token 32 (i & 1) + 8 r + (i >> 1)
+// of the block, for every head; one 256-byte store per head.
+template <int G>
+__device__ inline void k8_stream(const KArgs &a, int bh, int blk_begin, int blk_end, int wave, int lane,
+                                 uint8_t *lds0, int buf_base, const uint2 *table) {
+    const int h = bh % a.H, b = bh / a.H;
+    const int64_t head0 = int64_t(b) * a.H * G + h * G;
+    KQuery8<G> kq;
+    kq.load(a.q + head0 * D, lane);
+    const int row = lane >> 4, i = lane & 15;
+    const int tok_in_blk = 32 * (i & 1) + 8 * row + k8_token_of_lane(i);
+
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        vmem_order_fence();
+        chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
+        vmem_order_fence();
+        const uint32_t *meta = a.meta + b * a.meta_stride + tok_in_blk;
+        uint32_t mt_next = meta[int64_t(first) * N];
+        for (int it = 0; it < n_it; ++it) {
+            const int cur = buf_base + (it & 1) * CHUNK8_LDS;
+            const int64_t tok = int64_t(first + 4 * it) * N + tok_in_blk;
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER8 / 16);
+            // issued after this chunk's transfers, and allowed to stay in flight: the metadata
+            // load and, from the second iteration on, the previous iteration's G score stores
+            if (it == 0)
+                wait_chunk_landed_except<1>();
+            else
+                wait_chunk_landed_except<1 + G>();
+            uint32_t mt = mt_next;
+            consume_here(mt);
+            if (it + 1 < n_it) {
+                chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(it + 1), ib.end16(it + 1),
+                                                     lds0 + buf_base + ((it + 1) & 1) * CHUNK8_LDS, lane);
+                vmem_order_fence();
+                mt_next = meta[int64_t(first + 4 * (it + 1)) * N];
+            }
+            if (!valid) {  // block dropped by an arena overflow: defined output
+#pragma unroll
+                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                wait_chunk_landed();  // rare path: keep the next wait's count independent of it
+                continue;
+            }
+            float u0[G], u1[G];
+            const uint2 hdr0 = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
+            LanePacks8 lp0;
+            lp0.init(hdr0.x, hdr0.y, cur + HEADER8);
+            k8_half<G>(lds0, table, lp0, kq, lane, u0);
+            const uint2 hdr1 = *reinterpret_cast<const uint2 *>(lds0 + cur + 512 + lane * 8);
+            LanePacks8 lp1;
+            lp1.init(hdr1.x, hdr1.y, lp0.end_all);
+            k8_half<G>(lds0, table, lp1, kq, lane, u1);
+            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                a.scores[(head0 + g) * a.ld + tok] =
+                    a.sm_scale * fmaf(scale, (i & 1) ? u1[g] : u0[g], mn * kq.qsum[g]);
+        }
+        wait_chunk_landed();  // nothing may still be streaming into LDS when the buffers are reused
+    }
+}
+
 // Raw fp16 tail (Sec. III-B.1 buffer): plain dot products, one lane per token.
 template <int G>
 __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
@@ -252,6 +319,26 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     }
 }
 
+template <int G>
+__global__ __launch_bounds__(256) void k8_matvec_kernel(KArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK8_LDS + LDS_TAIL_PAD];
+    __shared__ uint2 table[PACK_TABLE_ENTRIES];
+    build_pair_table(table);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = blockIdx.x;
+    if (grp < a.n_stream_groups) {
+        const int bh = grp / a.groups_per_stream;
+        const int part = grp % a.groups_per_stream;
+        const int blk_begin = part * a.blocks_per_group;
+        const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
+        k8_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK8_LDS, table);
+    } else {
+        const int bh = (grp - a.n_stream_groups) * 4 + wave;
+        if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
+    }
+}
+
 int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *scores,
                     int64_t ld_scores, hipStream_t s) {
     KArgs a;
@@ -282,12 +369,22 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     const int tail_groups = a.n_tail > 0 ? (streams + 3) / 4 : 0;
     const int grid = a.n_stream_groups + tail_groups;
     if (grid == 0) return KV_OK;
-    switch (c->group) {
-        case 1: hipLaunchKernelGGL(k_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
-        case 2: hipLaunchKernelGGL(k_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
-        case 4: hipLaunchKernelGGL(k_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
-        case 8: hipLaunchKernelGGL(k_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
-        default: return KV_ERR_UNSUPPORTED;
+    if (c->cfg.pack_size == 8) {
+        switch (c->group) {
+            case 1: hipLaunchKernelGGL(k8_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
+            case 2: hipLaunchKernelGGL(k8_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
+            case 4: hipLaunchKernelGGL(k8_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
+            case 8: hipLaunchKernelGGL(k8_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
+            default: return KV_ERR_UNSUPPORTED;
+        }
+    } else {
+        switch (c->group) {
+            case 1: hipLaunchKernelGGL(k_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
+            case 2: hipLaunchKernelGGL(k_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
+            case 4: hipLaunchKernelGGL(k_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
+            case 8: hipLaunchKernelGGL(k_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
+            default: return KV_ERR_UNSUPPORTED;
+        }
     }
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;

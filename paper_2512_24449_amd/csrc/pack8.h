@@ -1,0 +1,251 @@
+// Decode-side pieces for chunks whose packs hold 8 tokens (the second pack size of the
+// pack-size study, PackKV Sec. IV-B).
+//
+// Such a chunk has 1024 header bytes, indexed [token group of 8][channel], and packs of
+// `width` bytes in the same order.  It is decoded as two halves of 32 tokens: half s covers
+// token groups 4s..4s+3, its header bytes are the contiguous range [512s, 512s + 512) and its
+// packs the contiguous payload range that follows the packs of half 0 -- so each half has
+// exactly the shape the wave mapping of the 16-token packs is built for (512 packs, lane l
+// owns token group l/16 of the half and channels 8(l%16)..+7, eight contiguous packs), and
+// only the pack decode itself differs: 8 codes in at most 32 bits, two 16-bit fields.
+#pragma once
+
+#include "k_chunk.h"
+#include "unpack.h"
+#include "v_chunk.h"
+
+namespace packkv {
+
+constexpr int CHUNK8_LDS = CHUNK8_MAX;
+constexpr int DPP_ROW_HALF_MIRROR = 0x141;  // lane i <- lane 7 - i of its half row
+
+// Per-lane view of the header of one half and of where its eight packs sit in LDS.
+struct LanePacks8 {
+    uint32_t hlo, hhi;  // eight header bytes, pack j in byte j
+    uint32_t plo, phi;  // byte j = w_0 + .. + w_j: payload bytes up to and including pack j
+    int start;          // LDS byte address of pack 0
+    int end_all;        // LDS byte address behind the last pack of the half (wave-uniform)
+
+    // lds_base: LDS byte address of the half's payload
+    __device__ inline void init(uint32_t lo, uint32_t hi, int lds_base) {
+        hlo = lo;
+        hhi = hi;
+        uint32_t wl = (lo >> 4) & 0x0F0F0F0Fu, wh = (hi >> 4) & 0x0F0F0F0Fu;  // width = bytes per pack
+        wl += wl << 8;
+        wl += wl << 16;
+        wh += wh << 8;
+        wh += wh << 16;
+        const uint32_t tl = wl >> 24;
+        wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
+        plo = wl;
+        phi = wh;
+        const int bytes = int(wh >> 24);
+        const int inc = wave_inclusive_scan(bytes);
+        start = inc - bytes + lds_base;
+        end_all = __builtin_amdgcn_readlane(inc, 63) + lds_base;
+    }
+    __device__ inline uint32_t header_byte(int j) const { return ((j < 4 ? hlo : hhi) >> (8 * (j & 3))) & 0xFFu; }
+    __device__ inline int pos(int j) const {
+        if (j == 0) return start;
+        const int k = j - 1;
+        return start + int(((k < 4 ? plo : phi) >> (8 * (k & 3))) & 0xFFu);
+    }
+};
+
+// The 32-bit window of a pack of 8 (its 8w <= 32 bits, from bit 0 up): two aligned dwords and
+// a byte funnel shift; pos is byte aligned.
+__device__ inline uint32_t fetch_window8(const uint8_t *lds0, int pos) {
+    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
+    return __builtin_amdgcn_alignbyte(pp[1], pp[0], uint32_t(pos));
+}
+
+// ---- K -------------------------------------------------------------------------------
+template <int G>
+struct KQuery8 {
+    uint32_t qp[G][4];  // q of this lane's 8 channels as fp16 pairs, per head
+    float qsum[G];      // sum of all 128 q values per head
+
+    // q_group: the G query heads of the kv-head, [G][128] fp16
+    __device__ inline void load(const __half *q_group, int lane) {
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint4 raw = *reinterpret_cast<const uint4 *>(q_group + g * D + 8 * (lane & 15));
+            qp[g][0] = raw.x, qp[g][1] = raw.y, qp[g][2] = raw.z, qp[g][3] = raw.w;
+            float s = 0.0f;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) s += half_lo(qp[g][k]) + half_hi(qp[g][k]);
+            qsum[g] = row_all_reduce16(s);
+        }
+    }
+};
+
+// Token (0..7 of its group) whose sum lane i of a row holds after row_reduce_scatter8.
+__device__ inline int k8_token_of_lane(int i) { return i >> 1; }
+
+// Reduce-scatter inside each row of 16 lanes for eight sums per lane (v[t] belongs to token
+// t): on return lanes 2t and 2t+1 of the row both hold the row's sum for token t.  The first
+// two rounds use DPP adds whose write is restricted to half of the row (see
+// row_reduce_scatter16, also for the wait states the leading s_nop stands for).
+__device__ inline float row_reduce_scatter8(float (&v)[8], int lane) {
+    float a[4], b[2];
+    asm("s_nop 3\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %2, %6, %6 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %3, %7, %7 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
+        "v_add_f32_dpp %0, %8, %8 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %1, %9, %9 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %2, %10, %10 row_ror:8 row_mask:0xf bank_mask:0xc\n\t"
+        "v_add_f32_dpp %3, %11, %11 row_ror:8 row_mask:0xf bank_mask:0xc"
+        : "=&v"(a[0]), "=&v"(a[1]), "=&v"(a[2]), "=&v"(a[3])
+        : "v"(v[0]), "v"(v[1]), "v"(v[2]), "v"(v[3]), "v"(v[4]), "v"(v[5]), "v"(v[6]), "v"(v[7]));
+    asm("s_nop 1\n\t"
+        "v_add_f32_dpp %0, %2, %2 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %1, %3, %3 row_ror:12 row_mask:0xf bank_mask:0x5\n\t"
+        "v_add_f32_dpp %0, %4, %4 row_ror:4 row_mask:0xf bank_mask:0xa\n\t"
+        "v_add_f32_dpp %1, %5, %5 row_ror:4 row_mask:0xf bank_mask:0xa"
+        : "=&v"(b[0]), "=&v"(b[1])
+        : "v"(a[0]), "v"(a[1]), "v"(a[2]), "v"(a[3]));
+    const bool b1 = lane & 2;
+    const float keep = b1 ? b[1] : b[0];
+    const float send = b1 ? b[0] : b[1];
+    float c = keep + dpp_f32<DPP_QUAD_XOR2>(send);
+    c += dpp_f32<DPP_QUAD_XOR1>(c);
+    return c;
+}
+
+// One half (32 tokens) of a chunk: u[g] = sum_d q[g][d] (code[t, d] + m[group, d]) for token
+// t = 8 * (lane / 16) + k8_token_of_lane(lane % 16) of the half, head g.  `table`: the pair
+// table (build_pair_table).  Two packs (channels 2jp, 2jp+1) are unpacked side by side and
+// contracted with two-element fp16 dot products, as in the single-head path of the 16-token
+// packs; with G heads the unpacked words are reused G times.
+template <int G>
+__device__ inline void k8_half(const uint8_t *lds0, const uint2 *table, const LanePacks8 &lp,
+                               const KQuery8<G> &kq, int lane, float (&u)[G]) {
+    float acc[G][8], msum[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        msum[g] = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) acc[g][t] = 0.0f;
+    }
+#pragma unroll
+    for (int jp = 0; jp < 4; ++jp) {
+        const uint32_t Aa = fetch_window8(lds0, lp.pos(2 * jp));
+        const uint32_t Ab = fetch_window8(lds0, lp.pos(2 * jp + 1));
+        const uint2 ka = table[lp.header_byte(2 * jp)], kb = table[lp.header_byte(2 * jp + 1)];
+        // fields of four codes: tokens 0..3 from bit 0, tokens 4..7 from bit 4w (clean)
+        const uint32_t Fa[2] = {Aa, __builtin_amdgcn_ubfe(Aa, ka.x, ka.x)};
+        const uint32_t Fb[2] = {Ab, __builtin_amdgcn_ubfe(Ab, kb.x, kb.x)};
+        const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(kb.x, ka.x, 0x0c050c01u));
+        const uint32_t masks = __builtin_amdgcn_perm(kb.x, ka.x, 0x07060302u);
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            msum[g] = fmaf(half_lo(kq.qp[g][jp]), half_hi(ka.y), msum[g]);
+            msum[g] = fmaf(half_hi(kq.qp[g][jp]), half_hi(kb.y), msum[g]);
+        }
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+            u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t P = __builtin_bit_cast(uint32_t, Z) & (f == 1 && m == 3 ? ~0u : masks);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    acc[g][4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P),
+                                                               __builtin_bit_cast(half2_t, kq.qp[g][jp]),
+                                                               acc[g][4 * f + m], false);
+                if (m < 3) Z = Z >> widths;
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        u[g] = row_reduce_scatter8(acc[g], lane) * CODE_SCALE + row_all_reduce16(msum[g]);
+}
+
+// ---- V -------------------------------------------------------------------------------
+// Where token t (0..63) of a block sits in the B operand staging (column 0): half s = t / 32
+// takes the place of the `half` index of the 16-token layout, k-run t / 8 % 4, and inside the
+// run the order in which v8_half leaves the codes: words of tokens (m, m + 4).
+template <int G>
+__device__ inline int v8_bslot(int t) {
+    const int s = t >> 5, kg = (t >> 3) & 3, uu = t & 7;
+    const int e = uu < 4 ? 2 * uu : 2 * (uu - 4) + 1;
+    return (((kg * 2 + s) * BLds<G>::COLS) * 8 + e) * 2;
+}
+
+// Sum over the aligned groups of eight lanes, result in every lane of the group.
+__device__ inline float lanes8_all_reduce(float v) {
+    v += dpp_f32<DPP_QUAD_XOR1>(v);
+    v += dpp_f32<DPP_QUAD_XOR2>(v);
+    v += dpp_f32<DPP_ROW_HALF_MIRROR>(v);
+    return v;
+}
+
+// Adds one chunk (both halves) from the LDS buffer at byte offset `cur`: lane l is token l of
+// the block with weight pt[g] for head g and token metadata mt.  `table`: build_pack_table with
+// lift CODE_LIFT and fold = fold_min<G>().  vl.bslot must come from v8_bslot.
+template <int G>
+__device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *table, const VLane<G> &vl,
+                                uint32_t mt, const float (&pt)[G], VState<G> &st) {
+    const int lane = threadIdx.x & 63;
+    const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+    float wsum[2][G];  // per half: sum of the weights of this lane's token group (8 tokens)
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float w = pt[g] * scale;
+        st.pm[g] = fmaf(pt[g], mn, st.pm[g]);
+        const _Float16 hi = __builtin_bit_cast(
+            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
+        const float lo = (w - float(hi)) * 2048.0f;
+        const _Float16 lo16 = __builtin_bit_cast(
+            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+        *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
+        *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
+        if (!fold_min<G>()) {
+            const float w8 = lanes8_all_reduce(w);  // tokens 8k..8k+7 live in lanes 8k..8k+7
+            wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
+            wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+        }
+    }
+    wave_lds_fence();
+    const vhalf8 b0 = *reinterpret_cast<const vhalf8 *>(vl.blds + vl.bread0);
+    const vhalf8 b1 = *reinterpret_cast<const vhalf8 *>(vl.blds + vl.bread1);
+
+    int payload = cur + HEADER8;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + cur + 512 * s + lane * 8);
+        LanePacks8 lp;
+        lp.init(hdr.x, hdr.y, payload);
+        payload = lp.end_all;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t A = fetch_window8(lds_all, lp.pos(j));
+            const uint4 k = table[lp.header_byte(j)];
+            const uint32_t w = k.y, M = k.x;
+            // tokens 0..3 in the low half, tokens 4..7 in the high half, lifted together
+            uint32_t Z = __builtin_amdgcn_perm(A >> (4 * w), A, 0x05040100u);
+            Z = __builtin_amdgcn_alignbit(Z, Z, 32 - CODE_LIFT);
+            uint32_t P[4];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                P[m] = (Z & M) + (fold_min<G>() ? k.w : 0u);
+                if (m < 3) Z = __builtin_amdgcn_alignbit(Z, Z, w);
+            }
+            if constexpr (!fold_min<G>()) {
+                const float m = __uint_as_float(k.w);
+#pragma unroll
+                for (int g = 0; g < G; ++g) st.macc[g][j] = fmaf(m, wsum[s][g], st.macc[g][j]);
+            }
+            typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+            const vhalf8 a = __builtin_bit_cast(vhalf8, u32x4v{P[0], P[1], P[2], P[3]});
+            st.acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, s ? b1 : b0, st.acc[j], 0, 0, 0);
+        }
+    }
+    wave_lds_fence();  // the B operand is rewritten by the next chunk
+}
+
+}  // namespace packkv

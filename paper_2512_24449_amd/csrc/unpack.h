@@ -163,8 +163,8 @@ constexpr int CHUNK_LDS = CHUNK_MAX;
 // vector registers involved), so that it is in flight while the previous chunk
 // is unpacked.  o0/o1: the chunk's index words; buf: wave-uniform.  A dropped
 // block (size 0) transfers nothing.  Lanes past the chunk end re-read its last
-// 16 bytes into buffer bytes nobody decodes; the fifth slice only uses lanes
-// 0..31 because the buffer is 4608 bytes.
+// 16 bytes into buffer bytes nobody decodes; the last slice only uses the lanes
+// that stay inside the buffer (0..31 of the fifth slice for the 4608-byte buffer).
 //
 // The instruction is issued from inline assembly on purpose.  Issued through the
 // compiler's builtin, every later LDS read of the wave -- also of the OTHER buffer --
@@ -174,16 +174,18 @@ constexpr int CHUNK_LDS = CHUNK_MAX;
 // the s_nop is the wait state between writing M0 and the transfer that reads it.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // M0 is a reserved register; naming it as clobbered is the point
+// MAXB: buffer bytes = largest chunk; HDR: header bytes, the smallest valid chunk.
+template <int MAXB = CHUNK_MAX, int HDR = HEADER>
 __device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
                                        uint8_t *buf, int lane) {
     const int size = int(o1 - o0) * 16;
-    if (size < HEADER) return;
+    if (size < HDR) return;
     const uint8_t *chunk = arena + size_t(o0) * 16;
     const int last = size - 16;
     const uint32_t lds = uint32_t(uintptr_t((__attribute__((address_space(3))) void *)buf));
 #pragma unroll
-    for (int k = 0; k < 5; ++k) {
-        if (k * 1024 < size && (k < 4 || lane < 32)) {
+    for (int k = 0; k < (MAXB + 1023) / 1024; ++k) {
+        if (k * 1024 < size && ((k + 1) * 1024 <= MAXB || k * 1024 + lane * 16 < MAXB)) {
             const int off = k * 1024 + lane * 16;
             asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
                          :
@@ -203,7 +205,7 @@ __device__ inline void wait_chunk_landed() { asm volatile("s_waitcnt vmcnt(0)" :
 // in issue order.  Callers keep the issue order fixed with vmem_order_fence().
 template <int LATER>
 __device__ inline void wait_chunk_landed_except() {
-    static_assert(LATER >= 0 && LATER < 8, "");
+    static_assert(LATER >= 0 && LATER < 64, "the counter has six bits");
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(LATER) : "memory");
 }
 // Compiler-only fence: memory operations are not moved across it.
@@ -299,13 +301,14 @@ __device__ inline float half_hi(uint32_t p) { return float(__builtin_bit_cast(_F
 // round adds the partner lane's value (eight lanes away) with the write restricted to one
 // half of the row per instruction: lanes 0..7 take index k, lanes 8..15 index k+8 -- two adds
 // per output and no selects; the second round does the same with the lane four away.  The
-// leading s_nop covers the two wait states between a vector
-// write and a DPP read of the same register, which the compiler does not track into inline
-// assembly.
+// leading s_nop covers the wait states between the instruction that produced an input and
+// its DPP read, which the compiler does not track into inline assembly: two after an ordinary
+// vector instruction, three after a dot-product instruction (the callers' accumulators) --
+// four are inserted.
 __device__ inline float row_reduce_scatter16(float (&v)[16], int lane) {
     float a[8], b[4], c[2];
     const bool b1 = lane & 2, b0 = lane & 1;
-    asm("s_nop 1\n\t"
+    asm("s_nop 3\n\t"
         "v_add_f32_dpp %0, %8, %8 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
         "v_add_f32_dpp %1, %9, %9 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"
         "v_add_f32_dpp %2, %10, %10 row_ror:8 row_mask:0xf bank_mask:0x3\n\t"

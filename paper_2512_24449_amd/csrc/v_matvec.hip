@@ -18,6 +18,7 @@
 //   out_d = sum_t w_t code[t,d] + sum_g m[g,d] sum_{t in g} w_t + sum_t p_t min_t
 #include <algorithm>
 
+#include "pack8.h"
 #include "v_chunk.h"
 
 namespace packkv {
@@ -106,6 +107,79 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     }
 }
 
+// The same for chunks with packs of 8 tokens (Sec. IV-B; pack8.h).
+template <int G>
+__global__ __launch_bounds__(256) void v8_matvec_kernel(VArgs a) {
+    // two chunk buffers per wave; after the main loop the same memory holds the
+    // cross-wave reduction array red[4][G][D + 4]
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK8_LDS + LDS_TAIL_PAD];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
+    __shared__ uint4 table[PACK_TABLE_ENTRIES];
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK8_LDS, "reduction array must fit");
+    float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
+    build_pack_table(table, CODE_LIFT, fold_min<G>());
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int split = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int h = bh % a.H, b = bh / a.H;
+    const int buf_base = wave * 2 * CHUNK8_LDS;
+    VLane<G> vl;
+    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
+    vl.bslot = v8_bslot<G>(lane);  // lane l is token l of the block
+    VState<G> st;
+    st.clear();
+
+    const int blk_begin = split * a.blocks_per_split;
+    const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
+        uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
+        float p_next[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+            p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + int64_t(first) * N + lane];
+        for (int it = 0; it < n_it; ++it) {
+            const int cur = buf_base + (it & 1) * CHUNK8_LDS;
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER8 / 16);
+            wait_chunk_landed();
+            uint32_t mt = mt_next;
+            consume_here(mt);
+            float pt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                pt[g] = p_next[g];
+                consume_here(pt[g]);
+            }
+            // the next chunk streams into the other buffer while this one is unpacked
+            if (it + 1 < n_it) {
+                chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(it + 1), ib.end16(it + 1),
+                                lds_all + buf_base + ((it + 1) & 1) * CHUNK8_LDS, lane);
+                const int64_t tok = int64_t(first + 4 * (it + 1)) * N + lane;
+                mt_next = a.meta[b * a.meta_stride + tok];
+#pragma unroll
+                for (int g = 0; g < G; ++g) p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
+            }
+            if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
+            v8_chunk<G>(lds_all, cur, table, vl, mt, pt, st);
+        }
+        wait_chunk_landed();
+    }
+    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
+
+    v_state_store<G>(st, red[wave], lane);
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
+        const int g = i / (D + 1), d = i % (D + 1);
+        const float v = (red[0][g][d] + red[1][g][d]) + (red[2][g][d] + red[3][g][d]);
+        a.partial[(int64_t(split) * a.B * a.H * G + (int64_t(b) * a.H * G + h * G + g)) * V_PART_STRIDE + d] = v;
+    }
+}
+
 // Fixed-order combination of the split partial sums, plus the raw fp16 tail.
 __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__ partial,
                                                        int n_splits, int n_rows,
@@ -163,12 +237,22 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
-        switch (G) {
-            case 1: hipLaunchKernelGGL(v_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
-            case 2: hipLaunchKernelGGL(v_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
-            case 4: hipLaunchKernelGGL(v_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
-            case 8: hipLaunchKernelGGL(v_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
-            default: return KV_ERR_UNSUPPORTED;
+        if (c->cfg.pack_size == 8) {
+            switch (G) {
+                case 1: hipLaunchKernelGGL(v8_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
+                case 2: hipLaunchKernelGGL(v8_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
+                case 4: hipLaunchKernelGGL(v8_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
+                case 8: hipLaunchKernelGGL(v8_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
+                default: return KV_ERR_UNSUPPORTED;
+            }
+        } else {
+            switch (G) {
+                case 1: hipLaunchKernelGGL(v_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
+                case 2: hipLaunchKernelGGL(v_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
+                case 4: hipLaunchKernelGGL(v_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
+                case 8: hipLaunchKernelGGL(v_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
+                default: return KV_ERR_UNSUPPORTED;
+            }
         }
     }
     hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,

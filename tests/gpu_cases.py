@@ -35,12 +35,12 @@ def assert_close_vectors(got, ref, what, tol=REL_TOL):
         float((mx / np.maximum(ref_mx, 1e-300)).max()))
 
 
-def oracle_cache(K, V, k_rel=0.1, v_rel=0.2):
+def oracle_cache(K, V, k_rel=0.1, v_rel=0.2, pack_size=16):
     """Compress the packed prefix of K and V with the oracle.  K, V: numpy fp16 [B, L, H, D]."""
     L = K.shape[1]
     n_packed = L // 64 * 64
-    ck = oracle.compress(np.ascontiguousarray(K[:, :n_packed]), k_rel) if n_packed else None
-    cv = oracle.compress(np.ascontiguousarray(V[:, :n_packed]), v_rel) if n_packed else None
+    ck = oracle.compress(np.ascontiguousarray(K[:, :n_packed]), k_rel, pack_size) if n_packed else None
+    cv = oracle.compress(np.ascontiguousarray(V[:, :n_packed]), v_rel, pack_size) if n_packed else None
     return n_packed, ck, cv
 
 
@@ -79,12 +79,13 @@ def check_packed_state(cache, n_packed, ck, cv, B, H):
 
 
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
-             max_tokens=None):
-    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything."""
+             max_tokens=None, pack_size=16):
+    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
+    With packs of 8 tokens the fused attention entry point must refuse (three-step path only)."""
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
-    cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), device=device)
+    cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), device=device, pack_size=pack_size)
     Kd, Vd, qd = K.to(device), V.to(device), q.to(device)
     pos = 0
     for n in (pieces or [L]):
@@ -92,7 +93,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
         pos += n
     assert pos == L and cache.tokens == L
 
-    n_packed, ck, cv = oracle_cache(Kn, Vn)
+    n_packed, ck, cv = oracle_cache(Kn, Vn, pack_size=pack_size)
     if check_bytes:
         check_packed_state(cache, n_packed, ck, cv, B, H)
 
@@ -122,16 +123,26 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     assert_close_vectors(out3.cpu().numpy(), o_e2e, "three-step path with the library softmax")
 
     # fused decode attention against the oracle's definition of Att(q, K, V)
-    attn = cache.kv_decode_attention(qd, sm_scale)
-    torch.cuda.synchronize()
-    a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
-    assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
+    if pack_size == 16:
+        attn = cache.kv_decode_attention(qd, sm_scale)
+        torch.cuda.synchronize()
+        a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
+        assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
+    else:
+        try:
+            cache.kv_decode_attention(qd, sm_scale)
+            raise AssertionError("fused attention must refuse packs of 8 tokens")
+        except binding.PackKVError as e:
+            assert e.code == binding.KV_ERR_UNSUPPORTED
 
     # determinism: a second pass gives the same bits
     scores2 = cache.kv_k_matvec(qd, sm_scale)
     out2 = cache.kv_v_matvec(p)
-    attn2 = cache.kv_decode_attention(qd, sm_scale)
     torch.cuda.synchronize()
-    assert torch.equal(scores, scores2) and torch.equal(out, out2) and torch.equal(attn, attn2)
+    assert torch.equal(scores, scores2) and torch.equal(out, out2)
+    if pack_size == 16:
+        attn2 = cache.kv_decode_attention(qd, sm_scale)
+        torch.cuda.synchronize()
+        assert torch.equal(attn, attn2)
     cache.close()
     return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)

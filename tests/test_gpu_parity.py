@@ -29,6 +29,20 @@ def test_append_then_decode_matches_oracle(B, H, Hq, L, seed):
     gpu_cases.run_case(B, H, Hq, L, seed)
 
 
+@pytest.mark.parametrize("B,H,Hq,L,seed,pieces", [
+    (1, 1, 1, 64, 30, None),             # one chunk
+    (1, 1, 1, 1024, 31, None),           # benchmark configuration 0 with packs of 8
+    (2, 3, 6, 192 + 9, 32, None),        # G = 2, ragged
+    (1, 8, 32, 512, 33, None),           # G = 4
+    (1, 2, 16, 256 + 63, 34, None),      # G = 8, full tail
+    (3, 5, 5, 7 * 64 + 1, 35, None),     # odd number of blocks per wave
+    (2, 2, 4, 64 * 3 + 5, 36, [1, 62, 1, 1, 63, 64, 5]),  # incremental appends
+])
+def test_packs_of_8_tokens_match_oracle(B, H, Hq, L, seed, pieces):
+    """The second pack size (Sec. IV-B): packed bytes bit-exact, three-step path within the bar."""
+    gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8)
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
