@@ -67,8 +67,7 @@ typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library 
  * paper's defaults), pack size 16, repacking none, block 64.  Pack size 8 (the
  * other good point of the pack-size study, Sec. IV-B): a chunk then has 1024
  * header bytes, indexed [token_group * 128 + channel] with token groups of 8,
- * and packs of `width` bytes; kv_decode_attention is not available with it
- * (KV_ERR_UNSUPPORTED), the three-step path is.  KV_REPACK_V_MEDIAN
+ * and packs of `width` bytes.  KV_REPACK_V_MEDIAN
  * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
  * tokens, K and V are packed with their tokens sorted by the lower median of the
  * token's quantized V vector over all kv-heads (ascending, ties in arrival

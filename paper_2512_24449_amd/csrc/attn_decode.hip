@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "k_chunk.h"
+#include "pack8.h"
 #include "v_chunk.h"
 
 namespace packkv {
@@ -60,6 +61,72 @@ __device__ inline float wave_all_sum(float v) {
 
 // 2^(a - b) with the convention that an empty side (a = -inf) weighs nothing.
 __device__ inline float exp2_diff(float a, float b) { return a == -INFINITY ? 0.0f : exp2f(a - b); }
+
+// Online softmax bookkeeping: raise a head's reference only when a score of this block runs
+// away from it, and rescale the running sums then.  s: this lane's scores (log2 units).
+template <int G>
+__device__ inline void attn_raise_reference(const float (&s)[G], float (&m_ref)[G], float (&l_lane)[G],
+                                            VState<G> &st, int col) {
+    bool raise = false;
+#pragma unroll
+    for (int g = 0; g < G; ++g) raise |= s[g] > m_ref[g] + RAISE_MARGIN;
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        float alpha_col = 1.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            // the same value in every lane: keep it in a scalar register
+            const float m_new = __int_as_float(__builtin_amdgcn_readfirstlane(
+                __float_as_int(fmaxf(m_ref[g], wave_all_max(s[g])))));
+            const float alpha = exp2_diff(m_ref[g], m_new);
+            m_ref[g] = m_new;
+            l_lane[g] *= alpha;
+            st.pm[g] *= alpha;
+            if constexpr (!fold_min<G>()) {
+#pragma unroll
+                for (int j = 0; j < 8; ++j) st.macc[g][j] *= alpha;
+            }
+            if ((col >> 1) == g) alpha_col = alpha;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[j] *= alpha_col;
+    }
+}
+
+// End of a fused attention workgroup: merges the four waves' running sums (each with its own
+// softmax reference) and writes the split's partial row.  red aliases the chunk buffers.
+template <int G>
+__device__ inline void attn_store_partial(const AArgs &a, const VState<G> &st, const float (&l_lane)[G],
+                                          const float (&m_ref)[G], float (*red)[G][D + 4], int wave,
+                                          int lane, int split, int64_t head0) {
+    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
+
+    v_state_store<G>(st, red[wave], lane);
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float l = wave_all_sum(l_lane[g]);
+        if (lane == 0) {
+            red[wave][g][D + 1] = l;
+            red[wave][g][D + 2] = m_ref[g];
+        }
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
+        const int g = i / (D + 1), d = i % (D + 1);
+        const float m0 = red[0][g][D + 2], m1 = red[1][g][D + 2], m2 = red[2][g][D + 2], m3 = red[3][g][D + 2];
+        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
+        const float f0 = exp2_diff(m0, M), f1 = exp2_diff(m1, M), f2 = exp2_diff(m2, M), f3 = exp2_diff(m3, M);
+        float *dst = a.partial + (int64_t(split) * a.B * a.H * G + head0 + g) * V_PART_STRIDE;
+        if (d < D) {
+            // outputs carry the per-head sum p*min term
+            dst[d] = (f0 * (red[0][g][d] + red[0][g][D]) + f1 * (red[1][g][d] + red[1][g][D])) +
+                     (f2 * (red[2][g][d] + red[2][g][D]) + f3 * (red[3][g][d] + red[3][g][D]));
+        } else {
+            dst[A_L] = (f0 * red[0][g][D + 1] + f1 * red[1][g][D + 1]) +
+                       (f2 * red[2][g][D + 1] + f3 * red[3][g][D + 1]);
+            dst[A_M] = M;
+        }
+    }
+}
 
 template <int G>
 __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
@@ -162,30 +229,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
 #pragma unroll
                 for (int g = 0; g < G; ++g) s[g] = a.sm_log2 * fmaf(kscale, u[g], kmn * qsum[g]);
 
-                // raise the reference only when a score runs away from it
-                bool raise = false;
-#pragma unroll
-                for (int g = 0; g < G; ++g) raise |= s[g] > m_ref[g] + RAISE_MARGIN;
-                if (__builtin_amdgcn_ballot_w64(raise) != 0) {
-                    float alpha_col = 1.0f;
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        // the same value in every lane: keep it in a scalar register
-                        const float m_new = __int_as_float(__builtin_amdgcn_readfirstlane(
-                            __float_as_int(fmaxf(m_ref[g], wave_all_max(s[g])))));
-                        const float alpha = exp2_diff(m_ref[g], m_new);
-                        m_ref[g] = m_new;
-                        l_lane[g] *= alpha;
-                        st.pm[g] *= alpha;
-                        if constexpr (!fold_min<G>()) {
-#pragma unroll
-                            for (int j = 0; j < 8; ++j) st.macc[g][j] *= alpha;
-                        }
-                        if ((col >> 1) == g) alpha_col = alpha;
-                    }
-#pragma unroll
-                    for (int j = 0; j < 8; ++j) st.acc[j] *= alpha_col;
-                }
+                attn_raise_reference<G>(s, m_ref, l_lane, st, col);
             }
             wait_chunk_landed();  // V chunk of this block
             if (it + 1 < n_it)
@@ -201,34 +245,102 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
         }
         wait_chunk_landed();
     }
-    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
+    attn_store_partial<G>(a, st, l_lane, m_ref, red, wave, lane, split, head0);
+}
 
-    v_state_store<G>(st, red[wave], lane);
+// The same for chunks with packs of 8 tokens (Sec. IV-B; pack8.h): the K phase runs the
+// pairwise dot-product form for all G heads and leaves lane l with token
+// k8_token_of_block_lane(l) of the block; the V phase stages the weights in that order.
+template <int G>
+__global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK8_LDS + LDS_TAIL_PAD];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
+    __shared__ uint2 table[PACK_TABLE_ENTRIES];   // K: pair table
+    __shared__ uint4 vtable[PACK_TABLE_ENTRIES];  // V: lifted codes
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK8_LDS, "reduction array must fit");
+    float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
+    build_pair_table(table);
+    build_pack_table(vtable, CODE_LIFT, fold_min<G>());
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int split = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int h = bh % a.H, b = bh / a.H;
+    const int col = lane & 15;
+    const int kbuf = wave * 2 * CHUNK8_LDS, vbuf = kbuf + CHUNK8_LDS;
+    const int64_t head0 = int64_t(b) * a.H * G + h * G;
+    const int tok_in_blk = k8_token_of_block_lane(lane);
+
+    KQuery8<G> kq;
+    kq.load(a.q + head0 * D, lane);
+    VLane<G> vl;
+    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
+    vl.bslot = v8_bslot<G>(tok_in_blk);
+    VState<G> st;
+    st.clear();
+    float m_ref[G], l_lane[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        const float l = wave_all_sum(l_lane[g]);
-        if (lane == 0) {
-            red[wave][g][D + 1] = l;
-            red[wave][g][D + 2] = m_ref[g];
+    for (int g = 0; g < G; ++g) m_ref[g] = -INFINITY, l_lane[g] = 0.0f;
+
+    const int blk_begin = split * a.blocks_per_split;
+    const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ik, iv;
+        ik.load(a.k_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        iv.load(a.v_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
+        const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + tok_in_blk;
+        uint32_t kmt_next = a.k_meta[tok0], vmt_next = a.v_meta[tok0];
+        for (int it = 0; it < n_it; ++it) {
+            // a block dropped by an arena overflow (in either tensor) takes no part
+            const bool valid = ik.end16(it) - ik.start16(it) >= uint32_t(HEADER8 / 16) &&
+                               iv.end16(it) - iv.start16(it) >= uint32_t(HEADER8 / 16);
+            wait_chunk_landed();  // K chunk of this block
+            uint32_t kmt = kmt_next, vmt = vmt_next;
+            consume_here(kmt), consume_here(vmt);
+            chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
+            if (it + 1 < n_it) {
+                const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + tok_in_blk;
+                kmt_next = a.k_meta[tok];
+                vmt_next = a.v_meta[tok];
+            }
+
+            float s[G];  // scores of this lane's token in log2 units
+            if (valid) {
+                float u0[G], u1[G];
+                const uint2 hdr0 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
+                LanePacks8 lp0;
+                lp0.init(hdr0.x, hdr0.y, kbuf + HEADER8);
+                k8_half<G>(lds_all, table, lp0, kq, lane, u0);
+                const uint2 hdr1 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 512 + lane * 8);
+                LanePacks8 lp1;
+                lp1.init(hdr1.x, hdr1.y, lp0.end_all);
+                k8_half<G>(lds_all, table, lp1, kq, lane, u1);
+                const float kscale = __half2float(__ushort_as_half(uint16_t(kmt & 0xFFFFu)));
+                const float kmn = __half2float(__ushort_as_half(uint16_t(kmt >> 16)));
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    s[g] = a.sm_log2 * fmaf(kscale, (lane & 1) ? u1[g] : u0[g], kmn * kq.qsum[g]);
+                attn_raise_reference<G>(s, m_ref, l_lane, st, col);
+            }
+            wait_chunk_landed();  // V chunk of this block
+            if (it + 1 < n_it)
+                chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1),
+                                                     lds_all + kbuf, lane);
+            if (!valid) continue;
+            float pt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                pt[g] = exp2f(s[g] - m_ref[g]);
+                l_lane[g] += pt[g];
+            }
+            v8_chunk<G, true>(lds_all, vbuf, vtable, vl, vmt, pt, st);
         }
+        wait_chunk_landed();
     }
-    __syncthreads();
-    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
-        const int g = i / (D + 1), d = i % (D + 1);
-        const float m0 = red[0][g][D + 2], m1 = red[1][g][D + 2], m2 = red[2][g][D + 2], m3 = red[3][g][D + 2];
-        const float M = fmaxf(fmaxf(m0, m1), fmaxf(m2, m3));
-        const float f0 = exp2_diff(m0, M), f1 = exp2_diff(m1, M), f2 = exp2_diff(m2, M), f3 = exp2_diff(m3, M);
-        float *dst = a.partial + (int64_t(split) * a.B * a.H * G + head0 + g) * V_PART_STRIDE;
-        if (d < D) {
-            // outputs carry the per-head sum p*min term
-            dst[d] = (f0 * (red[0][g][d] + red[0][g][D]) + f1 * (red[1][g][d] + red[1][g][D])) +
-                     (f2 * (red[2][g][d] + red[2][g][D]) + f3 * (red[3][g][d] + red[3][g][D]));
-        } else {
-            dst[A_L] = (f0 * red[0][g][D + 1] + f1 * red[1][g][D + 1]) +
-                       (f2 * red[2][g][D + 1] + f3 * red[3][g][D + 1]);
-            dst[A_M] = M;
-        }
-    }
+    attn_store_partial<G>(a, st, l_lane, m_ref, red, wave, lane, split, head0);
 }
 
 // Merges the splits of one (batch, query head) row in a fixed order and adds the raw fp16
@@ -323,12 +435,22 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
         a.sm_log2 = sm_log2;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
-        switch (G) {
-            case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), 0, s, a); break;
-            case 2: hipLaunchKernelGGL(attn_kernel<2>, grid, dim3(256), 0, s, a); break;
-            case 4: hipLaunchKernelGGL(attn_kernel<4>, grid, dim3(256), 0, s, a); break;
-            case 8: hipLaunchKernelGGL(attn_kernel<8>, grid, dim3(256), 0, s, a); break;
-            default: return KV_ERR_UNSUPPORTED;
+        if (c->cfg.pack_size == 8) {
+            switch (G) {
+                case 1: hipLaunchKernelGGL(attn8_kernel<1>, grid, dim3(256), 0, s, a); break;
+                case 2: hipLaunchKernelGGL(attn8_kernel<2>, grid, dim3(256), 0, s, a); break;
+                case 4: hipLaunchKernelGGL(attn8_kernel<4>, grid, dim3(256), 0, s, a); break;
+                case 8: hipLaunchKernelGGL(attn8_kernel<8>, grid, dim3(256), 0, s, a); break;
+                default: return KV_ERR_UNSUPPORTED;
+            }
+        } else {
+            switch (G) {
+                case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), 0, s, a); break;
+                case 2: hipLaunchKernelGGL(attn_kernel<2>, grid, dim3(256), 0, s, a); break;
+                case 4: hipLaunchKernelGGL(attn_kernel<4>, grid, dim3(256), 0, s, a); break;
+                case 8: hipLaunchKernelGGL(attn_kernel<8>, grid, dim3(256), 0, s, a); break;
+                default: return KV_ERR_UNSUPPORTED;
+            }
         }
     }
     hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,

@@ -183,10 +183,20 @@ __device__ inline float lanes8_all_reduce(float v) {
     return v;
 }
 
-// Adds one chunk (both halves) from the LDS buffer at byte offset `cur`: lane l is token l of
-// the block with weight pt[g] for head g and token metadata mt.  `table`: build_pack_table with
-// lift CODE_LIFT and fold = fold_min<G>().  vl.bslot must come from v8_bslot.
-template <int G>
+// Token of the block that lane `lane` holds after the two K halves (k8_half, second half in the
+// odd lanes): 32 (i & 1) + 8 (lane / 16) + (i >> 1), i = lane % 16.
+__device__ inline int k8_token_of_block_lane(int lane) {
+    const int i = lane & 15;
+    return 32 * (i & 1) + 8 * (lane >> 4) + k8_token_of_lane(i);
+}
+
+// Adds one chunk (both halves) from the LDS buffer at byte offset `cur`.  The lane is token
+// `lane` of the block (K8_ORDER false: the three-step path), or token
+// k8_token_of_block_lane(lane) (K8_ORDER true: the fused attention, where the K phase leaves
+// the scores in that order); pt[g]: its weight for head g, mt: its token metadata.  `table`:
+// build_pack_table with lift CODE_LIFT and fold = fold_min<G>().  vl.bslot must be
+// v8_bslot of the lane's token.
+template <int G, bool K8_ORDER = false>
 __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *table, const VLane<G> &vl,
                                 uint32_t mt, const float (&pt)[G], VState<G> &st) {
     const int lane = threadIdx.x & 63;
@@ -205,9 +215,19 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
         if (!fold_min<G>()) {
-            const float w8 = lanes8_all_reduce(w);  // tokens 8k..8k+7 live in lanes 8k..8k+7
-            wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
-            wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+            if constexpr (K8_ORDER) {
+                // the eight tokens of group (half s, row) sit in the lanes of this row with i & 1 = s
+                float v = w + dpp_f32<DPP_ROW_ROR8>(w);
+                v += dpp_f32<DPP_ROW_ROR4>(v);
+                v += dpp_f32<DPP_QUAD_XOR2>(v);
+                const float other = dpp_f32<DPP_QUAD_XOR1>(v);
+                wsum[0][g] = (lane & 1) ? other : v;
+                wsum[1][g] = (lane & 1) ? v : other;
+            } else {
+                const float w8 = lanes8_all_reduce(w);  // tokens 8k..8k+7 live in lanes 8k..8k+7
+                wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
+                wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+            }
         }
     }
     wave_lds_fence();

@@ -80,8 +80,7 @@ def check_packed_state(cache, n_packed, ck, cv, B, H):
 
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
              max_tokens=None, pack_size=16):
-    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
-    With packs of 8 tokens the fused attention entry point must refuse (three-step path only)."""
+    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything."""
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
@@ -123,26 +122,16 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     assert_close_vectors(out3.cpu().numpy(), o_e2e, "three-step path with the library softmax")
 
     # fused decode attention against the oracle's definition of Att(q, K, V)
-    if pack_size == 16:
-        attn = cache.kv_decode_attention(qd, sm_scale)
-        torch.cuda.synchronize()
-        a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
-        assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
-    else:
-        try:
-            cache.kv_decode_attention(qd, sm_scale)
-            raise AssertionError("fused attention must refuse packs of 8 tokens")
-        except binding.PackKVError as e:
-            assert e.code == binding.KV_ERR_UNSUPPORTED
+    attn = cache.kv_decode_attention(qd, sm_scale)
+    torch.cuda.synchronize()
+    a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
+    assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
 
     # determinism: a second pass gives the same bits
     scores2 = cache.kv_k_matvec(qd, sm_scale)
     out2 = cache.kv_v_matvec(p)
+    attn2 = cache.kv_decode_attention(qd, sm_scale)
     torch.cuda.synchronize()
-    assert torch.equal(scores, scores2) and torch.equal(out, out2)
-    if pack_size == 16:
-        attn2 = cache.kv_decode_attention(qd, sm_scale)
-        torch.cuda.synchronize()
-        assert torch.equal(attn, attn2)
+    assert torch.equal(scores, scores2) and torch.equal(out, out2) and torch.equal(attn, attn2)
     cache.close()
     return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)
