@@ -13,7 +13,7 @@ from tests.gpu_cases import assert_close_vectors
 pytestmark = pytest.mark.gpu
 
 
-def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, attn=None):
+def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, attn=None, pack_size=16):
     """Oracle over batch element b (all heads, all tokens) against the GPU state and outputs."""
     B, L, H, _ = K.shape
     Kb = K[b:b + 1].cpu().numpy()
@@ -25,7 +25,7 @@ def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, 
     max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
     codes = {}
     for name, x, rel, nbytes in (("k", Kb, 0.1, st.k_bytes), ("v", Vb, 0.2, st.v_bytes)):
-        c = oracle.compress(np.ascontiguousarray(x[:, :n_packed]), rel)
+        c = oracle.compress(np.ascontiguousarray(x[:, :n_packed]), rel, pack_size)
         meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[b, :n_packed]
         assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta[0]), name + " token meta"
         index = cache.view(name + "_index", torch.int32)[:st.n_chunks + 1].cpu().numpy().view(np.uint32).astype(np.int64)
@@ -52,13 +52,14 @@ def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, 
         assert_close_vectors(attn[b:b + 1].cpu().numpy(), a_ref, "fused decode attention, batch %d" % b)
 
 
-@pytest.mark.parametrize("index,batch_elements", [(3, [7]), (2, [0, 3])])
-def test_full_size_configuration(index, batch_elements):
-    """Benchmark configurations 3 (8 x 52 heads x 32000 tokens) and 2 (GQA, 4 x 8/32 heads x 32768)."""
+@pytest.mark.parametrize("index,batch_elements,pack_size", [(3, [7], 16), (2, [0, 3], 16), (2, [1], 8)])
+def test_full_size_configuration(index, batch_elements, pack_size):
+    """Benchmark configurations 3 (8 x 52 heads x 32000 tokens) and 2 (GQA, 4 x 8/32 heads x 32768),
+    the latter also with packs of 8 tokens."""
     w = synth.workload(index)
     K, V, q = synth.make_workload(w, device="cuda:0")
     L = w.tokens
-    cache = binding.PackedKVCache(w.batch, w.n_kv_heads, w.n_q_heads, L)
+    cache = binding.PackedKVCache(w.batch, w.n_kv_heads, w.n_q_heads, L, pack_size=pack_size)
     cache.kv_compress_append(K, V)
     sm_scale = 128 ** -0.5
     scores = cache.kv_k_matvec(q, sm_scale)
@@ -75,9 +76,10 @@ def test_full_size_configuration(index, batch_elements):
     assert st.n_chunks == n_chunks and st.overflow == 0
     index_t = cache.view("k_index", torch.int32)[:n_chunks + 1].to(torch.int64)
     sizes = (index_t[1:] - index_t[:-1]) * 16
-    assert int(sizes.min()) >= 512 and int(sizes.max()) <= binding.CHUNK_MAX_BYTES
+    header = 512 if pack_size == 16 else 1024
+    assert int(sizes.min()) >= header and int(sizes.max()) <= header + 4096
     for b in batch_elements:
-        _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, attn)
+        _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, attn, pack_size)
     cache.close()
 
 

@@ -61,6 +61,11 @@ def test_random_shapes_and_append_patterns(B, H, Hq, L, seed, pieces):
     gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces)
 
 
+@pytest.mark.parametrize("B,H,Hq,L,seed,pieces", _random_shapes(8, 808))
+def test_random_shapes_with_packs_of_8(B, H, Hq, L, seed, pieces):
+    gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8)
+
+
 def test_benchmark_configuration_1_llama2_7b_4k():
     w = synth.workload(1)
     sizes = gpu_cases.run_case(w.batch, w.n_kv_heads, w.n_q_heads, w.tokens, 1)
@@ -142,15 +147,15 @@ def test_degenerate_inputs():
     _special_case(K, V, 4)
 
 
-@pytest.mark.parametrize("Hq", [2, 4])
-def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq):
+@pytest.mark.parametrize("Hq,pack_size", [(2, 16), (4, 16), (2, 8), (8, 8)])
+def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size):
     B, H, L = 1, 2, 256
     K, V, q = synth.make_kv(B, L, H, Hq, 50)
-    cfg = binding.make_config(B, H, Hq, L)
-    cache = binding.PackedKVCache(B, H, Hq, L)
+    cfg = binding.make_config(B, H, Hq, L, pack_size=pack_size)
+    cache = binding.PackedKVCache(B, H, Hq, L, pack_size=pack_size)
     # rebuild the handle over a K arena that holds about two blocks only
     sizes = binding.kv_sizes_t.from_buffer_copy(cache.sizes)
-    sizes.k_arena = 2 * H * 3300
+    sizes.k_arena = 2 * H * (3300 if pack_size == 16 else 3800)
     bufs = binding.kv_buffers_t()
     for name in binding._BUFFER_NAMES:
         setattr(bufs, name, cache.tensors[name].data_ptr())
@@ -166,7 +171,7 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq):
     assert st.overflow == 1 and st.k_bytes <= sizes.k_arena
     scores = cache.kv_k_matvec(q.cuda(), 1.0)
     torch.cuda.synchronize()
-    n_packed, ck, _ = gpu_cases.oracle_cache(K.numpy(), V.numpy())
+    n_packed, ck, _ = gpu_cases.oracle_cache(K.numpy(), V.numpy(), pack_size=pack_size)
     s_ref = oracle.k_scores(ck.codes, K.numpy(), ck.meta, L, q.numpy(), 1.0)
     kept = st.k_bytes and int(np.searchsorted(ck.offsets16.astype(np.int64) * 16, st.k_bytes, "right") - 1) // (B * H)
     assert 1 <= kept < 4
@@ -174,11 +179,12 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq):
     assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
 
 
-@pytest.mark.parametrize("B,H,Hq,L,pieces", [
-    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21]),   # blocks from bulk appends and from tail flushes
-    (1, 52, 52, 128, None),                        # wide token vectors (6656 values per median)
+@pytest.mark.parametrize("B,H,Hq,L,pieces,pack_size", [
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 16),   # blocks from bulk appends and from tail flushes
+    (1, 52, 52, 128, None, 16),                        # wide token vectors (6656 values per median)
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8),    # the same with packs of 8 tokens
 ])
-def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces):
+def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size):
     """KV_REPACK_V_MEDIAN: order, packed bytes and token metadata bit-exact against the oracle's
     order applied before its compressor; scores in storage order; attention unchanged."""
     rng = np.random.default_rng(70 + B)
@@ -188,17 +194,18 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces):
     V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(72)) ** lean).to(torch.float16)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     n_packed = L // 64 * 64
-    cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN)
+    cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN, pack_size=pack_size)
     pos = 0
     for n in (pieces or [L]):
         cache.kv_compress_append(K[:, pos:pos + n].contiguous().cuda(), V[:, pos:pos + n].contiguous().cuda())
         pos += n
-    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), 0.2)
+    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), 0.2, pack_size)
     order = oracle.v_median_order(cv0.codes)
     assert len(np.unique(order[:, :64])) == 64 and not np.array_equal(order[0, :64], np.arange(64))
     Kp = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_packed:]], axis=1)
     Vp = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_packed:]], axis=1)
-    ck, cv = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), 0.1), oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), 0.2)
+    ck = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), 0.1, pack_size)
+    cv = oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), 0.2, pack_size)
     gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
     max_tokens = cache.tensors["token_order"].numel() // B
     got_order = cache.tensors["token_order"].view(B, max_tokens)[:, :n_packed].cpu().numpy()
@@ -216,7 +223,7 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces):
     a_perm = oracle.attention(kc, Kp, km, vc, Vp, vm, n_packed, qn, sm)
     assert_close_vectors(attn.cpu().numpy(), a_perm, "attention over the repacked cache")
     # and the repacked cache answers like the cache in arrival order (Att(q, PK, PV) = Att(q, K, V))
-    _, ck0, cv0b = gpu_cases.oracle_cache(Kn, Vn)
+    _, ck0, cv0b = gpu_cases.oracle_cache(Kn, Vn, pack_size=pack_size)
     kc0, km0 = gpu_cases.full_codes(ck0, Kn.shape, n_packed)
     vc0, vm0 = gpu_cases.full_codes(cv0b, Vn.shape, n_packed)
     a_orig = oracle.attention(kc0, Kn, km0, vc0, Vn, vm0, n_packed, qn, sm)

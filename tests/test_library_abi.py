@@ -53,6 +53,11 @@ def test_query_sizes_and_config_checks():
     assert worst.token_order == 0
     rp = binding.kv_query_sizes(binding.make_config(2, 32, 32, 4096, repack=binding.REPACK_V_MEDIAN))
     assert rp.token_order >= 2 * 4096 and rp.k_arena == binding.kv_query_sizes(binding.make_config(2, 32, 32, 4096)).k_arena
+    # packs of 8 tokens: twice the header bytes, worst case 1024 + 4096 bytes per chunk
+    p8 = binding.kv_query_sizes(binding.make_config(1, 32, 32, 4096, pack_size=8))
+    assert p8.k_arena >= n_chunks * 5120 and p8.k_arena > worst.k_arena and p8.k_index == worst.k_index
+    bad = binding.make_config(1, 32, 32, 4096, pack_size=4)        # only 16 and 8
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
     assert L.kv_decode_attention(None, None, 1.0, None, None) == -1
     assert L.kv_strerror(-3) == b"cache capacity exceeded"
     assert L.kv_cache_destroy(None) == -1
