@@ -58,10 +58,10 @@ def _event_pair(torch):
 class Replicas:
     """R identical packed caches (rotated so that successive steps do not hit the LLC)."""
 
-    def __init__(self, w, K, V, extra_tokens, binding, torch):
+    def __init__(self, w, K, V, extra_tokens, binding, torch, pack_size=16):
         B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
         L = K.shape[1]
-        first = binding.PackedKVCache(B, H, Hq, L + extra_tokens)
+        first = binding.PackedKVCache(B, H, Hq, L + extra_tokens, pack_size=pack_size)
         first.kv_compress_append(K, V)
         st = first.kv_cache_stats()
         assert st.overflow == 0
@@ -71,7 +71,7 @@ class Replicas:
         bits = max(st.k_bytes, st.v_bytes) * 8.0 / (B * H * 128 * max(st.packed_tokens, 64)) + 0.3
         self.caches = [first]
         for _ in range(R - 1):
-            c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, bits_per_element_budget=bits)
+            c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, bits_per_element_budget=bits, pack_size=pack_size)
             for name in ("k_arena", "v_arena"):
                 n = st.k_bytes if name[0] == "k" else st.v_bytes
                 c.tensors[name][:n].copy_(first.tensors[name][:n])
@@ -97,12 +97,12 @@ def algorithmic_bytes(st, w, tokens):
     return k, v
 
 
-def run_packed(w, K, V, q, steps, warmup, torch, binding, synth):
+def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16):
     """Timed decode steps over rotating replicas; returns a dict of measurements."""
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
     total = steps + warmup
-    reps = Replicas(w, K, V, 2 * total + 64, binding, torch)
+    reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size)
     R = len(reps)
     dev = K.device
     gen = torch.Generator(device=dev)
@@ -386,6 +386,8 @@ def main():
     K, V, q = synth.make_workload(w, device="cuda:0")
     packed = run_packed(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
+    # the second pack size (packs of 8 tokens) on the same data
+    packed8 = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8)
     del K, V
     torch.cuda.empty_cache()
     if args.copy_calibration:
@@ -449,6 +451,15 @@ def main():
         line["roofline_alu"] = {"bound": "alu", "kernel": "kv_%s_matvec" % dom, "achieved": round(slots / 1e9, 1),
                                 "peak": 614.4, "unit": "G wave-instructions/s", "frac": round(slots / 614.4e9, 4),
                                 "slots_per_chunk": ISSUE_SLOTS_PER_CHUNK[dom]}
+    if packed8 is not None:
+        line["pack_size_8"] = {"k_ms": round(packed8["k_ms"], 5), "v_ms": round(packed8["v_ms"], 5),
+                               "attn_ms": round(packed8["attn_ms"], 5),
+                               "k_bits_per_elem": round(packed8["k_bits_per_elem"], 3),
+                               "v_bits_per_elem": round(packed8["v_bits_per_elem"], 3),
+                               "speedup_k": round(fp16["k_ms"] / packed8["k_ms"], 3),
+                               "speedup_v": round(fp16["v_ms"] / packed8["v_ms"], 3),
+                               "ms_per_step": round(packed8["ms_per_step"], 5),
+                               "fused_ms_per_step": round(packed8["fused_ms_per_step"], 5)}
     if not args.no_side_workloads:
         side = {}
         for idx in (0, 1, 2):
