@@ -174,13 +174,17 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
     __syncthreads();
 
     PackBits pb[PER];
-    int off[PER];
-    int payload = 0;
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
         const int g = (tau >> 7) + 2 * k;
         const int64_t tok = int64_t(blk) * N + g * PK;  // first storage slot of the pack
         pb[k] = make_pack<PK>(tile, g, d, meta + b * meta_stride + first_token + tok, qmax);
+    }
+    // all packs are quantized before the first barrier of the scans
+    int off[PER];
+    int payload = 0;
+#pragma unroll
+    for (int k = 0; k < PER; ++k) {
         int total;
         off[k] = payload + block_exclusive_scan(PK / 8 * pb[k].w, &total);
         payload += total;
