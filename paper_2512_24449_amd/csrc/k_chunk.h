@@ -36,18 +36,38 @@ typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
 
 struct KQueryFma {
     uint32_t qp[4];  // q of this lane's 8 channels as fp16 pairs (channels 2k, 2k+1 in word k)
+    uint32_t qe[4];  // the same paired as (0,2) (1,3) (4,6) (5,7): the order pack_min_dot reads the header in
     float qsum;      // sum of all 128 q values
 
     // q_head: the 128 fp16 values of the query head
     __device__ inline void load(const __half *q_head, int lane) {
         const uint4 raw = *reinterpret_cast<const uint4 *>(q_head + 8 * (lane & 15));
         qp[0] = raw.x, qp[1] = raw.y, qp[2] = raw.z, qp[3] = raw.w;
+        qe[0] = __builtin_amdgcn_perm(qp[1], qp[0], 0x05040100u);
+        qe[1] = __builtin_amdgcn_perm(qp[1], qp[0], 0x07060302u);
+        qe[2] = __builtin_amdgcn_perm(qp[3], qp[2], 0x05040100u);
+        qe[3] = __builtin_amdgcn_perm(qp[3], qp[2], 0x07060302u);
         float s = 0.0f;
 #pragma unroll
         for (int k = 0; k < 4; ++k) s += half_lo(qp[k]) + half_hi(qp[k]);
         qsum = row_all_reduce16(s);
     }
 };
+
+// Pack-minimum term of a lane: sum_j q_j m_j * 2^-24 over its eight packs, straight from the
+// eight header bytes (minimum = low nibble): two nibbles at a time are, as they stand, a pair
+// of fp16 subnormals m * 2^-24, the scale the unpacked codes have too.  qe: KQueryFma::qe order.
+__device__ inline float pack_min_dot(uint32_t hlo, uint32_t hhi, const uint32_t (&qe)[4]) {
+    float ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hlo & 0x000F000Fu),
+                                      __builtin_bit_cast(half2_t, qe[0]), 0.0f, false);
+    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (hlo >> 8) & 0x000F000Fu),
+                                __builtin_bit_cast(half2_t, qe[1]), ms, false);
+    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hhi & 0x000F000Fu),
+                                __builtin_bit_cast(half2_t, qe[2]), ms, false);
+    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (hhi >> 8) & 0x000F000Fu),
+                                __builtin_bit_cast(half2_t, qe[3]), ms, false);
+    return ms;
+}
 
 // The four 16-bit fields of a pack, each in the low half of a word (the high half is
 // don't-care): F[f] holds the codes of tokens 4f..4f+3, w bits each, from bit 0 up.  The odd
@@ -71,7 +91,10 @@ __device__ inline void pack_fields(const PackRawPair &r, uint32_t (&F)[4]) {
 // products are exact.
 __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, const LanePacks &lp,
                                     const KQueryFma &kq, int lane) {
-    float acc[16], msum = 0.0f;
+    // every accumulator starts from the lane's pack-minimum term (the row reduction then adds the
+    // sixteen lanes' terms up): no accumulator to clear, no separate reduction for that term
+    const float ms = pack_min_dot(lp.hlo, lp.hhi, kq.qe);
+    float acc[16];
 #pragma unroll
     for (int jp = 0; jp < 4; ++jp) {
         const PackRawPair ra = fetch_pack_pair(lds0, table, lp.pos(2 * jp), lp.header_byte(2 * jp));
@@ -82,8 +105,6 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, con
         const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x0c050c01u));
         const uint32_t masks = __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x07060302u);
         const half2_t q2 = __builtin_bit_cast(half2_t, kq.qp[jp]);
-        msum = fmaf(half_lo(kq.qp[jp]), half_hi(ra.k.y), msum);
-        msum = fmaf(half_hi(kq.qp[jp]), half_hi(rb.k.y), msum);
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
@@ -91,15 +112,13 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, con
             for (int m = 0; m < 4; ++m) {
                 // token 4f+m, both channels; the last code of a clean field needs no mask
                 const uint32_t P = __builtin_bit_cast(uint32_t, Z) & ((f & 1) && m == 3 ? ~0u : masks);
-                if (jp == 0)  // three-address form with a literal zero: no accumulator to clear first
-                    asm("v_dot2_f32_f16 %0, %1, %2, 0" : "=v"(acc[4 * f + m]) : "v"(P), "v"(kq.qp[0]));
-                else
-                    acc[4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P), q2, acc[4 * f + m], false);
+                acc[4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P), q2,
+                                                        jp == 0 ? ms : acc[4 * f + m], false);
                 if (m < 3) Z = Z >> widths;
             }
         }
     }
-    return row_reduce_scatter16(acc, lane) * CODE_SCALE + row_all_reduce16(msum);
+    return row_reduce_scatter16(acc, lane) * CODE_SCALE;
 }
 
 // ---- grouped queries -------------------------------------------------------------

@@ -31,10 +31,8 @@ struct LanePacks8 {
         hlo = lo;
         hhi = hi;
         uint32_t wl = (lo >> 4) & 0x0F0F0F0Fu, wh = (hi >> 4) & 0x0F0F0F0Fu;  // width = bytes per pack
-        wl += wl << 8;
-        wl += wl << 16;
-        wh += wh << 8;
-        wh += wh << 16;
+        wl = byte_prefix_sums(wl);
+        wh = byte_prefix_sums(wh);
         const uint32_t tl = wl >> 24;
         wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
         plo = wl;

@@ -107,6 +107,18 @@ __device__ inline void build_pair_table(uint2 *table) {
     __syncthreads();
 }
 
+// Inclusive prefix sums of the four bytes of x (no byte overflows for the callers' values):
+// two shift-and-add instructions.  Written out as such because the compiler turns the plain C
+// form into a multiplication by 0x01010101, i.e. quarter-rate 32-bit multiplies, one of them a
+// 64-bit multiply-add whose undefined upper addend register made it wait for whatever load
+// happened to be in flight into that register -- which serialized transfer and unpack again.
+__device__ inline uint32_t byte_prefix_sums(uint32_t x) {
+    uint32_t y;
+    asm("v_lshl_add_u32 %0, %1, 8, %1" : "=v"(y) : "v"(x));
+    asm("v_lshl_add_u32 %0, %1, 16, %1" : "=v"(x) : "v"(y));
+    return x;
+}
+
 // Per-lane view of a chunk header and of where its eight packs sit in LDS.
 struct LanePacks {
     uint32_t hlo, hhi;  // eight header bytes, pack j in byte j
@@ -118,10 +130,8 @@ struct LanePacks {
         hlo = lo;
         hhi = hi;
         uint32_t wl = (lo >> 3) & 0x1E1E1E1Eu, wh = (hi >> 3) & 0x1E1E1E1Eu;  // 2 * width per byte
-        wl += wl << 8;
-        wl += wl << 16;
-        wh += wh << 8;
-        wh += wh << 16;
+        wl = byte_prefix_sums(wl);
+        wh = byte_prefix_sums(wh);
         const uint32_t tl = wl >> 24;
         wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
         plo = wl;
