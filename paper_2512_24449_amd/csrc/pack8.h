@@ -61,6 +61,7 @@ __device__ inline uint32_t fetch_window8(const uint8_t *lds0, int pos) {
 template <int G>
 struct KQuery8 {
     uint32_t qp[G][4];  // q of this lane's 8 channels as fp16 pairs, per head
+    uint32_t qe[G][4];  // the same in the pairing pack_min_dot reads the header in
     float qsum[G];      // sum of all 128 q values per head
 
     // q_group: the G query heads of the kv-head, [G][128] fp16
@@ -69,6 +70,10 @@ struct KQuery8 {
         for (int g = 0; g < G; ++g) {
             const uint4 raw = *reinterpret_cast<const uint4 *>(q_group + g * D + 8 * (lane & 15));
             qp[g][0] = raw.x, qp[g][1] = raw.y, qp[g][2] = raw.z, qp[g][3] = raw.w;
+            qe[g][0] = __builtin_amdgcn_perm(qp[g][1], qp[g][0], 0x05040100u);
+            qe[g][1] = __builtin_amdgcn_perm(qp[g][1], qp[g][0], 0x07060302u);
+            qe[g][2] = __builtin_amdgcn_perm(qp[g][3], qp[g][2], 0x05040100u);
+            qe[g][3] = __builtin_amdgcn_perm(qp[g][3], qp[g][2], 0x07060302u);
             float s = 0.0f;
 #pragma unroll
             for (int k = 0; k < 4; ++k) s += half_lo(qp[g][k]) + half_hi(qp[g][k]);
@@ -120,13 +125,10 @@ __device__ inline float row_reduce_scatter8(float (&v)[8], int lane) {
 template <int G>
 __device__ inline void k8_half(const uint8_t *lds0, const uint2 *table, const LanePacks8 &lp,
                                const KQuery8<G> &kq, int lane, float (&u)[G]) {
-    float acc[G][8], msum[G];
+    // every accumulator starts from the lane's pack-minimum term (see k_chunk_fma)
+    float acc[G][8], ms[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        msum[g] = 0.0f;
-#pragma unroll
-        for (int t = 0; t < 8; ++t) acc[g][t] = 0.0f;
-    }
+    for (int g = 0; g < G; ++g) ms[g] = pack_min_dot(lp.hlo, lp.hhi, kq.qe[g]);
 #pragma unroll
     for (int jp = 0; jp < 4; ++jp) {
         const uint32_t Aa = fetch_window8(lds0, lp.pos(2 * jp));
@@ -138,11 +140,6 @@ __device__ inline void k8_half(const uint8_t *lds0, const uint2 *table, const La
         const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(kb.x, ka.x, 0x0c050c01u));
         const uint32_t masks = __builtin_amdgcn_perm(kb.x, ka.x, 0x07060302u);
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            msum[g] = fmaf(half_lo(kq.qp[g][jp]), half_hi(ka.y), msum[g]);
-            msum[g] = fmaf(half_hi(kq.qp[g][jp]), half_hi(kb.y), msum[g]);
-        }
-#pragma unroll
         for (int f = 0; f < 2; ++f) {
             u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
 #pragma unroll
@@ -152,14 +149,13 @@ __device__ inline void k8_half(const uint8_t *lds0, const uint2 *table, const La
                 for (int g = 0; g < G; ++g)
                     acc[g][4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P),
                                                                __builtin_bit_cast(half2_t, kq.qp[g][jp]),
-                                                               acc[g][4 * f + m], false);
+                                                               jp == 0 ? ms[g] : acc[g][4 * f + m], false);
                 if (m < 3) Z = Z >> widths;
             }
         }
     }
 #pragma unroll
-    for (int g = 0; g < G; ++g)
-        u[g] = row_reduce_scatter8(acc[g], lane) * CODE_SCALE + row_all_reduce16(msum[g]);
+    for (int g = 0; g < G; ++g) u[g] = row_reduce_scatter8(acc[g], lane) * CODE_SCALE;
 }
 
 // ---- V -------------------------------------------------------------------------------
