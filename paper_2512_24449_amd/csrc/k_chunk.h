@@ -54,18 +54,28 @@ struct KQueryFma {
     }
 };
 
+// d = a.lo * b.lo + a.hi * b.hi + c with a, b pairs of fp16 and fp32 accumulation: the
+// three-address dot-product instruction, from inline assembly.  The compiler's own choice is the
+// two-address form, which costs a register copy for every accumulator that starts from a live
+// value.  Dot-product results need three wait states before an instruction of another kind reads
+// or overwrites them, which the compiler does not track into inline assembly: every dot product
+// of the K paths goes through this one function, so that their results are only ever consumed as
+// the addend of the same instruction (no wait states needed) or by the reduce-scatter, whose
+// assembly starts with the wait states.
+__device__ inline float dot2_f16(uint32_t a, uint32_t b, float c) {
+    float d;
+    asm("v_dot2_f32_f16 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+    return d;
+}
+
 // Pack-minimum term of a lane: sum_j q_j m_j * 2^-24 over its eight packs, straight from the
 // eight header bytes (minimum = low nibble): two nibbles at a time are, as they stand, a pair
 // of fp16 subnormals m * 2^-24, the scale the unpacked codes have too.  qe: KQueryFma::qe order.
 __device__ inline float pack_min_dot(uint32_t hlo, uint32_t hhi, const uint32_t (&qe)[4]) {
-    float ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hlo & 0x000F000Fu),
-                                      __builtin_bit_cast(half2_t, qe[0]), 0.0f, false);
-    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (hlo >> 8) & 0x000F000Fu),
-                                __builtin_bit_cast(half2_t, qe[1]), ms, false);
-    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, hhi & 0x000F000Fu),
-                                __builtin_bit_cast(half2_t, qe[2]), ms, false);
-    ms = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, (hhi >> 8) & 0x000F000Fu),
-                                __builtin_bit_cast(half2_t, qe[3]), ms, false);
+    float ms = dot2_f16(hlo & 0x000F000Fu, qe[0], 0.0f);
+    ms = dot2_f16((hlo >> 8) & 0x000F000Fu, qe[1], ms);
+    ms = dot2_f16(hhi & 0x000F000Fu, qe[2], ms);
+    ms = dot2_f16((hhi >> 8) & 0x000F000Fu, qe[3], ms);
     return ms;
 }
 
@@ -104,7 +114,6 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, con
         pack_fields(rb, Fb);
         const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x0c050c01u));
         const uint32_t masks = __builtin_amdgcn_perm(rb.k.x, ra.k.x, 0x07060302u);
-        const half2_t q2 = __builtin_bit_cast(half2_t, kq.qp[jp]);
 #pragma unroll
         for (int f = 0; f < 4; ++f) {
             u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
@@ -112,8 +121,7 @@ __device__ inline float k_chunk_fma(const uint8_t *lds0, const uint2 *table, con
             for (int m = 0; m < 4; ++m) {
                 // token 4f+m, both channels; the last code of a clean field needs no mask
                 const uint32_t P = __builtin_bit_cast(uint32_t, Z) & ((f & 1) && m == 3 ? ~0u : masks);
-                acc[4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P), q2,
-                                                        jp == 0 ? ms : acc[4 * f + m], false);
+                acc[4 * f + m] = dot2_f16(P, kq.qp[jp], jp == 0 ? ms : acc[4 * f + m]);
                 if (m < 3) Z = Z >> widths;
             }
         }

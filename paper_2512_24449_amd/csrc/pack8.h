@@ -147,9 +147,7 @@ __device__ inline void k8_half(const uint8_t *lds0, const uint2 *table, const La
                 const uint32_t P = __builtin_bit_cast(uint32_t, Z) & (f == 1 && m == 3 ? ~0u : masks);
 #pragma unroll
                 for (int g = 0; g < G; ++g)
-                    acc[g][4 * f + m] = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, P),
-                                                               __builtin_bit_cast(half2_t, kq.qp[g][jp]),
-                                                               jp == 0 ? ms[g] : acc[g][4 * f + m], false);
+                    acc[g][4 * f + m] = dot2_f16(P, kq.qp[g][jp], jp == 0 ? ms[g] : acc[g][4 * f + m]);
                 if (m < 3) Z = Z >> widths;
             }
         }
