@@ -57,6 +57,7 @@ def lib():
         _lib.orc_xhat.argtypes = [C.c_uint8, C.c_uint16, C.c_uint16]
         _lib.orc_pack_chunk.restype = C.c_int
         _lib.orc_pack_chunk_k.restype = C.c_int
+        _lib.orc_pack_chunk_wide.restype = C.c_int
         _lib.orc_compress.restype = C.c_int64
         _lib.orc_compress_k.restype = C.c_int64
         _lib.orc_threads.restype = C.c_int
@@ -132,6 +133,19 @@ def dequant(q, scale16, min16):
     return out
 
 
+def pack_chunk_wide(q_chunk):
+    """q_chunk: uint8 [64, 128], codes up to 255 -> (bytes, widths [1024], mins [1024]): the wide
+    chunk layout (packs of 8 tokens, two metadata bytes per pack)."""
+    q_chunk = np.ascontiguousarray(q_chunk, dtype=np.uint8)
+    assert q_chunk.shape == (N, D)
+    packs = N // 8 * D
+    buf = np.zeros(2 * packs + N * D + 16, np.uint8)
+    w = np.empty(packs, np.uint8)
+    m = np.empty(packs, np.uint8)
+    size = lib().orc_pack_chunk_wide(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m))
+    return buf[:size].copy(), w, m
+
+
 def pack_chunk(q_chunk, pack_size=K):
     """q_chunk: uint8 [64, 128] -> (bytes uint8 [size], widths [packs], mins [packs]), packs =
     (64 / pack_size) * 128."""
@@ -166,13 +180,14 @@ class Compressed:
 
 
 def compress(x, rel, pack_size=K) -> Compressed:
-    """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed (packs of pack_size tokens)."""
+    """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed (packs of pack_size tokens).
+    Scales finer than 1/15 (codes above 15) give wide chunks and need pack_size 8."""
     x = _u16(x)
     B, T, H, Dd = x.shape
     assert Dd == D and T % N == 0 and pack_size in (8, 16)
     packs = N // pack_size * D
     nchunks = (T // N) * B * H
-    cap = nchunks * (packs + N * D // 2)
+    cap = nchunks * (2 * packs + N * D)
     arena = np.zeros(cap, np.uint8)
     offsets = np.zeros(nchunks + 1, np.uint32)
     meta = np.empty((B, T), np.uint32)

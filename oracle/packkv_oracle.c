@@ -26,7 +26,10 @@
  *     per tensor, stored as fp16; quantization uses the stored fp16 values;
  *   - fp32 subtract and divide, round-half-to-even, clamp to [0, qmax],
  *     qmax = round(1/rel); scale == 0 gives code 0;
- *   - pack metadata is one byte, (width << 4) | min;
+ *   - pack metadata is one byte, (width << 4) | min, as long as the codes stay
+ *     below 16 (rel >= 1/15); for finer scales (codes up to 255, "wide" chunks,
+ *     packs of 8 tokens only) it is two bytes: all widths (0..8) first, one
+ *     byte per pack, then all minimums (0..255), one byte per pack;
  *   - chunk bytes: (64/k)*128 header bytes indexed [token_group*128 + channel]
  *     (512 for k = 16, 1024 for k = 8), then the packs in the same order, each
  *     k*width/8 bytes little-endian with the code of token i at bits
@@ -51,8 +54,8 @@
 #define ORC_PACKS (ORC_GROUPS * ORC_D)
 #define ORC_HEADER ORC_PACKS
 #define ORC_CHUNK_MAX (ORC_HEADER + ORC_PACKS * 8)
-/* any pack size k in {8, 16}: 64/k * 128 header bytes + 64*128*4/8 payload bytes */
-#define ORC_CHUNK_MAX_ANY (2 * ORC_PACKS + ORC_N * ORC_D / 2)
+/* any layout: at most 2 * 1024 header bytes + 64*128 payload bytes (wide chunks) */
+#define ORC_CHUNK_MAX_ANY (4 * ORC_PACKS + ORC_N * ORC_D)
 
 /* ---------------------------------------------------------------- fp16 -- */
 
@@ -234,6 +237,44 @@ int orc_pack_chunk_k(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
     return pos;
 }
 
+/*
+ * Pack one chunk whose codes may exceed 15 (quantization scales finer than
+ * 1/15, codes up to 255): packs of 8 tokens, widths up to 8 bits.  Layout:
+ * 1024 width bytes indexed [token_group*128 + channel], 1024 minimum bytes in
+ * the same order, then the packs, `width` bytes each, code of token i at bits
+ * [i*width, (i+1)*width), zero padding to 16 bytes.
+ */
+int orc_pack_chunk_wide(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
+                        uint8_t *widths, uint8_t *mins)
+{
+    const int k = 8, groups = ORC_N / 8, packs = groups * ORC_D;
+    int pos = 2 * packs;
+    for (int g = 0; g < groups; ++g)
+        for (int d = 0; d < ORC_D; ++d) {
+            int p = g * ORC_D + d;
+            int lo = 255, hi = 0;
+            for (int i = 0; i < k; ++i) {
+                int v = q[(int64_t)(g * k + i) * token_stride + d];
+                if (v < lo) lo = v;
+                if (v > hi) hi = v;
+            }
+            int w = orc_width(hi - lo);
+            bytes[p] = (uint8_t)w;
+            bytes[packs + p] = (uint8_t)lo;
+            if (widths) widths[p] = (uint8_t)w;
+            if (mins) mins[p] = (uint8_t)lo;
+            uint64_t bits = 0;
+            for (int i = 0; i < k; ++i) {
+                uint64_t c = (uint64_t)(q[(int64_t)(g * k + i) * token_stride + d] - lo);
+                bits |= c << (i * w);
+            }
+            for (int j = 0; j < w; ++j)
+                bytes[pos++] = (uint8_t)(bits >> (8 * j));
+        }
+    while (pos % 16) bytes[pos++] = 0;
+    return pos;
+}
+
 int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
                    uint8_t *widths, uint8_t *mins)
 {
@@ -256,6 +297,8 @@ int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
                        uint8_t *mins_out, int k)
 {
     if (D != ORC_D || T % ORC_N || (k != 8 && k != 16)) return -2;
+    int wide = orc_qmax(rel) > 15;  /* codes do not fit the 4-bit minimum of the one-byte metadata */
+    if (wide && (k != 8 || orc_qmax(rel) > 255)) return -2;
     int packs = ORC_N / k * ORC_D;
     int64_t n = (int64_t)B * T;
     uint16_t *scale16 = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)n);
@@ -274,9 +317,10 @@ int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
         for (int b = 0; b < B && rc == 0; ++b)
             for (int h = 0; h < H; ++h, ++c) {
                 const uint8_t *q0 = q + (((int64_t)b * T + (int64_t)blk * ORC_N) * H + h) * D;
-                int sz = orc_pack_chunk_k(q0, (int64_t)H * D, tmp,
-                                          widths_out ? widths_out + c * packs : NULL,
-                                          mins_out ? mins_out + c * packs : NULL, k);
+                uint8_t *wo = widths_out ? widths_out + c * packs : NULL;
+                uint8_t *mo = mins_out ? mins_out + c * packs : NULL;
+                int sz = wide ? orc_pack_chunk_wide(q0, (int64_t)H * D, tmp, wo, mo)
+                              : orc_pack_chunk_k(q0, (int64_t)H * D, tmp, wo, mo, k);
                 if (pos + sz > arena_cap) { rc = -1; break; }
                 memcpy(arena + pos, tmp, (size_t)sz);
                 offsets16[c] = (uint32_t)(pos / 16);

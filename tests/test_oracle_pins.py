@@ -49,7 +49,8 @@ def test_float_to_half_matches_ieee_rne(orc):
 
 # ------------------------------------------------------- quantizer pins --
 
-@pytest.mark.parametrize("rel,H,seed", [(0.1, 1, 0), (0.1, 8, 1), (0.2, 1, 2), (0.2, 32, 3), (1 / 15, 2, 4)])
+@pytest.mark.parametrize("rel,H,seed", [(0.1, 1, 0), (0.1, 8, 1), (0.2, 1, 2), (0.2, 32, 3), (1 / 15, 2, 4),
+                                        (0.04, 4, 5), (1 / 255, 2, 6)])   # the last two: codes above 15
 def test_error_bound_and_range(orc, rel, H, seed):
     """|x - x_hat| <= scale/2 = rel/2 * (max - min) (Sec. IV-A); codes in [0, round(1/rel)]."""
     K, V, _ = _kv(2, 128, H, seed)
@@ -104,6 +105,7 @@ def test_width_table(orc):
     """ceil(log2(range + 1)) (Sec. III-B.3): 0->0, 1->1, 2-3->2, 4-7->3, 8-15->4."""
     expect = {0: 0, 1: 1, 2: 2, 3: 2, 4: 3, 5: 3, 6: 3, 7: 3}
     expect.update({r: 4 for r in range(8, 16)})
+    expect.update({16: 5, 31: 5, 32: 6, 63: 6, 64: 7, 127: 7, 128: 8, 255: 8})   # wide chunks
     for r, w in expect.items():
         assert orc.width(r) == w
         assert w == int(np.ceil(np.log2(r + 1)))
@@ -128,6 +130,48 @@ def test_pack_chunk_against_independent_reader(orc, seed, k):
     assert np.array_equal(widths.reshape(64 // k, 128), np.ceil(np.log2(rng_ + 1)).astype(np.int64))
     # closed-form size: header + k/8 bytes per width bit per pack, padded to 16
     assert buf.size == (64 // k * 128 + k // 8 * int(widths.sum()) + 15) // 16 * 16
+
+
+@pytest.mark.parametrize("seed,top", [(0, 255), (1, 25), (2, 16)])
+def test_wide_chunk_against_independent_reader(orc, seed, top):
+    """Codes above 15 (scales finer than 1/15): two metadata bytes per pack of 8 tokens."""
+    rng = np.random.default_rng(seed)
+    q = rng.integers(0, top + 1, size=(64, 128)).astype(np.uint8)
+    q[:, 3] = top                          # constant channel: width 0, minimum above 15
+    q[8:16, 9] = [top - 1, top] * 4        # width 1 at a large minimum
+    q[:, 40:60] = rng.integers(top // 2, top // 2 + 3, size=(64, 20))
+    buf, widths, mins = orc.pack_chunk_wide(q)
+    codes, w2, m2 = chunk_reader.read_chunk_wide(buf)
+    assert np.array_equal(codes, q) and np.array_equal(w2, widths) and np.array_equal(m2, mins)
+    packs = q.reshape(8, 8, 128).astype(np.int64)
+    assert np.array_equal(mins.reshape(8, 128), packs.min(1))
+    rng_ = packs.max(1) - packs.min(1)
+    assert np.array_equal(widths.reshape(8, 128), np.ceil(np.log2(rng_ + 1)).astype(np.int64))
+    assert widths.max() <= 8 and buf.size == (2048 + int(widths.sum()) + 15) // 16 * 16
+
+
+@pytest.mark.parametrize("rel", [0.05, 1 / 40, 1 / 255])
+def test_compress_with_fine_scales_gives_wide_chunks(orc, rel):
+    """rel < 1/15: same quantizer, codes up to round(1/rel), wide chunk layout, packs of 8 only;
+    the matvecs over the decoded values stay the plain definitions."""
+    B, T, H = 2, 128, 3
+    K, V, q = _kv(B, T, H, 9)
+    c = orc.compress(K, rel, 8)
+    assert c.codes.max() == round(1 / rel) and c.codes.max() > 15
+    assert np.array_equal(chunk_reader.read_arena(c.arena, c.offsets16, B, T, H, wide=True), c.codes)
+    sizes = np.diff(c.offsets16.astype(np.int64)) * 16
+    assert np.array_equal(sizes, (2048 + c.widths.astype(np.int64).sum(1) + 15) // 16 * 16)
+    with pytest.raises(AssertionError):
+        orc.compress(K, rel, 16)            # wide chunks exist for packs of 8 only
+    # finer scale, smaller error: bound scale/2 with scale = rel * range
+    xhat = orc.dequant(c.codes, c.scale16, c.min16)
+    scale = c.scale16.view(np.float16).astype(np.float64)[:, :, None, None]
+    assert (np.abs(K.astype(np.float64) - xhat) <= scale * (0.5 + 2.0 ** -20)).all()
+    # brute force matvec on the reader's codes
+    codes = chunk_reader.read_arena(c.arena, c.offsets16, B, T, H, wide=True)
+    mn = c.min16.view(np.float16).astype(np.float64)[:, :, None, None]
+    s_ref = 0.3 * np.einsum("bhd,bthd->bht", q.astype(np.float64), codes * scale + mn)
+    assert np.allclose(orc.k_scores(c.codes, K, c.meta, T, q, 0.3), s_ref, rtol=1e-12, atol=1e-12)
 
 
 def test_pack_size_8_against_pack_size_16(orc):
