@@ -57,6 +57,8 @@ extern "C" {
 #define KV_CHUNK_MAX_BYTES (512 + 512 * 8)   /* largest chunk, packs of 16             */
 #define KV_CHUNK_HEADER_PACK8 1024           /* the same with packs of 8 tokens        */
 #define KV_CHUNK_MAX_BYTES_PACK8 (1024 + 1024 * 4)
+#define KV_CHUNK_HEADER_WIDE 2048            /* wide chunks: codes above 15            */
+#define KV_CHUNK_MAX_BYTES_WIDE (2048 + 1024 * 8)
 
 typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library */
 
@@ -67,7 +69,12 @@ typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library 
  * paper's defaults), pack size 16, repacking none, block 64.  Pack size 8 (the
  * other good point of the pack-size study, Sec. IV-B): a chunk then has 1024
  * header bytes, indexed [token_group * 128 + channel] with token groups of 8,
- * and packs of `width` bytes.  KV_REPACK_V_MEDIAN
+ * and packs of `width` bytes.  A relative scale below 1/15 gives codes above 15
+ * ("wide" chunks for that tensor: packs of 8 tokens with widths up to 8 bits,
+ * 1024 width bytes followed by 1024 minimum bytes, then the packs); it needs
+ * pack_size 8 and KV_REPACK_NONE, its lower bound is 1/255, and
+ * kv_decode_attention is not available with it (the three-step path is).
+ * KV_REPACK_V_MEDIAN
  * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
  * tokens, K and V are packed with their tokens sorted by the lower median of the
  * token's quantized V vector over all kv-heads (ascending, ties in arrival
@@ -81,8 +88,8 @@ typedef struct {
     int32_t pack_size;     /* 16 or 8                                             */
     int32_t repack;        /* KV_REPACK_NONE or KV_REPACK_V_MEDIAN                */
     int32_t tail_capacity; /* raw fp16 tail buffer in tokens, must be 64          */
-    float k_rel_scale;     /* in [1/15, 1]                                        */
-    float v_rel_scale;     /* in [1/15, 1]                                        */
+    float k_rel_scale;     /* in [1/15, 1]; down to 1/255 with pack_size 8        */
+    float v_rel_scale;     /* the same                                            */
     int64_t max_tokens;    /* per batch element, rounded up to a block internally */
 } kv_config_t;
 

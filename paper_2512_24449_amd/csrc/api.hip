@@ -25,10 +25,13 @@ int check_config(const kv_config_t *c) {
     if (c->n_q_heads % c->n_kv_heads) return KV_ERR_ARG;
     const int g = c->n_q_heads / c->n_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return KV_ERR_UNSUPPORTED;
-    // one pack byte holds a 4-bit minimum: codes must stay below 16
+    // one pack byte holds a 4-bit minimum: codes above 15 need the wide layout, which exists
+    // for packs of 8 tokens without repacking only; a code is one byte at most
     for (float rel : {c->k_rel_scale, c->v_rel_scale}) {
         if (!(rel > 0.0f) || rel > 1.0f) return KV_ERR_ARG;
-        if (lround(1.0 / double(rel)) > 15) return KV_ERR_UNSUPPORTED;
+        const long qmax = lround(1.0 / double(rel));
+        if (qmax > 255) return KV_ERR_UNSUPPORTED;
+        if (qmax > 15 && (c->pack_size != 8 || c->repack != KV_REPACK_NONE)) return KV_ERR_UNSUPPORTED;
     }
     if (int64_t(c->batch) * c->n_kv_heads > 65535) return KV_ERR_UNSUPPORTED;
     const int64_t max_tokens = (c->max_tokens + N - 1) / N * N;
@@ -47,16 +50,23 @@ extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_bu
     if (!out || bits_per_element_budget < 0.0) return KV_ERR_ARG;
     const int64_t max_tokens = (cfg->max_tokens + N - 1) / N * N;
     const int64_t max_chunks = max_tokens / N * cfg->batch * cfg->n_kv_heads;
-    const int header = chunk_header_bytes(cfg->pack_size);
-    const double worst_bits = double(chunk_max_bytes(cfg->pack_size)) * 8.0 / (N * D);
-    double bits = bits_per_element_budget == 0.0 ? worst_bits : bits_per_element_budget;
-    if (bits > worst_bits) bits = worst_bits;
-    // never less than the headers, plus one worst-case chunk of slack per stream for padding
-    double per_chunk = bits * (N * D) / 8.0;
-    if (per_chunk < header + 16) per_chunk = header + 16;
-    size_t arena = size_t(std::ceil(per_chunk * double(max_chunks))) + 16;
-    if (arena > size_t(0xFFFFFFFFull) * 16) return KV_ERR_UNSUPPORTED;  // index is in 16-byte units
-    out->k_arena = out->v_arena = round256(arena);
+    size_t arena[2];
+    int t = 0;
+    for (float rel : {cfg->k_rel_scale, cfg->v_rel_scale}) {
+        const bool wide = wide_codes(rel);
+        const int header = chunk_header_bytes(cfg->pack_size, wide);
+        const double worst_bits = double(chunk_max_bytes(cfg->pack_size, wide)) * 8.0 / (N * D);
+        double bits = bits_per_element_budget == 0.0 ? worst_bits : bits_per_element_budget;
+        if (bits > worst_bits) bits = worst_bits;
+        // never less than the headers, plus one worst-case chunk of slack per stream for padding
+        double per_chunk = bits * (N * D) / 8.0;
+        if (per_chunk < header + 16) per_chunk = header + 16;
+        arena[t] = size_t(std::ceil(per_chunk * double(max_chunks))) + 16;
+        if (arena[t] > size_t(0xFFFFFFFFull) * 16) return KV_ERR_UNSUPPORTED;  // index is in 16-byte units
+        ++t;
+    }
+    out->k_arena = round256(arena[0]);
+    out->v_arena = round256(arena[1]);
     out->k_index = out->v_index = round256(size_t(max_chunks + 1) * 4);
     out->k_token_meta = out->v_token_meta = round256(size_t(cfg->batch) * max_tokens * 4);
     out->k_tail = out->v_tail =
@@ -80,8 +90,9 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
     for (const void *p : ptrs)
         if (!aligned256(p)) return KV_ERR_ARG;
     // arenas may be any size >= one chunk; everything else must be complete
-    const size_t chunk_max = size_t(chunk_max_bytes(cfg->pack_size));
-    if (sizes->k_arena < chunk_max || sizes->v_arena < chunk_max || sizes->k_index < need.k_index ||
+    if (sizes->k_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->k_rel_scale))) ||
+        sizes->v_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->v_rel_scale))) ||
+        sizes->k_index < need.k_index ||
         sizes->v_index < need.v_index || sizes->k_token_meta < need.k_token_meta ||
         sizes->v_token_meta < need.v_token_meta || sizes->k_tail < need.k_tail ||
         sizes->v_tail < need.v_tail || sizes->workspace < need.workspace)
@@ -98,6 +109,8 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
     c->group = cfg->n_q_heads / cfg->n_kv_heads;
     c->qmax_k = int(lround(1.0 / double(cfg->k_rel_scale)));
     c->qmax_v = int(lround(1.0 / double(cfg->v_rel_scale)));
+    c->wide_k = c->qmax_k > 15;
+    c->wide_v = c->qmax_v > 15;
     c->packed_tokens = 0;
     c->tail_tokens = 0;
     rc = launch_init(c, nullptr);
@@ -139,6 +152,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         kjob.src = ksrc + int64_t(done) * N * job.token_stride;
         kjob.rel = c->cfg.k_rel_scale;
         kjob.qmax = c->qmax_k;
+        kjob.wide = c->wide_k;
         kjob.arena = static_cast<uint8_t *>(c->buf.k_arena);
         kjob.arena_cap16 = c->sizes.k_arena / 16;
         kjob.index = static_cast<uint32_t *>(c->buf.k_index);
@@ -147,6 +161,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         vjob.src = vsrc + int64_t(done) * N * job.token_stride;
         vjob.rel = c->cfg.v_rel_scale;
         vjob.qmax = c->qmax_v;
+        vjob.wide = c->wide_v;
         vjob.arena = static_cast<uint8_t *>(c->buf.v_arena);
         vjob.arena_cap16 = c->sizes.v_arena / 16;
         vjob.index = static_cast<uint32_t *>(c->buf.v_index);
@@ -233,6 +248,7 @@ extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale,
                                    void *hip_stream) {
     if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;
     if (c->packed_tokens + c->tail_tokens < 1) return KV_ERR_ARG;  // softmax over nothing
+    if (c->wide_k || c->wide_v) return KV_ERR_UNSUPPORTED;         // wide chunks: three-step path only
     return launch_decode_attention(c, static_cast<const __half *>(q), sm_scale, out,
                                    static_cast<hipStream_t>(hip_stream));
 }

@@ -4,6 +4,7 @@
 
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "packkv.h"
@@ -20,8 +21,16 @@ constexpr int CHUNK_MAX = KV_CHUNK_MAX_BYTES;
 // packs of 8 tokens: 8 token groups, twice the header bytes
 constexpr int HEADER8 = KV_CHUNK_HEADER_PACK8;
 constexpr int CHUNK8_MAX = KV_CHUNK_MAX_BYTES_PACK8;
-inline int chunk_header_bytes(int pack_size) { return pack_size == 8 ? HEADER8 : HEADER; }
-inline int chunk_max_bytes(int pack_size) { return pack_size == 8 ? CHUNK8_MAX : CHUNK_MAX; }
+// wide chunks (codes above 15; packs of 8 tokens): a width byte and a minimum byte per pack
+constexpr int HEADERW = KV_CHUNK_HEADER_WIDE;
+constexpr int CHUNKW_MAX = KV_CHUNK_MAX_BYTES_WIDE;
+inline bool wide_codes(float rel) { return lround(1.0 / double(rel)) > 15; }
+inline int chunk_header_bytes(int pack_size, bool wide = false) {
+    return wide ? HEADERW : (pack_size == 8 ? HEADER8 : HEADER);
+}
+inline int chunk_max_bytes(int pack_size, bool wide = false) {
+    return wide ? CHUNKW_MAX : (pack_size == 8 ? CHUNK8_MAX : CHUNK_MAX);
+}
 
 // Workspace layout (bytes).
 constexpr size_t WS_STATUS = 0;                 // uint32 status[64]
@@ -87,6 +96,7 @@ struct kv_cache {
     int64_t max_chunks;     // per tensor
     int group;              // query heads per kv head
     int qmax_k, qmax_v;
+    bool wide_k, wide_v;    // codes above 15: wide chunk layout for that tensor
     int64_t packed_tokens;  // per batch element
     int32_t tail_tokens;
 };
@@ -109,6 +119,7 @@ struct CompressJob {
     int64_t first_chunk;      // destination chunk index
     float rel;
     int qmax;
+    bool wide;                // wide chunk layout
     uint8_t *arena;
     uint64_t arena_cap16;     // capacity in 16-byte units
     uint32_t *index;

@@ -130,8 +130,9 @@ __device__ inline int block_exclusive_scan(int v, int *total) {
 
 // One workgroup per new chunk; packs of PK tokens (16, or 8: Sec. IV-B): the chunk has
 // 64/PK token groups of 128 packs, thread tau owns packs tau + 256k (token group (tau >> 7) + 2k,
-// channel tau & 127).  A pack takes PK*w/8 payload bytes.
-template <bool WRITE, int PK>
+// channel tau & 127).  A pack takes PK*w/8 payload bytes.  WIDE (codes above 15, packs of 8): the
+// header is a width byte per pack followed by a minimum byte per pack, widths go up to 8.
+template <bool WRITE, int PK, bool WIDE = false>
 __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ src,
                                                     int64_t batch_stride, int64_t token_stride,
                                                     int B, int H, int qmax,
@@ -142,7 +143,9 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     const uint32_t *__restrict__ index,
                                                     uint8_t *__restrict__ arena,
                                                     const uint8_t *__restrict__ order) {
-    constexpr int HDR = N / PK * D;        // header bytes: one per pack
+    static_assert(!WIDE || PK == 8, "wide chunks have packs of 8 tokens");
+    constexpr int NPACKS = N / PK * D;
+    constexpr int HDR = WIDE ? 2 * NPACKS : NPACKS;  // header bytes
     constexpr int PER = N / PK * D / 256;  // packs per thread
     const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
     const int h = cl % H;
@@ -197,7 +200,12 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
     }
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
-        dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
+        if constexpr (WIDE) {
+            dst[tau + 256 * k] = uint8_t(pb[k].w);
+            dst[NPACKS + tau + 256 * k] = uint8_t(pb[k].m);
+        } else {
+            dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
+        }
         if constexpr (PK == 16) {
             uint16_t *out = reinterpret_cast<uint16_t *>(dst + HDR + off[k]);
             for (int j = 0; j < pb[k].w; ++j) out[j] = uint16_t(pb[k].bits >> (16 * j));
@@ -392,8 +400,10 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
-    auto sizes_kernel = c->cfg.pack_size == 8 ? chunk_kernel<false, 8> : chunk_kernel<false, 16>;
-    auto write_kernel = c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>;
+    auto sizes_kernel = job.wide ? chunk_kernel<false, 8, true>
+                                 : (c->cfg.pack_size == 8 ? chunk_kernel<false, 8> : chunk_kernel<false, 16>);
+    auto write_kernel = job.wide ? chunk_kernel<true, 8, true>
+                                 : (c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>);
     hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                        job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);

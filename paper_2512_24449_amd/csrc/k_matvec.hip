@@ -264,6 +264,56 @@ __device__ inline void k8_stream(const KArgs &a, int bh, int blk_begin, int blk_
     }
 }
 
+// Wide chunks (codes above 15; pack8.h): same result layout as k8_stream.  A wide chunk is up to
+// 10 KB, so each wave has one buffer: the transfer is waited for before the unpack starts, and
+// the overlap comes from the other waves of the compute unit only.
+template <int G>
+__device__ inline void kw_stream(const KArgs &a, int bh, int blk_begin, int blk_end, int wave, int lane,
+                                 uint8_t *lds0, int buf, const uint2 *ktable) {
+    const int h = bh % a.H, b = bh / a.H;
+    const int64_t head0 = int64_t(b) * a.H * G + h * G;
+    KQuery8<G> kq;
+    kq.load(a.q + head0 * D, lane);
+    const int tok_in_blk = k8_token_of_block_lane(lane);
+    const uint32_t *meta = a.meta + b * a.meta_stride + tok_in_blk;
+
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        for (int it = 0; it < n_it; ++it) {
+            const int64_t tok = int64_t(first + 4 * it) * N + tok_in_blk;
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADERW / 16);
+            chunk_issue_lds<CHUNKW_MAX, HEADERW>(a.arena, ib.start16(it), ib.end16(it), lds0 + buf, lane);
+            const uint32_t mt = meta[int64_t(first + 4 * it) * N];
+            wait_chunk_landed();
+            if (!valid) {  // block dropped by an arena overflow: defined output
+#pragma unroll
+                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                continue;
+            }
+            float u0[G], u1[G];
+            const uint2 w0 = *reinterpret_cast<const uint2 *>(lds0 + buf + lane * 8);
+            const uint2 m0 = *reinterpret_cast<const uint2 *>(lds0 + buf + 1024 + lane * 8);
+            LanePacksW lp0;
+            lp0.init(w0, m0, buf + HEADERW);
+            kw_half<G>(lds0, ktable, lp0, kq, lane, u0);
+            const uint2 w1 = *reinterpret_cast<const uint2 *>(lds0 + buf + 512 + lane * 8);
+            const uint2 m1 = *reinterpret_cast<const uint2 *>(lds0 + buf + 1536 + lane * 8);
+            LanePacksW lp1;
+            lp1.init(w1, m1, lp0.end_all);
+            kw_half<G>(lds0, ktable, lp1, kq, lane, u1);
+            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                a.scores[(head0 + g) * a.ld + tok] =
+                    a.sm_scale * fmaf(scale, (lane & 1) ? u1[g] : u0[g], mn * kq.qsum[g]);
+            wave_lds_fence();  // every lane is done reading before the next transfer overwrites the buffer
+        }
+    }
+}
+
 // Raw fp16 tail (Sec. III-B.1 buffer): plain dot products, one lane per token.
 template <int G>
 __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
@@ -339,6 +389,26 @@ __global__ __launch_bounds__(256) void k8_matvec_kernel(KArgs a) {
     }
 }
 
+template <int G>
+__global__ __launch_bounds__(256) void kw_matvec_kernel(KArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * CHUNKW_LDS + LDS_TAIL_PAD];
+    __shared__ uint2 ktable[16];
+    build_wide_tables(ktable, nullptr);
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = blockIdx.x;
+    if (grp < a.n_stream_groups) {
+        const int bh = grp / a.groups_per_stream;
+        const int part = grp % a.groups_per_stream;
+        const int blk_begin = part * a.blocks_per_group;
+        const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
+        kw_stream<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * CHUNKW_LDS, ktable);
+    } else {
+        const int bh = (grp - a.n_stream_groups) * 4 + wave;
+        if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
+    }
+}
+
 int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *scores,
                     int64_t ld_scores, hipStream_t s) {
     KArgs a;
@@ -369,7 +439,15 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     const int tail_groups = a.n_tail > 0 ? (streams + 3) / 4 : 0;
     const int grid = a.n_stream_groups + tail_groups;
     if (grid == 0) return KV_OK;
-    if (c->cfg.pack_size == 8) {
+    if (c->wide_k) {
+        switch (c->group) {
+            case 1: hipLaunchKernelGGL(kw_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
+            case 2: hipLaunchKernelGGL(kw_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
+            case 4: hipLaunchKernelGGL(kw_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
+            case 8: hipLaunchKernelGGL(kw_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
+            default: return KV_ERR_UNSUPPORTED;
+        }
+    } else if (c->cfg.pack_size == 8) {
         switch (c->group) {
             case 1: hipLaunchKernelGGL(k8_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
             case 2: hipLaunchKernelGGL(k8_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;

@@ -260,4 +260,178 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
     wave_lds_fence();  // the B operand is rewritten by the next chunk
 }
 
+// ---- wide chunks -----------------------------------------------------------------------
+// Codes above 15 (relative scales below 1/15): packs of 8 tokens with widths up to 8 bits; the
+// header is 1024 width bytes followed by 1024 minimum bytes, both indexed [token group][channel].
+// Decoded as two halves of 32 tokens like the narrow 8-token packs; a pack is at most 64 bits
+// (three aligned dwords), a 16-bit field holds two codes.  Codes up to 255 are still fp16
+// subnormals (code * 2^-24), so the K dot products stay exact; the V path can lift them by two
+// bits only (255 << 2 < 1024).
+constexpr int CHUNKW_LDS = CHUNKW_MAX;
+constexpr int WIDE_LIFT = 2;
+constexpr float CODE_SCALE_WIDE_LIFTED = 4194304.0f;  // 2^22
+constexpr int WIDE_TABLE_ENTRIES = 9;                  // widths 0..8
+
+// K form: x = 2w in bits 0..4 (bit-field offset/width), w in byte 1, the w-bit mask in the high
+// half; y = 4w (64-bit shift amount).  V form: x = mask << lift in both halves, y = w, z = 4w, w = 2w.
+__device__ inline void build_wide_tables(uint2 *ktable, uint4 *vtable) {
+    const uint32_t w = threadIdx.x;
+    if (w < WIDE_TABLE_ENTRIES) {
+        const uint32_t m1 = (1u << w) - 1u;
+        if (ktable) ktable[w] = make_uint2((2 * w) | (w << 8) | (m1 << 16), 4 * w);
+        if (vtable) vtable[w] = make_uint4(((m1 << WIDE_LIFT) * 0x10001u), w, 4 * w, 2 * w);
+    }
+    __syncthreads();
+}
+
+// Per-lane view of one half: eight width bytes, eight minimum bytes, pack positions.
+struct LanePacksW {
+    uint32_t wlo, whi;  // widths, pack j in byte j
+    uint32_t mlo, mhi;  // minimums
+    uint32_t plo, phi;  // byte j = w_0 + .. + w_j
+    int start, end_all;
+
+    __device__ inline void init(uint2 widths, uint2 mins, int lds_base) {
+        wlo = widths.x, whi = widths.y, mlo = mins.x, mhi = mins.y;
+        uint32_t wl = byte_prefix_sums(wlo), wh = byte_prefix_sums(whi);
+        const uint32_t tl = wl >> 24;
+        wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
+        plo = wl;
+        phi = wh;
+        const int bytes = int(wh >> 24);
+        const int inc = wave_inclusive_scan(bytes);
+        start = inc - bytes + lds_base;
+        end_all = __builtin_amdgcn_readlane(inc, 63) + lds_base;
+    }
+    __device__ inline uint32_t width(int j) const { return ((j < 4 ? wlo : whi) >> (8 * (j & 3))) & 0xFFu; }
+    __device__ inline uint32_t minimum(int j) const { return ((j < 4 ? mlo : mhi) >> (8 * (j & 3))) & 0xFFu; }
+    __device__ inline int pos(int j) const {
+        if (j == 0) return start;
+        const int k = j - 1;
+        return start + int(((k < 4 ? plo : phi) >> (8 * (k & 3))) & 0xFFu);
+    }
+};
+
+// The 64-bit window of a wide pack: low dword and the dword that starts 4w bits in.
+__device__ inline void fetch_window_wide(const uint8_t *lds0, int pos, uint32_t shift4w, uint32_t &A, uint32_t &R) {
+    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
+    const uint32_t d0 = pp[0], d1 = pp[1], d2 = pp[2];
+    A = __builtin_amdgcn_alignbyte(d1, d0, uint32_t(pos));
+    const uint32_t hi = __builtin_amdgcn_alignbyte(d2, d1, uint32_t(pos));
+    R = uint32_t(((uint64_t(hi) << 32) | A) >> (shift4w & 63u));
+}
+
+// Pack-minimum term from eight minimum bytes (see pack_min_dot): bytes, not nibbles.
+__device__ inline float pack_min_dot_bytes(uint32_t mlo, uint32_t mhi, const uint32_t (&qe)[4]) {
+    float ms = dot2_f16(mlo & 0x00FF00FFu, qe[0], 0.0f);
+    ms = dot2_f16((mlo >> 8) & 0x00FF00FFu, qe[1], ms);
+    ms = dot2_f16(mhi & 0x00FF00FFu, qe[2], ms);
+    ms = dot2_f16((mhi >> 8) & 0x00FF00FFu, qe[3], ms);
+    return ms;
+}
+
+// K, one half of a wide chunk; same result layout as k8_half.  ktable: build_wide_tables.
+template <int G>
+__device__ inline void kw_half(const uint8_t *lds0, const uint2 *ktable, const LanePacksW &lp,
+                               const KQuery8<G> &kq, int lane, float (&u)[G]) {
+    float acc[G][8], ms[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) ms[g] = pack_min_dot_bytes(lp.mlo, lp.mhi, kq.qe[g]);
+#pragma unroll
+    for (int jp = 0; jp < 4; ++jp) {
+        const uint2 ka = ktable[lp.width(2 * jp)], kb = ktable[lp.width(2 * jp + 1)];
+        uint32_t Aa, Ra, Ab, Rb;
+        fetch_window_wide(lds0, lp.pos(2 * jp), ka.y, Aa, Ra);
+        fetch_window_wide(lds0, lp.pos(2 * jp + 1), kb.y, Ab, Rb);
+        // fields of two codes: tokens (0,1) (2,3) (4,5) (6,7); the odd fields are clean
+        const uint32_t Fa[4] = {Aa, __builtin_amdgcn_ubfe(Aa, ka.x, ka.x), Ra, __builtin_amdgcn_ubfe(Ra, ka.x, ka.x)};
+        const uint32_t Fb[4] = {Ab, __builtin_amdgcn_ubfe(Ab, kb.x, kb.x), Rb, __builtin_amdgcn_ubfe(Rb, kb.x, kb.x)};
+        const u16x2 widths = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(kb.x, ka.x, 0x0c050c01u));
+        const uint32_t masks = __builtin_amdgcn_perm(kb.x, ka.x, 0x07060302u);
+#pragma unroll
+        for (int f = 0; f < 4; ++f) {
+            u16x2 Z = __builtin_bit_cast(u16x2, __builtin_amdgcn_perm(Fb[f], Fa[f], 0x05040100u));
+#pragma unroll
+            for (int m = 0; m < 2; ++m) {
+                const uint32_t P = __builtin_bit_cast(uint32_t, Z) & ((f & 1) && m == 1 ? ~0u : masks);
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    acc[g][2 * f + m] = dot2_f16(P, kq.qp[g][jp], jp == 0 ? ms[g] : acc[g][2 * f + m]);
+                if (m < 1) Z = Z >> widths;
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < G; ++g) u[g] = row_reduce_scatter8(acc[g], lane) * CODE_SCALE;
+}
+
+// V, one wide chunk (both halves); lane l is token l of the block (three-step path).  vtable:
+// build_wide_tables.  The accumulators are in units of CODE_SCALE_WIDE_LIFTED.
+template <int G>
+__device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vtable, const VLane<G> &vl,
+                                uint32_t mt, const float (&pt)[G], VState<G> &st) {
+    const int lane = threadIdx.x & 63;
+    const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+    float wsum[2][G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        const float w = pt[g] * scale;
+        st.pm[g] = fmaf(pt[g], mn, st.pm[g]);
+        const _Float16 hi = __builtin_bit_cast(
+            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
+        const float lo = (w - float(hi)) * 2048.0f;
+        const _Float16 lo16 = __builtin_bit_cast(
+            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+        *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
+        *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
+        if (!fold_min<G>()) {
+            const float w8 = lanes8_all_reduce(w);
+            wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
+            wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+        }
+    }
+    wave_lds_fence();
+    const vhalf8 b0 = *reinterpret_cast<const vhalf8 *>(vl.blds + vl.bread0);
+    const vhalf8 b1 = *reinterpret_cast<const vhalf8 *>(vl.blds + vl.bread1);
+
+    int payload = cur + HEADERW;
+#pragma unroll
+    for (int s = 0; s < 2; ++s) {
+        const uint2 wb = *reinterpret_cast<const uint2 *>(lds_all + cur + 512 * s + lane * 8);
+        const uint2 mb = *reinterpret_cast<const uint2 *>(lds_all + cur + 1024 + 512 * s + lane * 8);
+        LanePacksW lp;
+        lp.init(wb, mb, payload);
+        payload = lp.end_all;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint4 k = vtable[lp.width(j)];
+            uint32_t A, R;
+            fetch_window_wide(lds_all, lp.pos(j), k.z, A, R);
+            const uint32_t w = k.y, M = k.x, s2 = k.w;
+            const uint32_t mj = lp.minimum(j);
+            const uint32_t fold = fold_min<G>() ? (mj << WIDE_LIFT) * 0x10001u : 0u;
+            // tokens (0,1 | 4,5) and (2,3 | 6,7): low half | high half, lifted together
+            uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);
+            uint32_t Z1 = __builtin_amdgcn_perm(R >> s2, A >> s2, 0x05040100u);
+            Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - WIDE_LIFT);
+            Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - WIDE_LIFT);
+            uint32_t P[4];
+            P[0] = (Z0 & M) + fold;                                      // tokens (0, 4)
+            P[1] = (__builtin_amdgcn_alignbit(Z0, Z0, w) & M) + fold;    // tokens (1, 5)
+            P[2] = (Z1 & M) + fold;                                      // tokens (2, 6)
+            P[3] = (__builtin_amdgcn_alignbit(Z1, Z1, w) & M) + fold;    // tokens (3, 7)
+            if constexpr (!fold_min<G>()) {
+                const float m = float(mj);
+#pragma unroll
+                for (int g = 0; g < G; ++g) st.macc[g][j] = fmaf(m, wsum[s][g], st.macc[g][j]);
+            }
+            typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+            const vhalf8 a = __builtin_bit_cast(vhalf8, u32x4v{P[0], P[1], P[2], P[3]});
+            st.acc[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(a, s ? b1 : b0, st.acc[j], 0, 0, 0);
+        }
+    }
+    wave_lds_fence();
+}
+
 }  // namespace packkv

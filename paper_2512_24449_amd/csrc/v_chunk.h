@@ -129,15 +129,17 @@ __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *tab
 }
 
 // Writes this wave's sums as red[g][0..127] (outputs) and red[g][128] (sum p*min).
+// code_scale: what one unit of the A operand stands for (codes enter as code * 2^-24 * 2^lift).
 template <int G>
-__device__ inline void v_state_store(const VState<G> &st, float (*red)[D + 4], int lane) {
+__device__ inline void v_state_store(const VState<G> &st, float (*red)[D + 4], int lane,
+                                     float code_scale = CODE_SCALE_LIFTED) {
     const int row = lane >> 4, col = lane & 15;
     const int head = col >> 1;
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
-            float v = st.acc[j][r] * ((col & 1) ? CODE_SCALE_LIFTED / 2048.0f : CODE_SCALE_LIFTED);
+            float v = st.acc[j][r] * ((col & 1) ? code_scale / 2048.0f : code_scale);
             v += dpp_f32<DPP_QUAD_XOR1>(v);  // hi column + lo column
             if (!(col & 1) && head < G) red[head][8 * (4 * row + r) + j] = v;
         }

@@ -180,6 +180,59 @@ __global__ __launch_bounds__(256) void v8_matvec_kernel(VArgs a) {
     }
 }
 
+// Wide chunks (codes above 15; pack8.h): one buffer per wave (a chunk is up to 10 KB), so the
+// transfer is waited for before the unpack; the other waves of the compute unit overlap with it.
+template <int G>
+__global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * CHUNKW_LDS + LDS_TAIL_PAD];
+    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
+    __shared__ uint4 vtable[16];
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * CHUNKW_LDS, "reduction array must fit");
+    float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
+    build_wide_tables(nullptr, vtable);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int split = blockIdx.x;
+    const int bh = blockIdx.y;
+    const int h = bh % a.H, b = bh / a.H;
+    const int buf = wave * CHUNKW_LDS;
+    VLane<G> vl;
+    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
+    vl.bslot = v8_bslot<G>(lane);  // lane l is token l of the block
+    VState<G> st;
+    st.clear();
+
+    const int blk_begin = split * a.blocks_per_split;
+    const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
+    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+        IndexBatch ib;
+        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        const int n_it = min(64, (blk_end - first + 3) / 4);
+        for (int it = 0; it < n_it; ++it) {
+            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADERW / 16);
+            chunk_issue_lds<CHUNKW_MAX, HEADERW>(a.arena, ib.start16(it), ib.end16(it), lds_all + buf, lane);
+            const int64_t tok = int64_t(first + 4 * it) * N + lane;
+            const uint32_t mt = a.meta[b * a.meta_stride + tok];
+            float pt[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) pt[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
+            wait_chunk_landed();
+            if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
+            vw_chunk<G>(lds_all, buf, vtable, vl, mt, pt, st);
+        }
+    }
+    __syncthreads();  // every wave is done with its chunk buffer: reuse the memory as red[][][]
+
+    v_state_store<G>(st, red[wave], lane, CODE_SCALE_WIDE_LIFTED);
+    __syncthreads();
+    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
+        const int g = i / (D + 1), d = i % (D + 1);
+        const float v = (red[0][g][d] + red[1][g][d]) + (red[2][g][d] + red[3][g][d]);
+        a.partial[(int64_t(split) * a.B * a.H * G + (int64_t(b) * a.H * G + h * G + g)) * V_PART_STRIDE + d] = v;
+    }
+}
+
 // Fixed-order combination of the split partial sums, plus the raw fp16 tail.
 __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__ partial,
                                                        int n_splits, int n_rows,
@@ -237,7 +290,15 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
-        if (c->cfg.pack_size == 8) {
+        if (c->wide_v) {
+            switch (G) {
+                case 1: hipLaunchKernelGGL(vw_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
+                case 2: hipLaunchKernelGGL(vw_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
+                case 4: hipLaunchKernelGGL(vw_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
+                case 8: hipLaunchKernelGGL(vw_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
+                default: return KV_ERR_UNSUPPORTED;
+            }
+        } else if (c->cfg.pack_size == 8) {
             switch (G) {
                 case 1: hipLaunchKernelGGL(v8_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
                 case 2: hipLaunchKernelGGL(v8_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;

@@ -79,12 +79,15 @@ def check_packed_state(cache, n_packed, ck, cv, B, H):
 
 
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
-             max_tokens=None, pack_size=16):
-    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything."""
+             max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2):
+    """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
+    With a relative scale below 1/15 (wide chunks) the fused attention entry point must refuse."""
+    wide = round(1 / k_rel) > 15 or round(1 / v_rel) > 15
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
-    cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), device=device, pack_size=pack_size)
+    cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), k_rel_scale=k_rel, v_rel_scale=v_rel,
+                                  device=device, pack_size=pack_size)
     Kd, Vd, qd = K.to(device), V.to(device), q.to(device)
     pos = 0
     for n in (pieces or [L]):
@@ -92,7 +95,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
         pos += n
     assert pos == L and cache.tokens == L
 
-    n_packed, ck, cv = oracle_cache(Kn, Vn, pack_size=pack_size)
+    n_packed, ck, cv = oracle_cache(Kn, Vn, k_rel, v_rel, pack_size)
     if check_bytes:
         check_packed_state(cache, n_packed, ck, cv, B, H)
 
@@ -121,17 +124,26 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     torch.cuda.synchronize()
     assert_close_vectors(out3.cpu().numpy(), o_e2e, "three-step path with the library softmax")
 
-    # fused decode attention against the oracle's definition of Att(q, K, V)
-    attn = cache.kv_decode_attention(qd, sm_scale)
-    torch.cuda.synchronize()
-    a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
-    assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
-
     # determinism: a second pass gives the same bits
     scores2 = cache.kv_k_matvec(qd, sm_scale)
     out2 = cache.kv_v_matvec(p)
-    attn2 = cache.kv_decode_attention(qd, sm_scale)
     torch.cuda.synchronize()
-    assert torch.equal(scores, scores2) and torch.equal(out, out2) and torch.equal(attn, attn2)
+    assert torch.equal(scores, scores2) and torch.equal(out, out2)
+
+    if wide:
+        try:
+            cache.kv_decode_attention(qd, sm_scale)
+            raise AssertionError("fused attention must refuse wide chunks")
+        except binding.PackKVError as e:
+            assert e.code == binding.KV_ERR_UNSUPPORTED
+    else:
+        # fused decode attention against the oracle's definition of Att(q, K, V)
+        attn = cache.kv_decode_attention(qd, sm_scale)
+        torch.cuda.synchronize()
+        a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
+        assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
+        attn2 = cache.kv_decode_attention(qd, sm_scale)
+        torch.cuda.synchronize()
+        assert torch.equal(attn, attn2)
     cache.close()
     return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)

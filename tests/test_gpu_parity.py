@@ -43,6 +43,20 @@ def test_packs_of_8_tokens_match_oracle(B, H, Hq, L, seed, pieces):
     gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8)
 
 
+@pytest.mark.parametrize("B,H,Hq,L,seed,pieces,k_rel,v_rel", [
+    (1, 1, 1, 64, 40, None, 0.05, 0.05),               # one chunk, codes up to 20
+    (1, 1, 1, 1024, 41, None, 1 / 255, 1 / 255),        # finest scale: codes up to 255, widths up to 8
+    (2, 3, 6, 192 + 9, 42, None, 0.04, 0.2),            # wide K, narrow V (packs of 8), G = 2
+    (1, 8, 32, 512, 43, None, 0.1, 1 / 30),             # narrow K, wide V, G = 4
+    (1, 2, 16, 256 + 63, 44, None, 1 / 60, 1 / 100),    # G = 8, full tail
+    (3, 5, 5, 7 * 64 + 1, 45, [100, 64, 200, 85], 0.02, 0.03),
+])
+def test_wide_chunks_match_oracle(B, H, Hq, L, seed, pieces, k_rel, v_rel):
+    """Relative scales below 1/15: codes above 15, wide chunk layout (packs of 8 tokens): packed
+    bytes bit-exact, K, V and the three-step path within the bar."""
+    gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8, k_rel=k_rel, v_rel=v_rel)
+
+
 def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     cases = []

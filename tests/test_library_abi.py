@@ -40,8 +40,14 @@ def test_query_sizes_and_config_checks():
     bad = binding.make_config(1, 32, 32, 4096)
     bad.head_dim = 64
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
-    bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05)   # codes would exceed 15
+    bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05)   # codes above 15 need packs of 8
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8, repack=binding.REPACK_V_MEDIAN)
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    bad = binding.make_config(1, 32, 32, 4096, v_rel_scale=1 / 300, pack_size=8)   # a code is one byte
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    wide = binding.kv_query_sizes(binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8))
+    assert wide.k_arena >= n_chunks * 10240 and wide.v_arena >= n_chunks * 5120 and wide.v_arena < wide.k_arena
     bad = binding.make_config(1, 3, 32, 4096)
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
     bad = binding.make_config(0, 1, 1, 64)
