@@ -202,8 +202,7 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
         const _Float16 hi = __builtin_bit_cast(
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
         const float lo = (w - float(hi)) * 2048.0f;
-        const _Float16 lo16 = __builtin_bit_cast(
-            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+        const _Float16 lo16 = _Float16(lo);  // to nearest: the residual's rounding error has no sign bias
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
         if (!fold_min<G>()) {
@@ -265,21 +264,23 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
 // header is 1024 width bytes followed by 1024 minimum bytes, both indexed [token group][channel].
 // Decoded as two halves of 32 tokens like the narrow 8-token packs; a pack is at most 64 bits
 // (three aligned dwords), a 16-bit field holds two codes.  Codes up to 255 are still fp16
-// subnormals (code * 2^-24), so the K dot products stay exact; the V path can lift them by two
-// bits only (255 << 2 < 1024).
+// subnormals (code * 2^-24), so the K dot products stay exact.  The V path cannot lift them far
+// enough inside the subnormal range for the matrix cores (255 << 2 is the limit, and with two
+// bits the measured output error at 32 Ki tokens and 255 levels was 6e-3): it turns every
+// pair into the normal numbers `code` instead, exactly: OR in the bit pattern of 1024.0, then
+// subtract 1024.0 in packed fp16 -- two instructions per word.
 constexpr int CHUNKW_LDS = CHUNKW_MAX;
-constexpr int WIDE_LIFT = 2;
-constexpr float CODE_SCALE_WIDE_LIFTED = 4194304.0f;  // 2^22
-constexpr int WIDE_TABLE_ENTRIES = 9;                  // widths 0..8
+constexpr int WIDE_TABLE_ENTRIES = 9;   // widths 0..8
+typedef _Float16 vhalf2 __attribute__((ext_vector_type(2)));
 
 // K form: x = 2w in bits 0..4 (bit-field offset/width), w in byte 1, the w-bit mask in the high
-// half; y = 4w (64-bit shift amount).  V form: x = mask << lift in both halves, y = w, z = 4w, w = 2w.
+// half; y = 4w (64-bit shift amount).  V form: x = mask in both halves, y = w, z = 4w, w = 2w.
 __device__ inline void build_wide_tables(uint2 *ktable, uint4 *vtable) {
     const uint32_t w = threadIdx.x;
     if (w < WIDE_TABLE_ENTRIES) {
         const uint32_t m1 = (1u << w) - 1u;
         if (ktable) ktable[w] = make_uint2((2 * w) | (w << 8) | (m1 << 16), 4 * w);
-        if (vtable) vtable[w] = make_uint4(((m1 << WIDE_LIFT) * 0x10001u), w, 4 * w, 2 * w);
+        if (vtable) vtable[w] = make_uint4(m1 * 0x10001u, w, 4 * w, 2 * w);
     }
     __syncthreads();
 }
@@ -366,7 +367,7 @@ __device__ inline void kw_half(const uint8_t *lds0, const uint2 *ktable, const L
 }
 
 // V, one wide chunk (both halves); lane l is token l of the block (three-step path).  vtable:
-// build_wide_tables.  The accumulators are in units of CODE_SCALE_WIDE_LIFTED.
+// build_wide_tables.  The A operand holds the codes as numbers: accumulators in units of 1.
 template <int G>
 __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vtable, const VLane<G> &vl,
                                 uint32_t mt, const float (&pt)[G], VState<G> &st) {
@@ -381,8 +382,7 @@ __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vt
         const _Float16 hi = __builtin_bit_cast(
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
         const float lo = (w - float(hi)) * 2048.0f;
-        const _Float16 lo16 = __builtin_bit_cast(
-            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+        const _Float16 lo16 = _Float16(lo);  // to nearest: the residual's rounding error has no sign bias
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
         if (!fold_min<G>()) {
@@ -410,17 +410,17 @@ __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vt
             fetch_window_wide(lds_all, lp.pos(j), k.z, A, R);
             const uint32_t w = k.y, M = k.x, s2 = k.w;
             const uint32_t mj = lp.minimum(j);
-            const uint32_t fold = fold_min<G>() ? (mj << WIDE_LIFT) * 0x10001u : 0u;
-            // tokens (0,1 | 4,5) and (2,3 | 6,7): low half | high half, lifted together
-            uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);
-            uint32_t Z1 = __builtin_amdgcn_perm(R >> s2, A >> s2, 0x05040100u);
-            Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - WIDE_LIFT);
-            Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - WIDE_LIFT);
-            uint32_t P[4];
-            P[0] = (Z0 & M) + fold;                                      // tokens (0, 4)
-            P[1] = (__builtin_amdgcn_alignbit(Z0, Z0, w) & M) + fold;    // tokens (1, 5)
-            P[2] = (Z1 & M) + fold;                                      // tokens (2, 6)
-            P[3] = (__builtin_amdgcn_alignbit(Z1, Z1, w) & M) + fold;    // tokens (3, 7)
+            const uint32_t fold = fold_min<G>() ? mj * 0x10001u : 0u;   // code + minimum < 256
+            // tokens (0,1 | 4,5) and (2,3 | 6,7): low half | high half
+            const uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);
+            const uint32_t Z1 = __builtin_amdgcn_perm(R >> s2, A >> s2, 0x05040100u);
+            const uint32_t raw[4] = {Z0, __builtin_amdgcn_alignbit(Z0, Z0, w), Z1, __builtin_amdgcn_alignbit(Z1, Z1, w)};
+            uint32_t P[4];   // tokens (0,4) (1,5) (2,6) (3,7) as fp16 numbers
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const uint32_t biased = ((raw[m] & M) | 0x64006400u) + fold;   // 1024 + code (+ minimum), exact
+                P[m] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(vhalf2, biased) - vhalf2{1024.0f16, 1024.0f16});
+            }
             if constexpr (!fold_min<G>()) {
                 const float m = float(mj);
 #pragma unroll

@@ -87,12 +87,11 @@ __device__ inline void v_chunk(const uint8_t *lds_all, int cur, const uint4 *tab
     for (int g = 0; g < G; ++g) {
         const float w = pt[g] * scale;
         st.pm[g] = fmaf(pt[g], mn, st.pm[g]);
-        // w = hi + lo with both parts fp16 (lo scaled by 2^11); truncation keeps lo >= 0
+        // w = hi + lo with both parts fp16 (lo scaled by 2^11); hi is truncated, so lo >= 0
         const _Float16 hi = __builtin_bit_cast(
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
         const float lo = (w - float(hi)) * 2048.0f;
-        const _Float16 lo16 = __builtin_bit_cast(
-            _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(lo, 0.0f)) & 0xFFFFu));
+        const _Float16 lo16 = _Float16(lo);  // to nearest: the residual's rounding error has no sign bias
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
         if (!fold_min<G>()) wsum[g] = row_all_reduce16(w);

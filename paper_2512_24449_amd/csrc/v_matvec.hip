@@ -224,7 +224,7 @@ __global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
     }
     __syncthreads();  // every wave is done with its chunk buffer: reuse the memory as red[][][]
 
-    v_state_store<G>(st, red[wave], lane, CODE_SCALE_WIDE_LIFTED);
+    v_state_store<G>(st, red[wave], lane, 1.0f);  // the wide path feeds the codes as numbers
     __syncthreads();
     for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
         const int g = i / (D + 1), d = i % (D + 1);
