@@ -13,7 +13,8 @@ from tests.gpu_cases import assert_close_vectors
 pytestmark = pytest.mark.gpu
 
 
-def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, attn=None, pack_size=16):
+def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, attn=None, pack_size=16,
+                         k_rel=0.1, v_rel=0.2):
     """Oracle over batch element b (all heads, all tokens) against the GPU state and outputs."""
     B, L, H, _ = K.shape
     Kb = K[b:b + 1].cpu().numpy()
@@ -24,7 +25,7 @@ def _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, 
     n_blk = n_packed // 64
     max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
     codes = {}
-    for name, x, rel, nbytes in (("k", Kb, 0.1, st.k_bytes), ("v", Vb, 0.2, st.v_bytes)):
+    for name, x, rel, nbytes in (("k", Kb, k_rel, st.k_bytes), ("v", Vb, v_rel, st.v_bytes)):
         c = oracle.compress(np.ascontiguousarray(x[:, :n_packed]), rel, pack_size)
         meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[b, :n_packed]
         assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta[0]), name + " token meta"
@@ -81,6 +82,30 @@ def test_full_size_configuration(index, batch_elements, pack_size):
     for b in batch_elements:
         _check_batch_element(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, attn, pack_size)
     cache.close()
+
+
+@pytest.mark.parametrize("B,H,Hq,L,k_rel,v_rel", [(1, 8, 32, 32768, 1 / 255, 1 / 255), (2, 4, 4, 16384 + 33, 0.05, 0.04)])
+def test_wide_chunks_long_context(B, H, Hq, L, k_rel, v_rel):
+    """Fine scales over long contexts: the softmax weights are tiny and the code sums large, so the
+    V output is the difference of large terms -- the case in which a sign bias in the weight
+    split showed up as 6e-3 output error.  Whole outputs against the oracle."""
+    K, V, q = synth.make_kv(B, L, H, Hq, 90)
+    cache = binding.PackedKVCache(B, H, Hq, L, k_rel_scale=k_rel, v_rel_scale=v_rel, pack_size=8)
+    cache.kv_compress_append(K.cuda(), V.cuda())
+    sm_scale = 128 ** -0.5
+    scores = cache.kv_k_matvec(q.cuda(), sm_scale)
+    p = synth.make_probs(scores)
+    out = cache.kv_v_matvec(p)
+    torch.cuda.synchronize()
+    assert cache.kv_cache_stats().overflow == 0
+    for b in range(B):
+        _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, k_rel, v_rel)
+    cache.close()
+
+
+def _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, k_rel, v_rel):
+    _check_batch_element(cache, K.cuda(), V.cuda(), q.cuda(), scores, p, out, b, sm_scale, n_packed, None, 8,
+                         k_rel, v_rel)
 
 
 def test_growing_cache_decode_steps():

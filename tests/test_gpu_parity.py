@@ -161,15 +161,15 @@ def test_degenerate_inputs():
     _special_case(K, V, 4)
 
 
-@pytest.mark.parametrize("Hq,pack_size", [(2, 16), (4, 16), (2, 8), (8, 8)])
-def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size):
+@pytest.mark.parametrize("Hq,pack_size,k_rel", [(2, 16, 0.1), (4, 16, 0.1), (2, 8, 0.1), (8, 8, 0.1), (4, 8, 0.05)])
+def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_rel):
     B, H, L = 1, 2, 256
     K, V, q = synth.make_kv(B, L, H, Hq, 50)
-    cfg = binding.make_config(B, H, Hq, L, pack_size=pack_size)
-    cache = binding.PackedKVCache(B, H, Hq, L, pack_size=pack_size)
+    cfg = binding.make_config(B, H, Hq, L, pack_size=pack_size, k_rel_scale=k_rel)
+    cache = binding.PackedKVCache(B, H, Hq, L, pack_size=pack_size, k_rel_scale=k_rel)
     # rebuild the handle over a K arena that holds about two blocks only
     sizes = binding.kv_sizes_t.from_buffer_copy(cache.sizes)
-    sizes.k_arena = 2 * H * (3300 if pack_size == 16 else 3800)
+    sizes.k_arena = 2 * H * (3300 if pack_size == 16 else (3800 if k_rel == 0.1 else 5600))
     bufs = binding.kv_buffers_t()
     for name in binding._BUFFER_NAMES:
         setattr(bufs, name, cache.tensors[name].data_ptr())
@@ -185,7 +185,7 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size):
     assert st.overflow == 1 and st.k_bytes <= sizes.k_arena
     scores = cache.kv_k_matvec(q.cuda(), 1.0)
     torch.cuda.synchronize()
-    n_packed, ck, _ = gpu_cases.oracle_cache(K.numpy(), V.numpy(), pack_size=pack_size)
+    n_packed, ck, _ = gpu_cases.oracle_cache(K.numpy(), V.numpy(), k_rel, 0.2, pack_size)
     s_ref = oracle.k_scores(ck.codes, K.numpy(), ck.meta, L, q.numpy(), 1.0)
     kept = st.k_bytes and int(np.searchsorted(ck.offsets16.astype(np.int64) * 16, st.k_bytes, "right") - 1) // (B * H)
     assert 1 <= kept < 4
