@@ -58,10 +58,11 @@ def _event_pair(torch):
 class Replicas:
     """R identical packed caches (rotated so that successive steps do not hit the LLC)."""
 
-    def __init__(self, w, K, V, extra_tokens, binding, torch, pack_size=16):
+    def __init__(self, w, K, V, extra_tokens, binding, torch, pack_size=16, rel=(0.1, 0.2)):
         B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
         L = K.shape[1]
-        first = binding.PackedKVCache(B, H, Hq, L + extra_tokens, pack_size=pack_size)
+        first = binding.PackedKVCache(B, H, Hq, L + extra_tokens, k_rel_scale=rel[0], v_rel_scale=rel[1],
+                                      pack_size=pack_size)
         first.kv_compress_append(K, V)
         st = first.kv_cache_stats()
         assert st.overflow == 0
@@ -71,7 +72,8 @@ class Replicas:
         bits = max(st.k_bytes, st.v_bytes) * 8.0 / (B * H * 128 * max(st.packed_tokens, 64)) + 0.3
         self.caches = [first]
         for _ in range(R - 1):
-            c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, bits_per_element_budget=bits, pack_size=pack_size)
+            c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, k_rel_scale=rel[0], v_rel_scale=rel[1],
+                                      bits_per_element_budget=bits, pack_size=pack_size)
             for name in ("k_arena", "v_arena"):
                 n = st.k_bytes if name[0] == "k" else st.v_bytes
                 c.tensors[name][:n].copy_(first.tensors[name][:n])
@@ -97,12 +99,13 @@ def algorithmic_bytes(st, w, tokens):
     return k, v
 
 
-def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16):
+def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2)):
     """Timed decode steps over rotating replicas; returns a dict of measurements."""
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
     total = steps + warmup
-    reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size)
+    reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size, rel)
+    fused = round(1 / rel[0]) <= 15 and round(1 / rel[1]) <= 15   # wide chunks: three-step path only
     R = len(reps)
     dev = K.device
     gen = torch.Generator(device=dev)
@@ -160,14 +163,16 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16):
             e1.record()
             a_ev.append((e0, e1))
 
-    for i in range(warmup):
-        fused_step(i, False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(warmup, total):
-        fused_step(i, True)
-    torch.cuda.synchronize()
-    fused_elapsed = time.perf_counter() - t0
+    fused_elapsed = float("nan")
+    if fused:
+        for i in range(warmup):
+            fused_step(i, False)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(warmup, total):
+            fused_step(i, True)
+        torch.cuda.synchronize()
+        fused_elapsed = time.perf_counter() - t0
 
     st = reps.stats
     k_ms = sum(a.elapsed_time(b) for a, b in k_ev) / len(k_ev)
@@ -178,7 +183,7 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16):
                k_alg_bytes=int(k_alg), v_alg_bytes=int(v_alg),
                k_bits_per_elem=st.k_bytes * 8.0 / (w.batch * w.n_kv_heads * 128 * st.packed_tokens),
                v_bits_per_elem=st.v_bytes * 8.0 / (w.batch * w.n_kv_heads * 128 * st.packed_tokens))
-    res["attn_ms"] = sum(a.elapsed_time(b) for a, b in a_ev) / len(a_ev)
+    res["attn_ms"] = sum(a.elapsed_time(b) for a, b in a_ev) / len(a_ev) if a_ev else float("nan")
     res["fused_ms_per_step"] = fused_elapsed * 1e3 / steps
     res["value_gbps"] = (st.k_bytes + st.v_bytes) / (res["ms_per_step"] * 1e-3) / 1e9
     res["k_gbps_compressed"] = st.k_bytes / (k_ms * 1e-3) / 1e9
@@ -388,6 +393,9 @@ def main():
     fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     # the second pack size (packs of 8 tokens) on the same data
     packed8 = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8)
+    # finer scales (codes above 15, wide chunks) on the same data: three-step path only
+    packedw = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8,
+                                                             rel=(0.05, 0.05))
     del K, V
     torch.cuda.empty_cache()
     if args.copy_calibration:
@@ -460,6 +468,13 @@ def main():
                                "speedup_v": round(fp16["v_ms"] / packed8["v_ms"], 3),
                                "ms_per_step": round(packed8["ms_per_step"], 5),
                                "fused_ms_per_step": round(packed8["fused_ms_per_step"], 5)}
+    if packedw is not None:
+        line["wide_chunks_rel_0.05"] = {"k_ms": round(packedw["k_ms"], 5), "v_ms": round(packedw["v_ms"], 5),
+                                        "k_bits_per_elem": round(packedw["k_bits_per_elem"], 3),
+                                        "v_bits_per_elem": round(packedw["v_bits_per_elem"], 3),
+                                        "speedup_k": round(fp16["k_ms"] / packedw["k_ms"], 3),
+                                        "speedup_v": round(fp16["v_ms"] / packedw["v_ms"], 3),
+                                        "ms_per_step": round(packedw["ms_per_step"], 5)}
     if not args.no_side_workloads:
         side = {}
         for idx in (0, 1, 2):
