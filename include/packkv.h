@@ -30,6 +30,8 @@
  *                     little-endian, token i of the group at bits
  *                     [i*width, (i+1)*width)
  *     then            zero padding to a multiple of 16 bytes
+ * (the default layout, packs of 16 tokens; see kv_config_t for packs of 8 tokens
+ * and for the wide layout that fine quantization scales use).
  * index[c] (uint32) is the chunk start in 16-byte units, index[n_chunks] the
  * arena end.  token_meta[b*max_tokens + t] (uint32) = scale_fp16 | min_fp16<<16
  * (Sec. III-B.2: one scale and minimum per token over all kv-heads).
@@ -132,8 +134,9 @@ typedef struct {
 
 /*
  * Buffer sizes for a configuration.  `bits_per_element_budget` sizes the two
- * arenas: 0 means worst case (every pack 4 bits wide, 4.5 bits per element
- * with headers); a positive value reserves that many bits per cached element
+ * arenas: 0 means worst case (every pack at its largest width: 4.5 bits per
+ * element with headers for packs of 16, 5 for packs of 8, 10 for wide chunks);
+ * a positive value reserves that many bits per cached element
  * (it is clamped to the worst case).  Host only.
  */
 int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_budget, kv_sizes_t *out);
@@ -154,7 +157,7 @@ int kv_cache_destroy(kv_cache_t *cache);
  * k_new, v_new: device fp16 [B][n_new][H_kv][128].  Tokens go to the raw
  * tail; whenever the tail holds 64 tokens they are quantized token-wise
  * (scale = rel*(max-min) over the token's H_kv*128 values, fp16 scale and
- * minimum), bit-packed in packs of 16 tokens per channel, and appended to the
+ * minimum), bit-packed in packs of 16 (or 8) tokens per channel, and appended to the
  * arenas as one chunk per (batch, kv-head); the tail then empties.  Several
  * full blocks in one call are compressed straight from k_new/v_new.
  * Errors: KV_ERR_CAPACITY if tokens + n_new > max_tokens (nothing is done).
@@ -204,8 +207,8 @@ int kv_softmax(kv_cache_t *cache, float *scores, int64_t ld_scores, void *hip_st
  * [B][H_q][128].  Equivalent to kv_k_matvec -> softmax -> kv_v_matvec up to
  * fp32 rounding.  Fixed-order fp32 accumulation, bitwise reproducible.  Uses the
  * workspace for per-split partial results; calls on one cache must not overlap.
- * KV_ERR_ARG on an empty cache.  Blocks dropped by an arena overflow are left
- * out of the softmax.
+ * KV_ERR_ARG on an empty cache, KV_ERR_UNSUPPORTED when a tensor uses the wide
+ * chunk layout.  Blocks dropped by an arena overflow are left out of the softmax.
  */
 int kv_decode_attention(kv_cache_t *cache, const void *q, float sm_scale, float *out, void *hip_stream);
 
