@@ -298,6 +298,66 @@ def run_growing(w, steps, torch, binding, synth):
     return res
 
 
+def run_graph_replay(w, K, V, q, torch, binding):
+    """Whole attention of one decode step (K product, softmax, V product) over a fixed cache,
+    captured once in a HIP graph and replayed: what the step costs without the Python caller
+    between the launches.  Packed three-step path, the same three steps over an uncompressed
+    fp16 cache, and the fused entry point.  Every capture is replayed three times with eager
+    work and synchronization in between and checked against the eager result first."""
+    B, H, Hq, L = w.batch, w.n_kv_heads, w.n_q_heads, K.shape[1]
+    c = binding.PackedKVCache(B, H, Hq, L)
+    c.kv_compress_append(K, V)
+    Kh, Vh = K.permute(0, 2, 1, 3).contiguous(), V.permute(0, 2, 1, 3).contiguous()
+    dev = K.device
+    scores = torch.empty(B, Hq, L, dtype=torch.float32, device=dev)
+    scores_f = torch.empty_like(scores)
+    out = torch.empty(B, Hq, 128, dtype=torch.float32, device=dev)
+    out_f, out_a = torch.empty_like(out), torch.empty_like(out)
+    ws = torch.zeros(binding.lib().kv_fp16_v_workspace_bytes(B, Hq), dtype=torch.uint8, device=dev)
+    sm = 128 ** -0.5
+
+    def packed3(st):
+        c.kv_k_matvec(q, sm, scores, stream=st)
+        c.kv_softmax(scores, stream=st)
+        c.kv_v_matvec(scores, out, stream=st)
+
+    def fp16_3(st):
+        binding.kv_fp16_k_matvec(Kh, q, sm, H, scores_f, stream=st)
+        c.kv_softmax(scores_f, stream=st)
+        binding.kv_fp16_v_matvec(Vh, scores_f, out_f, ws, stream=st)
+
+    def fused(st):
+        c.kv_decode_attention(q, sm, out_a, stream=st)
+
+    side = torch.cuda.Stream()
+    res = {}
+    for name, fn, buf in (("packed_three_step_us", packed3, out), ("fp16_three_step_us", fp16_3, out_f),
+                          ("packed_fused_us", fused, out_a)):
+        fn(torch.cuda.current_stream().cuda_stream)
+        torch.cuda.synchronize()
+        ref = buf.clone()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            fn(torch.cuda.current_stream().cuda_stream)
+        for _ in range(3):
+            buf.zero_()
+            g.replay()
+            torch.cuda.synchronize()
+            if not torch.equal(buf, ref):
+                raise RuntimeError("graph replay of %s differs from the eager result" % name)
+            torch.ones(1024, device=dev).sum().item()
+        e0, e1 = _event_pair(torch)
+        e0.record()
+        for _ in range(200):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        res[name] = round(e0.elapsed_time(e1) / 200 * 1e3, 2)
+        del g
+    c.close()
+    return res
+
+
 def run_repack(w, torch, binding, synth):
     """V-median repacking in the compressor: packed size and bulk compression time with and
     without it, on the workload's synthetic data and on the same data with the V tokens given
@@ -493,6 +553,8 @@ def main():
                              "ms_per_step": round(sp["ms_per_step"], 5),
                              "attn_ms": round(sp["attn_ms"], 5),
                              "fused_ms_per_step": round(sp["fused_ms_per_step"], 5)}
+            if idx < 2:   # launch-bound workloads: the same steps as a replayed HIP graph
+                side[sw.name]["graph_replay"] = run_graph_replay(sw, Ks, Vs, qs, torch, binding)
             del Ks, Vs
             torch.cuda.empty_cache()
         gw = synth.workload(4)
