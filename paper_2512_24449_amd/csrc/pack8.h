@@ -238,7 +238,7 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
             const uint4 k = table[lp.header_byte(j)];
             const uint32_t w = k.y, M = k.x;
             // tokens 0..3 in the low half, tokens 4..7 in the high half, lifted together
-            uint32_t Z = __builtin_amdgcn_perm(A >> (4 * w), A, 0x05040100u);
+            uint32_t Z = __builtin_amdgcn_perm(shr_by_byte1(A, k.y), A, 0x05040100u);  // byte 1 of the field: 4w
             Z = __builtin_amdgcn_alignbit(Z, Z, 32 - CODE_LIFT);
             uint32_t P[4];
 #pragma unroll

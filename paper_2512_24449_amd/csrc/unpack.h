@@ -65,7 +65,8 @@ __device__ inline int wave_inclusive_scan(int v) {
 
 // Per-header-byte constants, kept in LDS so that a pack's width-dependent
 // values cost one LDS read instead of several vector instructions:
-//   x = pair mask ((1 << w) - 1) * 0x10001, y = w, z = 8 * w, w = float(min)
+//   x = pair mask ((1 << w) - 1) * 0x10001, y = w (bits 0..4, a rotate amount as it stands)
+//   with 4w in byte 1, z = 8 * w, w = float(min)
 // Valid header bytes are below 0x50 (width <= 4); a corrupt byte would index past
 // the table, which on this hardware reads other LDS contents or zero, never faults.
 constexpr int PACK_TABLE_ENTRIES = 80;
@@ -85,7 +86,7 @@ __device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = 
     if (hb < PACK_TABLE_ENTRIES) {
         const uint32_t w = hb >> 4, m = hb & 15u;
         const uint32_t m1 = ((1u << w) - 1u) << lift;
-        table[hb] = make_uint4(m1 | (m1 << 16), w, 8 * w,
+        table[hb] = make_uint4(m1 | (m1 << 16), w | (4 * w << 8), 8 * w,
                                fold ? (m << lift) * 0x10001u : __float_as_uint(float(m)));
     }
     __syncthreads();
@@ -276,6 +277,16 @@ __device__ inline PackRawPair fetch_pack_pair(const uint8_t *lds0, const uint2 *
     return r;
 }
 
+// x >> (byte 1 of amount): the sub-dword operand select reads the byte in place, which saves
+// the instruction that would extract it (the compiler does not form this by itself).
+__device__ inline uint32_t shr_by_byte1(uint32_t x, uint32_t amount) {
+    uint32_t y;
+    asm("v_lshrrev_b32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD"
+        : "=v"(y)
+        : "v"(amount), "v"(x));
+    return y;
+}
+
 // Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
 // 16-bit half is the bit pattern of fp16(code * 2^(LIFT-24)); the table must have been
 // built with the same lift.
@@ -284,10 +295,10 @@ __device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
     const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32): tokens 0..7
     const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
     const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32): tokens 8..15
-    const uint32_t w = r.k.y, M = r.k.x;
-    const uint32_t s = 4 * w;
-    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);            // tokens 0..3 | 8..11
-    uint32_t Z1 = __builtin_amdgcn_perm(R >> s, A >> s, 0x05040100u);  // tokens 4..7 | 12..15
+    const uint32_t w = r.k.y, M = r.k.x;  // the rotates read the low five bits of w only
+    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);  // tokens 0..3 | 8..11
+    // tokens 4..7 | 12..15: both words shifted right by 4w, taken straight from byte 1 of the table field
+    uint32_t Z1 = __builtin_amdgcn_perm(shr_by_byte1(R, r.k.y), shr_by_byte1(A, r.k.y), 0x05040100u);
     if (LIFT) {  // rotate left: the codes of both halves move up together, the mask picks them there
         Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - LIFT);
         Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - LIFT);
