@@ -34,7 +34,7 @@ ROTATE_BYTES = 1.1e9             # working set to rotate over so reads come from
 # these kernels (measured constants of profiles/issue_counters_*.txt; an MFMA counts as 2 slots:
 # about 8 cycles of the port when mixed with vector work).  Peak = 256 CUs x 4 SIMDs x 2.4 GHz /
 # 4 cycles per instruction = 614.4 G wave-instructions/s.
-ISSUE_SLOTS_PER_CHUNK = {"k": 344, "v": 311 + 16}
+ISSUE_SLOTS_PER_CHUNK = {"k": 344, "v": 303 + 16}
 
 
 def parse_args():
