@@ -4,11 +4,14 @@
 // The paper walks a 32-lane warp over K rows and reduces with a warp sum.
 // Here a 64-lane wave owns whole chunks (64 tokens x 128 channels): lane l
 // owns token group g = l/16 and channels 8*(l%16)..+7 (unpack.h); the per-chunk
-// arithmetic (FMA form for one query head per kv-head, matrix-core form for
-// grouped queries) is in k_chunk.h.  De-quantization is folded in:
+// arithmetic (pairwise dot-product form for one query head per kv-head, matrix-core
+// form for grouped queries) is in k_chunk.h; chunks with packs of 8 tokens and wide
+// chunks have their own kernels here and their helpers in pack8.h.  De-quantization
+// is folded in:
 //   score_t = sm_scale * (scale_t * (sum_d q_d code[t,d] + sum_d q_d m[g,d])
 //                         + min_t * sum_d q_d)
-// so a pack minimum costs one FMA per pack and (scale_t, min_t) one per token.
+// so the pack minimums cost a few instructions per chunk and (scale_t, min_t) one
+// FMA per token.
 // A workgroup of four waves walks a contiguous range of blocks of one
 // (batch, kv-head) stream; every wave double-buffers whole chunks in LDS with
 // direct global->LDS transfers, so the next chunk is in flight while the

@@ -13,7 +13,7 @@
 // whose low/high 16-bit halves hold tokens (m, m+8) at equal bit offsets, and
 // a rotate + mask per token pair leaves each code in the low bits of a 16-bit
 // half.  Read as fp16 that bit pattern is the subnormal code * 2^-24 -- exact,
-// no conversion instruction -- ready for v_fma_mix_f32 or an fp16 MFMA; the
+// no conversion instruction -- ready for an fp16 dot-product instruction or an fp16 MFMA; the
 // factor 2^24 is applied once per output.
 #pragma once
 
