@@ -58,8 +58,9 @@ def _event_pair(torch):
 class Replicas:
     """R identical packed caches (rotated so that successive steps do not hit the LLC)."""
 
-    def __init__(self, w, K, V, extra_tokens, binding, torch, pack_size=16, rel=(0.1, 0.2)):
+    def __init__(self, w, K, V, extra_tokens, binding, torch, pack_size=16, rel=(0.1, 0.2), paged=False):
         B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
+        self.pool = None
         L = K.shape[1]
         first = binding.PackedKVCache(B, H, Hq, L + extra_tokens, k_rel_scale=rel[0], v_rel_scale=rel[1],
                                       pack_size=pack_size)
@@ -71,6 +72,21 @@ class Replicas:
         R = int(min(max(2, math.ceil(ROTATE_BYTES / max(step_bytes, 1))), 128))
         bits = max(st.k_bytes, st.v_bytes) * 8.0 / (B * H * 128 * max(st.packed_tokens, 64)) + 0.3
         self.caches = [first]
+        if paged:
+            # R paged caches over one pool, each compressing the prompt itself; the contiguous
+            # cache above only served to size the pool (chunk bytes + 3 % page-end waste + growth)
+            first.close()
+            per_cache = int(step_bytes * 1.03) // binding.PAGE_BYTES + 2 * extra_tokens // 64 + 8
+            self.pool = binding.PagePool(R * per_cache)
+            self.caches = []
+            for _ in range(R):
+                c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, k_rel_scale=rel[0], v_rel_scale=rel[1],
+                                          pack_size=pack_size, pool=self.pool)
+                c.kv_compress_append(K, V)
+                self.caches.append(c)
+            self.paged_stats = self.caches[0].kv_cache_stats()
+            assert self.paged_stats.overflow == 0
+            R = 1  # skip the copies below
         for _ in range(R - 1):
             c = binding.PackedKVCache(B, H, Hq, L + extra_tokens, k_rel_scale=rel[0], v_rel_scale=rel[1],
                                       bits_per_element_budget=bits, pack_size=pack_size)
@@ -99,12 +115,12 @@ def algorithmic_bytes(st, w, tokens):
     return k, v
 
 
-def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2)):
+def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2), paged=False):
     """Timed decode steps over rotating replicas; returns a dict of measurements."""
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
     total = steps + warmup
-    reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size, rel)
+    reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size, rel, paged)
     fused = round(1 / rel[0]) <= 15 and round(1 / rel[1]) <= 15   # wide chunks: three-step path only
     R = len(reps)
     dev = K.device
@@ -188,8 +204,18 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
     res["value_gbps"] = (st.k_bytes + st.v_bytes) / (res["ms_per_step"] * 1e-3) / 1e9
     res["k_gbps_compressed"] = st.k_bytes / (k_ms * 1e-3) / 1e9
     res["v_gbps_compressed"] = st.v_bytes / (v_ms * 1e-3) / 1e9
+    if paged:
+        ps = reps.paged_stats
+        assert all(c.kv_cache_stats().overflow == 0 for c in reps.caches)
+        worst = binding.kv_query_sizes(reps.caches[0].cfg)
+        res["paged"] = {"page_bytes_held": int(ps.k_bytes + ps.v_bytes),
+                        "chunk_bytes": int(st.k_bytes + st.v_bytes),
+                        "worst_case_arena_bytes": int(worst.k_arena + worst.v_arena)}
     for c in reps.caches:
         c.close()
+    if reps.pool is not None:
+        assert reps.pool.kv_page_pool_free_pages() == reps.pool.n_pages
+        reps.pool.close()
     del reps
     torch.cuda.empty_cache()
     return res
@@ -456,6 +482,10 @@ def main():
     # finer scales (codes above 15, wide chunks) on the same data: three-step path only
     packedw = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8,
                                                              rel=(0.05, 0.05))
+    # the same workload in paged caches over one shared page pool
+    packedp = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, paged=True)
+    # and its control: contiguous caches timed right after, with the same short run
+    packedc = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth)
     del K, V
     torch.cuda.empty_cache()
     if args.copy_calibration:
@@ -535,6 +565,15 @@ def main():
                                         "speedup_k": round(fp16["k_ms"] / packedw["k_ms"], 3),
                                         "speedup_v": round(fp16["v_ms"] / packedw["v_ms"], 3),
                                         "ms_per_step": round(packedw["ms_per_step"], 5)}
+    if packedp is not None:
+        line["paged_arena"] = dict({"k_ms": round(packedp["k_ms"], 5), "v_ms": round(packedp["v_ms"], 5),
+                                    "attn_ms": round(packedp["attn_ms"], 5),
+                                    "ms_per_step": round(packedp["ms_per_step"], 5),
+                                    "fused_ms_per_step": round(packedp["fused_ms_per_step"], 5),
+                                    "contiguous_control": {"k_ms": round(packedc["k_ms"], 5),
+                                                           "v_ms": round(packedc["v_ms"], 5),
+                                                           "attn_ms": round(packedc["attn_ms"], 5)}},
+                                   **packedp["paged"])
     if not args.no_side_workloads:
         side = {}
         for idx in (0, 1, 2):

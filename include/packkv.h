@@ -61,8 +61,10 @@ extern "C" {
 #define KV_CHUNK_MAX_BYTES_PACK8 (1024 + 1024 * 4)
 #define KV_CHUNK_HEADER_WIDE 2048            /* wide chunks: codes above 15            */
 #define KV_CHUNK_MAX_BYTES_WIDE (2048 + 1024 * 8)
+#define KV_PAGE_BYTES 65536                  /* page of a paged arena (kv_page_pool_t) */
 
 typedef struct kv_cache kv_cache_t; /* opaque, host memory owned by the library */
+typedef struct kv_page_pool kv_page_pool_t; /* the same: pages shared by paged caches */
 
 #define KV_REPACK_NONE 0
 #define KV_REPACK_V_MEDIAN 1
@@ -103,6 +105,7 @@ typedef struct {
     size_t k_tail, v_tail;             /* fp16 [B][tail_capacity][H_kv][128]      */
     size_t workspace;                  /* status words, chunk sizes, V partials   */
     size_t token_order;                /* uint8 [B][max_tokens]; 0 without repacking */
+    size_t k_pages, v_pages;           /* paged caches only: uint32 page lists; else 0 */
 } kv_sizes_t;
 
 /* Device buffers, each at least as large as kv_query_sizes said and 256-byte
@@ -117,6 +120,10 @@ typedef struct {
      * arrival order) of the token stored at slot s; scores[b][hq][blk*64 + s] belongs
      * to token blk*64 + token_order[b][blk*64 + s].  Unused (may be null) without. */
     void *token_order;
+    /* Paged caches only (kv_cache_create_paged; k_arena and v_arena are then unused and may be
+     * null): [0] = pages held by the tensor, [1] = 16-byte units used in the newest of them,
+     * [2 + i] = number of the i-th page taken.  Written by the library. */
+    void *k_pages, *v_pages;
 } kv_buffers_t;
 
 /* Filled by kv_cache_stats. */
@@ -212,7 +219,63 @@ int kv_softmax(kv_cache_t *cache, float *scores, int64_t ld_scores, void *hip_st
  */
 int kv_decode_attention(kv_cache_t *cache, const void *q, float sm_scale, float *out, void *hip_stream);
 
-/* Counters and byte accounting.  Reads device state: synchronizes `hip_stream`. */
+/*
+ * ---- paged arena ------------------------------------------------------------
+ * The packed format stores chunks wherever the index says (Sec. III-B.4 needs an
+ * appendable layout, not a contiguous one).  A paged cache keeps no arena of its
+ * own: its chunks live in fixed pages of KV_PAGE_BYTES that it takes, as it grows,
+ * from a pool shared with other caches, and gives back with kv_cache_release -- so
+ * the memory a cache holds follows its compressed size, not its worst case.
+ *   - a chunk never crosses a page boundary: a chunk that does not fit behind the
+ *     previous one of its tensor starts a fresh page (K and V fill their own pages);
+ *   - the index of a paged cache has two words per chunk, index[2c] = start and
+ *     index[2c + 1] = end, in 16-byte units from the start of the pool's pages
+ *     (a pool is therefore limited to 64 GiB); a dropped chunk has start = end;
+ *   - pages are taken and returned on the device, inside the stream of the call
+ *     (no host synchronization).  If the pool cannot cover an append, all chunks of
+ *     that tensor in that call are dropped and the sticky overflow flag is set,
+ *     exactly as with a full contiguous arena.
+ *   - calls that take or return pages of one pool (kv_compress_append,
+ *     kv_cache_release, kv_cache_destroy of its caches) must be ordered by the
+ *     caller: one stream, or events between streams.  Reads never touch the pool state.
+ * Everything else (token metadata, tails, token order, every read entry point)
+ * works as with a contiguous cache and gives bitwise the same results.
+ */
+/* Device bytes of the pool's bookkeeping (`state`) for n_pages pages. */
+size_t kv_page_pool_state_bytes(int64_t n_pages);
+/*
+ * pages: device, n_pages * KV_PAGE_BYTES bytes, 256-byte aligned; state: device,
+ * kv_page_pool_state_bytes(n_pages), 256-byte aligned; both caller-owned and valid
+ * until kv_page_pool_destroy.  1 <= n_pages < 2^20.  Marks every page free (a
+ * small kernel on `hip_stream`, synchronized before returning); page 0 is handed
+ * out first.
+ */
+int kv_page_pool_create(void *pages, int64_t n_pages, void *state, void *hip_stream, kv_page_pool_t **out);
+/* Host bookkeeping only; destroy the caches that use the pool first. */
+int kv_page_pool_destroy(kv_page_pool_t *pool);
+/* Number of free pages.  Reads device state: synchronizes `hip_stream`. */
+int kv_page_pool_free_pages(kv_page_pool_t *pool, int64_t *free_pages, void *hip_stream);
+/*
+ * Buffer sizes of a paged cache: arenas 0, indices of 2 * max_chunks words, page
+ * lists sized for the worst case, the rest as kv_query_sizes.  Host only.
+ */
+int kv_query_sizes_paged(const kv_config_t *cfg, kv_sizes_t *out);
+/*
+ * As kv_cache_create, over the pages of `pool` (buffers->k_arena / v_arena are ignored).
+ */
+int kv_cache_create_paged(const kv_config_t *cfg, kv_page_pool_t *pool, const kv_buffers_t *buffers,
+                          const kv_sizes_t *sizes, kv_cache_t **out);
+/*
+ * Empties the cache: 0 tokens, overflow flag cleared; a paged cache gives all its
+ * pages back to its pool (a kernel on `hip_stream`, no synchronization).  The
+ * cache can be filled again.  kv_cache_destroy of a paged cache that still holds
+ * tokens does the same on the default stream and synchronizes.
+ */
+int kv_cache_release(kv_cache_t *cache, void *hip_stream);
+
+/* Counters and byte accounting.  Reads device state: synchronizes `hip_stream`.
+ * For a paged cache k_bytes / v_bytes are the bytes of the pages held and
+ * index_bytes counts two words per chunk. */
 int kv_cache_stats(kv_cache_t *cache, kv_stats_t *out, void *hip_stream);
 
 /*

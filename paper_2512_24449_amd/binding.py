@@ -29,7 +29,8 @@ class kv_config_t(C.Structure):
 
 
 _BUFFER_NAMES = ("k_arena", "v_arena", "k_index", "v_index", "k_token_meta", "v_token_meta",
-                 "k_tail", "v_tail", "workspace", "token_order")
+                 "k_tail", "v_tail", "workspace", "token_order", "k_pages", "v_pages")
+PAGE_BYTES = 65536
 REPACK_NONE, REPACK_V_MEDIAN = 0, 1
 
 
@@ -51,7 +52,8 @@ class kv_stats_t(C.Structure):
 EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append",
            "kv_k_matvec", "kv_v_matvec", "kv_softmax", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
            "kv_strerror", "kv_fp16_k_matvec", "kv_fp16_v_matvec", "kv_fp16_v_workspace_bytes",
-           "kv_stream_read")
+           "kv_stream_read", "kv_page_pool_state_bytes", "kv_page_pool_create", "kv_page_pool_destroy",
+           "kv_page_pool_free_pages", "kv_query_sizes_paged", "kv_cache_create_paged", "kv_cache_release")
 
 _lib = None
 
@@ -72,6 +74,15 @@ def lib():
         L.kv_cache_create.argtypes = [C.POINTER(kv_config_t), C.POINTER(kv_buffers_t),
                                       C.POINTER(kv_sizes_t), C.POINTER(vp)]
         L.kv_cache_destroy.argtypes = [vp]
+        L.kv_page_pool_state_bytes.argtypes = [i64]
+        L.kv_page_pool_state_bytes.restype = C.c_size_t
+        L.kv_page_pool_create.argtypes = [vp, i64, vp, vp, C.POINTER(vp)]
+        L.kv_page_pool_destroy.argtypes = [vp]
+        L.kv_page_pool_free_pages.argtypes = [vp, C.POINTER(i64), vp]
+        L.kv_query_sizes_paged.argtypes = [C.POINTER(kv_config_t), C.POINTER(kv_sizes_t)]
+        L.kv_cache_create_paged.argtypes = [C.POINTER(kv_config_t), vp, C.POINTER(kv_buffers_t),
+                                            C.POINTER(kv_sizes_t), C.POINTER(vp)]
+        L.kv_cache_release.argtypes = [vp, vp]
         L.kv_compress_append.argtypes = [vp, vp, vp, i32, vp]
         L.kv_k_matvec.argtypes = [vp, vp, f32, vp, i64, vp]
         L.kv_v_matvec.argtypes = [vp, vp, i64, vp, vp]
@@ -89,7 +100,8 @@ def lib():
         L.kv_fp16_v_workspace_bytes.restype = C.c_size_t
         L.kv_stream_read.argtypes = [vp, C.c_size_t, vp, vp]
         for name in EXPORTS:
-            if name not in ("kv_cache_tokens", "kv_strerror", "kv_fp16_v_workspace_bytes"):
+            if name not in ("kv_cache_tokens", "kv_strerror", "kv_fp16_v_workspace_bytes",
+                            "kv_page_pool_state_bytes"):
                 getattr(L, name).restype = C.c_int
         _lib = L
     return _lib
@@ -129,15 +141,60 @@ def kv_query_sizes(cfg: kv_config_t, bits_per_element_budget: float = 0.0) -> kv
     return out
 
 
+def kv_query_sizes_paged(cfg: kv_config_t) -> kv_sizes_t:
+    out = kv_sizes_t()
+    _check(lib().kv_query_sizes_paged(C.byref(cfg), C.byref(out)), "kv_query_sizes_paged")
+    return out
+
+
+class PagePool:
+    """Owns the pages and the bookkeeping words (torch tensors) and the kv_page_pool_t handle."""
+
+    def __init__(self, n_pages, device="cuda:0"):
+        self.device = torch.device(device)
+        self.n_pages = n_pages
+        state_bytes = lib().kv_page_pool_state_bytes(n_pages)
+        if state_bytes == 0:
+            raise PackKVError("kv_page_pool_state_bytes: invalid argument", KV_ERR_ARG)
+        with torch.cuda.device(self.device):
+            self.pages = torch.empty(n_pages * PAGE_BYTES, dtype=torch.uint8, device=self.device)
+            self.state = torch.empty(state_bytes, dtype=torch.uint8, device=self.device)
+            torch.cuda.synchronize()
+            handle = C.c_void_p()
+            _check(lib().kv_page_pool_create(self.pages.data_ptr(), n_pages, self.state.data_ptr(),
+                                             _stream_ptr(None), C.byref(handle)), "kv_page_pool_create")
+        self.handle = handle
+
+    def kv_page_pool_free_pages(self, stream=None) -> int:
+        n = C.c_int64()
+        _check(lib().kv_page_pool_free_pages(self.handle, C.byref(n), _stream_ptr(stream)),
+               "kv_page_pool_free_pages")
+        return int(n.value)
+
+    def close(self):
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.kv_page_pool_destroy(self.handle)
+        self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
 class PackedKVCache:
-    """Owns the device buffers (torch tensors) and the kv_cache_t handle."""
+    """Owns the device buffers (torch tensors) and the kv_cache_t handle.  With `pool` (a PagePool)
+    the cache is paged: it has no arenas of its own and keeps its chunks in pages of the pool."""
 
     def __init__(self, batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale=0.1, v_rel_scale=0.2,
-                 bits_per_element_budget=0.0, device="cuda:0", repack=REPACK_NONE, pack_size=16):
+                 bits_per_element_budget=0.0, device="cuda:0", repack=REPACK_NONE, pack_size=16, pool=None):
         self.cfg = make_config(batch, n_kv_heads, n_q_heads, max_tokens, k_rel_scale, v_rel_scale, repack,
                                pack_size)
         self.device = torch.device(device)
-        self.sizes = kv_query_sizes(self.cfg, bits_per_element_budget)
+        self.pool = pool
+        self.sizes = (kv_query_sizes_paged(self.cfg) if pool is not None
+                      else kv_query_sizes(self.cfg, bits_per_element_budget))
         self.tensors = {}
         bufs = kv_buffers_t()
         with torch.cuda.device(self.device):
@@ -148,8 +205,12 @@ class PackedKVCache:
                 setattr(bufs, name, t.data_ptr() if t.numel() else None)
             torch.cuda.synchronize()
             handle = C.c_void_p()
-            _check(lib().kv_cache_create(C.byref(self.cfg), C.byref(bufs), C.byref(self.sizes),
-                                         C.byref(handle)), "kv_cache_create")
+            if pool is not None:
+                _check(lib().kv_cache_create_paged(C.byref(self.cfg), pool.handle, C.byref(bufs),
+                                                   C.byref(self.sizes), C.byref(handle)), "kv_cache_create_paged")
+            else:
+                _check(lib().kv_cache_create(C.byref(self.cfg), C.byref(bufs), C.byref(self.sizes),
+                                             C.byref(handle)), "kv_cache_create")
         self.handle = handle
         self.batch, self.n_kv_heads, self.n_q_heads = batch, n_kv_heads, n_q_heads
 
@@ -222,6 +283,9 @@ class PackedKVCache:
         st = kv_stats_t()
         _check(lib().kv_cache_stats(self.handle, C.byref(st), _stream_ptr(stream)), "kv_cache_stats")
         return st
+
+    def kv_cache_release(self, stream=None):
+        _check(lib().kv_cache_release(self.handle, _stream_ptr(stream)), "kv_cache_release")
 
     def kv_cache_restore(self, tokens: int):
         _check(lib().kv_cache_restore(self.handle, tokens), "kv_cache_restore")

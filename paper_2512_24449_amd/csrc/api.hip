@@ -42,6 +42,12 @@ int check_config(const kv_config_t *c) {
 
 size_t round256(size_t n) { return (n + 255) & ~size_t(255); }
 
+// Pages one tensor of a paged cache can come to hold: every chunk at its largest.
+int64_t worst_case_pages(int64_t max_chunks, int pack_size, bool wide) {
+    const int64_t per_page = KV_PAGE_BYTES / chunk_max_bytes(pack_size, wide);
+    return (max_chunks + per_page - 1) / per_page + 1;
+}
+
 }  // namespace
 
 extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_budget, kv_sizes_t *out) {
@@ -73,26 +79,85 @@ extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_bu
         round256(size_t(cfg->batch) * cfg->tail_capacity * cfg->n_kv_heads * D * 2);
     out->workspace = round256(WS_VPART + v_partial_bytes(cfg->batch, cfg->n_q_heads));
     out->token_order = cfg->repack ? round256(size_t(cfg->batch) * max_tokens) : 0;
+    out->k_pages = out->v_pages = 0;
     return KV_OK;
 }
 
-extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffers,
-                               const kv_sizes_t *sizes, kv_cache_t **out) {
+extern "C" int kv_query_sizes_paged(const kv_config_t *cfg, kv_sizes_t *out) {
+    int rc = kv_query_sizes(cfg, 0.0, out);
+    if (rc) return rc;
+    const int64_t max_tokens = (cfg->max_tokens + N - 1) / N * N;
+    const int64_t max_chunks = max_tokens / N * cfg->batch * cfg->n_kv_heads;
+    out->k_arena = out->v_arena = 0;
+    out->k_index = out->v_index = round256(size_t(max_chunks) * 8);
+    out->k_pages = round256(size_t(2 + worst_case_pages(max_chunks, cfg->pack_size, wide_codes(cfg->k_rel_scale))) * 4);
+    out->v_pages = round256(size_t(2 + worst_case_pages(max_chunks, cfg->pack_size, wide_codes(cfg->v_rel_scale))) * 4);
+    return KV_OK;
+}
+
+extern "C" size_t kv_page_pool_state_bytes(int64_t n_pages) {
+    return n_pages < 1 ? 0 : round256(size_t(n_pages + 1) * 4);
+}
+
+extern "C" int kv_page_pool_create(void *pages, int64_t n_pages, void *state, void *hip_stream,
+                                   kv_page_pool_t **out) {
+    if (!out || !aligned256(pages) || !aligned256(state)) return KV_ERR_ARG;
+    if (n_pages < 1 || n_pages >= (int64_t(1) << 20)) return KV_ERR_ARG;  // positions are uint32 16-byte units
+    kv_page_pool *pool = new (std::nothrow) kv_page_pool;
+    if (!pool) return KV_ERR_ARG;
+    pool->pages = static_cast<uint8_t *>(pages);
+    pool->state = static_cast<uint32_t *>(state);
+    pool->n_pages = n_pages;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc = launch_pool_init(pool, s);
+    if (rc == KV_OK && hipStreamSynchronize(s) != hipSuccess) rc = KV_ERR_HIP;
+    if (rc) {
+        delete pool;
+        return rc;
+    }
+    *out = pool;
+    return KV_OK;
+}
+
+extern "C" int kv_page_pool_destroy(kv_page_pool_t *pool) {
+    if (!pool) return KV_ERR_ARG;
+    delete pool;
+    return KV_OK;
+}
+
+extern "C" int kv_page_pool_free_pages(kv_page_pool_t *pool, int64_t *free_pages, void *hip_stream) {
+    if (!pool || !free_pages) return KV_ERR_ARG;
+    KV_HIP_CHECK(hipStreamSynchronize(static_cast<hipStream_t>(hip_stream)));
+    uint32_t n = 0;
+    KV_HIP_CHECK(hipMemcpy(&n, pool->state, 4, hipMemcpyDeviceToHost));
+    *free_pages = n;
+    return KV_OK;
+}
+
+namespace {
+
+int create_cache(const kv_config_t *cfg, kv_page_pool *pool, const kv_buffers_t *buffers,
+                 const kv_sizes_t *sizes, kv_cache_t **out) {
     int rc = check_config(cfg);
     if (rc) return rc;
     if (!buffers || !sizes || !out) return KV_ERR_ARG;
     kv_sizes_t need;
-    rc = kv_query_sizes(cfg, 0.0, &need);
+    rc = pool ? kv_query_sizes_paged(cfg, &need) : kv_query_sizes(cfg, 0.0, &need);
     if (rc) return rc;
-    const void *ptrs[] = {buffers->k_arena, buffers->v_arena, buffers->k_index, buffers->v_index,
-                          buffers->k_token_meta, buffers->v_token_meta, buffers->k_tail,
-                          buffers->v_tail, buffers->workspace};
+    const void *ptrs[] = {buffers->k_index, buffers->v_index, buffers->k_token_meta,
+                          buffers->v_token_meta, buffers->k_tail, buffers->v_tail, buffers->workspace,
+                          pool ? buffers->k_pages : buffers->k_arena,
+                          pool ? buffers->v_pages : buffers->v_arena};
     for (const void *p : ptrs)
         if (!aligned256(p)) return KV_ERR_ARG;
     // arenas may be any size >= one chunk; everything else must be complete
-    if (sizes->k_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->k_rel_scale))) ||
-        sizes->v_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->v_rel_scale))) ||
-        sizes->k_index < need.k_index ||
+    if (pool) {
+        if (sizes->k_pages < need.k_pages || sizes->v_pages < need.v_pages) return KV_ERR_ARG;
+    } else if (sizes->k_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->k_rel_scale))) ||
+               sizes->v_arena < size_t(chunk_max_bytes(cfg->pack_size, wide_codes(cfg->v_rel_scale)))) {
+        return KV_ERR_ARG;
+    }
+    if (sizes->k_index < need.k_index ||
         sizes->v_index < need.v_index || sizes->k_token_meta < need.k_token_meta ||
         sizes->v_token_meta < need.v_token_meta || sizes->k_tail < need.k_tail ||
         sizes->v_tail < need.v_tail || sizes->workspace < need.workspace)
@@ -113,6 +178,15 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
     c->wide_v = c->qmax_v > 15;
     c->packed_tokens = 0;
     c->tail_tokens = 0;
+    c->pool = pool;
+    c->index_words = pool ? 2 : 1;
+    c->max_pages = 0;
+    if (pool) {
+        c->buf.k_arena = c->buf.v_arena = pool->pages;
+        c->sizes.k_arena = c->sizes.v_arena = size_t(pool->n_pages) * KV_PAGE_BYTES;
+        // what the caller's page lists can take
+        c->max_pages = int64_t(std::min(sizes->k_pages, sizes->v_pages) / 4) - 2;
+    }
     rc = launch_init(c, nullptr);
     if (rc == KV_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = KV_ERR_HIP;
     if (rc) {
@@ -123,10 +197,40 @@ extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffe
     return KV_OK;
 }
 
+}  // namespace
+
+extern "C" int kv_cache_create(const kv_config_t *cfg, const kv_buffers_t *buffers,
+                               const kv_sizes_t *sizes, kv_cache_t **out) {
+    return create_cache(cfg, nullptr, buffers, sizes, out);
+}
+
+extern "C" int kv_cache_create_paged(const kv_config_t *cfg, kv_page_pool_t *pool,
+                                     const kv_buffers_t *buffers, const kv_sizes_t *sizes,
+                                     kv_cache_t **out) {
+    if (!pool) return KV_ERR_ARG;
+    return create_cache(cfg, pool, buffers, sizes, out);
+}
+
+extern "C" int kv_cache_release(kv_cache_t *c, void *hip_stream) {
+    if (!c) return KV_ERR_ARG;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    int rc;
+    if (c->pool && (rc = launch_release_pages(c, s))) return rc;
+    if ((rc = launch_init(c, s))) return rc;  // status words, index[0]; the page lists are empty already
+    c->packed_tokens = 0;
+    c->tail_tokens = 0;
+    return KV_OK;
+}
+
 extern "C" int kv_cache_destroy(kv_cache_t *cache) {
     if (!cache) return KV_ERR_ARG;
+    int rc = KV_OK;
+    if (cache->pool && cache->packed_tokens > 0) {
+        rc = kv_cache_release(cache, nullptr);
+        if (rc == KV_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = KV_ERR_HIP;
+    }
     delete cache;
-    return KV_OK;
+    return rc;
 }
 
 namespace {
@@ -158,6 +262,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         kjob.index = static_cast<uint32_t *>(c->buf.k_index);
         kjob.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
         kjob.status = status + ST_OVERFLOW_K;
+        kjob.page_list = static_cast<uint32_t *>(c->buf.k_pages);
         vjob.src = vsrc + int64_t(done) * N * job.token_stride;
         vjob.rel = c->cfg.v_rel_scale;
         vjob.qmax = c->qmax_v;
@@ -167,6 +272,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         vjob.index = static_cast<uint32_t *>(c->buf.v_index);
         vjob.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
         vjob.status = status + ST_OVERFLOW_V;
+        vjob.page_list = static_cast<uint32_t *>(c->buf.v_pages);
         int rc;
         if ((rc = launch_token_params(c, kjob, s))) return rc;
         if ((rc = launch_token_params(c, vjob, s))) return rc;
@@ -259,17 +365,21 @@ extern "C" int kv_cache_stats(kv_cache_t *c, kv_stats_t *out, void *hip_stream) 
     KV_HIP_CHECK(hipStreamSynchronize(s));
     const int64_t n_chunks = c->packed_tokens / N * c->cfg.batch * c->cfg.n_kv_heads;
     uint32_t kend = 0, vend = 0, status[2] = {0, 0};
-    KV_HIP_CHECK(hipMemcpy(&kend, static_cast<uint32_t *>(c->buf.k_index) + n_chunks, 4, hipMemcpyDeviceToHost));
-    KV_HIP_CHECK(hipMemcpy(&vend, static_cast<uint32_t *>(c->buf.v_index) + n_chunks, 4, hipMemcpyDeviceToHost));
+    // contiguous: the arena end in 16-byte units; paged: the number of pages held
+    const void *kword = c->pool ? c->buf.k_pages : static_cast<uint32_t *>(c->buf.k_index) + n_chunks;
+    const void *vword = c->pool ? c->buf.v_pages : static_cast<uint32_t *>(c->buf.v_index) + n_chunks;
+    KV_HIP_CHECK(hipMemcpy(&kend, kword, 4, hipMemcpyDeviceToHost));
+    KV_HIP_CHECK(hipMemcpy(&vend, vword, 4, hipMemcpyDeviceToHost));
     KV_HIP_CHECK(hipMemcpy(status, static_cast<uint8_t *>(c->buf.workspace) + WS_STATUS, 8, hipMemcpyDeviceToHost));
     std::memset(out, 0, sizeof(*out));
     out->tokens = c->packed_tokens + c->tail_tokens;
     out->packed_tokens = c->packed_tokens;
     out->tail_tokens = c->tail_tokens;
     out->n_chunks = n_chunks;
-    out->k_bytes = int64_t(kend) * 16;
-    out->v_bytes = int64_t(vend) * 16;
-    out->index_bytes = (n_chunks + 1) * 4;
+    const int64_t unit = c->pool ? KV_PAGE_BYTES : 16;
+    out->k_bytes = int64_t(kend) * unit;
+    out->v_bytes = int64_t(vend) * unit;
+    out->index_bytes = c->pool ? n_chunks * 8 : (n_chunks + 1) * 4;
     out->token_meta_bytes = int64_t(c->cfg.batch) * c->packed_tokens * 4;
     out->overflow = (status[ST_OVERFLOW_K] || status[ST_OVERFLOW_V]) ? 1 : 0;
     return KV_OK;

@@ -38,6 +38,7 @@ struct AArgs {
     float *partial;                   // [splits][B*Hq][V_PART_STRIDE]
     int64_t meta_stride;
     int B, H;
+    int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
     int n_blocks;                     // packed blocks per stream
     int blocks_per_split;
     float sm_log2;                    // sm_scale * log2(e)
@@ -177,8 +178,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ik, iv;
-        ik.load(a.k_index, first, 4, blk_end, a.B, a.H, b, h, lane);
-        iv.load(a.v_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + lane;
@@ -287,8 +288,8 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ik, iv;
-        ik.load(a.k_index, first, 4, blk_end, a.B, a.H, b, h, lane);
-        iv.load(a.v_index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + tok_in_blk;
@@ -429,6 +430,7 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
         a.partial = partial;
         a.meta_stride = c->max_tokens;
         a.B = B;
+        a.index_words = c->index_words;
         a.H = H;
         a.n_blocks = n_blocks;
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;

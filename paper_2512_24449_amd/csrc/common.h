@@ -41,6 +41,7 @@ constexpr size_t WS_SIZES_BYTES = size_t(MAX_NEW_CHUNKS) * 4;
 constexpr size_t WS_VPART = WS_SIZES + WS_SIZES_BYTES;
 constexpr int V_SPLITS_MAX = 64;                // split-L partial sums of the V path
 constexpr int V_PART_STRIDE = 132;              // floats: 128 outputs, [128] = sum p*min
+constexpr int PAGE16 = KV_PAGE_BYTES / 16;      // 16-byte units per page of a paged arena
 
 enum { ST_OVERFLOW_K = 0, ST_OVERFLOW_V = 1 };
 
@@ -88,6 +89,14 @@ __device__ inline float reduce_split_partials(const float *__restrict__ partial,
 
 }  // namespace packkv
 
+// A pool of fixed-size pages shared by paged caches.  Device state: uint32 state[0] = number of
+// free pages, state[1 + i] for i < state[0] = the free page numbers, the top of the stack last.
+struct kv_page_pool {
+    uint8_t *pages;
+    uint32_t *state;
+    int64_t n_pages;
+};
+
 struct kv_cache {
     kv_config_t cfg;
     kv_buffers_t buf;
@@ -99,6 +108,11 @@ struct kv_cache {
     bool wide_k, wide_v;    // codes above 15: wide chunk layout for that tensor
     int64_t packed_tokens;  // per batch element
     int32_t tail_tokens;
+    // paged arena: both tensors live in the pool's pages (buf.k_arena = buf.v_arena = pool->pages),
+    // the index has a (start, end) pair per chunk, buf.k_pages / buf.v_pages list the pages held
+    kv_page_pool *pool;     // null: chunks back to back in the cache's own arenas
+    int index_words;        // 1, or 2 when paged
+    int64_t max_pages;      // per tensor
 };
 
 #define KV_HIP_CHECK(expr)                      \
@@ -125,6 +139,7 @@ struct CompressJob {
     uint32_t *index;
     uint32_t *meta;
     uint32_t *status;         // status word to set on overflow
+    uint32_t *page_list;      // paged arena: [0] pages held, [1] 16-byte units used in the newest, [2..] page numbers
     const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
 };
 
@@ -137,6 +152,9 @@ int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *
 int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t src_batch_stride,
                      int n, int tail_pos, hipStream_t s);
 int launch_init(const kv_cache *c, hipStream_t s);
+int launch_pool_init(const kv_page_pool *pool, hipStream_t s);
+// Gives the pages of both tensors back to the pool and empties the page lists.
+int launch_release_pages(const kv_cache *c, hipStream_t s);
 int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *scores,
                     int64_t ld_scores, hipStream_t s);
 int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s);

@@ -7,6 +7,8 @@
 //                  order of the 64 tokens of a block, metadata into storage order
 //   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
 //   scan_offsets   one workgroup: prefix sum of the new chunk sizes -> index
+//   place_chunks   (paged arena instead of scan_offsets) one wave: chunk positions inside
+//                  pages taken from a shared pool -> index of (start, end) pairs
 //   pack_chunks    one workgroup per chunk: quantize again and write header +
 //                  payload at its final place (no staging copy, no atomics, so
 //                  the arena bytes are a pure function of the input)
@@ -141,6 +143,7 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     int64_t first_chunk,
                                                     uint32_t *__restrict__ sizes16,
                                                     const uint32_t *__restrict__ index,
+                                                    int index_words,
                                                     uint8_t *__restrict__ arena,
                                                     const uint8_t *__restrict__ order) {
     static_assert(!WIDE || PK == 8, "wide chunks have packs of 8 tokens");
@@ -156,7 +159,8 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
 
     uint8_t *dst = nullptr;
     if (WRITE) {
-        uint32_t o0 = index[first_chunk + cl], o1 = index[first_chunk + cl + 1];
+        const int64_t e = (first_chunk + cl) * index_words;
+        uint32_t o0 = index[e], o1 = index[e + 1];
         if (o1 == o0) return;  // dropped: the arena was full
         dst = arena + size_t(o0) * 16;
     }
@@ -253,6 +257,112 @@ __global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__re
     }
 }
 
+// Paged arena: places the n new chunks of one tensor (sizes in 16-byte units) in chunk order.  A
+// chunk goes right behind the previous one while it still fits into the tensor's newest page,
+// else to the start of a fresh page, so no chunk crosses a page boundary; positions count
+// 16-byte units from the start of the pool.  The fresh pages come off the pool's stack, all of
+// them with one atomic update of its height.  If the pool (or the tensor's page list) cannot
+// take them, nothing is taken, every chunk of the call is dropped (start = end) and the flag
+// is set, as with a full contiguous arena.  One wave: the walk is sequential and wave-uniform.
+__global__ __launch_bounds__(64) void place_chunks_kernel(const uint32_t *__restrict__ sizes16, int n,
+                                                          uint32_t *__restrict__ index2,
+                                                          int64_t first_chunk,
+                                                          uint32_t *__restrict__ page_list,
+                                                          int64_t max_pages, uint32_t *pool_state,
+                                                          uint32_t *__restrict__ status) {
+    const int lane = threadIdx.x;
+    const uint32_t held = page_list[0];
+    const uint32_t fill0 = held ? page_list[1] : uint32_t(PAGE16);  // no page yet: like a full one
+    uint32_t fill = fill0, need = 0;
+    for (int base = 0; base < n; base += 64) {
+        const uint32_t sz = base + lane < n ? sizes16[base + lane] : 0u;
+        const int m = min(64, n - base);
+        for (int i = 0; i < m; ++i) {
+            const uint32_t s = __builtin_amdgcn_readlane(sz, i);
+            if (fill + s > uint32_t(PAGE16)) ++need, fill = 0;
+            fill += s;
+        }
+    }
+    uint32_t ok = held + need <= uint64_t(max_pages), top = 0;
+    if (lane == 0 && ok && need) {
+        uint32_t old = __atomic_load_n(&pool_state[0], __ATOMIC_RELAXED);
+        while (true) {
+            if (old < need) {
+                ok = 0;
+                break;
+            }
+            const uint32_t seen = atomicCAS(&pool_state[0], old, old - need);
+            if (seen == old) break;
+            old = seen;
+        }
+        top = old;
+    }
+    ok = __builtin_amdgcn_readfirstlane(ok);
+    top = __builtin_amdgcn_readfirstlane(top);
+    if (!ok) {
+        if (lane == 0) status[0] = 1;
+        for (int i = lane; i < n; i += 64) {
+            index2[2 * (first_chunk + i)] = 0;
+            index2[2 * (first_chunk + i) + 1] = 0;
+        }
+        return;
+    }
+    fill = fill0;
+    uint32_t cnt = held, taken = 0;
+    uint32_t page = held ? page_list[1 + held] : 0u;
+    for (int base = 0; base < n; base += 64) {
+        const uint32_t sz = base + lane < n ? sizes16[base + lane] : 0u;
+        const int m = min(64, n - base);
+        uint32_t mine = 0;
+        for (int i = 0; i < m; ++i) {
+            const uint32_t s = __builtin_amdgcn_readlane(sz, i);
+            if (fill + s > uint32_t(PAGE16)) {
+                page = pool_state[top - taken];  // stack entry top - 1 - taken sits at word top - taken
+                ++taken;
+                if (lane == 0) page_list[2 + cnt] = page;
+                ++cnt;
+                fill = 0;
+            }
+            if (lane == i) mine = page * uint32_t(PAGE16) + fill;
+            fill += s;
+        }
+        if (base + lane < n) {
+            index2[2 * (first_chunk + base + lane)] = mine;
+            index2[2 * (first_chunk + base + lane) + 1] = mine + sz;
+        }
+    }
+    if (lane == 0) {
+        page_list[0] = cnt;
+        page_list[1] = fill;
+    }
+}
+
+// Pool of n free pages: the stack holds n - 1 down to 0, so page 0 is handed out first.
+__global__ void pool_init_kernel(uint32_t *state, int64_t n_pages) {
+    const int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x;
+    if (i == 0) state[0] = uint32_t(n_pages);
+    if (i < n_pages) state[1 + i] = uint32_t(n_pages - 1 - i);
+}
+
+// Pushes the pages of both tensors back onto the pool's stack (the newest page of a list first,
+// so a cache that refills an otherwise idle pool gets its pages in the same order again) and
+// empties the lists.  One wave.
+__global__ __launch_bounds__(64) void release_pages_kernel(uint32_t *k_list, uint32_t *v_list,
+                                                           uint32_t *pool_state, int64_t n_pages) {
+    const int lane = threadIdx.x;
+    for (int t = 0; t < 2; ++t) {
+        uint32_t *list = t ? v_list : k_list;
+        const uint32_t cnt = list[0];
+        uint32_t base = 0;
+        if (lane == 0 && cnt) base = atomicAdd(&pool_state[0], cnt);
+        base = __builtin_amdgcn_readfirstlane(base);
+        for (uint32_t i = lane; i < cnt; i += 64)
+            if (int64_t(base) + i < n_pages) pool_state[1 + base + i] = list[2 + cnt - 1 - i];
+    }
+    __syncthreads();
+    if (lane == 0) k_list[0] = k_list[1] = v_list[0] = v_list[1] = 0;
+}
+
 // New tokens of both tensors into their raw tails: blockIdx.z = 0 copies K, 1 copies V.
 __global__ void tail_copy_kernel(const uint4 *__restrict__ ksrc, const uint4 *__restrict__ vsrc,
                                  int64_t src_batch_stride16, uint4 *__restrict__ kdst,
@@ -265,11 +375,13 @@ __global__ void tail_copy_kernel(const uint4 *__restrict__ ksrc, const uint4 *__
         dst[b * dst_batch_stride16 + i] = src[b * src_batch_stride16 + i];
 }
 
-__global__ void init_kernel(uint32_t *status, uint32_t *k_index, uint32_t *v_index) {
+__global__ void init_kernel(uint32_t *status, uint32_t *k_index, uint32_t *v_index, uint32_t *k_pages,
+                            uint32_t *v_pages) {
     if (threadIdx.x < 64) status[threadIdx.x] = 0;
     if (threadIdx.x == 0) {
         k_index[0] = 0;
         v_index[0] = 0;
+        if (k_pages) k_pages[0] = k_pages[1] = v_pages[0] = v_pages[1] = 0;
     }
 }
 
@@ -347,7 +459,25 @@ int launch_init(const kv_cache *c, hipStream_t s) {
     hipLaunchKernelGGL(init_kernel, dim3(1), dim3(64), 0, s,
                        reinterpret_cast<uint32_t *>(ws + WS_STATUS),
                        static_cast<uint32_t *>(c->buf.k_index),
-                       static_cast<uint32_t *>(c->buf.v_index));
+                       static_cast<uint32_t *>(c->buf.v_index),
+                       c->pool ? static_cast<uint32_t *>(c->buf.k_pages) : nullptr,
+                       c->pool ? static_cast<uint32_t *>(c->buf.v_pages) : nullptr);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_pool_init(const kv_page_pool *pool, hipStream_t s) {
+    const int64_t blocks = (pool->n_pages + 255) / 256;
+    hipLaunchKernelGGL(pool_init_kernel, dim3(uint32_t(blocks)), dim3(256), 0, s, pool->state, pool->n_pages);
+    KV_HIP_CHECK(hipGetLastError());
+    return KV_OK;
+}
+
+int launch_release_pages(const kv_cache *c, hipStream_t s) {
+    if (!c->pool) return KV_ERR_ARG;
+    hipLaunchKernelGGL(release_pages_kernel, dim3(1), dim3(64), 0, s,
+                       static_cast<uint32_t *>(c->buf.k_pages), static_cast<uint32_t *>(c->buf.v_pages),
+                       c->pool->state, c->pool->n_pages);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }
@@ -406,12 +536,18 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
                                  : (c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>);
     hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
-    hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
-                       job.index, job.first_chunk, job.arena_cap16, job.status);
+                       job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                       job.order);
+    if (c->pool)
+        hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(64), 0, s, sizes16, n_chunks, job.index,
+                           job.first_chunk, job.page_list, c->max_pages, c->pool->state, job.status);
+    else
+        hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
+                           job.index, job.first_chunk, job.arena_cap16, job.status);
     hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, job.arena, job.order);
+                       job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                       job.order);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

@@ -40,6 +40,7 @@ struct KArgs {
     int64_t meta_stride;
     int64_t packed_tokens;
     int B, H;
+    int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
     int n_blocks;           // packed blocks per stream
     int blocks_per_group;   // blocks walked by one workgroup
     int groups_per_stream;
@@ -59,7 +60,7 @@ __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int b
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -124,7 +125,7 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -216,7 +217,7 @@ __device__ inline void k8_stream(const KArgs &a, int bh, int blk_begin, int blk_
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -282,7 +283,7 @@ __device__ inline void kw_stream(const KArgs &a, int bh, int blk_begin, int blk_
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         for (int it = 0; it < n_it; ++it) {
             const int64_t tok = int64_t(first + 4 * it) * N + tok_in_blk;
@@ -425,6 +426,7 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     a.meta_stride = c->max_tokens;
     a.packed_tokens = c->packed_tokens;
     a.B = c->cfg.batch;
+    a.index_words = c->index_words;
     a.H = c->cfg.n_kv_heads;
     a.n_blocks = int(c->packed_tokens / N);
     const int streams = a.B * a.H;

@@ -152,15 +152,16 @@ struct LanePacks {
 // Chunk offsets of up to 64 blocks of one wave, one block per lane: lane i holds
 // the index words of block first + stride*i of stream (b, h).  Read once per 64
 // blocks; iterations pick their words with v_readlane, so no chunk waits on an
-// index load.
+// index load.  words = 1: chunks lie back to back, chunk c spans index[c]..index[c+1];
+// words = 2 (paged arena): index[2c] and index[2c+1] are the chunk's own start and end.
 struct IndexBatch {
     uint32_t o0, o1;
-    __device__ inline void load(const uint32_t *__restrict__ index, int first, int stride, int end,
-                                int B, int H, int b, int h, int lane) {
+    __device__ inline void load(const uint32_t *__restrict__ index, int words, int first, int stride,
+                                int end, int B, int H, int b, int h, int lane) {
         const int blk = first + stride * lane;
-        const int c = blk < end ? (blk * B + b) * H + h : 0;
-        o0 = index[c];
-        o1 = index[c + 1];
+        const int64_t c = blk < end ? (int64_t(blk) * B + b) * H + h : 0;
+        o0 = index[c * words];
+        o1 = index[c * words + 1];
     }
     __device__ inline uint32_t start16(int it) const { return __builtin_amdgcn_readlane(o0, it); }
     __device__ inline uint32_t end16(int it) const { return __builtin_amdgcn_readlane(o1, it); }
@@ -252,11 +253,7 @@ __device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, in
     r.d1 = pp[1];
     r.d2 = pp[2];
     r.sh = uint32_t(pos);
-#ifdef EXP_TABLE_SAME
-    r.k = table[0x21 + (hb & 0)];
-#else
     r.k = table[hb];
-#endif
     return r;
 }
 

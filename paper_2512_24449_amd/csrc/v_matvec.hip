@@ -32,6 +32,7 @@ struct VArgs {
     int64_t ld;
     int64_t meta_stride;
     int B, H;
+    int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
     int n_blocks;           // packed blocks per stream
     int blocks_per_split;
 };
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
         uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
@@ -135,7 +136,7 @@ __global__ __launch_bounds__(256) void v8_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
         uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
@@ -207,7 +208,7 @@ __global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         for (int it = 0; it < n_it; ++it) {
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADERW / 16);
@@ -285,6 +286,7 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
         a.ld = ld_p;
         a.meta_stride = c->max_tokens;
         a.B = B;
+        a.index_words = c->index_words;
         a.H = H;
         a.n_blocks = n_blocks;
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;

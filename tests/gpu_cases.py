@@ -78,16 +78,92 @@ def check_packed_state(cache, n_packed, ck, cv, B, H):
     return st
 
 
+PAGE16 = binding.PAGE_BYTES // 16
+
+
+class PagePlacementModel:
+    """The placement rule of the paged arena as the header states it, for one pool: a chunk goes
+    behind the previous one of its tensor while it fits into that tensor's newest page, else to
+    the start of a fresh page; an append takes all its fresh pages or none; page 0 comes first and
+    released pages are handed out again newest first."""
+
+    def __init__(self, n_pages):
+        self.free = list(range(n_pages - 1, -1, -1))  # stack, top last
+
+    def new_tensor(self):
+        return dict(pages=[], fill=PAGE16)
+
+    def place(self, t, sizes16):
+        """-> list of (start16, end16) for the chunks of one append call, or None if dropped."""
+        fill, need = t["fill"], 0
+        for s in sizes16:
+            if fill + s > PAGE16:
+                need, fill = need + 1, 0
+            fill += s
+        if need > len(self.free):
+            return None
+        out, fill = [], t["fill"]
+        for s in sizes16:
+            if fill + s > PAGE16:
+                t["pages"].append(self.free.pop())
+                fill = 0
+            start = t["pages"][-1] * PAGE16 + fill
+            out.append((start, start + s))
+            fill += s
+        t["fill"] = fill
+        return out
+
+    def release(self, *tensors):
+        for t in tensors:
+            self.free.extend(reversed(t["pages"]))
+            t["pages"], t["fill"] = [], PAGE16
+
+
+def check_paged_state(cache, n_packed, ck, cv, B, H):
+    """Paged cache: every chunk's bytes (read through its index pair from the pool's pages), and the
+    token metadata, equal the oracle's bit for bit; no chunk crosses a page boundary, chunks lie
+    inside pages their tensor holds and do not overlap."""
+    st = cache.kv_cache_stats()
+    assert st.overflow == 0 and st.packed_tokens == n_packed
+    if not n_packed:
+        return st
+    n_chunks = n_packed // 64 * B * H
+    max_tokens = cache.tensors["k_token_meta"].numel() // 4 // B
+    pages = cache.pool.pages.cpu().numpy()
+    held_all = []
+    for name, c, nbytes in (("k", ck, st.k_bytes), ("v", cv, st.v_bytes)):
+        plist = cache.view(name + "_pages", torch.int32).cpu().numpy().view(np.uint32)
+        held = plist[2:2 + int(plist[0])].astype(np.int64)
+        assert nbytes == held.size * binding.PAGE_BYTES
+        held_all.append(held)
+        pairs = cache.view(name + "_index", torch.int32)[:2 * n_chunks].cpu().numpy().view(np.uint32)
+        pairs = pairs.reshape(n_chunks, 2).astype(np.int64)
+        assert np.array_equal(pairs[:, 1] - pairs[:, 0], np.diff(c.offsets16.astype(np.int64))), name + " chunk sizes"
+        assert np.array_equal(pairs[:, 0] // PAGE16, (pairs[:, 1] - 1) // PAGE16), name + " chunk crosses a page"
+        assert np.isin(pairs[:, 0] // PAGE16, held).all(), name + " chunk outside the tensor's pages"
+        order = np.argsort(pairs[:, 0])
+        assert (pairs[order][1:, 0] >= pairs[order][:-1, 1]).all(), name + " chunks overlap"
+        for i in range(n_chunks):
+            got = pages[pairs[i, 0] * 16:pairs[i, 1] * 16]
+            ref = c.arena[int(c.offsets16[i]) * 16:int(c.offsets16[i + 1]) * 16]
+            assert np.array_equal(got, ref), "%s chunk %d differs" % (name, i)
+        meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[:, :n_packed]
+        assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta), name + " token meta"
+    assert not np.intersect1d(held_all[0], held_all[1]).size, "K and V share a page"
+    return st
+
+
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
-             max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2):
+             max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2, pool=None):
     """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
-    With a relative scale below 1/15 (wide chunks) the fused attention entry point must refuse."""
+    With a relative scale below 1/15 (wide chunks) the fused attention entry point must refuse.
+    pool: a binding.PagePool -> the cache is paged."""
     wide = round(1 / k_rel) > 15 or round(1 / v_rel) > 15
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
     cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), k_rel_scale=k_rel, v_rel_scale=v_rel,
-                                  device=device, pack_size=pack_size)
+                                  device=device, pack_size=pack_size, pool=pool)
     Kd, Vd, qd = K.to(device), V.to(device), q.to(device)
     pos = 0
     for n in (pieces or [L]):
@@ -97,7 +173,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
 
     n_packed, ck, cv = oracle_cache(Kn, Vn, k_rel, v_rel, pack_size)
     if check_bytes:
-        check_packed_state(cache, n_packed, ck, cv, B, H)
+        (check_paged_state if pool is not None else check_packed_state)(cache, n_packed, ck, cv, B, H)
 
     scores = cache.kv_k_matvec(qd, sm_scale)
     torch.cuda.synchronize()
@@ -136,6 +212,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
             raise AssertionError("fused attention must refuse wide chunks")
         except binding.PackKVError as e:
             assert e.code == binding.KV_ERR_UNSUPPORTED
+        attn = None
     else:
         # fused decode attention against the oracle's definition of Att(q, K, V)
         attn = cache.kv_decode_attention(qd, sm_scale)
@@ -146,4 +223,5 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
         torch.cuda.synchronize()
         assert torch.equal(attn, attn2)
     cache.close()
-    return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0)
+    return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0,
+                scores=scores.cpu(), out=out.cpu(), attn=None if attn is None else attn.cpu())

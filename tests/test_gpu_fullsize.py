@@ -193,3 +193,63 @@ def test_packed_arena_beyond_4_gib():
     assert torch.isfinite(attn).all()
     assert_close_vectors(attn.cpu().numpy(), out3.cpu().numpy().astype(np.float64), "fused vs three-step")
     cache.close()
+
+
+@pytest.mark.parametrize("B,H,Hq,L", [(8, 52, 52, 32000), (4, 8, 32, 32768 + 77), (8, 52, 52, 294912)])
+def test_paged_cache_at_full_size(B, H, Hq, L):
+    """The paged arena at the headline shape, at the grouped-query shape and past 4 GiB of pages per
+    tensor: every result is bitwise the contiguous cache's (whose bytes the tests above compare with
+    the oracle), every chunk has the contiguous chunk's size, stays inside one page and overlaps no
+    other, and sampled chunks hold the same bytes."""
+    K, V, q = synth.make_kv(B, L, H, Hq, 11, device="cuda:0")
+    flat = binding.PackedKVCache(B, H, Hq, L, bits_per_element_budget=3.0)
+    flat.kv_compress_append(K, V)
+    st = flat.kv_cache_stats()
+    assert st.overflow == 0
+    page = binding.PAGE_BYTES
+    n_pages = int((st.k_bytes + st.v_bytes) * 1.04) // page + 16
+    pool = binding.PagePool(n_pages)
+    paged = binding.PackedKVCache(B, H, Hq, L, pool=pool)
+    paged.kv_compress_append(K, V)
+    del K, V
+    pst = paged.kv_cache_stats()
+    assert pst.overflow == 0 and pst.n_chunks == st.n_chunks
+    assert pst.k_bytes <= 1.04 * st.k_bytes + 2 * page and pst.v_bytes <= 1.04 * st.v_bytes + 2 * page
+    assert pool.kv_page_pool_free_pages() == n_pages - (pst.k_bytes + pst.v_bytes) // page
+
+    sm_scale = 128 ** -0.5
+    results = []
+    for cache in (flat, paged):
+        scores = cache.kv_k_matvec(q, sm_scale)
+        p = synth.make_probs(scores)
+        results.append((scores, cache.kv_v_matvec(p), cache.kv_decode_attention(q, sm_scale)))
+        del p
+    torch.cuda.synchronize()
+    for a, b, what in zip(results[0], results[1], ("scores", "V product", "fused attention")):
+        assert torch.equal(a, b), what + ": paged and contiguous caches differ"
+    del results
+
+    n = st.n_chunks
+    rng = np.random.default_rng(5)
+    sample = sorted(set(rng.integers(0, n, 48).tolist()) | {0, n - 1})
+    top = 0
+    for name in ("k", "v"):
+        pairs = (paged.view(name + "_index", torch.int32)[:2 * n].to(torch.int64) & 0xFFFFFFFF).view(n, 2)
+        index = flat.view(name + "_index", torch.int32)[:n + 1].to(torch.int64) & 0xFFFFFFFF
+        assert torch.equal(pairs[:, 1] - pairs[:, 0], index[1:] - index[:-1]), name + " chunk sizes"
+        units = page // 16
+        assert torch.equal(pairs[:, 0] // units, (pairs[:, 1] - 1) // units), name + " chunk crosses a page"
+        srt = pairs[torch.argsort(pairs[:, 0])]
+        assert bool((srt[1:, 0] >= srt[:-1, 1]).all()), name + " chunks overlap"
+        top = max(top, int(pairs[:, 1].max().item()) * 16)
+        assert top <= n_pages * page
+        for c in sample:
+            s, e = (int(x) * 16 for x in pairs[c].tolist())
+            lo, hi = int(index[c].item()) * 16, int(index[c + 1].item()) * 16
+            assert torch.equal(pool.pages[s:e], flat.tensors[name + "_arena"][lo:hi]), "%s chunk %d bytes" % (name, c)
+    if L > 200000:
+        assert top > 2 ** 32, "this case is meant to place chunks past 4 GiB"
+    flat.close()
+    paged.close()
+    assert pool.kv_page_pool_free_pages() == n_pages
+    pool.close()

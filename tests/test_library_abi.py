@@ -70,6 +70,31 @@ def test_query_sizes_and_config_checks():
     assert L.kv_k_matvec(None, None, 1.0, None, 0, None) == -1
 
 
+def test_paged_sizes_and_pool_bookkeeping_bytes():
+    L = binding.lib()
+    cfg = binding.make_config(2, 32, 32, 4096)
+    flat, paged = binding.kv_query_sizes(cfg), binding.kv_query_sizes_paged(cfg)
+    max_chunks = 4096 // 64 * 2 * 32
+    assert paged.k_arena == 0 and paged.v_arena == 0 and flat.k_pages == 0 and flat.v_pages == 0
+    assert paged.k_index >= max_chunks * 8 and paged.v_index == paged.k_index
+    # 14 largest chunks of 4608 bytes fit a page of 65536
+    assert paged.k_pages >= 4 * (2 + -(-max_chunks // 14)) and paged.k_pages % 256 == 0
+    for name in ("k_token_meta", "v_token_meta", "k_tail", "v_tail", "workspace", "token_order"):
+        assert getattr(paged, name) == getattr(flat, name)
+    wide = binding.kv_query_sizes_paged(binding.make_config(2, 32, 32, 4096, k_rel_scale=0.05, pack_size=8))
+    assert wide.k_pages >= 4 * (2 + -(-max_chunks // 6)) and wide.v_pages >= 4 * (2 + -(-max_chunks // 12))
+    out = binding.kv_sizes_t()
+    bad = binding.make_config(2, 32, 32, 4096, pack_size=4)
+    assert L.kv_query_sizes_paged(C.byref(bad), C.byref(out)) == -2
+    assert L.kv_page_pool_state_bytes(1000) >= 4 * 1001 and L.kv_page_pool_state_bytes(1000) % 256 == 0
+    assert L.kv_page_pool_state_bytes(0) == 0
+    # argument checks that need no device
+    handle = C.c_void_p()
+    assert L.kv_page_pool_create(None, 4, None, None, C.byref(handle)) == -1
+    assert L.kv_page_pool_destroy(None) == -1 and L.kv_cache_release(None, None) == -1
+    assert L.kv_page_pool_free_pages(None, None, None) == -1
+
+
 def test_binding_fails_loudly_without_library(monkeypatch, tmp_path):
     """No CPU fallback: a missing library with no compiler is an error."""
     from paper_2512_24449_amd import build
