@@ -257,83 +257,148 @@ __global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__re
     }
 }
 
-// Paged arena: places the n new chunks of one tensor (sizes in 16-byte units) in chunk order.  A
-// chunk goes right behind the previous one while it still fits into the tensor's newest page,
-// else to the start of a fresh page, so no chunk crosses a page boundary; positions count
-// 16-byte units from the start of the pool.  The fresh pages come off the pool's stack, all of
-// them with one atomic update of its height.  If the pool (or the tensor's page list) cannot
-// take them, nothing is taken, every chunk of the call is dropped (start = end) and the flag
-// is set, as with a full contiguous arena.  One wave: the walk is sequential and wave-uniform.
-__global__ __launch_bounds__(64) void place_chunks_kernel(const uint32_t *__restrict__ sizes16, int n,
-                                                          uint32_t *__restrict__ index2,
-                                                          int64_t first_chunk,
-                                                          uint32_t *__restrict__ page_list,
-                                                          int64_t max_pages, uint32_t *pool_state,
-                                                          uint32_t *__restrict__ status) {
-    const int lane = threadIdx.x;
+// Paged arena: places the n new chunks of one tensor (sizes16: their sizes in 16-byte units;
+// overwritten with their exclusive prefix sums) in chunk order.  A chunk goes right behind the
+// previous one while it still fits into the tensor's newest page, else to the start of a fresh
+// page, so no chunk crosses a page boundary; positions count 16-byte units from the start of the
+// pool.  The fresh pages come off the pool's stack, all of them with one atomic update of its
+// height.  If the pool (or the tensor's page list) cannot take them, nothing is taken, every
+// chunk of the call is dropped (start = end) and the flag is set, as with a full contiguous arena.
+//
+// One workgroup.  The rule is sequential in the fill level only, so the work is split: (1) prefix
+// sums S of the sizes; (2) for every chunk j, in parallel, how many chunks a page holds that
+// starts with j (two pointers over S); (3) one thread follows that chain from the first chunk
+// that does not fit the newest page -- one LDS step per fresh page, not per chunk -- and marks
+// the chunks that start a page; (4) in parallel again, every chunk finds its page (a count of the
+// marks before it) and its offset inside it (S[j] - S[page start]).
+__global__ __launch_bounds__(1024) void place_chunks_kernel(uint32_t *__restrict__ sizes16, int n,
+                                                            uint32_t *__restrict__ index2,
+                                                            int64_t first_chunk,
+                                                            uint32_t *__restrict__ page_list,
+                                                            int64_t max_pages, uint32_t *pool_state,
+                                                            uint32_t *__restrict__ status) {
+    // bit 7: the chunk starts a fresh page; bits 0..6: chunks that fit a page starting here, minus 1
+    // (a chunk is at least 512 bytes, so a page holds at most 128)
+    __shared__ uint8_t step[MAX_NEW_CHUNKS];
+    __shared__ uint32_t wave_a[16], wave_b[16];
+    __shared__ uint32_t sh_total, sh_top, sh_ok;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int per = (n + 1023) / 1024;
+    const int lo = min(tid * per, n), hi = min(lo + per, n);
+    constexpr uint32_t P = PAGE16;
+
+    // (1) exclusive prefix sums, in place
+    uint32_t local = 0;
+    for (int i = lo; i < hi; ++i) local += sizes16[i];
+    uint32_t inc = local;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_up(inc, o);
+        if (lane >= o) inc += v;
+    }
+    if (lane == 63) wave_a[wave] = inc;
+    __syncthreads();
+    uint32_t run = inc - local;
+    for (int k = 0; k < wave; ++k) run += wave_a[k];
+    if (tid == 1023) sh_total = run + local;
+    for (int i = lo; i < hi; ++i) {
+        const uint32_t sz = sizes16[i];
+        sizes16[i] = run;
+        run += sz;
+    }
+    __syncthreads();
+    const uint32_t total = sh_total;
+    auto S = [&](int i) -> uint32_t { return i < n ? sizes16[i] : total; };
+
+    // (2) chunks per page for a page that starts with chunk j
+    {
+        int k = lo;
+        for (int j = lo; j < hi; ++j) {
+            k = max(k, j + 1);
+            const uint32_t limit = S(j) + P;
+            while (k < n && S(k + 1) <= limit) ++k;
+            step[j] = uint8_t(k - j - 1);
+        }
+    }
+    __syncthreads();
+
+    // (3) the chain of page starts, and the pages for it
     const uint32_t held = page_list[0];
-    const uint32_t fill0 = held ? page_list[1] : uint32_t(PAGE16);  // no page yet: like a full one
-    uint32_t fill = fill0, need = 0;
-    for (int base = 0; base < n; base += 64) {
-        const uint32_t sz = base + lane < n ? sizes16[base + lane] : 0u;
-        const int m = min(64, n - base);
-        for (int i = 0; i < m; ++i) {
-            const uint32_t s = __builtin_amdgcn_readlane(sz, i);
-            if (fill + s > uint32_t(PAGE16)) ++need, fill = 0;
-            fill += s;
+    const uint32_t fill0 = held ? page_list[1] : P;  // no page yet: like a full one
+    if (tid == 0) {
+        int j = 0;
+        while (j < n && fill0 + S(j + 1) <= P) ++j;  // these still go into the newest page
+        uint32_t need = 0;
+        while (j < n) {
+            const uint32_t c = step[j];
+            step[j] = uint8_t(c | 0x80u);
+            ++need;
+            j += int(c) + 1;
         }
-    }
-    uint32_t ok = held + need <= uint64_t(max_pages), top = 0;
-    if (lane == 0 && ok && need) {
-        uint32_t old = __atomic_load_n(&pool_state[0], __ATOMIC_RELAXED);
-        while (true) {
-            if (old < need) {
-                ok = 0;
-                break;
+        uint32_t ok = held + need <= uint64_t(max_pages), top = 0;
+        if (ok && need) {
+            uint32_t old = __atomic_load_n(&pool_state[0], __ATOMIC_RELAXED);
+            while (true) {
+                if (old < need) {
+                    ok = 0;
+                    break;
+                }
+                const uint32_t seen = atomicCAS(&pool_state[0], old, old - need);
+                if (seen == old) break;
+                old = seen;
             }
-            const uint32_t seen = atomicCAS(&pool_state[0], old, old - need);
-            if (seen == old) break;
-            old = seen;
+            top = old;
         }
-        top = old;
+        sh_ok = ok;
+        sh_top = top;
     }
-    ok = __builtin_amdgcn_readfirstlane(ok);
-    top = __builtin_amdgcn_readfirstlane(top);
-    if (!ok) {
-        if (lane == 0) status[0] = 1;
-        for (int i = lane; i < n; i += 64) {
+    __syncthreads();
+    if (!sh_ok) {
+        if (tid == 0) status[0] = 1;
+        for (int i = lo; i < hi; ++i) {
             index2[2 * (first_chunk + i)] = 0;
             index2[2 * (first_chunk + i) + 1] = 0;
         }
         return;
     }
-    fill = fill0;
-    uint32_t cnt = held, taken = 0;
-    uint32_t page = held ? page_list[1 + held] : 0u;
-    for (int base = 0; base < n; base += 64) {
-        const uint32_t sz = base + lane < n ? sizes16[base + lane] : 0u;
-        const int m = min(64, n - base);
-        uint32_t mine = 0;
-        for (int i = 0; i < m; ++i) {
-            const uint32_t s = __builtin_amdgcn_readlane(sz, i);
-            if (fill + s > uint32_t(PAGE16)) {
-                page = pool_state[top - taken];  // stack entry top - 1 - taken sits at word top - taken
-                ++taken;
-                if (lane == 0) page_list[2 + cnt] = page;
-                ++cnt;
-                fill = 0;
-            }
-            if (lane == i) mine = page * uint32_t(PAGE16) + fill;
-            fill += s;
-        }
-        if (base + lane < n) {
-            index2[2 * (first_chunk + base + lane)] = mine;
-            index2[2 * (first_chunk + base + lane) + 1] = mine + sz;
-        }
+    const uint32_t top = sh_top;
+
+    // (4) marks before this thread's slice, and the last marked chunk before it (+1; 0 = none)
+    uint32_t marks = 0, last = 0;
+    for (int j = lo; j < hi; ++j)
+        if (step[j] & 0x80u) ++marks, last = uint32_t(j) + 1;
+    uint32_t marks_inc = marks, last_inc = last;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t a = __shfl_up(marks_inc, o), b = __shfl_up(last_inc, o);
+        if (lane >= o) marks_inc += a, last_inc = max(last_inc, b);
     }
-    if (lane == 0) {
-        page_list[0] = cnt;
-        page_list[1] = fill;
+    if (lane == 63) wave_a[wave] = marks_inc, wave_b[wave] = last_inc;
+    __syncthreads();
+    uint32_t ord = marks_inc - marks;      // fresh pages started before the slice
+    uint32_t start_j = __shfl_up(last_inc, 1);
+    if (lane == 0) start_j = 0;
+    for (int k = 0; k < wave; ++k) ord += wave_a[k], start_j = max(start_j, wave_b[k]);
+    const uint32_t newest = held ? page_list[1 + held] : 0u;
+    uint32_t page = 0, page_s = 0;  // the page the slice starts in, S of the chunk that starts it
+    if (start_j) page = pool_state[top - (ord - 1)], page_s = S(int(start_j) - 1);
+    for (int j = lo; j < hi; ++j) {
+        if (step[j] & 0x80u) {
+            page = pool_state[top - ord];  // stack entry top - 1 - ord sits at word top - ord
+            page_list[2 + held + ord] = page;
+            ++ord;
+            page_s = S(j);
+        }
+        const uint32_t at = ord ? page * P + (S(j) - page_s) : newest * P + fill0 + S(j);
+        index2[2 * (first_chunk + j)] = at;
+        index2[2 * (first_chunk + j) + 1] = at + (S(j + 1) - S(j));
+    }
+    if (tid == 1023) {
+        const uint32_t all_last = max(last_inc, start_j);  // with the waves before: the last marked chunk of all
+        uint32_t l = all_last;
+        for (int k = 0; k < 16; ++k) l = max(l, wave_b[k]);
+        page_list[0] = held + ord;
+        page_list[1] = l ? total - S(int(l) - 1) : fill0 + total;
     }
 }
 
@@ -539,7 +604,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
                        job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
                        job.order);
     if (c->pool)
-        hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(64), 0, s, sizes16, n_chunks, job.index,
+        hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
                            job.first_chunk, job.page_list, c->max_pages, c->pool->state, job.status);
     else
         hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,

@@ -197,3 +197,39 @@ def test_paged_host_argument_errors():
     gpu_cases.check_packed_state(cache, n_packed, ck, cv, 1, 2)
     cache.close()
     pool.close()
+
+
+def test_bulk_append_placement_equals_the_rule():
+    """Thousands of chunks per call (several chunks per thread of the placement kernel, many fresh
+    pages per call): every chunk position equals the sequential rule's."""
+    B, H, Hq = 2, 8, 8
+    calls = [64 * 330, 64 * 70, 64, 64 * 99]   # 5280, 1120, 16 and 1584 chunks per tensor
+    L = sum(calls)
+    n_pages = 900
+    pool = binding.PagePool(n_pages)
+    model = gpu_cases.PagePlacementModel(n_pages)
+    cache = binding.PackedKVCache(B, H, Hq, L, pool=pool)
+    K, V, q = synth.make_kv(B, L, H, Hq, 31)
+    tensors = (model.new_tensor(), model.new_tensor())
+    expected = ([], [])
+    lo = 0
+    for n in calls:
+        cache.kv_compress_append(K[:, lo:lo + n].contiguous().cuda(), V[:, lo:lo + n].contiguous().cuda())
+        for t, (x, rel) in enumerate(((K, 0.1), (V, 0.2))):
+            c = oracle.compress(np.ascontiguousarray(x.numpy()[:, lo:lo + n]), rel)
+            placed = model.place(tensors[t], np.diff(c.offsets16.astype(np.int64)).tolist())
+            assert placed is not None
+            expected[t].extend(placed)
+        lo += n
+    torch.cuda.synchronize()
+    assert cache.kv_cache_stats().overflow == 0
+    n_chunks = L // 64 * B * H
+    for t, name in enumerate(("k", "v")):
+        got = _chunk_pairs(cache, name, n_chunks)
+        bad = [i for i in range(n_chunks) if got[i] != expected[t][i]]
+        assert not bad, "%s: %d chunks misplaced, first %d: %s vs %s" % (name, len(bad), bad[0], got[bad[0]], expected[t][bad[0]])
+        pages, fill = _page_list(cache, name)
+        assert pages == tensors[t]["pages"] and fill == tensors[t]["fill"]
+    assert pool.kv_page_pool_free_pages() == len(model.free)
+    cache.close()
+    pool.close()
