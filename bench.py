@@ -121,7 +121,6 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
     L = K.shape[1]
     total = steps + warmup
     reps = Replicas(w, K, V, 2 * total + 64, binding, torch, pack_size, rel, paged)
-    fused = round(1 / rel[0]) <= 15 and round(1 / rel[1]) <= 15   # wide chunks: three-step path only
     R = len(reps)
     dev = K.device
     gen = torch.Generator(device=dev)
@@ -179,16 +178,14 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
             e1.record()
             a_ev.append((e0, e1))
 
-    fused_elapsed = float("nan")
-    if fused:
-        for i in range(warmup):
-            fused_step(i, False)
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for i in range(warmup, total):
-            fused_step(i, True)
-        torch.cuda.synchronize()
-        fused_elapsed = time.perf_counter() - t0
+    for i in range(warmup):
+        fused_step(i, False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(warmup, total):
+        fused_step(i, True)
+    torch.cuda.synchronize()
+    fused_elapsed = time.perf_counter() - t0
 
     st = reps.stats
     k_ms = sum(a.elapsed_time(b) for a, b in k_ev) / len(k_ev)
@@ -479,7 +476,7 @@ def main():
     fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     # the second pack size (packs of 8 tokens) on the same data
     packed8 = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8)
-    # finer scales (codes above 15, wide chunks) on the same data: three-step path only
+    # finer scales (codes above 15, wide chunks) on the same data
     packedw = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8,
                                                              rel=(0.05, 0.05))
     # the same workload in paged caches over one shared page pool
@@ -560,6 +557,8 @@ def main():
                                "fused_ms_per_step": round(packed8["fused_ms_per_step"], 5)}
     if packedw is not None:
         line["wide_chunks_rel_0.05"] = {"k_ms": round(packedw["k_ms"], 5), "v_ms": round(packedw["v_ms"], 5),
+                                        "attn_ms": round(packedw["attn_ms"], 5),
+                                        "fused_ms_per_step": round(packedw["fused_ms_per_step"], 5),
                                         "k_bits_per_elem": round(packedw["k_bits_per_elem"], 3),
                                         "v_bits_per_elem": round(packedw["v_bits_per_elem"], 3),
                                         "speedup_k": round(fp16["k_ms"] / packedw["k_ms"], 3),

@@ -76,8 +76,7 @@ typedef struct kv_page_pool kv_page_pool_t; /* the same: pages shared by paged c
  * and packs of `width` bytes.  A relative scale below 1/15 gives codes above 15
  * ("wide" chunks for that tensor: packs of 8 tokens with widths up to 8 bits,
  * 1024 width bytes followed by 1024 minimum bytes, then the packs); it needs
- * pack_size 8 and KV_REPACK_NONE, its lower bound is 1/255, and
- * kv_decode_attention is not available with it (the three-step path is).
+ * pack_size 8 and KV_REPACK_NONE, and its lower bound is 1/255.
  * KV_REPACK_V_MEDIAN
  * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
  * tokens, K and V are packed with their tokens sorted by the lower median of the
@@ -214,8 +213,8 @@ int kv_softmax(kv_cache_t *cache, float *scores, int64_t ld_scores, void *hip_st
  * [B][H_q][128].  Equivalent to kv_k_matvec -> softmax -> kv_v_matvec up to
  * fp32 rounding.  Fixed-order fp32 accumulation, bitwise reproducible.  Uses the
  * workspace for per-split partial results; calls on one cache must not overlap.
- * KV_ERR_ARG on an empty cache, KV_ERR_UNSUPPORTED when a tensor uses the wide
- * chunk layout.  Blocks dropped by an arena overflow are left out of the softmax.
+ * KV_ERR_ARG on an empty cache.  Blocks dropped by an arena overflow are left out
+ * of the softmax.
  */
 int kv_decode_attention(kv_cache_t *cache, const void *q, float sm_scale, float *out, void *hip_stream);
 

@@ -354,7 +354,6 @@ extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale,
                                    void *hip_stream) {
     if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;
     if (c->packed_tokens + c->tail_tokens < 1) return KV_ERR_ARG;  // softmax over nothing
-    if (c->wide_k || c->wide_v) return KV_ERR_UNSUPPORTED;         // wide chunks: three-step path only
     return launch_decode_attention(c, static_cast<const __half *>(q), sm_scale, out,
                                    static_cast<hipStream_t>(hip_stream));
 }

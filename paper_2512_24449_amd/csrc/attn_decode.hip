@@ -98,10 +98,11 @@ __device__ inline void attn_raise_reference(const float (&s)[G], float (&m_ref)[
 template <int G>
 __device__ inline void attn_store_partial(const AArgs &a, const VState<G> &st, const float (&l_lane)[G],
                                           const float (&m_ref)[G], float (*red)[G][D + 4], int wave,
-                                          int lane, int split, int64_t head0) {
+                                          int lane, int split, int64_t head0,
+                                          float code_scale = CODE_SCALE_LIFTED) {
     __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
 
-    v_state_store<G>(st, red[wave], lane);
+    v_state_store<G>(st, red[wave], lane, code_scale);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const float l = wave_all_sum(l_lane[g]);
@@ -252,16 +253,28 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
 // The same for chunks with packs of 8 tokens (Sec. IV-B; pack8.h): the K phase runs the
 // pairwise dot-product form for all G heads and leaves lane l with token
 // k8_token_of_block_lane(l) of the block; the V phase stages the weights in that order.
-template <int G>
+// KW / VW: that tensor uses the wide chunk layout (codes above 15); the two tensors choose
+// their layout independently, and a wide chunk needs a buffer twice as large.  With both wide,
+// two buffers per wave would leave room for one workgroup per compute unit only (measured 0.76 ms
+// at the headline shape, slower than the three-step path); the K and the V chunk then take turns
+// in ONE buffer, transfers overlap with the unpacking of other waves only, and three workgroups
+// fit.
+template <int G, bool KW, bool VW>
 __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK8_LDS + LDS_TAIL_PAD];
+    constexpr bool SHARED = KW && VW;
+    constexpr int KLDS = KW ? CHUNKW_LDS : CHUNK8_LDS, VLDS = SHARED ? 0 : (VW ? CHUNKW_LDS : CHUNK8_LDS);
+    constexpr int KMAX = KW ? CHUNKW_MAX : CHUNK8_MAX, VMAX = VW ? CHUNKW_MAX : CHUNK8_MAX;
+    constexpr int KHDR = KW ? HEADERW : HEADER8, VHDR = VW ? HEADERW : HEADER8;
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * (KLDS + VLDS) + LDS_TAIL_PAD];
     __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
-    __shared__ uint2 table[PACK_TABLE_ENTRIES];   // K: pair table
-    __shared__ uint4 vtable[PACK_TABLE_ENTRIES];  // V: lifted codes
-    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK8_LDS, "reduction array must fit");
+    __shared__ uint2 table[KW ? 16 : PACK_TABLE_ENTRIES];   // K: the wide K table, or the pair table
+    __shared__ uint4 vtable[VW ? 16 : PACK_TABLE_ENTRIES];  // V: the wide V table, or lifted codes
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * (KLDS + VLDS), "reduction array must fit");
+    static_assert(WIDE_TABLE_ENTRIES <= 16, "table sizes above");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
-    build_pair_table(table);
-    build_pack_table(vtable, CODE_LIFT, fold_min<G>());
+    if constexpr (!KW) build_pair_table(table);
+    if constexpr (!VW) build_pack_table(vtable, CODE_LIFT, fold_min<G>());
+    if constexpr (KW || VW) build_wide_tables(KW ? table : nullptr, VW ? vtable : nullptr);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -269,7 +282,7 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
     const int col = lane & 15;
-    const int kbuf = wave * 2 * CHUNK8_LDS, vbuf = kbuf + CHUNK8_LDS;
+    const int kbuf = wave * (KLDS + VLDS), vbuf = SHARED ? kbuf : kbuf + KLDS;
     const int64_t head0 = int64_t(b) * a.H * G + h * G;
     const int tok_in_blk = k8_token_of_block_lane(lane);
 
@@ -291,17 +304,18 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
         ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
-        chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
+        chunk_issue_lds<KMAX, KHDR>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + tok_in_blk;
         uint32_t kmt_next = a.k_meta[tok0], vmt_next = a.v_meta[tok0];
         for (int it = 0; it < n_it; ++it) {
             // a block dropped by an arena overflow (in either tensor) takes no part
-            const bool valid = ik.end16(it) - ik.start16(it) >= uint32_t(HEADER8 / 16) &&
-                               iv.end16(it) - iv.start16(it) >= uint32_t(HEADER8 / 16);
+            const bool valid = ik.end16(it) - ik.start16(it) >= uint32_t(KHDR / 16) &&
+                               iv.end16(it) - iv.start16(it) >= uint32_t(VHDR / 16);
             wait_chunk_landed();  // K chunk of this block
             uint32_t kmt = kmt_next, vmt = vmt_next;
             consume_here(kmt), consume_here(vmt);
-            chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
+            if constexpr (!SHARED)
+                chunk_issue_lds<VMAX, VHDR>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             if (it + 1 < n_it) {
                 const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + tok_in_blk;
                 kmt_next = a.k_meta[tok];
@@ -311,14 +325,27 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
             float s[G];  // scores of this lane's token in log2 units
             if (valid) {
                 float u0[G], u1[G];
-                const uint2 hdr0 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
-                LanePacks8 lp0;
-                lp0.init(hdr0.x, hdr0.y, kbuf + HEADER8);
-                k8_half<G>(lds_all, table, lp0, kq, lane, u0);
-                const uint2 hdr1 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 512 + lane * 8);
-                LanePacks8 lp1;
-                lp1.init(hdr1.x, hdr1.y, lp0.end_all);
-                k8_half<G>(lds_all, table, lp1, kq, lane, u1);
+                if constexpr (KW) {
+                    const uint2 w0 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
+                    const uint2 m0 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 1024 + lane * 8);
+                    LanePacksW lp0;
+                    lp0.init(w0, m0, kbuf + HEADERW);
+                    kw_half<G>(lds_all, table, lp0, kq, lane, u0);
+                    const uint2 w1 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 512 + lane * 8);
+                    const uint2 m1 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 1536 + lane * 8);
+                    LanePacksW lp1;
+                    lp1.init(w1, m1, lp0.end_all);
+                    kw_half<G>(lds_all, table, lp1, kq, lane, u1);
+                } else {
+                    const uint2 hdr0 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
+                    LanePacks8 lp0;
+                    lp0.init(hdr0.x, hdr0.y, kbuf + HEADER8);
+                    k8_half<G>(lds_all, table, lp0, kq, lane, u0);
+                    const uint2 hdr1 = *reinterpret_cast<const uint2 *>(lds_all + kbuf + 512 + lane * 8);
+                    LanePacks8 lp1;
+                    lp1.init(hdr1.x, hdr1.y, lp0.end_all);
+                    k8_half<G>(lds_all, table, lp1, kq, lane, u1);
+                }
                 const float kscale = __half2float(__ushort_as_half(uint16_t(kmt & 0xFFFFu)));
                 const float kmn = __half2float(__ushort_as_half(uint16_t(kmt >> 16)));
 #pragma unroll
@@ -326,22 +353,37 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
                     s[g] = a.sm_log2 * fmaf(kscale, (lane & 1) ? u1[g] : u0[g], kmn * kq.qsum[g]);
                 attn_raise_reference<G>(s, m_ref, l_lane, st, col);
             }
-            wait_chunk_landed();  // V chunk of this block
-            if (it + 1 < n_it)
-                chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1),
-                                                     lds_all + kbuf, lane);
-            if (!valid) continue;
-            float pt[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                pt[g] = exp2f(s[g] - m_ref[g]);
-                l_lane[g] += pt[g];
+            if constexpr (SHARED) {
+                // one buffer: the K chunk has been read completely before the V chunk overwrites it
+                lds_reads_returned();
+                chunk_issue_lds<VMAX, VHDR>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             }
-            v8_chunk<G, true>(lds_all, vbuf, vtable, vl, vmt, pt, st);
+            wait_chunk_landed();  // V chunk of this block
+            if constexpr (!SHARED)
+                if (it + 1 < n_it)
+                    chunk_issue_lds<KMAX, KHDR>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
+            if (valid) {
+                float pt[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    pt[g] = exp2f(s[g] - m_ref[g]);
+                    l_lane[g] += pt[g];
+                }
+                if constexpr (VW)
+                    vw_chunk<G, true>(lds_all, vbuf, vtable, vl, vmt, pt, st);
+                else
+                    v8_chunk<G, true>(lds_all, vbuf, vtable, vl, vmt, pt, st);
+            }
+            if constexpr (SHARED) {
+                lds_reads_returned();
+                if (it + 1 < n_it)
+                    chunk_issue_lds<KMAX, KHDR>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
+            }
         }
         wait_chunk_landed();
     }
-    attn_store_partial<G>(a, st, l_lane, m_ref, red, wave, lane, split, head0);
+    // wide V codes enter the matrix cores as the numbers themselves
+    attn_store_partial<G>(a, st, l_lane, m_ref, red, wave, lane, split, head0, VW ? 1.0f : CODE_SCALE_LIFTED);
 }
 
 // Merges the splits of one (batch, query head) row in a fixed order and adds the raw fp16
@@ -438,13 +480,24 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
         if (c->cfg.pack_size == 8) {
-            switch (G) {
-                case 1: hipLaunchKernelGGL(attn8_kernel<1>, grid, dim3(256), 0, s, a); break;
-                case 2: hipLaunchKernelGGL(attn8_kernel<2>, grid, dim3(256), 0, s, a); break;
-                case 4: hipLaunchKernelGGL(attn8_kernel<4>, grid, dim3(256), 0, s, a); break;
-                case 8: hipLaunchKernelGGL(attn8_kernel<8>, grid, dim3(256), 0, s, a); break;
-                default: return KV_ERR_UNSUPPORTED;
+#define PACKKV_LAUNCH_ATTN8(KW, VW)                                                                  \
+    switch (G) {                                                                                     \
+        case 1: hipLaunchKernelGGL((attn8_kernel<1, KW, VW>), grid, dim3(256), 0, s, a); break;      \
+        case 2: hipLaunchKernelGGL((attn8_kernel<2, KW, VW>), grid, dim3(256), 0, s, a); break;      \
+        case 4: hipLaunchKernelGGL((attn8_kernel<4, KW, VW>), grid, dim3(256), 0, s, a); break;      \
+        case 8: hipLaunchKernelGGL((attn8_kernel<8, KW, VW>), grid, dim3(256), 0, s, a); break;      \
+        default: return KV_ERR_UNSUPPORTED;                                                          \
+    }
+            if (c->wide_k && c->wide_v) {
+                PACKKV_LAUNCH_ATTN8(true, true)
+            } else if (c->wide_k) {
+                PACKKV_LAUNCH_ATTN8(true, false)
+            } else if (c->wide_v) {
+                PACKKV_LAUNCH_ATTN8(false, true)
+            } else {
+                PACKKV_LAUNCH_ATTN8(false, false)
             }
+#undef PACKKV_LAUNCH_ATTN8
         } else {
             switch (G) {
                 case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), 0, s, a); break;

@@ -7,7 +7,7 @@
 //                  order of the 64 tokens of a block, metadata into storage order
 //   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
 //   scan_offsets   one workgroup: prefix sum of the new chunk sizes -> index
-//   place_chunks   (paged arena instead of scan_offsets) one wave: chunk positions inside
+//   place_chunks   (paged arena instead of scan_offsets) one workgroup: chunk positions inside
 //                  pages taken from a shared pool -> index of (start, end) pairs
 //   pack_chunks    one workgroup per chunk: quantize again and write header +
 //                  payload at its final place (no staging copy, no atomics, so

@@ -313,7 +313,7 @@ __device__ inline void kw_stream(const KArgs &a, int bh, int blk_begin, int blk_
             for (int g = 0; g < G; ++g)
                 a.scores[(head0 + g) * a.ld + tok] =
                     a.sm_scale * fmaf(scale, (lane & 1) ? u1[g] : u0[g], mn * kq.qsum[g]);
-            wave_lds_fence();  // every lane is done reading before the next transfer overwrites the buffer
+            lds_reads_returned();  // one buffer: read completely before the next transfer overwrites it
         }
     }
 }

@@ -366,9 +366,9 @@ __device__ inline void kw_half(const uint8_t *lds0, const uint2 *ktable, const L
     for (int g = 0; g < G; ++g) u[g] = row_reduce_scatter8(acc[g], lane) * CODE_SCALE;
 }
 
-// V, one wide chunk (both halves); lane l is token l of the block (three-step path).  vtable:
+// V, one wide chunk (both halves); the lane's token as in v8_chunk (K8_ORDER).  vtable:
 // build_wide_tables.  The A operand holds the codes as numbers: accumulators in units of 1.
-template <int G>
+template <int G, bool K8_ORDER = false>
 __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vtable, const VLane<G> &vl,
                                 uint32_t mt, const float (&pt)[G], VState<G> &st) {
     const int lane = threadIdx.x & 63;
@@ -386,9 +386,19 @@ __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vt
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g) * 16) = hi;
         *reinterpret_cast<_Float16 *>(vl.blds + vl.bslot + (2 * g + 1) * 16) = lo16;
         if (!fold_min<G>()) {
-            const float w8 = lanes8_all_reduce(w);
-            wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
-            wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+            if constexpr (K8_ORDER) {
+                // the eight tokens of group (half s, row) sit in the lanes of this row with i & 1 = s
+                float v = w + dpp_f32<DPP_ROW_ROR8>(w);
+                v += dpp_f32<DPP_ROW_ROR4>(v);
+                v += dpp_f32<DPP_QUAD_XOR2>(v);
+                const float other = dpp_f32<DPP_QUAD_XOR1>(v);
+                wsum[0][g] = (lane & 1) ? other : v;
+                wsum[1][g] = (lane & 1) ? v : other;
+            } else {
+                const float w8 = lanes8_all_reduce(w);
+                wsum[0][g] = __shfl(w8, 8 * (lane >> 4));
+                wsum[1][g] = __shfl(w8, 32 + 8 * (lane >> 4));
+            }
         }
     }
     wave_lds_fence();

@@ -228,6 +228,10 @@ __device__ inline void vmem_order_fence() { asm volatile("" ::: "memory"); }
 __device__ inline void consume_here(uint32_t &x) { asm volatile("" : "+v"(x)); }
 __device__ inline void consume_here(float &x) { asm volatile("" : "+v"(x)); }
 
+// Every LDS read this wave has issued has returned its data (needed before a transfer may
+// overwrite a buffer the wave has just decoded: the transfer does not queue behind LDS reads).
+__device__ inline void lds_reads_returned() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
 // LDS writes of this wave become visible to its own later LDS reads in program
 // order; the fences only stop the compiler from moving accesses across.
 __device__ inline void wave_lds_fence() {

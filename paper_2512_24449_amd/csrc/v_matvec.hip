@@ -212,6 +212,7 @@ __global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
         const int n_it = min(64, (blk_end - first + 3) / 4);
         for (int it = 0; it < n_it; ++it) {
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADERW / 16);
+            lds_reads_returned();  // one buffer: the previous chunk has been read completely
             chunk_issue_lds<CHUNKW_MAX, HEADERW>(a.arena, ib.start16(it), ib.end16(it), lds_all + buf, lane);
             const int64_t tok = int64_t(first + 4 * it) * N + lane;
             const uint32_t mt = a.meta[b * a.meta_stride + tok];

@@ -156,9 +156,7 @@ def check_paged_state(cache, n_packed, ck, cv, B, H):
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
              max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2, pool=None):
     """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
-    With a relative scale below 1/15 (wide chunks) the fused attention entry point must refuse.
     pool: a binding.PagePool -> the cache is paged."""
-    wide = round(1 / k_rel) > 15 or round(1 / v_rel) > 15
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
@@ -206,22 +204,14 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     torch.cuda.synchronize()
     assert torch.equal(scores, scores2) and torch.equal(out, out2)
 
-    if wide:
-        try:
-            cache.kv_decode_attention(qd, sm_scale)
-            raise AssertionError("fused attention must refuse wide chunks")
-        except binding.PackKVError as e:
-            assert e.code == binding.KV_ERR_UNSUPPORTED
-        attn = None
-    else:
-        # fused decode attention against the oracle's definition of Att(q, K, V)
-        attn = cache.kv_decode_attention(qd, sm_scale)
-        torch.cuda.synchronize()
-        a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
-        assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
-        attn2 = cache.kv_decode_attention(qd, sm_scale)
-        torch.cuda.synchronize()
-        assert torch.equal(attn, attn2)
+    # fused decode attention against the oracle's definition of Att(q, K, V)
+    attn = cache.kv_decode_attention(qd, sm_scale)
+    torch.cuda.synchronize()
+    a_ref = oracle.attention(kcodes, Kn, kmeta, vcodes, Vn, vmeta, n_packed, qn, sm_scale)
+    assert_close_vectors(attn.cpu().numpy(), a_ref, "fused decode attention")
+    attn2 = cache.kv_decode_attention(qd, sm_scale)
+    torch.cuda.synchronize()
+    assert torch.equal(attn, attn2)
     cache.close()
     return dict(k_bytes=ck.arena.size if ck else 0, v_bytes=cv.arena.size if cv else 0,
                 scores=scores.cpu(), out=out.cpu(), attn=None if attn is None else attn.cpu())

@@ -96,15 +96,16 @@ def test_wide_chunks_long_context(B, H, Hq, L, k_rel, v_rel):
     scores = cache.kv_k_matvec(q.cuda(), sm_scale)
     p = synth.make_probs(scores)
     out = cache.kv_v_matvec(p)
+    attn = cache.kv_decode_attention(q.cuda(), sm_scale)
     torch.cuda.synchronize()
     assert cache.kv_cache_stats().overflow == 0
     for b in range(B):
-        _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, k_rel, v_rel)
+        _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, L // 64 * 64, k_rel, v_rel, attn)
     cache.close()
 
 
-def _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, k_rel, v_rel):
-    _check_batch_element(cache, K.cuda(), V.cuda(), q.cuda(), scores, p, out, b, sm_scale, n_packed, None, 8,
+def _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, n_packed, k_rel, v_rel, attn):
+    _check_batch_element(cache, K.cuda(), V.cuda(), q.cuda(), scores, p, out, b, sm_scale, n_packed, attn, 8,
                          k_rel, v_rel)
 
 

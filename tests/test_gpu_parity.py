@@ -53,7 +53,7 @@ def test_packs_of_8_tokens_match_oracle(B, H, Hq, L, seed, pieces):
 ])
 def test_wide_chunks_match_oracle(B, H, Hq, L, seed, pieces, k_rel, v_rel):
     """Relative scales below 1/15: codes above 15, wide chunk layout (packs of 8 tokens): packed
-    bytes bit-exact, K, V and the three-step path within the bar."""
+    bytes bit-exact, K, V, the three-step path and the fused attention within the bar."""
     gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8, k_rel=k_rel, v_rel=v_rel)
 
 
