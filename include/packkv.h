@@ -76,7 +76,7 @@ typedef struct kv_page_pool kv_page_pool_t; /* the same: pages shared by paged c
  * and packs of `width` bytes.  A relative scale below 1/15 gives codes above 15
  * ("wide" chunks for that tensor: packs of 8 tokens with widths up to 8 bits,
  * 1024 width bytes followed by 1024 minimum bytes, then the packs); it needs
- * pack_size 8 and KV_REPACK_NONE, and its lower bound is 1/255.
+ * pack_size 8, and its lower bound is 1/255.
  * KV_REPACK_V_MEDIAN
  * (Sec. III-B.3, "Faster Repacking with V Median"): inside every block of 64
  * tokens, K and V are packed with their tokens sorted by the lower median of the

@@ -26,12 +26,12 @@ int check_config(const kv_config_t *c) {
     const int g = c->n_q_heads / c->n_kv_heads;
     if (g != 1 && g != 2 && g != 4 && g != 8) return KV_ERR_UNSUPPORTED;
     // one pack byte holds a 4-bit minimum: codes above 15 need the wide layout, which exists
-    // for packs of 8 tokens without repacking only; a code is one byte at most
+    // for packs of 8 tokens only; a code is one byte at most
     for (float rel : {c->k_rel_scale, c->v_rel_scale}) {
         if (!(rel > 0.0f) || rel > 1.0f) return KV_ERR_ARG;
         const long qmax = lround(1.0 / double(rel));
         if (qmax > 255) return KV_ERR_UNSUPPORTED;
-        if (qmax > 15 && (c->pack_size != 8 || c->repack != KV_REPACK_NONE)) return KV_ERR_UNSUPPORTED;
+        if (qmax > 15 && c->pack_size != 8) return KV_ERR_UNSUPPORTED;
     }
     if (int64_t(c->batch) * c->n_kv_heads > 65535) return KV_ERR_UNSUPPORTED;
     const int64_t max_tokens = (c->max_tokens + N - 1) / N * N;

@@ -458,29 +458,39 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
                                                            const uint32_t *__restrict__ meta,
                                                            int64_t meta_stride, int64_t first_token,
                                                            uint8_t *__restrict__ keys) {
-    __shared__ int hist[16];
+    __shared__ int hist[256];
     const int t = blockIdx.x, b = blockIdx.y;
-    if (threadIdx.x < 16) hist[threadIdx.x] = 0;
+    hist[threadIdx.x] = 0;
     __syncthreads();
     const __half *row = src + b * batch_stride + t * token_stride;
     const uint32_t mt = meta[b * meta_stride + first_token + t];
-    // sixteen 8-bit counters in two words; a thread sees at most 8 * ceil(row_elems / 2048) values
-    uint64_t lo = 0, hi = 0;
-    for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
-        uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
-        const __half *hv = reinterpret_cast<const __half *>(&raw);
+    if (qmax > 15) {
+        // codes up to 255: count straight into the LDS histogram
+        for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+            const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
-        for (int k = 0; k < 8; ++k) {
-            const int v = quantize_value(__half2float(hv[k]), mt, qmax);
-            const uint64_t one = 1ull << (8 * (v & 7));
-            if (v < 8) lo += one; else hi += one;
+            for (int k = 0; k < 8; ++k) atomicAdd(&hist[quantize_value(__half2float(hv[k]), mt, qmax)], 1);
         }
-    }
-    for (int bin = 0; bin <= qmax; ++bin) {
-        int c = int(((bin < 8 ? lo : hi) >> (8 * (bin & 7))) & 0xFFu);
+    } else {
+        // sixteen 8-bit counters in two words; a thread sees at most 8 * ceil(row_elems / 2048) values
+        uint64_t lo = 0, hi = 0;
+        for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
+            uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+            const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
-        for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
-        if ((threadIdx.x & 63) == 0) atomicAdd(&hist[bin], c);
+            for (int k = 0; k < 8; ++k) {
+                const int v = quantize_value(__half2float(hv[k]), mt, qmax);
+                const uint64_t one = 1ull << (8 * (v & 7));
+                if (v < 8) lo += one; else hi += one;
+            }
+        }
+        for (int bin = 0; bin <= qmax; ++bin) {
+            int c = int(((bin < 8 ? lo : hi) >> (8 * (bin & 7))) & 0xFFu);
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) c += __shfl_xor(c, o);
+            if ((threadIdx.x & 63) == 0) atomicAdd(&hist[bin], c);
+        }
     }
     __syncthreads();
     if (threadIdx.x == 0) {

@@ -193,12 +193,14 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_re
     assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
 
 
-@pytest.mark.parametrize("B,H,Hq,L,pieces,pack_size", [
-    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 16),   # blocks from bulk appends and from tail flushes
-    (1, 52, 52, 128, None, 16),                        # wide token vectors (6656 values per median)
-    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8),    # the same with packs of 8 tokens
+@pytest.mark.parametrize("B,H,Hq,L,pieces,pack_size,k_rel,v_rel", [
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 16, 0.1, 0.2),   # blocks from bulk appends and from tail flushes
+    (1, 52, 52, 128, None, 16, 0.1, 0.2),                        # wide token vectors (6656 values per median)
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8, 0.1, 0.2),    # the same with packs of 8 tokens
+    (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8, 0.1, 1 / 40), # medians of codes up to 40 (wide V chunks)
+    (1, 52, 52, 128, None, 8, 1 / 255, 1 / 255),                 # both tensors wide, codes up to 255
 ])
-def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size):
+def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel, v_rel):
     """KV_REPACK_V_MEDIAN: order, packed bytes and token metadata bit-exact against the oracle's
     order applied before its compressor; scores in storage order; attention unchanged."""
     rng = np.random.default_rng(70 + B)
@@ -208,18 +210,19 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size):
     V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(72)) ** lean).to(torch.float16)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     n_packed = L // 64 * 64
-    cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN, pack_size=pack_size)
+    cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN, pack_size=pack_size,
+                                  k_rel_scale=k_rel, v_rel_scale=v_rel)
     pos = 0
     for n in (pieces or [L]):
         cache.kv_compress_append(K[:, pos:pos + n].contiguous().cuda(), V[:, pos:pos + n].contiguous().cuda())
         pos += n
-    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), 0.2, pack_size)
+    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), v_rel, pack_size)
     order = oracle.v_median_order(cv0.codes)
     assert len(np.unique(order[:, :64])) == 64 and not np.array_equal(order[0, :64], np.arange(64))
     Kp = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_packed:]], axis=1)
     Vp = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_packed:]], axis=1)
-    ck = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), 0.1, pack_size)
-    cv = oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), 0.2, pack_size)
+    ck = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), k_rel, pack_size)
+    cv = oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), v_rel, pack_size)
     gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
     max_tokens = cache.tensors["token_order"].numel() // B
     got_order = cache.tensors["token_order"].view(B, max_tokens)[:, :n_packed].cpu().numpy()
@@ -237,7 +240,7 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size):
     a_perm = oracle.attention(kc, Kp, km, vc, Vp, vm, n_packed, qn, sm)
     assert_close_vectors(attn.cpu().numpy(), a_perm, "attention over the repacked cache")
     # and the repacked cache answers like the cache in arrival order (Att(q, PK, PV) = Att(q, K, V))
-    _, ck0, cv0b = gpu_cases.oracle_cache(Kn, Vn, pack_size=pack_size)
+    _, ck0, cv0b = gpu_cases.oracle_cache(Kn, Vn, k_rel, v_rel, pack_size)
     kc0, km0 = gpu_cases.full_codes(ck0, Kn.shape, n_packed)
     vc0, vm0 = gpu_cases.full_codes(cv0b, Vn.shape, n_packed)
     a_orig = oracle.attention(kc0, Kn, km0, vc0, Vn, vm0, n_packed, qn, sm)

@@ -42,8 +42,8 @@ def test_query_sizes_and_config_checks():
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
     bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05)   # codes above 15 need packs of 8
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
-    bad = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8, repack=binding.REPACK_V_MEDIAN)
-    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
+    ok = binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8, repack=binding.REPACK_V_MEDIAN)
+    assert L.kv_query_sizes(C.byref(ok), 0.0, C.byref(out)) == 0 and out.token_order >= 4096
     bad = binding.make_config(1, 32, 32, 4096, v_rel_scale=1 / 300, pack_size=8)   # a code is one byte
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
     wide = binding.kv_query_sizes(binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8))
