@@ -193,6 +193,7 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_re
     assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
 
 
+@pytest.mark.parametrize("paged", [False, True])
 @pytest.mark.parametrize("B,H,Hq,L,pieces,pack_size,k_rel,v_rel", [
     (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 16, 0.1, 0.2),   # blocks from bulk appends and from tail flushes
     (1, 52, 52, 128, None, 16, 0.1, 0.2),                        # wide token vectors (6656 values per median)
@@ -200,7 +201,7 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_re
     (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8, 0.1, 1 / 40), # medians of codes up to 40 (wide V chunks)
     (1, 52, 52, 128, None, 8, 1 / 255, 1 / 255),                 # both tensors wide, codes up to 255
 ])
-def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel, v_rel):
+def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel, v_rel, paged):
     """KV_REPACK_V_MEDIAN: order, packed bytes and token metadata bit-exact against the oracle's
     order applied before its compressor; scores in storage order; attention unchanged."""
     rng = np.random.default_rng(70 + B)
@@ -210,8 +211,9 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(72)) ** lean).to(torch.float16)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     n_packed = L // 64 * 64
+    pool = binding.PagePool(40) if paged else None   # the same through a paged arena
     cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN, pack_size=pack_size,
-                                  k_rel_scale=k_rel, v_rel_scale=v_rel)
+                                  k_rel_scale=k_rel, v_rel_scale=v_rel, pool=pool)
     pos = 0
     for n in (pieces or [L]):
         cache.kv_compress_append(K[:, pos:pos + n].contiguous().cuda(), V[:, pos:pos + n].contiguous().cuda())
@@ -223,7 +225,7 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     Vp = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_packed:]], axis=1)
     ck = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), k_rel, pack_size)
     cv = oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), v_rel, pack_size)
-    gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
+    (gpu_cases.check_paged_state if paged else gpu_cases.check_packed_state)(cache, n_packed, ck, cv, B, H)
     max_tokens = cache.tensors["token_order"].numel() // B
     got_order = cache.tensors["token_order"].view(B, max_tokens)[:, :n_packed].cpu().numpy()
     assert np.array_equal(got_order, order)
@@ -246,6 +248,9 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     a_orig = oracle.attention(kc0, Kn, km0, vc0, Vn, vm0, n_packed, qn, sm)
     assert_close_vectors(attn.cpu().numpy(), a_orig, "attention, arrival order")
     cache.close()
+    if paged:
+        assert pool.kv_page_pool_free_pages() == 40
+        pool.close()
 
 
 @pytest.mark.parametrize("B,Hq,tokens,ld", [
