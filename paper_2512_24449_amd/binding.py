@@ -216,7 +216,10 @@ class PackedKVCache:
 
     def close(self):
         if getattr(self, "handle", None) and _lib is not None:
-            _lib.kv_cache_destroy(self.handle)
+            # a paged cache returns its pages to the pool here: the pool must still exist
+            # (if it was closed first, the handle is dropped without the call)
+            if getattr(self, "pool", None) is None or self.pool.handle:
+                _lib.kv_cache_destroy(self.handle)
         self.handle = None
 
     def __del__(self):
