@@ -397,6 +397,8 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
                                                            float sm_log2, float *__restrict__ out) {
     __shared__ float st[N];             // tail scores (log2 units), then tail weights
     __shared__ float ms[V_SPLITS_MAX];  // split references, then split factors
+    __shared__ float red[16][V_PART_STRIDE];
+    static_assert(A_L == 128, "the splits' weight sums sit in the column the reduction returns separately");
     const int r = blockIdx.x;           // b*Hq + hq
     const int hq = r % (H * G), b = r / (H * G);
     const int h = hq / G;
@@ -431,23 +433,15 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     if (int(threadIdx.x) < n_splits) ms[threadIdx.x] = exp2_diff(ms[threadIdx.x], M);
     if (threadIdx.x >= 64 && int(threadIdx.x) - 64 < n_tail) st[threadIdx.x - 64] = exp2f(st[threadIdx.x - 64] - M);
     __syncthreads();
+    // weighted sum of the split rows (column 128 = the splits' weight sums), then the tail tokens
+    float l;
+    float o = reduce_split_partials(partial, n_splits, n_rows, r, red, &l, ms);
+    if (n_tail > 0) {
+        o += tail_weighted_sum(v_tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D, st, n_tail, red);
+        for (int t = 0; t < n_tail; ++t) l += st[t];
+    }
     const int d = threadIdx.x;
-    if (d >= D) return;
-    float o = 0.0f, l = 0.0f;
-#pragma unroll 8
-    for (int s = 0; s < n_splits; ++s) {
-        const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
-        o = fmaf(ms[s], src[d], o);
-        l = fmaf(ms[s], src[A_L], l);
-    }
-    const __half *vrow = v_tail + (int64_t(b) * tail_cap * H + h) * D + d;
-#pragma unroll 8
-    for (int t = 0; t < n_tail; ++t) {
-        const float v = __half2float(vrow[int64_t(t) * H * D]);
-        o = fmaf(st[t], v, o);
-        l += st[t];
-    }
-    out[int64_t(r) * D + d] = l > 0.0f ? o / l : 0.0f;  // every block dropped and no tail: defined output
+    if (d < D) out[int64_t(r) * D + d] = l > 0.0f ? o / l : 0.0f;  // every block dropped and no tail: defined output
 }
 
 int v_splits_for(int n_blocks, int streams);

@@ -243,22 +243,19 @@ __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__
                                                        const __half *__restrict__ tail, int n_tail,
                                                        int tail_cap, int H, int G,
                                                        float *__restrict__ out) {
-    __shared__ float lds[8][V_PART_STRIDE];
+    __shared__ float lds[16][V_PART_STRIDE];
     const int r = blockIdx.x;  // b*Hq + hq
     const int d = threadIdx.x;
     float pmin;
     float acc = reduce_split_partials(partial, n_splits, n_rows, r, lds, &pmin);
-    if (d >= D) return;
     acc += pmin;
     if (n_tail > 0) {
         const int hq = r % (H * G), b = r / (H * G);
         const int h = hq / G;
-        const float *prow = p + int64_t(r) * ld + packed_tokens;
-        const __half *vrow = tail + (int64_t(b) * tail_cap * H + h) * D + d;
-#pragma unroll 8
-        for (int t = 0; t < n_tail; ++t) acc = fmaf(prow[t], __half2float(vrow[int64_t(t) * H * D]), acc);
+        acc += tail_weighted_sum(tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D,
+                                 p + int64_t(r) * ld + packed_tokens, n_tail, lds);
     }
-    out[int64_t(r) * D + d] = acc;
+    if (d < D) out[int64_t(r) * D + d] = acc;
 }
 
 int v_splits_for(int n_blocks, int streams) {
