@@ -402,6 +402,13 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     const int r = blockIdx.x;           // b*Hq + hq
     const int hq = r % (H * G), b = r / (H * G);
     const int h = hq / G;
+    // every global load of the kernel is issued before the first result is needed
+    SplitRows rows;
+    TailRows trows;
+    rows.load(partial, n_splits, n_rows, r);
+    trows.load(v_tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D, n_tail);
+    if (int(threadIdx.x) < n_splits)
+        ms[threadIdx.x] = partial[(int64_t(threadIdx.x) * n_rows + r) * V_PART_STRIDE + A_M];
     // tail scores: thread (t, seg) takes 32 channels of tail token t, four threads per token
     {
         const int t = threadIdx.x >> 2, seg = threadIdx.x & 3;
@@ -423,8 +430,6 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         s += dpp_f32<DPP_QUAD_XOR2>(s);
         if (seg == 0 && t < n_tail) st[t] = sm_log2 * s;
     }
-    if (int(threadIdx.x) < n_splits)
-        ms[threadIdx.x] = partial[(int64_t(threadIdx.x) * n_rows + r) * V_PART_STRIDE + A_M];
     __syncthreads();
     float M = -INFINITY;
     for (int s = 0; s < n_splits; ++s) M = fmaxf(M, ms[s]);
@@ -435,9 +440,9 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     __syncthreads();
     // weighted sum of the split rows (column 128 = the splits' weight sums), then the tail tokens
     float l;
-    float o = reduce_split_partials(partial, n_splits, n_rows, r, red, &l, ms);
+    float o = rows.sum(n_splits, red, &l, ms);
     if (n_tail > 0) {
-        o += tail_weighted_sum(v_tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D, st, n_tail, red);
+        o += trows.sum(st, n_tail, red);
         for (int t = 0; t < n_tail; ++t) l += st[t];
     }
     const int d = threadIdx.x;

@@ -59,80 +59,114 @@ inline size_t v_partial_bytes(int batch, int n_q_heads) {
     return size_t(V_SPLITS_MAX) * batch * n_q_heads * V_PART_STRIDE * sizeof(float);
 }
 
-// Sum of the per-split partial rows partial[(s * n_rows + r) * V_PART_STRIDE + 0..128] over
-// s < n_splits, in a fixed order, by a workgroup of 256 threads: eight thread groups take every
-// eighth split with independent 16-byte loads, then the eight sums are added pairwise.  With
-// `weight` (n_splits floats, LDS or global) row s counts weight[s] times.
-// Returns column d = threadIdx.x (threads < 128; others return 0) and the sum of column 128.
-// All 256 threads must call; lds is free again when the call returns.
-__device__ inline float reduce_split_partials(const float *__restrict__ partial, int n_splits,
-                                              int n_rows, int r, float (*lds)[V_PART_STRIDE],
-                                              float *col128, const float *weight = nullptr) {
-    const int sg = threadIdx.x >> 5, q4 = threadIdx.x & 31;
-    float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    float last = 0.0f;
-#pragma unroll 4
-    for (int s = sg; s < n_splits; s += 8) {
-        const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
-        const float4 v = *reinterpret_cast<const float4 *>(src + 4 * q4);
-        if (weight) {
-            const float w = weight[s];
-            acc.x = fmaf(w, v.x, acc.x), acc.y = fmaf(w, v.y, acc.y);
-            acc.z = fmaf(w, v.z, acc.z), acc.w = fmaf(w, v.w, acc.w);
-            if (q4 == 0) last = fmaf(w, src[128], last);
-        } else {
-            acc.x += v.x, acc.y += v.y, acc.z += v.z, acc.w += v.w;
-            if (q4 == 0) last += src[128];
+// The two small reductions that end a split-L pass, for a workgroup of 256 threads.  Each is cut
+// into a load step and a sum step so that a kernel can issue ALL its global loads first and pay
+// one memory latency instead of one per phase (these kernels run for a few microseconds).
+//
+// Split rows: partial[(s * n_rows + r) * V_PART_STRIDE + 0..128] for s < n_splits <= 64.  Eight
+// thread groups take every eighth split with 16-byte loads; the sum step adds row s weight[s]
+// times (weight null: once), the eight group sums pairwise, all in a fixed order.
+struct SplitRows {
+    float4 v[V_SPLITS_MAX / 8];
+    float last[V_SPLITS_MAX / 8];  // column 128, thread group leaders only
+
+    __device__ inline void load(const float *__restrict__ partial, int n_splits, int n_rows, int r) {
+        const int sg = threadIdx.x >> 5, q4 = threadIdx.x & 31;
+#pragma unroll
+        for (int i = 0; i < V_SPLITS_MAX / 8; ++i) {
+            const int s = sg + 8 * i;
+            v[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+            last[i] = 0.0f;
+            if (s < n_splits) {
+                const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
+                v[i] = *reinterpret_cast<const float4 *>(src + 4 * q4);
+                if (q4 == 0) last[i] = src[128];
+            }
         }
     }
-    *reinterpret_cast<float4 *>(&lds[sg][4 * q4]) = acc;
-    if (q4 == 0) lds[sg][128] = last;
-    __syncthreads();
-    const int d = threadIdx.x < 128 ? threadIdx.x : 128;
-    const float v = ((lds[0][d] + lds[1][d]) + (lds[2][d] + lds[3][d])) +
-                    ((lds[4][d] + lds[5][d]) + (lds[6][d] + lds[7][d]));
-    *col128 = ((lds[0][128] + lds[1][128]) + (lds[2][128] + lds[3][128])) +
-              ((lds[4][128] + lds[5][128]) + (lds[6][128] + lds[7][128]));
-    __syncthreads();
-    return threadIdx.x < 128 ? v : 0.0f;
+    // Returns column d = threadIdx.x (threads < 128; others 0) and the sum of column 128.  All
+    // 256 threads must call; lds is free again when the call returns.
+    __device__ inline float sum(int n_splits, float (*lds)[V_PART_STRIDE], float *col128,
+                                const float *weight = nullptr) const {
+        const int sg = threadIdx.x >> 5, q4 = threadIdx.x & 31;
+        float4 acc = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+        float l = 0.0f;
+#pragma unroll
+        for (int i = 0; i < V_SPLITS_MAX / 8; ++i) {
+            const int s = sg + 8 * i;
+            if (s < n_splits) {
+                const float w = weight ? weight[s] : 1.0f;
+                acc.x = fmaf(w, v[i].x, acc.x), acc.y = fmaf(w, v[i].y, acc.y);
+                acc.z = fmaf(w, v[i].z, acc.z), acc.w = fmaf(w, v[i].w, acc.w);
+                l = fmaf(w, last[i], l);
+            }
+        }
+        *reinterpret_cast<float4 *>(&lds[sg][4 * q4]) = acc;
+        if (q4 == 0) lds[sg][128] = l;
+        __syncthreads();
+        const int d = threadIdx.x < 128 ? threadIdx.x : 128;
+        const float out = ((lds[0][d] + lds[1][d]) + (lds[2][d] + lds[3][d])) +
+                          ((lds[4][d] + lds[5][d]) + (lds[6][d] + lds[7][d]));
+        *col128 = ((lds[0][128] + lds[1][128]) + (lds[2][128] + lds[3][128])) +
+                  ((lds[4][128] + lds[5][128]) + (lds[6][128] + lds[7][128]));
+        __syncthreads();
+        return threadIdx.x < 128 ? out : 0.0f;
+    }
+};
+
+inline __device__ float reduce_split_partials(const float *__restrict__ partial, int n_splits, int n_rows,
+                                              int r, float (*lds)[V_PART_STRIDE], float *col128) {
+    SplitRows rows;
+    rows.load(partial, n_splits, n_rows, r);
+    return rows.sum(n_splits, lds, col128);
 }
 
-// sum_t weight[t] * V[t][d] over the n_tail <= 64 raw fp16 tail tokens of one (batch, kv-head),
-// d = threadIdx.x (threads < 128; others return 0), by a workgroup of 256 threads: thread
-// (token lane x / 16, channel group x % 16) takes tokens lane, lane + 16, .. with independent
-// 16-byte loads -- one memory latency instead of one per few tokens -- and the sixteen token
-// lanes are added in a fixed order.  vrow: the head's 128 values of tail token 0; token_stride in
-// elements; weight: n_tail floats (LDS or global).  All 256 threads must call; lds is free again
-// when the call returns.
-__device__ inline float tail_weighted_sum(const __half *__restrict__ vrow, int64_t token_stride,
-                                          const float *weight, int n_tail, float (*lds)[V_PART_STRIDE]) {
-    const int cg = threadIdx.x & 15, tl = threadIdx.x >> 4;
-    float acc[8];
+// Raw tail: sum_t weight[t] * V[t][d] over the n_tail <= 64 raw fp16 tail tokens of one (batch,
+// kv-head).  Thread (token lane x / 16, channel group x % 16) takes tokens lane, lane + 16, ..
+// with 16-byte loads; the sixteen token lanes are added in a fixed order.  vrow: the head's 128
+// values of tail token 0; token_stride in elements.
+struct TailRows {
+    uint4 raw[4];
+
+    __device__ inline void load(const __half *__restrict__ vrow, int64_t token_stride, int n_tail) {
+        const int cg = threadIdx.x & 15, tl = threadIdx.x >> 4;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int t = tl + 16 * i;
-        if (t < n_tail) {
-            const uint4 raw = *reinterpret_cast<const uint4 *>(vrow + t * token_stride + 8 * cg);
-            const __half *hv = reinterpret_cast<const __half *>(&raw);
-            const float w = weight[t];
-#pragma unroll
-            for (int k = 0; k < 8; ++k) acc[k] = fmaf(w, __half2float(hv[k]), acc[k]);
+        for (int i = 0; i < 4; ++i) {
+            const int t = tl + 16 * i;
+            raw[i] = make_uint4(0, 0, 0, 0);
+            if (t < n_tail) raw[i] = *reinterpret_cast<const uint4 *>(vrow + t * token_stride + 8 * cg);
         }
     }
-    *reinterpret_cast<float4 *>(&lds[tl][8 * cg]) = make_float4(acc[0], acc[1], acc[2], acc[3]);
-    *reinterpret_cast<float4 *>(&lds[tl][8 * cg + 4]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
-    __syncthreads();
-    float v = 0.0f;
-    if (threadIdx.x < 128) {
-        const int d = threadIdx.x;
-        v = (((lds[0][d] + lds[1][d]) + (lds[2][d] + lds[3][d])) + ((lds[4][d] + lds[5][d]) + (lds[6][d] + lds[7][d]))) +
-            (((lds[8][d] + lds[9][d]) + (lds[10][d] + lds[11][d])) + ((lds[12][d] + lds[13][d]) + (lds[14][d] + lds[15][d])));
+    // weight: n_tail floats (LDS or global).  Returns column d = threadIdx.x (threads < 128;
+    // others 0).  All 256 threads must call; lds is free again when the call returns.
+    __device__ inline float sum(const float *weight, int n_tail, float (*lds)[V_PART_STRIDE]) const {
+        const int cg = threadIdx.x & 15, tl = threadIdx.x >> 4;
+        float acc[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) acc[k] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = tl + 16 * i;
+            if (t < n_tail) {
+                const __half *hv = reinterpret_cast<const __half *>(&raw[i]);
+                const float w = weight[t];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) acc[k] = fmaf(w, __half2float(hv[k]), acc[k]);
+            }
+        }
+        *reinterpret_cast<float4 *>(&lds[tl][8 * cg]) = make_float4(acc[0], acc[1], acc[2], acc[3]);
+        *reinterpret_cast<float4 *>(&lds[tl][8 * cg + 4]) = make_float4(acc[4], acc[5], acc[6], acc[7]);
+        __syncthreads();
+        float v = 0.0f;
+        if (threadIdx.x < 128) {
+            const int d = threadIdx.x;
+            v = (((lds[0][d] + lds[1][d]) + (lds[2][d] + lds[3][d])) + ((lds[4][d] + lds[5][d]) + (lds[6][d] + lds[7][d]))) +
+                (((lds[8][d] + lds[9][d]) + (lds[10][d] + lds[11][d])) + ((lds[12][d] + lds[13][d]) + (lds[14][d] + lds[15][d])));
+        }
+        __syncthreads();
+        return v;
     }
-    __syncthreads();
-    return v;
-}
+};
 
 }  // namespace packkv
 

@@ -244,17 +244,21 @@ __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__
                                                        int tail_cap, int H, int G,
                                                        float *__restrict__ out) {
     __shared__ float lds[16][V_PART_STRIDE];
+    __shared__ float wt[N];
     const int r = blockIdx.x;  // b*Hq + hq
     const int d = threadIdx.x;
+    const int hq = r % (H * G), b = r / (H * G);
+    const int h = hq / G;
+    // every global load of the kernel is issued before the first result is needed
+    SplitRows rows;
+    TailRows trows;
+    rows.load(partial, n_splits, n_rows, r);
+    trows.load(tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D, n_tail);
+    if (d < n_tail) wt[d] = p[int64_t(r) * ld + packed_tokens + d];
     float pmin;
-    float acc = reduce_split_partials(partial, n_splits, n_rows, r, lds, &pmin);
+    float acc = rows.sum(n_splits, lds, &pmin);  // its barriers also publish wt
     acc += pmin;
-    if (n_tail > 0) {
-        const int hq = r % (H * G), b = r / (H * G);
-        const int h = hq / G;
-        acc += tail_weighted_sum(tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D,
-                                 p + int64_t(r) * ld + packed_tokens, n_tail, lds);
-    }
+    if (n_tail > 0) acc += trows.sum(wt, n_tail, lds);
     if (d < D) out[int64_t(r) * D + d] = acc;
 }
 
