@@ -324,15 +324,19 @@ __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
     const int h = bh % a.H, b = bh / a.H;
     if (lane >= a.n_tail) return;
     const __half *row = a.tail + ((int64_t(b) * a.tail_cap + lane) * a.H + h) * D;
+    // the whole row first: sixteen independent 16-byte loads, one memory latency
+    uint4 kr[D / 8];
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) kr[i] = *reinterpret_cast<const uint4 *>(row + 8 * i);
     float acc[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) acc[g] = 0.0f;
-    for (int d0 = 0; d0 < D; d0 += 8) {
-        uint4 raw = *reinterpret_cast<const uint4 *>(row + d0);
-        const __half *kv = reinterpret_cast<const __half *>(&raw);
+#pragma unroll
+    for (int i = 0; i < D / 8; ++i) {
+        const __half *kv = reinterpret_cast<const __half *>(&kr[i]);
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            uint4 qraw = *reinterpret_cast<const uint4 *>(a.q + (int64_t(b) * a.H * G + h * G + g) * D + d0);
+            uint4 qraw = *reinterpret_cast<const uint4 *>(a.q + (int64_t(b) * a.H * G + h * G + g) * D + 8 * i);
             const __half *qv = reinterpret_cast<const __half *>(&qraw);
 #pragma unroll
             for (int k = 0; k < 8; ++k) acc[g] = fmaf(__half2float(qv[k]), __half2float(kv[k]), acc[g]);
