@@ -233,3 +233,40 @@ def test_bulk_append_placement_equals_the_rule():
     assert pool.kv_page_pool_free_pages() == len(model.free)
     cache.close()
     pool.close()
+
+
+def test_smallest_chunks_fill_pages_exactly():
+    """Constant tensors give header-only chunks of 512 bytes: 128 of them fill a page to the last
+    byte, the most chunks a page can hold (the placement kernel's per-page chunk count is at its
+    limit) and a fill level that reaches the page size exactly."""
+    B, H, Hq, L = 1, 2, 2, 64 * 200
+    pool = binding.PagePool(12)
+    model = gpu_cases.PagePlacementModel(12)
+    cache = binding.PackedKVCache(B, H, Hq, L, pool=pool)
+    K = torch.full((B, L, H, 128), 0.5, dtype=torch.float16)
+    V = torch.zeros((B, L, H, 128), dtype=torch.float16)
+    tensors = (model.new_tensor(), model.new_tensor())
+    expected = ([], [])
+    lo = 0
+    for n in (64 * 70, 64 * 58, 64 * 72):   # 140, 116 and 144 chunks per tensor: page boundaries inside and at call ends
+        cache.kv_compress_append(K[:, lo:lo + n].contiguous().cuda(), V[:, lo:lo + n].contiguous().cuda())
+        for t in range(2):
+            placed = model.place(tensors[t], [32] * (n // 64 * B * H))
+            assert placed is not None
+            expected[t].extend(placed)
+        lo += n
+    torch.cuda.synchronize()
+    n_chunks = L // 64 * B * H
+    for t, name in enumerate(("k", "v")):
+        assert _chunk_pairs(cache, name, n_chunks) == expected[t], name
+        pages, fill = _page_list(cache, name)
+        assert pages == tensors[t]["pages"] and fill == tensors[t]["fill"]
+    assert 128 in [len([1 for s, e in expected[0] if s // PAGE16 == p]) for p in tensors[0]["pages"]]
+    n_packed, ck, cv = gpu_cases.oracle_cache(K.numpy(), V.numpy())
+    gpu_cases.check_paged_state(cache, n_packed, ck, cv, B, H)
+    q = torch.ones((B, Hq, 128), dtype=torch.float16)
+    attn = cache.kv_decode_attention(q.cuda(), 0.1)
+    torch.cuda.synchronize()
+    assert_close_vectors(attn.cpu().numpy(), np.zeros((B, Hq, 128)) + V.numpy()[0, 0, 0, 0], "attention over constant V")
+    cache.close()
+    pool.close()
