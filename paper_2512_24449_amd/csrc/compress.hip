@@ -73,10 +73,8 @@ struct PackBits {
     int w, m;
 };
 
-// Token-wise quantization of one value (Sec. III-B.2) with the stored fp16 scale and minimum.
-__device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
-    const float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+// Token-wise quantization of one value (Sec. III-B.2) with the token's scale and minimum.
+__device__ inline int quantize_value(float x, float s, float mn, int qmax) {
     int v = 0;
     if (s != 0.0f) {
         float ratio = (x - mn) / s;  // IEEE fp32 divide
@@ -86,17 +84,22 @@ __device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
     }
     return v;
 }
+// The same from the stored token metadata word (fp16 scale | fp16 minimum << 16).
+__device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
+    return quantize_value(x, __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu))),
+                          __half2float(__ushort_as_half(uint16_t(mt >> 16))), qmax);
+}
 
 // tile: the block's 64 x 128 values in LDS, rows already in storage order; the pack holds rows
-// PK*g..PK*g+PK-1 of channel d; meta_g: their token metadata (storage order).
+// PK*g..PK*g+PK-1 of channel d; sm: (scale, minimum) of the block's 64 tokens (storage order), in LDS.
 template <int PK>
-__device__ inline PackBits make_pack(const __half *tile, int g, int d,
-                                     const uint32_t *__restrict__ meta_g, int qmax) {
+__device__ inline PackBits make_pack(const __half *tile, int g, int d, const float2 *sm, int qmax) {
     int q[PK];
     int lo = 255, hi = 0;
 #pragma unroll
     for (int i = 0; i < PK; ++i) {
-        const int v = quantize_value(__half2float(tile[(g * PK + i) * D + d]), meta_g[i], qmax);
+        const float2 t = sm[g * PK + i];
+        const int v = quantize_value(__half2float(tile[(g * PK + i) * D + d]), t.x, t.y, qmax);
         q[i] = v;
         lo = min(lo, v);
         hi = max(hi, v);
@@ -165,8 +168,15 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
         dst = arena + size_t(o0) * 16;
     }
 
-    // stage the block's 64 x 128 values in LDS with 16-byte loads, rows in storage order
+    // stage the block's 64 x 128 values in LDS with 16-byte loads, rows in storage order, and the
+    // tokens' scales and minimums as floats (every thread needs all 64 of them)
     __shared__ __attribute__((aligned(16))) __half tile[N * D];
+    __shared__ float2 sm[N];
+    if (tau < N) {
+        const uint32_t mt = meta[b * meta_stride + first_token + int64_t(blk) * N + tau];
+        sm[tau] = make_float2(__half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu))),
+                              __half2float(__ushort_as_half(uint16_t(mt >> 16))));
+    }
     {
         const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D;
         const uint8_t *ord = order ? order + b * meta_stride + first_token + int64_t(blk) * N : nullptr;
@@ -184,8 +194,7 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
 #pragma unroll
     for (int k = 0; k < PER; ++k) {
         const int g = (tau >> 7) + 2 * k;
-        const int64_t tok = int64_t(blk) * N + g * PK;  // first storage slot of the pack
-        pb[k] = make_pack<PK>(tile, g, d, meta + b * meta_stride + first_token + tok, qmax);
+        pb[k] = make_pack<PK>(tile, g, d, sm, qmax);
     }
     // all packs are quantized before the first barrier of the scans
     int off[PER];
