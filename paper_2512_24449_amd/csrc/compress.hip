@@ -331,18 +331,50 @@ __global__ __launch_bounds__(1024) void place_chunks_kernel(uint32_t *__restrict
     }
     __syncthreads();
 
-    // (3) the chain of page starts, and the pages for it
+    // (3) the chain of page starts, and the pages for it.  Following the chain is one dependent LDS
+    // read per fresh page; with many chunks it is cut into sixteen segments, one per wave: a chain
+    // enters a segment within its first 128 chunks (a page holds no more), so every wave follows
+    // the chain from each of these 128 possible entries to the segment's end (lanes in parallel)
+    // and notes where it leaves and how many pages it starts; thread 0 then hops through the
+    // sixteen tables, and every wave marks its own segment from its true entry.
+    constexpr int WAVES = 16, ENTRIES = 128;
+    __shared__ uint32_t seg_exit[WAVES][ENTRIES];
+    __shared__ uint16_t seg_pages[WAVES][ENTRIES];
+    __shared__ uint32_t seg_entry[WAVES];
+    const int seg = (n + WAVES - 1) / WAVES;
+    const bool segmented = seg >= ENTRIES;
+    const int seg_a = min(wave * seg, n), seg_e = min(seg_a + seg, n);
+    if (segmented) {
+        for (int c = lane; c < ENTRIES; c += 64) {
+            int j = seg_a + c;
+            uint32_t pages = 0;
+            while (j < seg_e) {
+                ++pages;
+                j += int(step[j]) + 1;
+            }
+            seg_exit[wave][c] = uint32_t(j);
+            seg_pages[wave][c] = uint16_t(pages);
+        }
+    }
+    __syncthreads();
     const uint32_t held = page_list[0];
     const uint32_t fill0 = held ? page_list[1] : P;  // no page yet: like a full one
     if (tid == 0) {
         int j = 0;
         while (j < n && fill0 + S(j + 1) <= P) ++j;  // these still go into the newest page
         uint32_t need = 0;
-        while (j < n) {
-            const uint32_t c = step[j];
-            step[j] = uint8_t(c | 0x80u);
-            ++need;
-            j += int(c) + 1;
+        for (int w = 0; w < (segmented ? WAVES : 1); ++w) {
+            const int a = segmented ? min(w * seg, n) : 0, e = segmented ? min(a + seg, n) : n;
+            seg_entry[w] = uint32_t(j);
+            if (segmented && j < e && j - a < ENTRIES) {
+                need += seg_pages[w][j - a];
+                j = int(seg_exit[w][j - a]);
+            } else {
+                while (j < e) {  // few chunks, or an entry the tables do not cover: step by step
+                    ++need;
+                    j += int(step[j]) + 1;
+                }
+            }
         }
         uint32_t ok = held + need <= uint64_t(max_pages), top = 0;
         if (ok && need) {
@@ -360,6 +392,16 @@ __global__ __launch_bounds__(1024) void place_chunks_kernel(uint32_t *__restrict
         }
         sh_ok = ok;
         sh_top = top;
+    }
+    __syncthreads();
+    if (sh_ok && lane == 0 && (segmented || wave == 0)) {  // mark the page starts of this wave's part
+        int j = int(seg_entry[wave]);
+        const int e = segmented ? seg_e : n;
+        while (j < e) {
+            const uint32_t c = step[j];
+            step[j] = uint8_t(c | 0x80u);
+            j += int(c) + 1;
+        }
     }
     __syncthreads();
     if (!sh_ok) {
