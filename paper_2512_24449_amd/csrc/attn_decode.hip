@@ -192,6 +192,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
             wait_chunk_landed();  // K chunk of this block
             uint32_t kmt = kmt_next, vmt = vmt_next;
             consume_here(kmt), consume_here(vmt);
+            lds_reads_returned();  // the previous V chunk has been read completely
             chunk_issue_lds(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             if (it + 1 < n_it) {
                 const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane;
@@ -234,6 +235,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                 attn_raise_reference<G>(s, m_ref, l_lane, st, col);
             }
             wait_chunk_landed();  // V chunk of this block
+            lds_reads_returned();  // the K chunk has been read completely before the next one overwrites it
             if (it + 1 < n_it)
                 chunk_issue_lds(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
             if (!valid) continue;
@@ -314,8 +316,10 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
             wait_chunk_landed();  // K chunk of this block
             uint32_t kmt = kmt_next, vmt = vmt_next;
             consume_here(kmt), consume_here(vmt);
-            if constexpr (!SHARED)
+            if constexpr (!SHARED) {
+                lds_reads_returned();  // the previous V chunk has been read completely
                 chunk_issue_lds<VMAX, VHDR>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
+            }
             if (it + 1 < n_it) {
                 const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + tok_in_blk;
                 kmt_next = a.k_meta[tok];
@@ -359,9 +363,11 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
                 chunk_issue_lds<VMAX, VHDR>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             }
             wait_chunk_landed();  // V chunk of this block
-            if constexpr (!SHARED)
+            if constexpr (!SHARED) {
+                lds_reads_returned();  // the K chunk has been read completely before the next one overwrites it
                 if (it + 1 < n_it)
                     chunk_issue_lds<KMAX, KHDR>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
+            }
             if (valid) {
                 float pt[G];
 #pragma unroll
