@@ -475,14 +475,14 @@ def main():
     packed = run_packed(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     fp16 = run_fp16(w, K, V, q, args.steps, args.warmup, torch, binding, synth)
     # the second pack size (packs of 8 tokens) on the same data
-    packed8 = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8)
+    packed8 = None if args.no_side_workloads else run_packed(w, K, V, q, 40, 10, torch, binding, synth, pack_size=8)
     # finer scales (codes above 15, wide chunks) on the same data
-    packedw = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, pack_size=8,
+    packedw = None if args.no_side_workloads else run_packed(w, K, V, q, 40, 10, torch, binding, synth, pack_size=8,
                                                              rel=(0.05, 0.05))
     # the same workload in paged caches over one shared page pool
-    packedp = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth, paged=True)
+    packedp = None if args.no_side_workloads else run_packed(w, K, V, q, 40, 10, torch, binding, synth, paged=True)
     # and its control: contiguous caches timed right after, with the same short run
-    packedc = None if args.no_side_workloads else run_packed(w, K, V, q, 20, 5, torch, binding, synth)
+    packedc = None if args.no_side_workloads else run_packed(w, K, V, q, 40, 10, torch, binding, synth)
     del K, V
     torch.cuda.empty_cache()
     if args.copy_calibration:
@@ -580,8 +580,8 @@ def main():
             if sw.name == w.name:
                 continue
             Ks, Vs, qs = synth.make_workload(sw, device="cuda:0")
-            sp = run_packed(sw, Ks, Vs, qs, 20, 5, torch, binding, synth)
-            sf = run_fp16(sw, Ks, Vs, qs, 20, 5, torch, binding, synth)
+            sp = run_packed(sw, Ks, Vs, qs, 40, 10, torch, binding, synth)
+            sf = run_fp16(sw, Ks, Vs, qs, 40, 10, torch, binding, synth)
             side[sw.name] = {"k_ms": round(sp["k_ms"], 5), "v_ms": round(sp["v_ms"], 5),
                              "fp16_k_ms": round(sf["k_ms"], 5), "fp16_v_ms": round(sf["v_ms"], 5),
                              "speedup_k": round(sf["k_ms"] / sp["k_ms"], 3),
