@@ -180,12 +180,12 @@ int create_cache(const kv_config_t *cfg, kv_page_pool *pool, const kv_buffers_t 
     c->tail_tokens = 0;
     c->pool = pool;
     c->index_words = pool ? 2 : 1;
-    c->max_pages = 0;
+    c->max_pages_k = c->max_pages_v = 0;
     if (pool) {
         c->buf.k_arena = c->buf.v_arena = pool->pages;
         c->sizes.k_arena = c->sizes.v_arena = size_t(pool->n_pages) * KV_PAGE_BYTES;
-        // what the caller's page lists can take
-        c->max_pages = int64_t(std::min(sizes->k_pages, sizes->v_pages) / 4) - 2;
+        c->max_pages_k = int64_t(sizes->k_pages / 4) - 2;
+        c->max_pages_v = int64_t(sizes->v_pages / 4) - 2;
     }
     rc = launch_init(c, nullptr);
     if (rc == KV_OK && hipStreamSynchronize(nullptr) != hipSuccess) rc = KV_ERR_HIP;
@@ -263,6 +263,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         kjob.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
         kjob.status = status + ST_OVERFLOW_K;
         kjob.page_list = static_cast<uint32_t *>(c->buf.k_pages);
+        kjob.max_pages = c->max_pages_k;
         vjob.src = vsrc + int64_t(done) * N * job.token_stride;
         vjob.rel = c->cfg.v_rel_scale;
         vjob.qmax = c->qmax_v;
@@ -273,6 +274,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         vjob.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
         vjob.status = status + ST_OVERFLOW_V;
         vjob.page_list = static_cast<uint32_t *>(c->buf.v_pages);
+        vjob.max_pages = c->max_pages_v;
         int rc;
         if ((rc = launch_token_params(c, kjob, s))) return rc;
         if ((rc = launch_token_params(c, vjob, s))) return rc;

@@ -193,7 +193,7 @@ struct kv_cache {
     // the index has a (start, end) pair per chunk, buf.k_pages / buf.v_pages list the pages held
     kv_page_pool *pool;     // null: chunks back to back in the cache's own arenas
     int index_words;        // 1, or 2 when paged
-    int64_t max_pages;      // per tensor
+    int64_t max_pages_k, max_pages_v;  // what the caller's page lists can take
 };
 
 #define KV_HIP_CHECK(expr)                      \
@@ -221,6 +221,7 @@ struct CompressJob {
     uint32_t *meta;
     uint32_t *status;         // status word to set on overflow
     uint32_t *page_list;      // paged arena: [0] pages held, [1] 16-byte units used in the newest, [2..] page numbers
+    int64_t max_pages;        // page numbers the list has room for
     const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
 };
 

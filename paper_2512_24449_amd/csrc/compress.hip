@@ -666,7 +666,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
                        job.order);
     if (c->pool)
         hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
-                           job.first_chunk, job.page_list, c->max_pages, c->pool->state, job.status);
+                           job.first_chunk, job.page_list, job.max_pages, c->pool->state, job.status);
     else
         hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
                            job.index, job.first_chunk, job.arena_cap16, job.status);

@@ -19,12 +19,15 @@ pytestmark = pytest.mark.gpu
     (2, 2, 8, 64 * 40 + 3, [64 * 40 + 3], dict()),                       # one bulk append over many pages
     (1, 5, 10, 64 * 21 + 40, [30, 64 * 20, 74], dict(pack_size=8)),
     (2, 2, 4, 64 * 18 + 9, [64 * 7, 64 * 11 + 9], dict(pack_size=8, k_rel=1 / 60, v_rel=1 / 255)),
+    # narrow K next to wide V at the finest scale: V takes several times the pages K takes (each
+    # tensor's page list has its own capacity)
+    (2, 5, 10, 64 * 64 + 31, [3081, 309, 652, 85], dict(pack_size=8, k_rel=0.1, v_rel=1 / 255)),
 ])
 def test_paged_cache_matches_oracle_and_contiguous_cache(B, H, Hq, L, pieces, kw):
-    pool = binding.PagePool(64)
+    pool = binding.PagePool(256)
     paged = gpu_cases.run_case(B, H, Hq, L, 4242, pieces=pieces, pool=pool, **kw)
     # run_case closed its cache: kv_cache_destroy of a paged cache gives the pages back
-    assert pool.kv_page_pool_free_pages() == 64
+    assert pool.kv_page_pool_free_pages() == 256
     flat = gpu_cases.run_case(B, H, Hq, L, 4242, pieces=pieces, **kw)
     for name in ("scores", "out", "attn"):
         if flat[name] is not None:
