@@ -154,14 +154,16 @@ def check_paged_state(cache, n_packed, ck, cv, B, H):
 
 
 def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, device="cuda:0",
-             max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2, pool=None):
+             max_tokens=None, pack_size=16, k_rel=0.1, v_rel=0.2, pool=None, repack=False):
     """Append L tokens (in `pieces`, default one call), then one decode step; compare everything.
-    pool: a binding.PagePool -> the cache is paged."""
+    pool: a binding.PagePool -> the cache is paged.  repack: V-median repacking; the oracle then
+    works on the tensors permuted by its own order, and scores compare in storage order."""
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
     cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), k_rel_scale=k_rel, v_rel_scale=v_rel,
-                                  device=device, pack_size=pack_size, pool=pool)
+                                  device=device, pack_size=pack_size, pool=pool,
+                                  repack=binding.REPACK_V_MEDIAN if repack else binding.REPACK_NONE)
     Kd, Vd, qd = K.to(device), V.to(device), q.to(device)
     pos = 0
     for n in (pieces or [L]):
@@ -169,6 +171,14 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
         pos += n
     assert pos == L and cache.tokens == L
 
+    if repack and L >= 64:
+        n_full = L // 64 * 64
+        order = oracle.v_median_order(oracle.compress(np.ascontiguousarray(Vn[:, :n_full]), v_rel, pack_size).codes)
+        Kn = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_full:]], axis=1)
+        Vn = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_full:]], axis=1)
+        mt = ((max_tokens or max(L, 64)) + 63) // 64 * 64
+        got = cache.tensors["token_order"][:B * mt].view(B, mt)[:, :n_full].cpu().numpy()
+        assert np.array_equal(got, order), "token order"
     n_packed, ck, cv = oracle_cache(Kn, Vn, k_rel, v_rel, pack_size)
     if check_bytes:
         (check_paged_state if pool is not None else check_packed_state)(cache, n_packed, ck, cv, B, H)

@@ -80,6 +80,21 @@ def test_random_shapes_with_packs_of_8(B, H, Hq, L, seed, pieces):
     gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8)
 
 
+@pytest.mark.parametrize("B,H,Hq,L,seed,pieces", _random_shapes(8, 4711))
+def test_random_shapes_with_repacking_paging_and_fine_scales(B, H, Hq, L, seed, pieces):
+    """The options in combination, chosen by the seed: V-median repacking, a paged arena, packs of
+    8 tokens, scales below 1/15 for either tensor."""
+    rng = np.random.default_rng(seed)
+    kw = dict(repack=bool(rng.integers(0, 2)))
+    if rng.integers(0, 2):
+        kw.update(pack_size=8, k_rel=float(rng.choice([0.1, 1 / 40])), v_rel=float(rng.choice([0.2, 1 / 255])))
+    pool = binding.PagePool(128) if rng.integers(0, 2) else None
+    gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pool=pool, **kw)
+    if pool is not None:
+        assert pool.kv_page_pool_free_pages() == 128
+        pool.close()
+
+
 def test_benchmark_configuration_1_llama2_7b_4k():
     w = synth.workload(1)
     sizes = gpu_cases.run_case(w.batch, w.n_kv_heads, w.n_q_heads, w.tokens, 1)
