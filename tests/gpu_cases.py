@@ -159,6 +159,10 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
     pool: a binding.PagePool -> the cache is paged.  repack: V-median repacking; the oracle then
     works on the tensors permuted by its own order, and scores compare in storage order."""
     K, V, q = synth.make_kv(B, L, H, Hq, seed)
+    if repack:
+        # give the V tokens differently leaning value distributions so that their medians differ
+        lean = torch.from_numpy(np.random.default_rng(seed).choice([0.3, 1.0, 3.0], size=(B, L, 1, 1))).float()
+        V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(seed)) ** lean).to(torch.float16)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     sm_scale = sm_scale if sm_scale is not None else 128 ** -0.5
     cache = binding.PackedKVCache(B, H, Hq, max_tokens or max(L, 64), k_rel_scale=k_rel, v_rel_scale=v_rel,
