@@ -166,6 +166,13 @@ def test_exhausted_pool_drops_the_call_and_keeps_its_pages():
     pz[:, :, kept["v"]:] = 0
     o_ref = oracle.v_out(cv.codes, V.numpy()[:, :L], cv.meta, L, pz)
     assert_close_vectors(out.cpu().numpy(), o_ref, "V out without the dropped blocks")
+    # the fused attention leaves out every block that lacks its K or its V chunk
+    both = min(kept["k"], kept["v"])
+    attn = cache.kv_decode_attention(q.cuda(), 0.09)
+    torch.cuda.synchronize()
+    a_ref = oracle.attention(ck.codes[:, :both], K.numpy()[:, :both], ck.meta[:, :both], cv.codes[:, :both],
+                             V.numpy()[:, :both], cv.meta[:, :both], both, q.numpy(), 0.09)
+    assert_close_vectors(attn.cpu().numpy(), a_ref, "attention over the blocks that have both chunks")
     cache.close()
     assert pool.kv_page_pool_free_pages() == 3
     pool.close()
