@@ -25,14 +25,34 @@ def sources():
 
 
 def build(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library; always recompiles."""
+    """Compile every HIP source (one hipcc process per file, in parallel) and link them into one
+    shared library; always recompiles."""
+    import concurrent.futures
+    import shutil
+    import tempfile
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + ".tmp%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + os.environ.get("PACKKV_EXTRA_FLAGS", "").split() + ["-I", os.path.join(ROOT, "include"), "-I", CSRC, "-o", tmp] + sources()
-    if verbose:
-        print(" ".join(cmd))
-    subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + os.environ.get("PACKKV_EXTRA_FLAGS", "").split()
+    flags += ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    objdir = tempfile.mkdtemp(prefix="packkv_build_")
+    try:
+        def compile_one(src):
+            obj = os.path.join(objdir, os.path.basename(src) + ".o")
+            cmd = [hipcc] + flags + ["-c", "-o", obj, src]
+            if verbose:
+                print(" ".join(cmd))
+            subprocess.check_call(cmd)
+            return obj
+        jobs = max(1, min(len(sources()), int(os.environ.get("MAX_JOBS", "0")) or os.cpu_count() or 1, 8))
+        with concurrent.futures.ThreadPoolExecutor(jobs) as pool:
+            objs = list(pool.map(compile_one, sources()))
+        tmp = LIB + ".tmp%d" % os.getpid()
+        cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp] + objs
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.check_call(cmd)
+        os.replace(tmp, LIB)
+    finally:
+        shutil.rmtree(objdir, ignore_errors=True)
     return LIB
 
 

@@ -24,7 +24,7 @@ int check_config(const kv_config_t *c) {
         return KV_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads) return KV_ERR_ARG;
     const int g = c->n_q_heads / c->n_kv_heads;
-    if (g != 1 && g != 2 && g != 4 && g != 8) return KV_ERR_UNSUPPORTED;
+    if (g > 8) return KV_ERR_UNSUPPORTED;
     // one pack byte holds a 4-bit minimum: codes above 15 need the wide layout, which exists
     // for packs of 8 tokens only; a code is one byte at most
     for (float rel : {c->k_rel_scale, c->v_rel_scale}) {

@@ -485,33 +485,28 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
         if (c->cfg.pack_size == 8) {
-#define PACKKV_LAUNCH_ATTN8(KW, VW)                                                                  \
-    switch (G) {                                                                                     \
-        case 1: hipLaunchKernelGGL((attn8_kernel<1, KW, VW>), grid, dim3(256), 0, s, a); break;      \
-        case 2: hipLaunchKernelGGL((attn8_kernel<2, KW, VW>), grid, dim3(256), 0, s, a); break;      \
-        case 4: hipLaunchKernelGGL((attn8_kernel<4, KW, VW>), grid, dim3(256), 0, s, a); break;      \
-        case 8: hipLaunchKernelGGL((attn8_kernel<8, KW, VW>), grid, dim3(256), 0, s, a); break;      \
-        default: return KV_ERR_UNSUPPORTED;                                                          \
-    }
+#define PACKKV_LAUNCH_A8NN(g) hipLaunchKernelGGL((attn8_kernel<g, false, false>), grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_A8WN(g) hipLaunchKernelGGL((attn8_kernel<g, true, false>), grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_A8NW(g) hipLaunchKernelGGL((attn8_kernel<g, false, true>), grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_A8WW(g) hipLaunchKernelGGL((attn8_kernel<g, true, true>), grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_A(g) hipLaunchKernelGGL(attn_kernel<g>, grid, dim3(256), 0, s, a)
             if (c->wide_k && c->wide_v) {
-                PACKKV_LAUNCH_ATTN8(true, true)
+                PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8WW)
             } else if (c->wide_k) {
-                PACKKV_LAUNCH_ATTN8(true, false)
+                PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8WN)
             } else if (c->wide_v) {
-                PACKKV_LAUNCH_ATTN8(false, true)
+                PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8NW)
             } else {
-                PACKKV_LAUNCH_ATTN8(false, false)
+                PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8NN)
             }
-#undef PACKKV_LAUNCH_ATTN8
         } else {
-            switch (G) {
-                case 1: hipLaunchKernelGGL(attn_kernel<1>, grid, dim3(256), 0, s, a); break;
-                case 2: hipLaunchKernelGGL(attn_kernel<2>, grid, dim3(256), 0, s, a); break;
-                case 4: hipLaunchKernelGGL(attn_kernel<4>, grid, dim3(256), 0, s, a); break;
-                case 8: hipLaunchKernelGGL(attn_kernel<8>, grid, dim3(256), 0, s, a); break;
-                default: return KV_ERR_UNSUPPORTED;
-            }
+            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A)
         }
+#undef PACKKV_LAUNCH_A8NN
+#undef PACKKV_LAUNCH_A8WN
+#undef PACKKV_LAUNCH_A8NW
+#undef PACKKV_LAUNCH_A8WW
+#undef PACKKV_LAUNCH_A
     }
     hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
                        B * H * G, q, static_cast<const __half *>(c->buf.k_tail),

@@ -196,6 +196,20 @@ struct kv_cache {
     int64_t max_pages_k, max_pages_v;  // what the caller's page lists can take
 };
 
+// Runs LAUNCH(g) with the group size as a compile-time constant; group sizes 1..8.
+#define PACKKV_DISPATCH_GROUP(group, LAUNCH)   \
+    switch (group) {                           \
+        case 1: LAUNCH(1); break;              \
+        case 2: LAUNCH(2); break;              \
+        case 3: LAUNCH(3); break;              \
+        case 4: LAUNCH(4); break;              \
+        case 5: LAUNCH(5); break;              \
+        case 6: LAUNCH(6); break;              \
+        case 7: LAUNCH(7); break;              \
+        case 8: LAUNCH(8); break;              \
+        default: return KV_ERR_UNSUPPORTED;    \
+    }
+
 #define KV_HIP_CHECK(expr)                      \
     do {                                        \
         hipError_t e_ = (expr);                 \

@@ -185,13 +185,7 @@ extern "C" int kv_fp16_k_matvec(const void *k_cache, const void *q, float sm_sca
 #define LAUNCH(GG)                                                                               \
     hipLaunchKernelGGL(fp16_k_kernel<GG>, dim3((unsigned)grid), dim3(256), 0, s, kc, qq, sm_scale, \
                        scores, ld_scores, n_kv_heads, tokens, tiles, units)
-    switch (G) {
-        case 1: LAUNCH(1); break;
-        case 2: LAUNCH(2); break;
-        case 4: LAUNCH(4); break;
-        case 8: LAUNCH(8); break;
-        default: return KV_ERR_UNSUPPORTED;
-    }
+    PACKKV_DISPATCH_GROUP(G, LAUNCH)
 #undef LAUNCH
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
@@ -224,13 +218,7 @@ extern "C" int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_
 #define LAUNCH(GG)                                                                            \
     hipLaunchKernelGGL(fp16_v_kernel<GG>, grid, dim3(256), 0, s, vc, p, ld_p, partial, n_kv_heads, \
                        tokens, tiles_per_split * 64)
-    switch (G) {
-        case 1: LAUNCH(1); break;
-        case 2: LAUNCH(2); break;
-        case 4: LAUNCH(4); break;
-        case 8: LAUNCH(8); break;
-        default: return KV_ERR_UNSUPPORTED;
-    }
+    PACKKV_DISPATCH_GROUP(G, LAUNCH)
 #undef LAUNCH
     hipLaunchKernelGGL(fp16_v_reduce_kernel, dim3(batch * n_q_heads), dim3(256), 0, s, partial,
                        n_splits, batch * n_q_heads, out);

@@ -448,31 +448,19 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     const int tail_groups = a.n_tail > 0 ? (streams + 3) / 4 : 0;
     const int grid = a.n_stream_groups + tail_groups;
     if (grid == 0) return KV_OK;
+#define PACKKV_LAUNCH_KW(g) hipLaunchKernelGGL(kw_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_K8(g) hipLaunchKernelGGL(k8_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_K(g) hipLaunchKernelGGL(k_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
     if (c->wide_k) {
-        switch (c->group) {
-            case 1: hipLaunchKernelGGL(kw_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
-            case 2: hipLaunchKernelGGL(kw_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
-            case 4: hipLaunchKernelGGL(kw_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
-            case 8: hipLaunchKernelGGL(kw_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
-            default: return KV_ERR_UNSUPPORTED;
-        }
+        PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_KW)
     } else if (c->cfg.pack_size == 8) {
-        switch (c->group) {
-            case 1: hipLaunchKernelGGL(k8_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
-            case 2: hipLaunchKernelGGL(k8_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
-            case 4: hipLaunchKernelGGL(k8_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
-            case 8: hipLaunchKernelGGL(k8_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
-            default: return KV_ERR_UNSUPPORTED;
-        }
+        PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_K8)
     } else {
-        switch (c->group) {
-            case 1: hipLaunchKernelGGL(k_matvec_kernel<1>, dim3(grid), dim3(256), 0, s, a); break;
-            case 2: hipLaunchKernelGGL(k_matvec_kernel<2>, dim3(grid), dim3(256), 0, s, a); break;
-            case 4: hipLaunchKernelGGL(k_matvec_kernel<4>, dim3(grid), dim3(256), 0, s, a); break;
-            case 8: hipLaunchKernelGGL(k_matvec_kernel<8>, dim3(grid), dim3(256), 0, s, a); break;
-            default: return KV_ERR_UNSUPPORTED;
-        }
+        PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_K)
     }
+#undef PACKKV_LAUNCH_KW
+#undef PACKKV_LAUNCH_K8
+#undef PACKKV_LAUNCH_K
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

@@ -294,31 +294,19 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * H);
+#define PACKKV_LAUNCH_VW(g) hipLaunchKernelGGL(vw_matvec_kernel<g>, grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_V8(g) hipLaunchKernelGGL(v8_matvec_kernel<g>, grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_V(g) hipLaunchKernelGGL(v_matvec_kernel<g>, grid, dim3(256), 0, s, a)
         if (c->wide_v) {
-            switch (G) {
-                case 1: hipLaunchKernelGGL(vw_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
-                case 2: hipLaunchKernelGGL(vw_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
-                case 4: hipLaunchKernelGGL(vw_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
-                case 8: hipLaunchKernelGGL(vw_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
-                default: return KV_ERR_UNSUPPORTED;
-            }
+            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_VW)
         } else if (c->cfg.pack_size == 8) {
-            switch (G) {
-                case 1: hipLaunchKernelGGL(v8_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
-                case 2: hipLaunchKernelGGL(v8_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
-                case 4: hipLaunchKernelGGL(v8_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
-                case 8: hipLaunchKernelGGL(v8_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
-                default: return KV_ERR_UNSUPPORTED;
-            }
+            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_V8)
         } else {
-            switch (G) {
-                case 1: hipLaunchKernelGGL(v_matvec_kernel<1>, grid, dim3(256), 0, s, a); break;
-                case 2: hipLaunchKernelGGL(v_matvec_kernel<2>, grid, dim3(256), 0, s, a); break;
-                case 4: hipLaunchKernelGGL(v_matvec_kernel<4>, grid, dim3(256), 0, s, a); break;
-                case 8: hipLaunchKernelGGL(v_matvec_kernel<8>, grid, dim3(256), 0, s, a); break;
-                default: return KV_ERR_UNSUPPORTED;
-            }
+            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_V)
         }
+#undef PACKKV_LAUNCH_VW
+#undef PACKKV_LAUNCH_V8
+#undef PACKKV_LAUNCH_V
     }
     hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
                        B * H * G, p, ld_p, c->packed_tokens,

@@ -61,7 +61,7 @@ def _random_shapes(n, seed):
     rng = np.random.default_rng(seed)
     cases = []
     for i in range(n):
-        B, H, G = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 4, 8]))
+        B, H, G = int(rng.integers(1, 4)), int(rng.choice([1, 2, 3, 5])), int(rng.choice([1, 2, 4, 8, 3, 5, 6, 7]))
         L = int(rng.integers(1, 900))
         cuts = sorted(set(int(c) for c in rng.integers(1, L + 1, size=int(rng.integers(0, 5))) if c < L))
         pieces = [b - a for a, b in zip([0] + cuts, cuts + [L])]
@@ -319,7 +319,7 @@ def test_host_argument_errors():
                                  torch.zeros(1, 65, 2, 128, dtype=torch.float16, device="cuda"))
 
 
-@pytest.mark.parametrize("B,H,Hq,L", [(1, 2, 2, 1000), (2, 2, 8, 333)])
+@pytest.mark.parametrize("B,H,Hq,L", [(1, 2, 2, 1000), (2, 2, 8, 333), (1, 3, 21, 500)])
 def test_fp16_companion_gemv(B, H, Hq, L):
     """The uncompressed fp16 comparison kernels against numpy fp64."""
     K, V, q = synth.make_kv(B, L, H, Hq, 60)

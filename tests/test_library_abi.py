@@ -48,8 +48,12 @@ def test_query_sizes_and_config_checks():
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
     wide = binding.kv_query_sizes(binding.make_config(1, 32, 32, 4096, k_rel_scale=0.05, pack_size=8))
     assert wide.k_arena >= n_chunks * 10240 and wide.v_arena >= n_chunks * 5120 and wide.v_arena < wide.k_arena
-    bad = binding.make_config(1, 3, 32, 4096)
+    bad = binding.make_config(1, 3, 32, 4096)                      # query heads not a multiple of kv heads
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
+    for g in range(1, 9):                                          # every group size up to 8
+        assert L.kv_query_sizes(C.byref(binding.make_config(1, 4, 4 * g, 4096)), 0.0, C.byref(out)) == 0
+    bad = binding.make_config(1, 4, 36, 4096)                      # nine query heads per kv head
+    assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -2
     bad = binding.make_config(0, 1, 1, 64)
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
     assert L.kv_query_sizes(None, 0.0, C.byref(out)) == -1
