@@ -39,6 +39,7 @@ struct AArgs {
     int64_t meta_stride;
     int B, H;
     int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
+    int dup;                // H counts every kv-head dup times (query groups above 8 are split): kv-head = h / dup
     int n_blocks;                     // packed blocks per stream
     int blocks_per_split;
     float sm_log2;                    // sm_scale * log2(e)
@@ -179,8 +180,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ik, iv;
-        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
-        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
+        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + lane;
@@ -303,8 +304,8 @@ __global__ __launch_bounds__(256) void attn8_kernel(AArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ik, iv;
-        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
-        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
+        iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds<KMAX, KHDR>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + tok_in_blk;
@@ -458,14 +459,16 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 int v_splits_for(int n_blocks, int streams);
 
 int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, float *out, hipStream_t s) {
-    const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group;
+    // Hs: kv-heads as the stream kernels count them (each dup times, see head_split); the combine
+    // kernel works per query head and sees the real kv-head count and the whole group
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group, Hs = H * c->head_split, Gq = G * c->head_split;
     const int n_blocks = int(c->packed_tokens / N);
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     float *partial = reinterpret_cast<float *>(ws + WS_VPART);
     const float sm_log2 = sm_scale * LOG2E;
     int n_splits = 0;
     if (n_blocks > 0) {
-        n_splits = v_splits_for(n_blocks, B * H);
+        n_splits = v_splits_for(n_blocks, B * Hs);
         AArgs a;
         a.k_arena = static_cast<const uint8_t *>(c->buf.k_arena);
         a.v_arena = static_cast<const uint8_t *>(c->buf.v_arena);
@@ -478,12 +481,13 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
         a.meta_stride = c->max_tokens;
         a.B = B;
         a.index_words = c->index_words;
-        a.H = H;
+        a.H = Hs;
+        a.dup = c->head_split;
         a.n_blocks = n_blocks;
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         a.sm_log2 = sm_log2;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
-        dim3 grid(n_splits, B * H);
+        dim3 grid(n_splits, B * Hs);
         if (c->cfg.pack_size == 8) {
 #define PACKKV_LAUNCH_A8NN(g) hipLaunchKernelGGL((attn8_kernel<g, false, false>), grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_A8WN(g) hipLaunchKernelGGL((attn8_kernel<g, true, false>), grid, dim3(256), 0, s, a)
@@ -508,10 +512,10 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
 #undef PACKKV_LAUNCH_A8WW
 #undef PACKKV_LAUNCH_A
     }
-    hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
-                       B * H * G, q, static_cast<const __half *>(c->buf.k_tail),
+    hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * Gq), dim3(256), 0, s, partial, n_splits,
+                       B * H * Gq, q, static_cast<const __half *>(c->buf.k_tail),
                        static_cast<const __half *>(c->buf.v_tail), c->tail_tokens,
-                       c->cfg.tail_capacity, H, G, sm_log2, out);
+                       c->cfg.tail_capacity, H, Gq, sm_log2, out);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

@@ -184,7 +184,8 @@ struct kv_cache {
     kv_sizes_t sizes;
     int64_t max_tokens;     // rounded up to a block
     int64_t max_chunks;     // per tensor
-    int group;              // query heads per kv head
+    int group;              // query heads per kv head as the kernels see them (1..8)
+    int head_split;         // groups above 8 are split: every kv-head counts head_split times, with `group` heads each
     int qmax_k, qmax_v;
     bool wide_k, wide_v;    // codes above 15: wide chunk layout for that tensor
     int64_t packed_tokens;  // per batch element

@@ -41,6 +41,7 @@ struct KArgs {
     int64_t packed_tokens;
     int B, H;
     int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
+    int dup;                // H counts every kv-head dup times (query groups above 8 are split): kv-head = h / dup
     int n_blocks;           // packed blocks per stream
     int blocks_per_group;   // blocks walked by one workgroup
     int groups_per_stream;
@@ -60,7 +61,7 @@ __device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int b
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -125,7 +126,7 @@ __device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int 
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -217,7 +218,7 @@ __device__ inline void k8_stream(const KArgs &a, int bh, int blk_begin, int blk_
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         vmem_order_fence();
         chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
@@ -283,7 +284,7 @@ __device__ inline void kw_stream(const KArgs &a, int bh, int blk_begin, int blk_
 
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         for (int it = 0; it < n_it; ++it) {
             const int64_t tok = int64_t(first + 4 * it) * N + tok_in_blk;
@@ -323,7 +324,7 @@ template <int G>
 __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
     const int h = bh % a.H, b = bh / a.H;
     if (lane >= a.n_tail) return;
-    const __half *row = a.tail + ((int64_t(b) * a.tail_cap + lane) * a.H + h) * D;
+    const __half *row = a.tail + ((int64_t(b) * a.tail_cap + lane) * (a.H / a.dup) + h / a.dup) * D;
     // the whole row first: sixteen independent 16-byte loads, one memory latency
     uint4 kr[D / 8];
 #pragma unroll
@@ -431,7 +432,8 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     a.packed_tokens = c->packed_tokens;
     a.B = c->cfg.batch;
     a.index_words = c->index_words;
-    a.H = c->cfg.n_kv_heads;
+    a.dup = c->head_split;
+    a.H = c->cfg.n_kv_heads * c->head_split;
     a.n_blocks = int(c->packed_tokens / N);
     const int streams = a.B * a.H;
     // never less than one block per wave

@@ -33,6 +33,7 @@ struct VArgs {
     int64_t meta_stride;
     int B, H;
     int index_words;        // index words per chunk: 1 back to back, 2 with a paged arena
+    int dup;                // H counts every kv-head dup times (query groups above 8 are split): kv-head = h / dup
     int n_blocks;           // packed blocks per stream
     int blocks_per_split;
 };
@@ -63,7 +64,7 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
         uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
@@ -136,7 +137,7 @@ __global__ __launch_bounds__(256) void v8_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         chunk_issue_lds<CHUNK8_MAX, HEADER8>(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
         uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
@@ -208,7 +209,7 @@ __global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
     const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
     for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
         IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H, b, h, lane);
+        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
         for (int it = 0; it < n_it; ++it) {
             const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADERW / 16);
@@ -272,13 +273,15 @@ int v_splits_for(int n_blocks, int streams) {
 }
 
 int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s) {
-    const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group;
+    // Hs: kv-heads as the stream kernels count them (each dup times, see head_split); the combine
+    // kernel works per query head and sees the real kv-head count and the whole group
+    const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group, Hs = H * c->head_split, Gq = G * c->head_split;
     const int n_blocks = int(c->packed_tokens / N);
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     float *partial = reinterpret_cast<float *>(ws + WS_VPART);
     int n_splits = 0;
     if (n_blocks > 0) {
-        n_splits = v_splits_for(n_blocks, B * H);
+        n_splits = v_splits_for(n_blocks, B * Hs);
         VArgs a;
         a.arena = static_cast<const uint8_t *>(c->buf.v_arena);
         a.index = static_cast<const uint32_t *>(c->buf.v_index);
@@ -289,11 +292,12 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
         a.meta_stride = c->max_tokens;
         a.B = B;
         a.index_words = c->index_words;
-        a.H = H;
+        a.H = Hs;
+        a.dup = c->head_split;
         a.n_blocks = n_blocks;
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
-        dim3 grid(n_splits, B * H);
+        dim3 grid(n_splits, B * Hs);
 #define PACKKV_LAUNCH_VW(g) hipLaunchKernelGGL(vw_matvec_kernel<g>, grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_V8(g) hipLaunchKernelGGL(v8_matvec_kernel<g>, grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_V(g) hipLaunchKernelGGL(v_matvec_kernel<g>, grid, dim3(256), 0, s, a)
@@ -308,10 +312,10 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
 #undef PACKKV_LAUNCH_V8
 #undef PACKKV_LAUNCH_V
     }
-    hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * G), dim3(256), 0, s, partial, n_splits,
-                       B * H * G, p, ld_p, c->packed_tokens,
+    hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * Gq), dim3(256), 0, s, partial, n_splits,
+                       B * H * Gq, p, ld_p, c->packed_tokens,
                        static_cast<const __half *>(c->buf.v_tail), c->tail_tokens,
-                       c->cfg.tail_capacity, H, G, out);
+                       c->cfg.tail_capacity, H, Gq, out);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

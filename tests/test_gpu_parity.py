@@ -80,6 +80,13 @@ def test_random_shapes_with_packs_of_8(B, H, Hq, L, seed, pieces):
     gpu_cases.run_case(B, H, Hq, L, seed, pieces=pieces, pack_size=8)
 
 
+@pytest.mark.parametrize("G,kw", [(16, dict()), (12, dict(pack_size=8)), (9, dict(repack=True)),
+                                  (16, dict(pack_size=8, k_rel=0.05, v_rel=1 / 255)), (64, dict())])
+def test_query_groups_above_8_heads(G, kw):
+    """Groups of s * g heads (s, g <= 8) run as s groups of g heads over the same kv-head."""
+    gpu_cases.run_case(2, 3, 3 * G, 64 * 9 + 17, 500 + G, pieces=[300, 293], **kw)
+
+
 @pytest.mark.parametrize("B,H,Hq,L,seed,pieces", _random_shapes(8, 4711))
 def test_random_shapes_with_repacking_paging_and_fine_scales(B, H, Hq, L, seed, pieces):
     """The options in combination, chosen by the seed: V-median repacking, a paged arena, packs of
