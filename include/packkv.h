@@ -297,6 +297,7 @@ const char *kv_strerror(int code);
  * The comparison kernels of Sec. IV-E, hand-written for the same shapes:
  * plain fp16 matrix-vector products over an uncompressed cache stored as
  * fp16 [B][H_kv][tokens][128] (head-major, each (b, h) matrix contiguous).
+ * n_q_heads / n_kv_heads from 1 to 8 (KV_ERR_UNSUPPORTED otherwise).
  */
 int kv_fp16_k_matvec(const void *k_cache, const void *q, float sm_scale, float *scores,
                      int64_t ld_scores, int32_t batch, int32_t n_kv_heads, int32_t n_q_heads,
