@@ -345,3 +345,45 @@ def test_fp16_companion_gemv(B, H, Hq, L):
     torch.cuda.synchronize()
     ref = np.bitwise_xor.reduce(Kh.cpu().numpy().view(np.uint32).ravel())
     assert int(chk.cpu().numpy().view(np.uint32)[0]) == int(ref)
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(pack_size=8), dict(pack_size=8, k_rel=1 / 255, v_rel=1 / 40),
+                                dict(repack=binding.REPACK_V_MEDIAN)])
+def test_non_finite_inputs_keep_the_format_valid(kw):
+    """NaN and infinities in the input give unspecified codes, but the packed format stays valid:
+    every chunk parses with the independent reader, widths and codes stay in range, sizes add up,
+    and the decode entry points run."""
+    from tests import chunk_reader
+    B, H, Hq, L = 2, 2, 4, 64 * 3 + 5
+    K, V, q = synth.make_kv(B, L, H, Hq, 66)
+    rng = np.random.default_rng(66)
+    for x in (K, V):
+        flat = x.view(-1)
+        idx = torch.from_numpy(rng.choice(flat.numel(), 400, replace=False))
+        flat[idx[:150]] = float("nan")
+        flat[idx[150:275]] = float("inf")
+        flat[idx[275:]] = float("-inf")
+    K[0, 70] = float("nan")          # a whole token of NaN
+    V[1, 3] = float("inf")           # and one of infinities
+    cache = binding.PackedKVCache(B, H, Hq, L, **{("k_rel_scale" if k == "k_rel" else "v_rel_scale" if k == "v_rel" else k): v
+                                                  for k, v in kw.items()})
+    cache.kv_compress_append(K.cuda(), V.cuda())
+    st = cache.kv_cache_stats()
+    assert st.overflow == 0 and st.packed_tokens == 192
+    n_chunks = 3 * B * H
+    pk = kw.get("pack_size", 16)
+    for name, rel in (("k", kw.get("k_rel", 0.1)), ("v", kw.get("v_rel", 0.2))):
+        qmax = round(1 / rel)
+        index = cache.view(name + "_index", torch.int32)[:n_chunks + 1].cpu().numpy().view(np.uint32).astype(np.int64)
+        assert index[0] == 0 and (np.diff(index) > 0).all() and index[-1] * 16 == (st.k_bytes if name == "k" else st.v_bytes)
+        arena = cache.tensors[name + "_arena"][:index[-1] * 16].cpu().numpy()
+        for c in range(n_chunks):
+            buf = arena[index[c] * 16:index[c + 1] * 16]
+            codes, widths, mins = chunk_reader.read_chunk_wide(buf) if qmax > 15 else chunk_reader.read_chunk(buf, pk)
+            assert codes.min() >= 0 and codes.max() <= qmax and widths.max() <= (8 if qmax > 15 else 4)
+    scores = cache.kv_k_matvec(q.cuda(), 0.1)
+    cache.kv_softmax(scores)
+    cache.kv_v_matvec(scores)
+    cache.kv_decode_attention(q.cuda(), 0.1)
+    torch.cuda.synchronize()
+    cache.close()
