@@ -87,7 +87,8 @@ typedef struct {
     int32_t n_kv_heads;    /* H_kv >= 1                                           */
     int32_t n_q_heads;     /* H_q, a multiple of H_kv; H_q / H_kv from 1 to 8, or a
                               product s * g with s, g <= 8 (12, 16, 24, 64 ...): such a
-                              group runs as s groups of g heads over the same kv-head */
+                              group runs as s groups of g heads over the same kv-head;
+                              B * H_kv * s at most 65535                          */
     int32_t head_dim;      /* must be 128                                         */
     int32_t block_tokens;  /* must be 64                                          */
     int32_t pack_size;     /* 16 or 8                                             */
