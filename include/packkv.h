@@ -175,6 +175,16 @@ int kv_cache_destroy(kv_cache_t *cache);
  */
 int kv_compress_append(kv_cache_t *cache, const void *k_new, const void *v_new, int32_t n_new,
                        void *hip_stream);
+/*
+ * The same for bf16 inputs (device bf16 [B][n_new][H_kv][128]): every value enters as
+ * its fp16 rounding (to nearest even) -- exact for values in fp16's normal range,
+ * since fp16 has the longer significand; smaller magnitudes round in fp16's
+ * subnormal grid, magnitudes above 65504 become infinities (see "Inputs must be
+ * finite").  From there on the path is the fp16 one: the tail stores fp16, and the
+ * packed bytes are those kv_compress_append gives for the rounded values.
+ */
+int kv_compress_append_bf16(kv_cache_t *cache, const void *k_new, const void *v_new, int32_t n_new,
+                            void *hip_stream);
 
 /*
  * Fused K path (Sec. III-C.1): scores[b][hq][t] = sm_scale * sum_d

@@ -49,7 +49,7 @@ class kv_stats_t(C.Structure):
                 ("overflow", C.c_int32)]
 
 
-EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append",
+EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append", "kv_compress_append_bf16",
            "kv_k_matvec", "kv_v_matvec", "kv_softmax", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
            "kv_strerror", "kv_fp16_k_matvec", "kv_fp16_v_matvec", "kv_fp16_v_workspace_bytes",
            "kv_stream_read", "kv_page_pool_state_bytes", "kv_page_pool_create", "kv_page_pool_destroy",
@@ -84,6 +84,7 @@ def lib():
                                             C.POINTER(kv_sizes_t), C.POINTER(vp)]
         L.kv_cache_release.argtypes = [vp, vp]
         L.kv_compress_append.argtypes = [vp, vp, vp, i32, vp]
+        L.kv_compress_append_bf16.argtypes = [vp, vp, vp, i32, vp]
         L.kv_k_matvec.argtypes = [vp, vp, f32, vp, i64, vp]
         L.kv_v_matvec.argtypes = [vp, vp, i64, vp, vp]
         L.kv_decode_attention.argtypes = [vp, vp, f32, vp, vp]
@@ -233,10 +234,14 @@ class PackedKVCache:
         return int(lib().kv_cache_tokens(self.handle))
 
     def kv_compress_append(self, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
-        """k_new, v_new: fp16 [B, n, H_kv, 128] contiguous device tensors."""
-        assert k_new.dtype == torch.float16 and v_new.dtype == torch.float16
+        """k_new, v_new: fp16 (or both bf16: kv_compress_append_bf16) [B, n, H_kv, 128] contiguous device tensors."""
+        assert k_new.dtype == v_new.dtype and k_new.dtype in (torch.float16, torch.bfloat16)
         assert k_new.is_contiguous() and v_new.is_contiguous() and k_new.shape == v_new.shape
         assert k_new.shape[0] == self.batch and tuple(k_new.shape[2:]) == (self.n_kv_heads, HEAD_DIM)
+        if k_new.dtype == torch.bfloat16:
+            _check(lib().kv_compress_append_bf16(self.handle, k_new.data_ptr(), v_new.data_ptr(),
+                                                 k_new.shape[1], _stream_ptr(stream)), "kv_compress_append_bf16")
+            return
         _check(lib().kv_compress_append(self.handle, k_new.data_ptr(), v_new.data_ptr(),
                                         k_new.shape[1], _stream_ptr(stream)), "kv_compress_append")
 

@@ -246,7 +246,7 @@ namespace {
 
 // Compress `n_blocks` full blocks whose tokens start at `src` (batch 0).
 int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t batch_stride,
-                    int n_blocks, hipStream_t s) {
+                    int n_blocks, bool bf16, hipStream_t s) {
     const int B = c->cfg.batch, H = c->cfg.n_kv_heads;
     const int per_round = std::max(1, MAX_NEW_CHUNKS / (B * H));
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
@@ -261,6 +261,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         job.first_token = c->packed_tokens;
         job.first_chunk = c->packed_tokens / N * B * H;
         job.order = nullptr;
+        job.bf16 = bf16;
         CompressJob kjob = job, vjob = job;
         kjob.src = ksrc + int64_t(done) * N * job.token_stride;
         kjob.rel = c->cfg.k_rel_scale;
@@ -302,8 +303,11 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
 
 }  // namespace
 
-extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *v_new, int32_t n_new,
-                                  void *hip_stream) {
+namespace {
+
+// bf16: the new tokens are bf16 values; they enter as their fp16 roundings (the tail stores fp16).
+int append_tokens(kv_cache_t *c, const void *k_new, const void *v_new, int32_t n_new, bool bf16,
+                  void *hip_stream) {
     if (!c || n_new < 0) return KV_ERR_ARG;
     if (n_new == 0) return KV_OK;
     if (!k_new || !v_new) return KV_ERR_ARG;
@@ -323,27 +327,39 @@ extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *
 
     if (c->tail_tokens > 0 || remaining < N) {
         const int take = int(std::min<int64_t>(remaining, N - c->tail_tokens));
-        if ((rc = launch_tail_copy(c, ksrc, vsrc, src_batch_stride, take, c->tail_tokens, s))) return rc;
+        if ((rc = launch_tail_copy(c, ksrc, vsrc, src_batch_stride, take, c->tail_tokens, bf16, s))) return rc;
         c->tail_tokens += take;
         pos += take;
         remaining -= take;
         if (c->tail_tokens == N) {
-            if ((rc = compress_blocks(c, ktail, vtail, int64_t(c->cfg.tail_capacity) * row, 1, s))) return rc;
+            if ((rc = compress_blocks(c, ktail, vtail, int64_t(c->cfg.tail_capacity) * row, 1, false, s))) return rc;
             c->tail_tokens = 0;
         }
     }
     const int full = int(remaining / N);
     if (full > 0) {
-        if ((rc = compress_blocks(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, full, s))) return rc;
+        if ((rc = compress_blocks(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, full, bf16, s))) return rc;
         pos += int64_t(full) * N;
         remaining -= int64_t(full) * N;
     }
     if (remaining > 0) {
-        if ((rc = launch_tail_copy(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, int(remaining), 0, s)))
+        if ((rc = launch_tail_copy(c, ksrc + pos * row, vsrc + pos * row, src_batch_stride, int(remaining), 0, bf16, s)))
             return rc;
         c->tail_tokens = int(remaining);
     }
     return KV_OK;
+}
+
+}  // namespace
+
+extern "C" int kv_compress_append(kv_cache_t *c, const void *k_new, const void *v_new, int32_t n_new,
+                                  void *hip_stream) {
+    return append_tokens(c, k_new, v_new, n_new, false, hip_stream);
+}
+
+extern "C" int kv_compress_append_bf16(kv_cache_t *c, const void *k_new, const void *v_new, int32_t n_new,
+                                       void *hip_stream) {
+    return append_tokens(c, k_new, v_new, n_new, true, hip_stream);
 }
 
 extern "C" int kv_k_matvec(kv_cache_t *c, const void *q, float sm_scale, float *scores,

@@ -222,6 +222,7 @@ namespace packkv {
 
 struct CompressJob {
     const __half *src;        // first token of the first block, batch 0
+    bool bf16;                // src holds bf16 values (read as their fp16 roundings); else fp16
     int64_t batch_stride;     // elements
     int64_t token_stride;     // elements (= H*128)
     int n_blocks;             // blocks of 64 tokens to compress
@@ -247,7 +248,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s);
 int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *k_meta, uint8_t *order,
                           hipStream_t s);
 int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t src_batch_stride,
-                     int n, int tail_pos, hipStream_t s);
+                     int n, int tail_pos, bool bf16, hipStream_t s);
 int launch_init(const kv_cache *c, hipStream_t s);
 int launch_pool_init(const kv_page_pool *pool, hipStream_t s);
 // Gives the pages of both tensors back to the pool and empties the page lists.

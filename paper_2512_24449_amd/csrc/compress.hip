@@ -18,18 +18,36 @@
 
 namespace packkv {
 
+// Eight consecutive input values as fp16.  fp16 inputs pass as they are; bf16 inputs are rounded
+// to fp16 (to nearest even; exact for every value in fp16's normal range, fp16 having the longer
+// significand) -- from there on the path does not know the input type.
+__device__ inline uint4 load8_as_fp16(const __half *p, bool bf16) {
+    uint4 raw = *reinterpret_cast<const uint4 *>(p);
+    if (bf16) {
+        uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const __half lo = __float2half_rn(__uint_as_float(w[k] << 16));
+            const __half hi = __float2half_rn(__uint_as_float(w[k] & 0xFFFF0000u));
+            w[k] = uint32_t(__half_as_ushort(lo)) | (uint32_t(__half_as_ushort(hi)) << 16);
+        }
+        raw = make_uint4(w[0], w[1], w[2], w[3]);
+    }
+    return raw;
+}
+
 // ---------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void token_params_kernel(const __half *__restrict__ src,
                                                            int64_t batch_stride,
                                                            int64_t token_stride, int row_elems,
                                                            float rel, uint32_t *__restrict__ meta,
                                                            int64_t meta_stride,
-                                                           int64_t first_token) {
+                                                           int64_t first_token, bool bf16) {
     const int t = blockIdx.x, b = blockIdx.y;
     const __half *row = src + b * batch_stride + t * token_stride;
     float mn = INFINITY, mx = -INFINITY;
     for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
-        uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+        uint4 raw = load8_as_fp16(row + i, bf16);
         const __half *h = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
@@ -148,7 +166,7 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     const uint32_t *__restrict__ index,
                                                     int index_words,
                                                     uint8_t *__restrict__ arena,
-                                                    const uint8_t *__restrict__ order) {
+                                                    const uint8_t *__restrict__ order, bool bf16) {
     static_assert(!WIDE || PK == 8, "wide chunks have packs of 8 tokens");
     constexpr int NPACKS = N / PK * D;
     constexpr int HDR = WIDE ? 2 * NPACKS : NPACKS;  // header bytes
@@ -184,8 +202,7 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
         for (int pass = 0; pass < 4; ++pass) {
             const int row = pass * 16 + (tau >> 4), c8 = (tau & 15) * 8;
             const int src_row = ord ? ord[row] : row;
-            *reinterpret_cast<uint4 *>(tile + row * D + c8) =
-                *reinterpret_cast<const uint4 *>(x_blk + src_row * token_stride + c8);
+            *reinterpret_cast<uint4 *>(tile + row * D + c8) = load8_as_fp16(x_blk + src_row * token_stride + c8, bf16);
         }
     }
     __syncthreads();
@@ -482,13 +499,15 @@ __global__ __launch_bounds__(64) void release_pages_kernel(uint32_t *k_list, uin
 // New tokens of both tensors into their raw tails: blockIdx.z = 0 copies K, 1 copies V.
 __global__ void tail_copy_kernel(const uint4 *__restrict__ ksrc, const uint4 *__restrict__ vsrc,
                                  int64_t src_batch_stride16, uint4 *__restrict__ kdst,
-                                 uint4 *__restrict__ vdst, int64_t dst_batch_stride16, int64_t n16) {
+                                 uint4 *__restrict__ vdst, int64_t dst_batch_stride16, int64_t n16,
+                                 bool bf16) {
     const int b = blockIdx.y;
     const uint4 *src = blockIdx.z ? vsrc : ksrc;
     uint4 *dst = blockIdx.z ? vdst : kdst;
     for (int64_t i = blockIdx.x * int64_t(blockDim.x) + threadIdx.x; i < n16;
          i += int64_t(gridDim.x) * blockDim.x)
-        dst[b * dst_batch_stride16 + i] = src[b * src_batch_stride16 + i];
+        dst[b * dst_batch_stride16 + i] =
+            load8_as_fp16(reinterpret_cast<const __half *>(src + b * src_batch_stride16 + i), bf16);
 }
 
 __global__ void init_kernel(uint32_t *status, uint32_t *k_index, uint32_t *v_index, uint32_t *k_pages,
@@ -508,7 +527,7 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
                                                            int row_elems, int qmax,
                                                            const uint32_t *__restrict__ meta,
                                                            int64_t meta_stride, int64_t first_token,
-                                                           uint8_t *__restrict__ keys) {
+                                                           uint8_t *__restrict__ keys, bool bf16) {
     __shared__ int hist[256];
     const int t = blockIdx.x, b = blockIdx.y;
     hist[threadIdx.x] = 0;
@@ -518,7 +537,7 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
     if (qmax > 15) {
         // codes up to 255: count straight into the LDS histogram
         for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
-            uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+            uint4 raw = load8_as_fp16(row + i, bf16);
             const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
             for (int k = 0; k < 8; ++k) atomicAdd(&hist[quantize_value(__half2float(hv[k]), mt, qmax)], 1);
@@ -527,7 +546,7 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
         // sixteen 8-bit counters in two words; a thread sees at most 8 * ceil(row_elems / 2048) values
         uint64_t lo = 0, hi = 0;
         for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
-            uint4 raw = *reinterpret_cast<const uint4 *>(row + i);
+            uint4 raw = load8_as_fp16(row + i, bf16);
             const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
@@ -609,7 +628,7 @@ int launch_release_pages(const kv_cache *c, hipStream_t s) {
 }
 
 int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t src_batch_stride,
-                     int n, int tail_pos, hipStream_t s) {
+                     int n, int tail_pos, bool bf16, hipStream_t s) {
     const int64_t row = int64_t(c->cfg.n_kv_heads) * D;  // elements per token
     const int64_t n16 = n * row / 8;
     if (n16 == 0) return KV_OK;
@@ -620,7 +639,7 @@ int launch_tail_copy(const kv_cache *c, const __half *ksrc, const __half *vsrc, 
                        reinterpret_cast<const uint4 *>(ksrc), reinterpret_cast<const uint4 *>(vsrc),
                        src_batch_stride / 8, reinterpret_cast<uint4 *>(ktail + int64_t(tail_pos) * row),
                        reinterpret_cast<uint4 *>(vtail + int64_t(tail_pos) * row),
-                       int64_t(c->cfg.tail_capacity) * row / 8, n16);
+                       int64_t(c->cfg.tail_capacity) * row / 8, n16, bf16);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }
@@ -631,7 +650,7 @@ int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s
     if (n_tokens <= 0) return KV_ERR_ARG;
     hipLaunchKernelGGL(token_params_kernel, dim3(n_tokens, B), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, H * D, job.rel, job.meta,
-                       c->max_tokens, job.first_token);
+                       c->max_tokens, job.first_token, job.bf16);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }
@@ -643,7 +662,7 @@ int launch_v_median_order(const kv_cache *c, const CompressJob &vjob, uint32_t *
     if (n_tokens <= 0 || H * D / 2048 + 1 > 31) return KV_ERR_ARG;  // 8-bit per-thread counters
     hipLaunchKernelGGL(v_median_key_kernel, dim3(n_tokens, B), dim3(256), 0, s, vjob.src,
                        vjob.batch_stride, vjob.token_stride, H * D, vjob.qmax, vjob.meta,
-                       c->max_tokens, vjob.first_token, order);
+                       c->max_tokens, vjob.first_token, order, vjob.bf16);
     hipLaunchKernelGGL(block_order_kernel, dim3(vjob.n_blocks, B), dim3(64), 0, s, order, vjob.qmax,
                        k_meta, vjob.meta, c->max_tokens, vjob.first_token);
     KV_HIP_CHECK(hipGetLastError());
@@ -663,7 +682,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                        job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                       job.order);
+                       job.order, job.bf16);
     if (c->pool)
         hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
                            job.first_chunk, job.page_list, job.max_pages, c->pool->state, job.status);
@@ -673,7 +692,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                        job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                        job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                       job.order);
+                       job.order, job.bf16);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

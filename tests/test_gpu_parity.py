@@ -387,3 +387,59 @@ def test_non_finite_inputs_keep_the_format_valid(kw):
     cache.kv_decode_attention(q.cuda(), 0.1)
     torch.cuda.synchronize()
     cache.close()
+
+
+@pytest.mark.parametrize("kw", [dict(), dict(pack_size=8, k_rel_scale=0.05, v_rel_scale=1 / 255),
+                                dict(repack=binding.REPACK_V_MEDIAN)])
+def test_bf16_inputs_enter_as_their_fp16_roundings(kw):
+    """kv_compress_append_bf16: packed bytes, index, token metadata, raw tail and every result are
+    bitwise those of kv_compress_append on the inputs rounded to fp16 -- and those are compared
+    with the oracle.  The values include magnitudes below fp16's normal range (rounded in its
+    subnormal grid) and bf16 values that fp16 holds exactly."""
+    B, H, Hq, L = 2, 3, 6, 64 * 5 + 23
+    g = torch.Generator().manual_seed(808)
+    K = torch.randn(B, L, H, 128, generator=g)
+    V = torch.randn(B, L, H, 128, generator=g) * 0.3
+    K[:, ::7] *= 1e-5                      # tokens of tiny magnitudes: fp16 subnormals
+    V[0, 5] = 0.0
+    Kb, Vb = K.to(torch.bfloat16), V.to(torch.bfloat16)
+    Kh, Vh = Kb.to(torch.float16), Vb.to(torch.float16)
+    assert not torch.equal(Kh.float(), Kb.float()), "some values are meant to round"
+    q = torch.randn(B, Hq, 128, generator=g).to(torch.float16)
+    pieces = [70, 64, 1, 190, 18]
+    caches = []
+    for Kx, Vx in ((Kb, Vb), (Kh, Vh)):
+        cache = binding.PackedKVCache(B, H, Hq, L, **kw)
+        pos = 0
+        for n in pieces:
+            cache.kv_compress_append(Kx[:, pos:pos + n].contiguous().cuda(), Vx[:, pos:pos + n].contiguous().cuda())
+            pos += n
+        caches.append(cache)
+    a, b = caches
+    sa, sb = a.kv_cache_stats(), b.kv_cache_stats()
+    assert (sa.k_bytes, sa.v_bytes, sa.packed_tokens, sa.tail_tokens) == (sb.k_bytes, sb.v_bytes, sb.packed_tokens, sb.tail_tokens)
+    n_chunks = sa.n_chunks
+    for name, n in (("k_arena", sa.k_bytes), ("v_arena", sa.v_bytes), ("k_index", 4 * (n_chunks + 1)),
+                    ("v_index", 4 * (n_chunks + 1)), ("k_token_meta", None), ("v_token_meta", None)):
+        ta, tb = a.tensors[name], b.tensors[name]
+        if name.endswith("token_meta"):
+            mt = ta.numel() // 4 // B
+            ta, tb = ta.view(torch.int32).view(B, mt)[:, :sa.packed_tokens], tb.view(torch.int32).view(B, mt)[:, :sa.packed_tokens]
+        else:
+            ta, tb = ta[:n], tb[:n]
+        assert torch.equal(ta, tb), name
+    tail_elems = sa.tail_tokens * H * 128
+    for name in ("k_tail", "v_tail"):
+        ta = a.tensors[name].view(torch.float16).view(B, 64 * H * 128)[:, :tail_elems]
+        tb = b.tensors[name].view(torch.float16).view(B, 64 * H * 128)[:, :tail_elems]
+        assert torch.equal(ta, tb), name
+    qd = q.cuda()
+    for fn in (lambda c: c.kv_k_matvec(qd, 0.09), lambda c: c.kv_decode_attention(qd, 0.09)):
+        assert torch.equal(fn(a), fn(b))
+    # and against the oracle on the rounded values
+    if not kw.get("repack"):
+        n_packed, ck, cv = gpu_cases.oracle_cache(Kh.numpy(), Vh.numpy(), kw.get("k_rel_scale", 0.1),
+                                                  kw.get("v_rel_scale", 0.2), kw.get("pack_size", 16))
+        gpu_cases.check_packed_state(a, n_packed, ck, cv, B, H)
+    a.close()
+    b.close()
