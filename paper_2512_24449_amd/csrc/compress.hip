@@ -126,9 +126,15 @@ __device__ inline PackBits make_pack(const __half *tile, int g, int d, const flo
     int range = hi - lo;
     pb.w = range == 0 ? 0 : 32 - __clz(range);
     pb.m = lo;
-    pb.bits = 0;
+    // two halves of PK/2 codes, at most 32 bits each, built with 32-bit shift-and-or steps from
+    // the top code down; one 64-bit shift joins them
+    uint32_t half_lo = 0, half_hi = 0;
 #pragma unroll
-    for (int i = 0; i < PK; ++i) pb.bits |= uint64_t(q[i] - lo) << (i * pb.w);
+    for (int i = PK / 2 - 1; i >= 0; --i) {
+        half_lo = (half_lo << pb.w) | uint32_t(q[i] - lo);
+        half_hi = (half_hi << pb.w) | uint32_t(q[PK / 2 + i] - lo);
+    }
+    pb.bits = uint64_t(half_lo) | (uint64_t(half_hi) << (PK / 2 * pb.w));
     return pb;
 }
 
