@@ -415,7 +415,7 @@ def run_compress(w, K, V, torch, binding):
     return {"prompt_ms": round(ms, 3), "fp16_input_gbps": round(in_bytes / (ms * 1e-3) / 1e9, 1),
             "pct_hbm_peak_on_input": round(100.0 * in_bytes / (ms * 1e-3) / 8e12, 2),
             "tail_flush_ms": round(flush_ms, 4),
-            "note": "quantizes every value twice (sizes pass, write pass) with an IEEE divide each: bound by that, not by HBM"}
+            "note": "quantizes every value twice (sizes pass, write pass): bound by that arithmetic, not by HBM"}
 
 
 def run_repack(w, torch, binding, synth):

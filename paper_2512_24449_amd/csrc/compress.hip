@@ -91,33 +91,44 @@ struct PackBits {
     int w, m;
 };
 
-// Token-wise quantization of one value (Sec. III-B.2) with the token's scale and minimum.
-__device__ inline int quantize_value(float x, float s, float mn, int qmax) {
+// Token-wise quantization of one value (Sec. III-B.2) with the token's scale and minimum:
+// clamp(rint(fl((x - mn) / s)), 0, qmax), the quotient rounded to fp32 as an IEEE divide does.
+// r is the token's 1 / s from an IEEE divide (once per token).  The product (x - mn) * r lies
+// within 1.5 * 2^-23 relative of that rounded quotient (half an ulp for r, half for the product,
+// half for the quotient's own rounding), which is below 5e-5 in absolute terms for every quotient
+// that is not clamped anyway (<= 256.5; beyond that both round to at least 256 > qmax).  So unless
+// the product is within 1e-3 of a rounding tie k + 0.5, rint of the product IS rint of the
+// quotient; the rare value near a tie takes the divide.
+__device__ inline int quantize_value(float x, float s, float mn, float r, int qmax) {
     int v = 0;
     if (s != 0.0f) {
-        float ratio = (x - mn) / s;  // IEEE fp32 divide
-        float r = rintf(ratio);      // ties to even
-        v = (int)r;
+        const float a = x - mn;
+        const float q1 = a * r;
+        float t = rintf(q1);  // ties to even
+        if (fabsf(fabsf(q1 - t) - 0.5f) < 1e-3f) t = rintf(a / s);  // IEEE fp32 divide
+        v = (int)t;
         v = v < 0 ? 0 : (v > qmax ? qmax : v);
     }
     return v;
 }
-// The same from the stored token metadata word (fp16 scale | fp16 minimum << 16).
-__device__ inline int quantize_value(float x, uint32_t mt, int qmax) {
-    return quantize_value(x, __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu))),
-                          __half2float(__ushort_as_half(uint16_t(mt >> 16))), qmax);
+
+// A token's (scale, minimum, 1 / scale) from its metadata word (fp16 scale | fp16 minimum << 16).
+__device__ inline float4 token_scale_min(uint32_t mt) {
+    const float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+    return make_float4(s, mn, s != 0.0f ? 1.0f / s : 0.0f, 0.0f);
 }
 
 // tile: the block's 64 x 128 values in LDS, rows already in storage order; the pack holds rows
-// PK*g..PK*g+PK-1 of channel d; sm: (scale, minimum) of the block's 64 tokens (storage order), in LDS.
+// PK*g..PK*g+PK-1 of channel d; sm: token_scale_min of the block's 64 tokens (storage order), in LDS.
 template <int PK>
-__device__ inline PackBits make_pack(const __half *tile, int g, int d, const float2 *sm, int qmax) {
+__device__ inline PackBits make_pack(const __half *tile, int g, int d, const float4 *sm, int qmax) {
     int q[PK];
     int lo = 255, hi = 0;
 #pragma unroll
     for (int i = 0; i < PK; ++i) {
-        const float2 t = sm[g * PK + i];
-        const int v = quantize_value(__half2float(tile[(g * PK + i) * D + d]), t.x, t.y, qmax);
+        const float4 t = sm[g * PK + i];
+        const int v = quantize_value(__half2float(tile[(g * PK + i) * D + d]), t.x, t.y, t.z, qmax);
         q[i] = v;
         lo = min(lo, v);
         hi = max(hi, v);
@@ -195,12 +206,8 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
     // stage the block's 64 x 128 values in LDS with 16-byte loads, rows in storage order, and the
     // tokens' scales and minimums as floats (every thread needs all 64 of them)
     __shared__ __attribute__((aligned(16))) __half tile[N * D];
-    __shared__ float2 sm[N];
-    if (tau < N) {
-        const uint32_t mt = meta[b * meta_stride + first_token + int64_t(blk) * N + tau];
-        sm[tau] = make_float2(__half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu))),
-                              __half2float(__ushort_as_half(uint16_t(mt >> 16))));
-    }
+    __shared__ float4 sm[N];
+    if (tau < N) sm[tau] = token_scale_min(meta[b * meta_stride + first_token + int64_t(blk) * N + tau]);
     {
         const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D;
         const uint8_t *ord = order ? order + b * meta_stride + first_token + int64_t(blk) * N : nullptr;
@@ -539,14 +546,14 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
     hist[threadIdx.x] = 0;
     __syncthreads();
     const __half *row = src + b * batch_stride + t * token_stride;
-    const uint32_t mt = meta[b * meta_stride + first_token + t];
+    const float4 tsm = token_scale_min(meta[b * meta_stride + first_token + t]);
     if (qmax > 15) {
         // codes up to 255: count straight into the LDS histogram
         for (int i = threadIdx.x * 8; i < row_elems; i += 256 * 8) {
             uint4 raw = load8_as_fp16(row + i, bf16);
             const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
-            for (int k = 0; k < 8; ++k) atomicAdd(&hist[quantize_value(__half2float(hv[k]), mt, qmax)], 1);
+            for (int k = 0; k < 8; ++k) atomicAdd(&hist[quantize_value(__half2float(hv[k]), tsm.x, tsm.y, tsm.z, qmax)], 1);
         }
     } else {
         // sixteen 8-bit counters in two words; a thread sees at most 8 * ceil(row_elems / 2048) values
@@ -556,7 +563,7 @@ __global__ __launch_bounds__(256) void v_median_key_kernel(const __half *__restr
             const __half *hv = reinterpret_cast<const __half *>(&raw);
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
-                const int v = quantize_value(__half2float(hv[k]), mt, qmax);
+                const int v = quantize_value(__half2float(hv[k]), tsm.x, tsm.y, tsm.z, qmax);
                 const uint64_t one = 1ull << (8 * (v & 7));
                 if (v < 8) lo += one; else hi += one;
             }
