@@ -206,6 +206,24 @@ int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores,
 int kv_v_matvec(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
 
 /*
+ * kv_v_matvec for callers that cannot allocate device memory or hand over a
+ * workspace for the call: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels, same result
+ * (bitwise, as long as the split count is not lowered, see below); the per-split
+ * partial sums go to a fixed array inside the library (KV_NOALLOC_MAX_SPLIT_ROWS
+ * rows of 132 floats, about 4.3 MB, held by every GPU the library runs on until
+ * the process ends) instead of the cache's workspace.  The call allocates and
+ * frees nothing.  The context axis is split over at most
+ * KV_NOALLOC_MAX_SPLIT_ROWS / (batch * n_q_heads) workgroups per stream;
+ * KV_ERR_CAPACITY if batch * n_q_heads exceeds KV_NOALLOC_MAX_SPLIT_ROWS.
+ * All calls on one GPU share the array: calls that overlap on one GPU (other
+ * streams, other caches, other threads) race and give wrong results; calls on
+ * one stream are ordered and safe.
+ */
+#define KV_NOALLOC_MAX_SPLIT_ROWS 8192
+int kv_v_matvec_noalloc(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
+
+/*
  * Row softmax between the two matvecs (smx in the attention definition of
  * Sec. III-B.3), in place: scores[b][hq][0..tokens) <- softmax over the cached
  * tokens, for every (b, hq); entries [tokens, ld_scores) are left alone.

@@ -50,7 +50,7 @@ class kv_stats_t(C.Structure):
 
 
 EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append", "kv_compress_append_bf16",
-           "kv_k_matvec", "kv_v_matvec", "kv_softmax", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
+           "kv_k_matvec", "kv_v_matvec", "kv_v_matvec_noalloc", "kv_softmax", "kv_decode_attention", "kv_cache_stats", "kv_cache_restore", "kv_cache_tokens",
            "kv_strerror", "kv_fp16_k_matvec", "kv_fp16_v_matvec", "kv_fp16_v_workspace_bytes",
            "kv_stream_read", "kv_page_pool_state_bytes", "kv_page_pool_create", "kv_page_pool_destroy",
            "kv_page_pool_free_pages", "kv_query_sizes_paged", "kv_cache_create_paged", "kv_cache_release")
@@ -87,6 +87,7 @@ def lib():
         L.kv_compress_append_bf16.argtypes = [vp, vp, vp, i32, vp]
         L.kv_k_matvec.argtypes = [vp, vp, f32, vp, i64, vp]
         L.kv_v_matvec.argtypes = [vp, vp, i64, vp, vp]
+        L.kv_v_matvec_noalloc.argtypes = [vp, vp, i64, vp, vp]
         L.kv_decode_attention.argtypes = [vp, vp, f32, vp, vp]
         L.kv_softmax.argtypes = [vp, vp, i64, vp]
         L.kv_cache_stats.argtypes = [vp, C.POINTER(kv_stats_t), vp]
@@ -266,6 +267,16 @@ class PackedKVCache:
                               device=self.device)
         _check(lib().kv_v_matvec(self.handle, p.data_ptr(), p.shape[2], out.data_ptr(),
                                  _stream_ptr(stream)), "kv_v_matvec")
+        return out
+
+    def kv_v_matvec_noalloc(self, p: torch.Tensor, out: torch.Tensor, stream=None):
+        """As kv_v_matvec, through the entry point that allocates nothing; `out` is the caller's."""
+        assert p.dtype == torch.float32 and p.is_contiguous()
+        assert tuple(p.shape[:2]) == (self.batch, self.n_q_heads)
+        assert out.dtype == torch.float32 and out.is_contiguous()
+        assert tuple(out.shape) == (self.batch, self.n_q_heads, HEAD_DIM)
+        _check(lib().kv_v_matvec_noalloc(self.handle, p.data_ptr(), p.shape[2], out.data_ptr(),
+                                         _stream_ptr(stream)), "kv_v_matvec_noalloc")
         return out
 
     def kv_softmax(self, scores: torch.Tensor, stream=None):

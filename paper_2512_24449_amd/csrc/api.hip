@@ -377,6 +377,12 @@ extern "C" int kv_v_matvec(kv_cache_t *c, const float *p, int64_t ld_p, float *o
     return launch_v_matvec(c, p, ld_p, out, static_cast<hipStream_t>(hip_stream));
 }
 
+extern "C" int kv_v_matvec_noalloc(kv_cache_t *c, const float *p, int64_t ld_p, float *out, void *hip_stream) {
+    if (!c || !p || !out) return KV_ERR_ARG;
+    if (ld_p < c->packed_tokens + c->tail_tokens) return KV_ERR_ARG;
+    return launch_v_matvec_noalloc(c, p, ld_p, out, static_cast<hipStream_t>(hip_stream));
+}
+
 extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale, float *out,
                                    void *hip_stream) {
     if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;

@@ -256,6 +256,7 @@ int launch_release_pages(const kv_cache *c, hipStream_t s);
 int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *scores,
                     int64_t ld_scores, hipStream_t s);
 int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s);
+int launch_v_matvec_noalloc(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s);
 int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, float *out, hipStream_t s);
 
 }  // namespace packkv

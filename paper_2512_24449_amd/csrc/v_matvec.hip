@@ -17,6 +17,7 @@
 // De-quantization is folded in:
 //   out_d = sum_t w_t code[t,d] + sum_g m[g,d] sum_{t in g} w_t + sum_t p_t min_t
 #include <algorithm>
+#include <mutex>
 
 #include "pack8.h"
 #include "v_chunk.h"
@@ -272,16 +273,19 @@ int v_splits_for(int n_blocks, int streams) {
     return int(s);
 }
 
-int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s) {
+// partial: [splits][B * H_q][V_PART_STRIDE] floats for the split sums; max_split_rows: how many
+// such rows it can take (the split count is lowered to fit).
+static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p, float *out, float *partial,
+                                int64_t max_split_rows, hipStream_t s) {
     // Hs: kv-heads as the stream kernels count them (each dup times, see head_split); the combine
     // kernel works per query head and sees the real kv-head count and the whole group
     const int B = c->cfg.batch, H = c->cfg.n_kv_heads, G = c->group, Hs = H * c->head_split, Gq = G * c->head_split;
     const int n_blocks = int(c->packed_tokens / N);
-    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
-    float *partial = reinterpret_cast<float *>(ws + WS_VPART);
+    const int64_t rows = int64_t(B) * H * Gq;
+    if (rows > max_split_rows) return KV_ERR_CAPACITY;
     int n_splits = 0;
     if (n_blocks > 0) {
-        n_splits = v_splits_for(n_blocks, B * Hs);
+        n_splits = int(std::min<int64_t>(v_splits_for(n_blocks, B * Hs), max_split_rows / rows));
         VArgs a;
         a.arena = static_cast<const uint8_t *>(c->buf.v_arena);
         a.index = static_cast<const uint32_t *>(c->buf.v_index);
@@ -318,6 +322,45 @@ int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out,
                        c->cfg.tail_capacity, H, Gq, out);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
+}
+
+int launch_v_matvec(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s) {
+    uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
+    return launch_v_matvec_into(c, p, ld_p, out, reinterpret_cast<float *>(ws + WS_VPART),
+                                int64_t(V_SPLITS_MAX) * c->cfg.batch * c->cfg.n_q_heads, s);
+}
+
+// ---- the V product for callers that cannot allocate ------------------------------------------
+// The split sums go to a file-scope device array instead of the caller's workspace.  Every GPU
+// the library runs on holds its own copy of the array (at its own address) until the process
+// ends; the address is looked up once per device, with that device current, and kept.
+static __device__ __align__(256) float scratch[size_t(KV_NOALLOC_MAX_SPLIT_ROWS) * V_PART_STRIDE];
+
+static int scratch_of_current_device(float **out) {
+    constexpr int MAX_DEVICES = 64;
+    static float *ptr_of_device[MAX_DEVICES];
+    static std::mutex lock;
+    int dev = -1;
+    KV_HIP_CHECK(hipGetDevice(&dev));
+    if (dev < 0 || dev >= MAX_DEVICES) return KV_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> guard(lock);
+    if (!ptr_of_device[dev]) {
+        float *p = nullptr;
+        KV_HIP_CHECK(hipGetSymbolAddress(reinterpret_cast<void **>(&p), HIP_SYMBOL(scratch)));
+        if (!p) return KV_ERR_HIP;
+        ptr_of_device[dev] = p;
+    }
+    *out = ptr_of_device[dev];
+    return KV_OK;
+}
+
+int launch_v_matvec_noalloc(const kv_cache *c, const float *p, int64_t ld_p, float *out, hipStream_t s) {
+    float *partial = nullptr;
+    const int rc = scratch_of_current_device(&partial);
+    if (rc != KV_OK) return rc;
+    // every split row that the combine kernel reads is written in full by the stream kernel of
+    // the same call: nothing in the array has to start at zero
+    return launch_v_matvec_into(c, p, ld_p, out, partial, KV_NOALLOC_MAX_SPLIT_ROWS, s);
 }
 
 }  // namespace packkv
