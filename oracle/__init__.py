@@ -57,6 +57,7 @@ def lib():
         _lib.orc_xhat.argtypes = [C.c_uint8, C.c_uint16, C.c_uint16]
         _lib.orc_pack_chunk.restype = C.c_int
         _lib.orc_pack_chunk_k.restype = C.c_int
+        _lib.orc_pack_chunk_planes.restype = C.c_int
         _lib.orc_pack_chunk_wide.restype = C.c_int
         _lib.orc_compress.restype = C.c_int64
         _lib.orc_compress_k.restype = C.c_int64
@@ -146,16 +147,25 @@ def pack_chunk_wide(q_chunk):
     return buf[:size].copy(), w, m
 
 
-def pack_chunk(q_chunk, pack_size=K):
+ORDERS = {"group": 0, "channel": 1}
+
+
+def pack_chunk(q_chunk, pack_size=K, order="group", contiguous=False):
     """q_chunk: uint8 [64, 128] -> (bytes uint8 [size], widths [packs], mins [packs]), packs =
-    (64 / pack_size) * 128."""
+    (64 / pack_size) * 128, widths and mins indexed [token_group*128 + channel].  Packs of 16 use
+    the plane layout with the given pack list order ("group" or "channel"); contiguous=True
+    packs them in the contiguous-pack layout instead (the layout of the packs of 8)."""
     q_chunk = np.ascontiguousarray(q_chunk, dtype=np.uint8)
     assert q_chunk.shape == (N, D) and pack_size in (8, 16)
     packs = N // pack_size * D
     buf = np.zeros(packs + N * D // 2 + 16, np.uint8)
     w = np.empty(packs, np.uint8)
     m = np.empty(packs, np.uint8)
-    size = lib().orc_pack_chunk_k(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), pack_size)
+    if pack_size == 16 and not contiguous:
+        size = lib().orc_pack_chunk_planes(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), ORDERS[order])
+    else:
+        assert order == "group"
+        size = lib().orc_pack_chunk_k(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), pack_size)
     return buf[:size].copy(), w, m
 
 
@@ -179,9 +189,11 @@ class Compressed:
         return (self.meta >> 16).astype(np.uint16)
 
 
-def compress(x, rel, pack_size=K) -> Compressed:
+def compress(x, rel, pack_size=K, order="group") -> Compressed:
     """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed (packs of pack_size tokens).
-    Scales finer than 1/15 (codes above 15) give wide chunks and need pack_size 8."""
+    Scales finer than 1/15 (codes above 15) give wide chunks and need pack_size 8.  order: pack
+    list of the chunks with packs of 16 tokens ("group" or "channel"; the cache keeps V
+    group-major and K channel-major)."""
     x = _u16(x)
     B, T, H, Dd = x.shape
     assert Dd == D and T % N == 0 and pack_size in (8, 16)
@@ -196,7 +208,8 @@ def compress(x, rel, pack_size=K) -> Compressed:
     mins = np.empty((nchunks, packs), np.uint8)
     size = lib().orc_compress_k(_p(x), B, T, H, Dd, C.c_int64(T * H * Dd), C.c_int64(H * Dd),
                                 C.c_float(rel), _p(arena), C.c_int64(cap), _p(offsets), _p(meta),
-                                _p(codes), _p(widths), _p(mins), pack_size)
+                                _p(codes), _p(widths), _p(mins), pack_size,
+                                ORDERS[order] if pack_size == 16 else 0)
     assert size >= 0, size
     return Compressed(arena[:size].copy(), offsets, meta, codes, widths, mins)
 

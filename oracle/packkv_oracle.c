@@ -30,15 +30,19 @@
  *     below 16 (rel >= 1/15); for finer scales (codes up to 255, "wide" chunks,
  *     packs of 8 tokens only) it is two bytes: all widths (0..8) first, one
  *     byte per pack, then all minimums (0..255), one byte per pack;
- *   - chunk bytes: (64/k)*128 header bytes indexed [token_group*128 + channel]
- *     (512 for k = 16, 1024 for k = 8), then the packs in the same order, each
- *     k*width/8 bytes little-endian with the code of token i at bits
- *     [i*width, (i+1)*width), zero padded to 16 bytes;
+ *   - chunk bytes, packs of 8: 1024 header bytes indexed [token_group*128 +
+ *     channel], then the packs in the same order, each `width` bytes
+ *     little-endian with the code of token i at bits [i*width, (i+1)*width),
+ *     zero padded to 16 bytes;
+ *   - chunk bytes, packs of 16 (orc_pack_chunk_planes): 512 header bytes, then
+ *     every pack's 16*width bits as two-bit planes and a one-bit plane (a fixed
+ *     order of exactly 16*width bits per pack, Sec. III-B.3), zero padded to 16
+ *     bytes; the packs of a chunk are listed group-major or channel-major;
  *   - repacking (V-median and greedy orders): see the comments of
  *     orc_v_median_order and orc_greedy_order; the median and tie conventions
  *     are "parity unpinned" readings (any order is a valid cache).
  *
- * Parity pins live in tests/test_oracle_*.py; the exact byte order inside a
+ * Parity pins live in tests/test_oracle_pins.py; the exact byte order inside a
  * chunk is "parity unpinned" (the paper's format figures are not available):
  * it is a choice of this build, checked only by an independent bit reader.
  */
@@ -201,8 +205,10 @@ int orc_width(int range)
 }
 
 /*
- * Pack one chunk: the 64 x 128 codes of one (batch, kv-head, block), packs of k
- * tokens (k = 8 or 16).  q points at code (token 0, channel 0); consecutive
+ * Pack one chunk in the contiguous-pack layout: the 64 x 128 codes of one (batch,
+ * kv-head, block), packs of k tokens (k = 8 is the layout of packs of 8 tokens; k = 16
+ * in this layout is kept as a second, plainer statement of the same packs that the
+ * tests compare the plane layout's sizes and metadata with).  q points at code (token 0, channel 0); consecutive
  * tokens are `token_stride` apart.  Writes the chunk bytes (header, payload,
  * zero padding to 16 bytes) and, when not NULL, the logical per-pack widths and
  * minimums [(64/k)*128].  Returns the chunk size in bytes (a multiple of 16).
@@ -275,10 +281,84 @@ int orc_pack_chunk_wide(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
     return pos;
 }
 
+
+/*
+ * Pack one chunk with packs of 16 tokens (the default pack size, Sec. IV-A) in the
+ * plane layout.  The paper fixes what a pack stores -- one minimum, one width w =
+ * ceil(log2(range+1)) and 16 codes of w bits (Sec. III-B.3) -- and that lengths and
+ * minimums come first in the block (Sec. III-C); the order of the 16*w bits is a
+ * choice of this build:
+ *   pack list     order 0 (group-major):   pack p = g*128 + d
+ *                 order 1 (channel-major): pack p = d*4 + g
+ *                 (g = token group of 16 tokens, d = channel)
+ *   bytes [0,512) header, byte p = (w << 4) | min of pack p
+ *   region E      for p = 0..511 in turn: if w >= 2 one little-endian 32-bit word
+ *                 with the low two bits (c & 3) of the 16 codes, and if w == 4 a
+ *                 second word with the high two bits (c >> 2); in both words token i
+ *                 of the pack sits at bits [4i, 4i+2) for i < 8 and at
+ *                 [4(i-8)+2, 4(i-8)+4) for i >= 8
+ *   region O      for p = 0..511 in turn: if w is odd one little-endian 16-bit word
+ *                 with the top bit (c >> (w-1)) of the 16 codes, token i at bit
+ *                 4*(i & 3) + (i >> 2)
+ *   zero padding to a multiple of 16 bytes
+ * so a pack takes 0, 16, 32, 48 or 64 bits for w = 0..4.  widths / mins (optional)
+ * receive the logical per-pack values indexed [g*128 + d] whatever the order.
+ * Returns the chunk size in bytes.
+ */
+int orc_pack_chunk_planes(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
+                          uint8_t *widths, uint8_t *mins, int order)
+{
+    int w_of[ORC_PACKS], lo_of[ORC_PACKS], g_of[ORC_PACKS], d_of[ORC_PACKS];
+    for (int p = 0; p < ORC_PACKS; ++p) {
+        int g = order ? p % ORC_GROUPS : p / ORC_D;
+        int d = order ? p / ORC_GROUPS : p % ORC_D;
+        int lo = 255, hi = 0;
+        for (int i = 0; i < ORC_K; ++i) {
+            int v = q[(int64_t)(g * ORC_K + i) * token_stride + d];
+            if (v < lo) lo = v;
+            if (v > hi) hi = v;
+        }
+        int w = orc_width(hi - lo);
+        g_of[p] = g, d_of[p] = d, w_of[p] = w, lo_of[p] = lo;
+        bytes[p] = (uint8_t)((w << 4) | lo);
+        if (widths) widths[g * ORC_D + d] = (uint8_t)w;
+        if (mins) mins[g * ORC_D + d] = (uint8_t)lo;
+    }
+    int pos = ORC_HEADER;
+    for (int p = 0; p < ORC_PACKS; ++p) {                 /* region E */
+        int w = w_of[p];
+        if (w < 2) continue;
+        uint32_t low = 0, high = 0;
+        for (int i = 0; i < ORC_K; ++i) {
+            uint32_t c = (uint32_t)(q[(int64_t)(g_of[p] * ORC_K + i) * token_stride + d_of[p]] - lo_of[p]);
+            int at = i < 8 ? 4 * i : 4 * (i - 8) + 2;
+            low |= (c & 3u) << at;
+            high |= (c >> 2) << at;
+        }
+        for (int j = 0; j < 4; ++j) bytes[pos++] = (uint8_t)(low >> (8 * j));
+        if (w == 4)
+            for (int j = 0; j < 4; ++j) bytes[pos++] = (uint8_t)(high >> (8 * j));
+    }
+    for (int p = 0; p < ORC_PACKS; ++p) {                 /* region O */
+        int w = w_of[p];
+        if (!(w & 1)) continue;
+        uint32_t top = 0;
+        for (int i = 0; i < ORC_K; ++i) {
+            uint32_t c = (uint32_t)(q[(int64_t)(g_of[p] * ORC_K + i) * token_stride + d_of[p]] - lo_of[p]);
+            top |= ((c >> (w - 1)) & 1u) << (4 * (i & 3) + (i >> 2));
+        }
+        bytes[pos++] = (uint8_t)top;
+        bytes[pos++] = (uint8_t)(top >> 8);
+    }
+    while (pos % 16) bytes[pos++] = 0;
+    return pos;
+}
+
+/* Packs of 16 tokens, group-major pack list. */
 int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
                    uint8_t *widths, uint8_t *mins)
 {
-    return orc_pack_chunk_k(q, token_stride, bytes, widths, mins, ORC_K);
+    return orc_pack_chunk_planes(q, token_stride, bytes, widths, mins, 0);
 }
 
 /*
@@ -287,16 +367,19 @@ int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
  * order, so chunk index c = (block*B + b)*H + h.  offsets16[c] is the start of
  * chunk c in 16-byte units, offsets16[nchunks] the end of the arena.
  * meta[b*T + t] = scale16 | min16 << 16.  q_out (optional) receives the codes,
- * widths_out / mins_out (optional) the per-pack values [nchunks][(64/k)*128].
+ * widths_out / mins_out (optional) the per-pack values [nchunks][(64/k)*128],
+ * indexed [token_group*128 + channel].  order: pack list of the chunks with packs
+ * of 16 (0 group-major, 1 channel-major; see orc_pack_chunk_planes).
  * Returns the arena size in bytes, or -1 if it would exceed arena_cap.
  */
 int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
                        int64_t batch_stride, int64_t token_stride, float rel,
                        uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
                        uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
-                       uint8_t *mins_out, int k)
+                       uint8_t *mins_out, int k, int order)
 {
     if (D != ORC_D || T % ORC_N || (k != 8 && k != 16)) return -2;
+    if (order != 0 && (order != 1 || k != 16)) return -2;  /* the pack list order exists for packs of 16 */
     int wide = orc_qmax(rel) > 15;  /* codes do not fit the 4-bit minimum of the one-byte metadata */
     if (wide && (k != 8 || orc_qmax(rel) > 255)) return -2;
     int packs = ORC_N / k * ORC_D;
@@ -320,7 +403,8 @@ int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
                 uint8_t *wo = widths_out ? widths_out + c * packs : NULL;
                 uint8_t *mo = mins_out ? mins_out + c * packs : NULL;
                 int sz = wide ? orc_pack_chunk_wide(q0, (int64_t)H * D, tmp, wo, mo)
-                              : orc_pack_chunk_k(q0, (int64_t)H * D, tmp, wo, mo, k);
+                         : k == 16 ? orc_pack_chunk_planes(q0, (int64_t)H * D, tmp, wo, mo, order)
+                                   : orc_pack_chunk_k(q0, (int64_t)H * D, tmp, wo, mo, k);
                 if (pos + sz > arena_cap) { rc = -1; break; }
                 memcpy(arena + pos, tmp, (size_t)sz);
                 offsets16[c] = (uint32_t)(pos / 16);
@@ -340,7 +424,7 @@ int64_t orc_compress(const uint16_t *x, int B, int T, int H, int D,
                      uint8_t *mins_out)
 {
     return orc_compress_k(x, B, T, H, D, batch_stride, token_stride, rel, arena, arena_cap,
-                          offsets16, meta, q_out, widths_out, mins_out, ORC_K);
+                          offsets16, meta, q_out, widths_out, mins_out, ORC_K, 0);
 }
 
 /*
