@@ -461,8 +461,8 @@ def cpu_baseline(w, synth, torch):
     K, V, q = synth.make_kv(B, L, w.n_kv_heads, w.n_q_heads, 7)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     t0 = time.perf_counter()
-    ck = oracle.compress(Kn, 0.1)
-    cv = oracle.compress(Vn, 0.2)
+    ck = oracle.compress_k(Kn, 0.1)
+    cv = oracle.compress_v(Vn, 0.2)
     compress_s = time.perf_counter() - t0
     reps, step_s = 10, 0.0
     for _ in range(reps):

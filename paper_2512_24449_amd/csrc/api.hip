@@ -15,11 +15,14 @@ namespace {
 
 bool aligned256(const void *p) { return p && (reinterpret_cast<uintptr_t>(p) & 255u) == 0; }
 
-// Query groups above 8 heads run as `split` groups of g / split <= 8 heads over the same kv-head.
-// Returns the smallest such split, 0 if there is none (a prime above 8, or more than 64 heads).
-int head_split_for(int g) {
-    for (int split = 1; split <= 8; ++split)
-        if (g % split == 0 && g / split <= 8) return split;
+// The kernels take up to 4 query heads per kv-head with packs of 16 tokens (the heads of a group
+// times the pieces of their operands fill the 16 rows or columns of a matrix-core tile) and up to
+// 8 with packs of 8.  Larger groups run as `split` groups of g / split heads over the same
+// kv-head.  Returns the smallest such split, 0 if there is none up to 16.
+int head_split_for(int g, int pack_size) {
+    const int most = pack_size == PACK ? 4 : 8;
+    for (int split = 1; split <= 16; ++split)
+        if (g % split == 0 && g / split <= most) return split;
     return 0;
 }
 
@@ -32,7 +35,7 @@ int check_config(const kv_config_t *c) {
         return KV_ERR_UNSUPPORTED;
     if (c->n_q_heads % c->n_kv_heads) return KV_ERR_ARG;
     const int g = c->n_q_heads / c->n_kv_heads;
-    if (head_split_for(g) == 0) return KV_ERR_UNSUPPORTED;
+    if (head_split_for(g, c->pack_size) == 0) return KV_ERR_UNSUPPORTED;
     // one pack byte holds a 4-bit minimum: codes above 15 need the wide layout, which exists
     // for packs of 8 tokens only; a code is one byte at most
     for (float rel : {c->k_rel_scale, c->v_rel_scale}) {
@@ -41,7 +44,7 @@ int check_config(const kv_config_t *c) {
         if (qmax > 255) return KV_ERR_UNSUPPORTED;
         if (qmax > 15 && c->pack_size != 8) return KV_ERR_UNSUPPORTED;
     }
-    if (int64_t(c->batch) * c->n_kv_heads * head_split_for(g) > 65535) return KV_ERR_UNSUPPORTED;
+    if (int64_t(c->batch) * c->n_kv_heads * head_split_for(g, c->pack_size) > 65535) return KV_ERR_UNSUPPORTED;
     const int64_t max_tokens = (c->max_tokens + N - 1) / N * N;
     const int64_t max_chunks = max_tokens / N * c->batch * c->n_kv_heads;
     if (max_chunks > 0x7FFFFFF0) return KV_ERR_UNSUPPORTED;
@@ -179,7 +182,7 @@ int create_cache(const kv_config_t *cfg, kv_page_pool *pool, const kv_buffers_t 
     c->sizes = *sizes;
     c->max_tokens = (cfg->max_tokens + N - 1) / N * N;
     c->max_chunks = c->max_tokens / N * cfg->batch * cfg->n_kv_heads;
-    c->head_split = head_split_for(cfg->n_q_heads / cfg->n_kv_heads);
+    c->head_split = head_split_for(cfg->n_q_heads / cfg->n_kv_heads, cfg->pack_size);
     c->group = cfg->n_q_heads / cfg->n_kv_heads / c->head_split;
     c->qmax_k = int(lround(1.0 / double(cfg->k_rel_scale)));
     c->qmax_v = int(lround(1.0 / double(cfg->v_rel_scale)));
@@ -261,12 +264,14 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         job.first_token = c->packed_tokens;
         job.first_chunk = c->packed_tokens / N * B * H;
         job.order = nullptr;
+        job.planes = true;
         job.bf16 = bf16;
         CompressJob kjob = job, vjob = job;
         kjob.src = ksrc + int64_t(done) * N * job.token_stride;
         kjob.rel = c->cfg.k_rel_scale;
         kjob.qmax = c->qmax_k;
         kjob.wide = c->wide_k;
+        kjob.planes = false;
         kjob.arena = static_cast<uint8_t *>(c->buf.k_arena);
         kjob.arena_cap16 = c->sizes.k_arena / 16;
         kjob.index = static_cast<uint32_t *>(c->buf.k_index);

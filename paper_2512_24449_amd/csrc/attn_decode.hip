@@ -22,6 +22,7 @@
 #include "k_chunk.h"
 #include "pack8.h"
 #include "v_chunk.h"
+#include "v_planes.h"
 
 namespace packkv {
 
@@ -94,16 +95,52 @@ __device__ inline void attn_raise_reference(const float (&s)[G], float (&m_ref)[
     }
 }
 
+// The same for the running sums of the plane-layout V phase (v_planes.h): the result tiles hold
+// one digit of one head per column.
+template <int G>
+__device__ inline void attn_raise_reference(const float (&s)[G], float (&m_ref)[G], float (&l_lane)[G],
+                                            VPlaneState<G> &st, int col) {
+    bool raise = false;
+#pragma unroll
+    for (int g = 0; g < G; ++g) raise |= s[g] > m_ref[g] + RAISE_MARGIN;
+    if (__builtin_amdgcn_ballot_w64(raise) != 0) {
+        float alpha_col = 1.0f;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float m_new = __int_as_float(__builtin_amdgcn_readfirstlane(
+                __float_as_int(fmaxf(m_ref[g], wave_all_max(s[g])))));
+            const float alpha = exp2_diff(m_ref[g], m_new);
+            m_ref[g] = m_new;
+            l_lane[g] *= alpha;
+            st.pm[g] *= alpha;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) st.macc[g][j] *= alpha;
+            if (col / v_pieces<G>() == g) alpha_col = alpha;
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.acc[j] *= alpha_col;
+    }
+}
+
+template <int G>
+__device__ inline void attn_store_state(const VState<G> &st, float (*red)[D + 4], int lane, float code_scale) {
+    v_state_store<G>(st, red, lane, code_scale);
+}
+template <int G>
+__device__ inline void attn_store_state(const VPlaneState<G> &st, float (*red)[D + 4], int lane, float) {
+    v_planes_store<G>(st, red, lane);
+}
+
 // End of a fused attention workgroup: merges the four waves' running sums (each with its own
 // softmax reference) and writes the split's partial row.  red aliases the chunk buffers.
-template <int G>
-__device__ inline void attn_store_partial(const AArgs &a, const VState<G> &st, const float (&l_lane)[G],
+template <int G, class State>
+__device__ inline void attn_store_partial(const AArgs &a, const State &st, const float (&l_lane)[G],
                                           const float (&m_ref)[G], float (*red)[G][D + 4], int wave,
                                           int lane, int split, int64_t head0,
                                           float code_scale = CODE_SCALE_LIFTED) {
     __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
 
-    v_state_store<G>(st, red[wave], lane, code_scale);
+    attn_store_state<G>(st, red[wave], lane, code_scale);
 #pragma unroll
     for (int g = 0; g < G; ++g) {
         const float l = wave_all_sum(l_lane[g]);
@@ -131,20 +168,25 @@ __device__ inline void attn_store_partial(const AArgs &a, const VState<G> &st, c
     }
 }
 
-template <int G>
+// HIGH: the V codes of the cache may need four bits (a plane H exists).
+template <int G, bool HIGH>
 __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     // per wave: buffer 0 holds the K chunk, buffer 1 the V chunk of the block in flight; after
     // the main loop the same memory holds the cross-wave reduction array red[4][G][D + 4]
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
-    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
-    __shared__ uint4 table[PACK_TABLE_ENTRIES], vtable[PACK_TABLE_ENTRIES];  // K form, V form (lifted codes)
+    constexpr int VB = vb_bytes<G>();
+    __shared__ __attribute__((aligned(16))) uint8_t vb_all[4 * VB];  // digit staging of the V phase
+    __shared__ uint4 table[PACK_TABLE_ENTRIES];                      // K chunks: contiguous bit fields
+    __shared__ uint4 vtable[PLANE_TABLE_ENTRIES];                    // V chunks: plane layout
+    __shared__ uint32_t vhighs[PLANE_TABLE_ENTRIES];
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
     if constexpr (G == 1)
         build_pair_table(reinterpret_cast<uint2 *>(table));
     else
         build_pack_table(table, 0, fold_min<G>());
-    build_pack_table(vtable, CODE_LIFT, fold_min<G>());
+    for (int i = threadIdx.x; i < 4 * VB / 4; i += 256) reinterpret_cast<uint32_t *>(vb_all)[i] = 0;
+    build_plane_table(vtable, vhighs);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -168,9 +210,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
         for (int g = 0; g < G; ++g)
             qsum[g] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(kqg.qsum[g])));
     }
-    VLane<G> vl;
-    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
-    VState<G> st;
+    uint8_t *vb = vb_all + wave * VB;
+    VPlaneState<G> st;
     st.clear();
     float m_ref[G], l_lane[G];
 #pragma unroll
@@ -214,9 +255,9 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                     float ms_row[G];
                     k_chunk_mfma<G>(lds_all, table, lp, kqg, acc, ms_row);
                     // lane (r, n) holds four consecutive tokens of heads 4r..4r+3: through LDS to lane = token
-                    // the B operand staging of the V phase is idle now and exactly G * 64 floats large
-                    static_assert(BLds<G>::ZERO == int(sizeof(float)) * G * N, "score tile must fit the B staging");
-                    float(*sc)[N] = reinterpret_cast<float(*)[N]>(vl.blds);
+                    // the digit staging of the V phase is idle now; its last row (zeros) stays untouched
+                    static_assert(VB - 64 >= int(sizeof(float)) * G * N, "score tile must fit the digit staging");
+                    float(*sc)[N] = reinterpret_cast<float(*)[N]>(vb);
                     const int tb = k_mfma_token_base(col);
 #pragma unroll
                     for (int x = 0; x < 4; ++x)
@@ -246,7 +287,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
                 pt[g] = exp2f(s[g] - m_ref[g]);
                 l_lane[g] += pt[g];
             }
-            v_chunk<G>(lds_all, vbuf, vtable, vl, vmt, pt, st);
+            v_planes_chunk<G, HIGH>(lds_all, vbuf, vtable, vhighs, vb, vmt, pt, st);
         }
         wait_chunk_landed();
     }
@@ -493,7 +534,8 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
 #define PACKKV_LAUNCH_A8WN(g) hipLaunchKernelGGL((attn8_kernel<g, true, false>), grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_A8NW(g) hipLaunchKernelGGL((attn8_kernel<g, false, true>), grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_A8WW(g) hipLaunchKernelGGL((attn8_kernel<g, true, true>), grid, dim3(256), 0, s, a)
-#define PACKKV_LAUNCH_A(g) hipLaunchKernelGGL(attn_kernel<g>, grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_A(g) hipLaunchKernelGGL((attn_kernel<g, false>), grid, dim3(256), 0, s, a)
+#define PACKKV_LAUNCH_AH(g) hipLaunchKernelGGL((attn_kernel<g, true>), grid, dim3(256), 0, s, a)
             if (c->wide_k && c->wide_v) {
                 PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8WW)
             } else if (c->wide_k) {
@@ -503,14 +545,17 @@ int launch_decode_attention(const kv_cache *c, const __half *q, float sm_scale, 
             } else {
                 PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A8NN)
             }
+        } else if (c->qmax_v > 7) {
+            PACKKV_DISPATCH_GROUP4(G, PACKKV_LAUNCH_AH)
         } else {
-            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_A)
+            PACKKV_DISPATCH_GROUP4(G, PACKKV_LAUNCH_A)
         }
 #undef PACKKV_LAUNCH_A8NN
 #undef PACKKV_LAUNCH_A8WN
 #undef PACKKV_LAUNCH_A8NW
 #undef PACKKV_LAUNCH_A8WW
 #undef PACKKV_LAUNCH_A
+#undef PACKKV_LAUNCH_AH
     }
     hipLaunchKernelGGL(attn_combine_kernel, dim3(B * H * Gq), dim3(256), 0, s, partial, n_splits,
                        B * H * Gq, q, static_cast<const __half *>(c->buf.k_tail),

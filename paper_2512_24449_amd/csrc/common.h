@@ -55,6 +55,19 @@ inline int64_t target_workgroups(int64_t total_blocks) {
     return w < 512 ? 512 : (w > 4096 ? 4096 : w);
 }
 
+// Work list of the kernels that walk chunks in the plane layout: the chunks of all streams in one
+// sequence (stream-major, n_blocks per stream), cut into n_groups equal ranges, one per workgroup.
+// A workgroup that crosses a stream boundary writes one partial row set per stream it touches:
+// the set of workgroup w for stream s has number w + s (unique, below n_groups + streams).
+struct FlatPlan {
+    int n_blocks;    // packed blocks per stream
+    int n_groups;    // workgroups
+    int64_t total;   // streams * n_blocks
+    __host__ __device__ int64_t begin(int w) const { return w * total / n_groups; }
+    // workgroup that holds flattened chunk f
+    __host__ __device__ int group_of(int64_t f) const { return int(((f + 1) * n_groups - 1) / total); }
+};
+
 inline size_t v_partial_bytes(int batch, int n_q_heads) {
     return size_t(V_SPLITS_MAX) * batch * n_q_heads * V_PART_STRIDE * sizeof(float);
 }
@@ -71,6 +84,10 @@ struct SplitRows {
     float last[V_SPLITS_MAX / 8];  // column 128, thread group leaders only
 
     __device__ inline void load(const float *__restrict__ partial, int n_splits, int n_rows, int r) {
+        load_strided(partial + int64_t(r) * V_PART_STRIDE, n_splits, n_rows);
+    }
+    // Rows first_row, first_row + row_stride * V_PART_STRIDE, ... (n_splits of them).
+    __device__ inline void load_strided(const float *__restrict__ first_row, int n_splits, int64_t row_stride) {
         const int sg = threadIdx.x >> 5, q4 = threadIdx.x & 31;
 #pragma unroll
         for (int i = 0; i < V_SPLITS_MAX / 8; ++i) {
@@ -78,7 +95,7 @@ struct SplitRows {
             v[i] = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
             last[i] = 0.0f;
             if (s < n_splits) {
-                const float *src = partial + (int64_t(s) * n_rows + r) * V_PART_STRIDE;
+                const float *src = first_row + int64_t(s) * row_stride * V_PART_STRIDE;
                 v[i] = *reinterpret_cast<const float4 *>(src + 4 * q4);
                 if (q4 == 0) last[i] = src[128];
             }
@@ -211,6 +228,16 @@ struct kv_cache {
         default: return KV_ERR_UNSUPPORTED;    \
     }
 
+// The same for the kernels of the plane layout (packs of 16 tokens): group sizes 1..4.
+#define PACKKV_DISPATCH_GROUP4(group, LAUNCH)  \
+    switch (group) {                           \
+        case 1: LAUNCH(1); break;              \
+        case 2: LAUNCH(2); break;              \
+        case 3: LAUNCH(3); break;              \
+        case 4: LAUNCH(4); break;              \
+        default: return KV_ERR_UNSUPPORTED;    \
+    }
+
 #define KV_HIP_CHECK(expr)                      \
     do {                                        \
         hipError_t e_ = (expr);                 \
@@ -239,6 +266,7 @@ struct CompressJob {
     uint32_t *page_list;      // paged arena: [0] pages held, [1] 16-byte units used in the newest, [2..] page numbers
     int64_t max_pages;        // page numbers the list has room for
     const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
+    bool planes;              // packs of 16: plane layout (V) instead of the contiguous bit fields (K)
 };
 
 int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s);

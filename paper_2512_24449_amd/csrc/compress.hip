@@ -260,6 +260,122 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
     if (tau < padded - HDR - payload) dst[HDR + payload + tau] = 0;
 }
 
+// Packs of 16 tokens in the plane layout (packkv.h): header bytes in pack-list order, region E
+// with a 32-bit word of low code bits per pack of width >= 2 (and a second word of high bits
+// for width 4), region O with a 16-bit word of top bits per pack of odd width.  One workgroup
+// per new chunk; thread tau owns packs tau and tau + 256 of the pack list (order 0: pack
+// p = g*128 + d, order 1: p = d*4 + g).
+struct PlaneBits {
+    uint32_t low, high, top;
+    int w, m;
+};
+
+__device__ inline PlaneBits make_planes(const __half *tile, int g, int d, const float4 *sm, int qmax) {
+    int q[PACK];
+    int lo = 255, hi = 0;
+#pragma unroll
+    for (int i = 0; i < PACK; ++i) {
+        const float4 t = sm[g * PACK + i];
+        const int v = quantize_value(__half2float(tile[(g * PACK + i) * D + d]), t.x, t.y, t.z, qmax);
+        q[i] = v;
+        lo = min(lo, v);
+        hi = max(hi, v);
+    }
+    PlaneBits pb;
+    const int range = hi - lo;
+    pb.w = range == 0 ? 0 : 32 - __clz(range);
+    pb.m = lo;
+    pb.low = pb.high = pb.top = 0;
+    const int top_bit = pb.w > 0 ? pb.w - 1 : 0;
+#pragma unroll
+    for (int i = 0; i < PACK; ++i) {
+        const uint32_t c = uint32_t(q[i] - lo);
+        const int at = i < 8 ? 4 * i : 4 * (i - 8) + 2;
+        pb.low |= (c & 3u) << at;
+        pb.high |= (c >> 2) << at;
+        pb.top |= ((c >> top_bit) & 1u) << (4 * (i & 3) + (i >> 2));
+    }
+    return pb;
+}
+
+template <bool WRITE>
+__global__ __launch_bounds__(256) void chunk16_kernel(const __half *__restrict__ src,
+                                                      int64_t batch_stride, int64_t token_stride,
+                                                      int B, int H, int qmax,
+                                                      const uint32_t *__restrict__ meta,
+                                                      int64_t meta_stride, int64_t first_token,
+                                                      int64_t first_chunk,
+                                                      uint32_t *__restrict__ sizes16,
+                                                      const uint32_t *__restrict__ index,
+                                                      int index_words,
+                                                      uint8_t *__restrict__ arena,
+                                                      const uint8_t *__restrict__ order, bool bf16,
+                                                      int pack_order) {
+    const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
+    const int h = cl % H;
+    const int b = (cl / H) % B;
+    const int blk = cl / (H * B);
+    const int tau = threadIdx.x;
+
+    uint8_t *dst = nullptr;
+    if (WRITE) {
+        const int64_t e = (first_chunk + cl) * index_words;
+        uint32_t o0 = index[e], o1 = index[e + 1];
+        if (o1 == o0) return;  // dropped: the arena was full
+        dst = arena + size_t(o0) * 16;
+    }
+
+    __shared__ __attribute__((aligned(16))) __half tile[N * D];
+    __shared__ float4 sm[N];
+    if (tau < N) sm[tau] = token_scale_min(meta[b * meta_stride + first_token + int64_t(blk) * N + tau]);
+    {
+        const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D;
+        const uint8_t *ord = order ? order + b * meta_stride + first_token + int64_t(blk) * N : nullptr;
+#pragma unroll
+        for (int pass = 0; pass < 4; ++pass) {
+            const int row = pass * 16 + (tau >> 4), c8 = (tau & 15) * 8;
+            const int src_row = ord ? ord[row] : row;
+            *reinterpret_cast<uint4 *>(tile + row * D + c8) = load8_as_fp16(x_blk + src_row * token_stride + c8, bf16);
+        }
+    }
+    __syncthreads();
+
+    PlaneBits pb[2];
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int p = tau + 256 * k;
+        const int g = pack_order ? (p & 3) : (p >> 7);
+        const int d = pack_order ? (p >> 2) : (p & 127);
+        pb[k] = make_planes(tile, g, d, sm, qmax);
+    }
+    // one scan per pack-list half carries both regions: E bytes in the low half, O bytes in the high half
+    int off[2];
+    int run = 0;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        int total;
+        off[k] = run + block_exclusive_scan(4 * (pb[k].w >> 1) + ((2 * (pb[k].w & 1)) << 16), &total);
+        run += total;
+    }
+    const int e_bytes = run & 0xFFFF, o_bytes = run >> 16;
+    const int padded = (HEADER + e_bytes + o_bytes + 15) & ~15;
+
+    if (!WRITE) {
+        if (tau == 0) sizes16[cl] = uint32_t(padded >> 4);
+        return;
+    }
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
+        uint32_t *e = reinterpret_cast<uint32_t *>(dst + HEADER + (off[k] & 0xFFFF));
+        if (pb[k].w >= 2) e[0] = pb[k].low;
+        if (pb[k].w == 4) e[1] = pb[k].high;
+        if (pb[k].w & 1)
+            *reinterpret_cast<uint16_t *>(dst + HEADER + e_bytes + (off[k] >> 16)) = uint16_t(pb[k].top);
+    }
+    if (tau < padded - HEADER - e_bytes - o_bytes) dst[HEADER + e_bytes + o_bytes + tau] = 0;
+}
+
 // Single workgroup: index[first+i+1] = index[first] + sum_{j<=i} sizes16[j].
 // If the new chunks do not fit, all of them get size 0 and the flag is set.
 __global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__restrict__ sizes16,
@@ -688,24 +804,37 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
+    const bool planes = !job.wide && c->cfg.pack_size == 16 && job.planes;
     auto sizes_kernel = job.wide ? chunk_kernel<false, 8, true>
                                  : (c->cfg.pack_size == 8 ? chunk_kernel<false, 8> : chunk_kernel<false, 16>);
     auto write_kernel = job.wide ? chunk_kernel<true, 8, true>
                                  : (c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>);
-    hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
-                       job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                       job.order, job.bf16);
+    if (planes)
+        hipLaunchKernelGGL(chunk16_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
+                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                           job.order, job.bf16, 0);
+    else
+        hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
+                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                           job.order, job.bf16);
     if (c->pool)
         hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
                            job.first_chunk, job.page_list, job.max_pages, c->pool->state, job.status);
     else
         hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
                            job.index, job.first_chunk, job.arena_cap16, job.status);
-    hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
-                       job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                       job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                       job.order, job.bf16);
+    if (planes)
+        hipLaunchKernelGGL(chunk16_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
+                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                           job.order, job.bf16, 0);
+    else
+        hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
+                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                           job.order, job.bf16);
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

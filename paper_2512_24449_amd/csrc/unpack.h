@@ -195,14 +195,25 @@ __device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32
     const uint8_t *chunk = arena + size_t(o0) * 16;
     const int last = size - 16;
     const uint32_t lds = uint32_t(uintptr_t((__attribute__((address_space(3))) void *)buf));
+    // One M0 write per chunk for the first four slices: the instruction offset moves the global
+    // and the LDS address alike.  Nothing between these statements touches M0 (no LDS-DMA
+    // builtin, no indexed register access, no message).
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds) : "memory", "m0");
 #pragma unroll
     for (int k = 0; k < (MAXB + 1023) / 1024; ++k) {
         if (k * 1024 < size && ((k + 1) * 1024 <= MAXB || k * 1024 + lane * 16 < MAXB)) {
-            const int off = k * 1024 + lane * 16;
-            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                         :
-                         : "s"(lds + k * 1024), "v"(off < last ? off : last), "s"(chunk)
-                         : "memory", "m0");
+            const int off = lane * 16;
+            const int lim = last - k * 1024;
+            const int voff = off < lim ? off : lim;
+            if (k == 0) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(chunk) : "memory", "m0");
+            if (k == 1) asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" : : "v"(voff), "s"(chunk) : "memory", "m0");
+            if (k == 2) asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" : : "v"(voff), "s"(chunk) : "memory", "m0");
+            if (k == 3) asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" : : "v"(voff), "s"(chunk) : "memory", "m0");
+            if (k >= 4)
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+                             :
+                             : "s"(lds + k * 1024), "v"(voff), "s"(chunk + k * 1024)
+                             : "memory", "m0");
         }
     }
 }
@@ -222,6 +233,49 @@ __device__ inline void wait_chunk_landed_except() {
 }
 // Compiler-only fence: memory operations are not moved across it.
 __device__ inline void vmem_order_fence() { asm volatile("" ::: "memory"); }
+// Three chunk buffers per wave (chunks n+1 and n+2 in flight while chunk n is decoded): the same
+// transfer, with the number of transfer instructions it issued as the result (wave-uniform; 0 for
+// a dropped block), which the caller needs to count the vector memory operations that may stay in
+// flight at its next wait.
+template <int MAXB = CHUNK_MAX, int HDR = HEADER>
+__device__ inline int chunk_issue_lds_counted(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
+                                              uint8_t *buf, int lane) {
+    const int size = int(o1 - o0) * 16;
+    if (size < HDR) return 0;
+    chunk_issue_lds<MAXB, HDR>(arena, o0, o1, buf, lane);
+    const int slices = (size + 1023) >> 10;
+    constexpr int MOST = (MAXB + 1023) / 1024;
+    return slices < MOST ? slices : MOST;
+}
+
+// One dword per lane straight from global memory into LDS: lane i's word row[i] lands at
+// buf + 4 i (one transfer instruction; same rules as chunk_issue_lds).  row, buf: wave-uniform.
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
+__device__ inline void row_issue_lds(const void *__restrict__ row, uint8_t *buf, int lane) {
+    const uint32_t lds = uint32_t(uintptr_t((__attribute__((address_space(3))) void *)buf));
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2"
+                 :
+                 : "s"(lds), "v"(lane * 4), "s"(row)
+                 : "memory", "m0");
+}
+#pragma clang diagnostic pop
+
+// Waits until at most `later` (wave-uniform, 0..MOST) + FIXED of this wave's newest vector memory
+// operations are still in flight (the counter retires in issue order).
+template <int FIXED, int MOST>
+__device__ inline void wait_vmem_except(int later) {
+    static_assert(FIXED + MOST < 64, "the counter has six bits");
+    switch (later) {
+        case 0: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED) : "memory"); break;
+        case 1: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED + (MOST >= 1 ? 1 : 0)) : "memory"); break;
+        case 2: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED + (MOST >= 2 ? 2 : 0)) : "memory"); break;
+        case 3: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED + (MOST >= 3 ? 3 : 0)) : "memory"); break;
+        case 4: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED + (MOST >= 4 ? 4 : 0)) : "memory"); break;
+        default: asm volatile("s_waitcnt vmcnt(%0)" ::"n"(FIXED + (MOST >= 5 ? 5 : 0)) : "memory"); break;
+    }
+}
+
 // Makes a value that was loaded ahead count as used here, so that the compiler's own wait
 // for that load sits at this point (right after an explicit wait, where it costs nothing) and
 // not later, behind the next chunk's transfers, which it would then wait for as well.

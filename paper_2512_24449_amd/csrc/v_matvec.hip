@@ -21,6 +21,11 @@
 
 #include "pack8.h"
 #include "v_chunk.h"
+#include "v_planes.h"
+
+#ifndef PACKKV_V_NBUF
+#define PACKKV_V_NBUF 2
+#endif
 
 namespace packkv {
 
@@ -39,74 +44,107 @@ struct VArgs {
     int blocks_per_split;
 };
 
-template <int G>
-__global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a) {
-    // two chunk buffers per wave; after the main loop the same memory holds the
-    // cross-wave reduction array red[4][G][D + 4]
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
-    __shared__ __attribute__((aligned(16))) uint8_t blds_all[4 * BLds<G>::BYTES];
-    __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
+// Packs of 16 tokens, plane layout (v_planes.h).  HIGH: the codes of the cache may need four bits
+// (otherwise a chunk is at most 512 + 512 * 6 bytes).  The chunks of all streams form one work
+// list that is cut into equal ranges, one per workgroup (FlatPlan): a launch is one round of
+// long-lived workgroups whatever the numbers of streams and blocks are.  The four waves of a
+// workgroup take every fourth block of its range.  A wave keeps NBUF chunk buffers: the next
+// chunks stream in while one is decoded, and the token metadata and the weights of a chunk
+// travel the same way (one dword per lane, global memory -> LDS, behind the chunk in its buffer):
+// no vector memory instruction of the loop is visible to the compiler, so the only waits are the
+// counted ones below.
+template <int G, bool HIGH>
+__global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a, FlatPlan plan) {
+    constexpr int CHUNK_BYTES = HIGH ? CHUNK_MAX : HEADER + PACKS * 6;
+    constexpr int SLICES = (CHUNK_BYTES + 1023) / 1024;
+    constexpr int SIDE = CHUNK_BYTES + LDS_TAIL_PAD;   // metadata row, then G weight rows
+    constexpr int BUF = SIDE + (1 + G) * 256;          // bytes of one chunk buffer
+    constexpr int NBUF = PACKKV_V_NBUF;                // chunks n+1 .. n+NBUF-1 in flight
+    static_assert(NBUF == 2 || NBUF == 3, "wait counts below");
+    // between the ranges of two streams the chunk buffers hold the cross-wave reduction array
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * NBUF * BUF];
+    constexpr int VB = vb_bytes<G>();
+    __shared__ __attribute__((aligned(16))) uint8_t vb_all[4 * VB];
+    __shared__ uint4 table[PLANE_TABLE_ENTRIES];
+    __shared__ uint32_t highs[PLANE_TABLE_ENTRIES];
+    static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * NBUF * BUF, "reduction array must fit");
+    static_assert(BUF % 16 == 0, "buffers are 16-byte aligned");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
-    build_pack_table(table, CODE_LIFT, fold_min<G>());
+    for (int i = threadIdx.x; i < 4 * VB / 4; i += 256) reinterpret_cast<uint32_t *>(vb_all)[i] = 0;
+    build_plane_table(table, highs);
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int split = blockIdx.x;
-    const int bh = blockIdx.y;
-    const int h = bh % a.H, b = bh / a.H;
-    const int buf_base = wave * 2 * CHUNK_LDS;
-    VLane<G> vl;
-    vl.init(blds_all + wave * BLds<G>::BYTES, lane);
-    VState<G> st;
-    st.clear();
+    const int buf_base = wave * NBUF * BUF;
+    uint8_t *vb = vb_all + wave * VB;
+    const int grp = blockIdx.x;
+    const int64_t range_end = plan.begin(grp + 1);
 
-    const int blk_begin = split * a.blocks_per_split;
-    const int blk_end = min(blk_begin + a.blocks_per_split, a.n_blocks);
-    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
-        IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
-        const int n_it = min(64, (blk_end - first + 3) / 4);
-        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds_all + buf_base, lane);
-        uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
-        float p_next[G];
+    for (int64_t f = plan.begin(grp); f < range_end;) {
+        const int stream = int(f / plan.n_blocks);
+        const int blk_begin = int(f - int64_t(stream) * plan.n_blocks);
+        const int blk_end = int(min<int64_t>(plan.n_blocks, blk_begin + (range_end - f)));
+        f += blk_end - blk_begin;
+        const int h = stream % a.H, b = stream / a.H;
+        const uint32_t *meta = a.meta + b * a.meta_stride;
+        const float *prow = a.p + int64_t(stream) * G * a.ld;
+        VPlaneState<G> st;
+        st.clear();
+
+        // everything chunk `blk` needs, into buffer `slot`: 1 + G row transfers, then the chunk
+        // itself; returns the number of transfer instructions of the chunk
+        auto issue = [&](const IndexBatch &ib, int it, int blk, int slot) -> int {
+            uint8_t *buf = lds_all + buf_base + slot * BUF;
+            row_issue_lds(meta + int64_t(blk) * N, buf + SIDE, lane);
 #pragma unroll
-        for (int g = 0; g < G; ++g)
-            p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + int64_t(first) * N + lane];
-        for (int it = 0; it < n_it; ++it) {
-            const int cur = buf_base + (it & 1) * CHUNK_LDS;
-            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+            for (int g = 0; g < G; ++g) row_issue_lds(prow + g * a.ld + int64_t(blk) * N, buf + SIDE + 256 * (1 + g), lane);
+            return chunk_issue_lds_counted<CHUNK_BYTES>(a.arena, ib.start16(it), ib.end16(it), buf, lane);
+        };
+
+        for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+            IndexBatch ib;
+            ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
+            const int n_it = min(64, (blk_end - first + 3) / 4);
+            wait_chunk_landed();  // the index words (the only loads the compiler sees)
+            issue(ib, 0, first, 0);
+            int slices_next = 0;  // transfer instructions of chunk it + 1
+            if (NBUF == 3 && n_it > 1) slices_next = issue(ib, 1, first + 4, 1);
+            int slot = 0;         // buffer of chunk it
+            for (int it = 0; it < n_it; ++it) {
+                const int cur = buf_base + slot * BUF;
+                const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+                // chunk it with its rows has landed; with three buffers the 1 + G rows and the
+                // chunk of it + 1 may still be in flight
+                if (NBUF == 3 && it + 1 < n_it)
+                    wait_vmem_except<1 + G, SLICES>(slices_next);
+                else
+                    wait_chunk_landed();
+                if (it + NBUF - 1 < n_it) {
+                    // into the buffer chunk it - 1 was decoded from: its LDS reads have returned
+                    lds_reads_returned();
+                    slices_next = issue(ib, it + NBUF - 1, first + 4 * (it + NBUF - 1), slot == 0 ? NBUF - 1 : slot - 1);
+                }
+                slot = slot == NBUF - 1 ? 0 : slot + 1;
+                if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
+                const uint32_t mt = *reinterpret_cast<const uint32_t *>(lds_all + cur + SIDE + 4 * lane);
+                float pt[G];
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    pt[g] = *reinterpret_cast<const float *>(lds_all + cur + SIDE + 256 * (1 + g) + 4 * lane);
+                v_planes_chunk<G, HIGH>(lds_all, cur, table, highs, vb, mt, pt, st);
+            }
             wait_chunk_landed();
-            uint32_t mt = mt_next;
-            consume_here(mt);
-            float pt[G];
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                pt[g] = p_next[g];
-                consume_here(pt[g]);
-            }
-            // the next chunk streams into the other buffer while this one is unpacked
-            if (it + 1 < n_it) {
-                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
-                                lds_all + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
-                const int64_t tok = int64_t(first + 4 * (it + 1)) * N + lane;
-                mt_next = a.meta[b * a.meta_stride + tok];
-#pragma unroll
-                for (int g = 0; g < G; ++g) p_next[g] = a.p[(int64_t(b) * a.H * G + h * G + g) * a.ld + tok];
-            }
-            if (!valid) continue;  // a block dropped by an arena overflow contributes nothing
-            v_chunk<G>(lds_all, cur, table, vl, mt, pt, st);
         }
-        wait_chunk_landed();
-    }
-    __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
+        __syncthreads();  // every wave is done with its chunk buffers: reuse them as red[][][]
 
-    v_state_store<G>(st, red[wave], lane);
-    __syncthreads();
-    for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
-        const int g = i / (D + 1), d = i % (D + 1);
-        const float v = (red[0][g][d] + red[1][g][d]) + (red[2][g][d] + red[3][g][d]);
-        a.partial[(int64_t(split) * a.B * a.H * G + (int64_t(b) * a.H * G + h * G + g)) * V_PART_STRIDE + d] = v;
+        v_planes_store<G>(st, red[wave], lane);
+        __syncthreads();
+        float *dst = a.partial + int64_t(grp + stream) * G * V_PART_STRIDE;
+        for (int i = threadIdx.x; i < G * (D + 1); i += 256) {
+            const int g = i / (D + 1), d = i % (D + 1);
+            dst[g * V_PART_STRIDE + d] = (red[0][g][d] + red[1][g][d]) + (red[2][g][d] + red[3][g][d]);
+        }
+        __syncthreads();  // red[][][] has been read: the buffers may be filled again
     }
 }
 
@@ -237,9 +275,11 @@ __global__ __launch_bounds__(256) void vw_matvec_kernel(VArgs a) {
     }
 }
 
-// Fixed-order combination of the split partial sums, plus the raw fp16 tail.
+// Fixed-order combination of the split partial sums, plus the raw fp16 tail.  plan.n_groups > 0:
+// the partial rows come from a kernel that walks the flat work list (kv-head group size Gk per
+// stream); the row sets of stream s are those of the workgroups that hold one of its chunks.
 __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__ partial,
-                                                       int n_splits, int n_rows,
+                                                       int n_splits, int n_rows, FlatPlan plan, int Gk,
                                                        const float *__restrict__ p, int64_t ld,
                                                        int64_t packed_tokens,
                                                        const __half *__restrict__ tail, int n_tail,
@@ -254,7 +294,15 @@ __global__ __launch_bounds__(256) void v_reduce_kernel(const float *__restrict__
     // every global load of the kernel is issued before the first result is needed
     SplitRows rows;
     TailRows trows;
-    rows.load(partial, n_splits, n_rows, r);
+    if (plan.n_groups > 0) {
+        const int stream = r / Gk, g = r % Gk;
+        const int w_lo = plan.group_of(int64_t(stream) * plan.n_blocks);
+        const int w_hi = plan.group_of(int64_t(stream + 1) * plan.n_blocks - 1);
+        n_splits = w_hi - w_lo + 1;
+        rows.load_strided(partial + (int64_t(w_lo + stream) * Gk + g) * V_PART_STRIDE, n_splits, Gk);
+    } else {
+        rows.load(partial, n_splits, n_rows, r);
+    }
     trows.load(tail + (int64_t(b) * tail_cap * H + h) * D, int64_t(H) * D, n_tail);
     if (d < n_tail) wt[d] = p[int64_t(r) * ld + packed_tokens + d];
     float pmin;
@@ -275,6 +323,28 @@ int v_splits_for(int n_blocks, int streams) {
 
 // partial: [splits][B * H_q][V_PART_STRIDE] floats for the split sums; max_split_rows: how many
 // such rows it can take (the split count is lowered to fit).
+// Workgroups for the flat work list of `total` chunks: one round of resident workgroups (per_cu
+// of them fit a compute unit), never less than one block per wave, at most 62 per stream (the
+// combine kernels take up to 64 row sets per stream).
+int flat_groups_for(int64_t total, int streams, int per_cu, int64_t max_row_sets) {
+    static int n_cu = 0;
+    if (n_cu == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n_cu = v;
+        else
+            n_cu = 256;
+    }
+    int64_t w = int64_t(n_cu) * per_cu;
+    w = std::min<int64_t>(w, (total + 3) / 4);
+    w = std::min<int64_t>(w, int64_t(62) * streams);
+    w = std::min<int64_t>(w, max_row_sets - streams);
+    return int(std::max<int64_t>(w, 1));
+}
+
+// partial: [row sets][V_PART_STRIDE] floats for the split sums; max_split_rows: how many rows
+// (one per query head and split or row set) it can take.
 static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p, float *out, float *partial,
                                 int64_t max_split_rows, hipStream_t s) {
     // Hs: kv-heads as the stream kernels count them (each dup times, see head_split); the combine
@@ -283,41 +353,53 @@ static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p,
     const int n_blocks = int(c->packed_tokens / N);
     const int64_t rows = int64_t(B) * H * Gq;
     if (rows > max_split_rows) return KV_ERR_CAPACITY;
+    const bool planes = !c->wide_v && c->cfg.pack_size == PACK;
     int n_splits = 0;
-    if (n_blocks > 0) {
+    FlatPlan plan = {n_blocks, 0, int64_t(B) * Hs * n_blocks};
+    VArgs a;
+    a.arena = static_cast<const uint8_t *>(c->buf.v_arena);
+    a.index = static_cast<const uint32_t *>(c->buf.v_index);
+    a.meta = static_cast<const uint32_t *>(c->buf.v_token_meta);
+    a.p = p;
+    a.partial = partial;
+    a.ld = ld_p;
+    a.meta_stride = c->max_tokens;
+    a.B = B;
+    a.index_words = c->index_words;
+    a.H = Hs;
+    a.dup = c->head_split;
+    a.n_blocks = n_blocks;
+    a.blocks_per_split = 0;
+    if (n_blocks > 0 && planes) {
+        // row sets: one per (workgroup, stream it touches), G rows each
+        if (max_split_rows / G <= int64_t(B) * Hs) return KV_ERR_CAPACITY;
+        plan.n_groups = flat_groups_for(plan.total, B * Hs, 4, max_split_rows / G);
+#define PACKKV_LAUNCH_V(g) hipLaunchKernelGGL((v_matvec_kernel<g, false>), dim3(plan.n_groups), dim3(256), 0, s, a, plan)
+#define PACKKV_LAUNCH_VH(g) hipLaunchKernelGGL((v_matvec_kernel<g, true>), dim3(plan.n_groups), dim3(256), 0, s, a, plan)
+        if (c->qmax_v > 7) {
+            PACKKV_DISPATCH_GROUP4(G, PACKKV_LAUNCH_VH)
+        } else {
+            PACKKV_DISPATCH_GROUP4(G, PACKKV_LAUNCH_V)
+        }
+#undef PACKKV_LAUNCH_VH
+#undef PACKKV_LAUNCH_V
+    } else if (n_blocks > 0) {
         n_splits = int(std::min<int64_t>(v_splits_for(n_blocks, B * Hs), max_split_rows / rows));
-        VArgs a;
-        a.arena = static_cast<const uint8_t *>(c->buf.v_arena);
-        a.index = static_cast<const uint32_t *>(c->buf.v_index);
-        a.meta = static_cast<const uint32_t *>(c->buf.v_token_meta);
-        a.p = p;
-        a.partial = partial;
-        a.ld = ld_p;
-        a.meta_stride = c->max_tokens;
-        a.B = B;
-        a.index_words = c->index_words;
-        a.H = Hs;
-        a.dup = c->head_split;
-        a.n_blocks = n_blocks;
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;
         n_splits = (n_blocks + a.blocks_per_split - 1) / a.blocks_per_split;
         dim3 grid(n_splits, B * Hs);
 #define PACKKV_LAUNCH_VW(g) hipLaunchKernelGGL(vw_matvec_kernel<g>, grid, dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_V8(g) hipLaunchKernelGGL(v8_matvec_kernel<g>, grid, dim3(256), 0, s, a)
-#define PACKKV_LAUNCH_V(g) hipLaunchKernelGGL(v_matvec_kernel<g>, grid, dim3(256), 0, s, a)
         if (c->wide_v) {
             PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_VW)
-        } else if (c->cfg.pack_size == 8) {
-            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_V8)
         } else {
-            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_V)
+            PACKKV_DISPATCH_GROUP(G, PACKKV_LAUNCH_V8)
         }
 #undef PACKKV_LAUNCH_VW
 #undef PACKKV_LAUNCH_V8
-#undef PACKKV_LAUNCH_V
     }
     hipLaunchKernelGGL(v_reduce_kernel, dim3(B * H * Gq), dim3(256), 0, s, partial, n_splits,
-                       B * H * Gq, p, ld_p, c->packed_tokens,
+                       B * H * Gq, plan, G, p, ld_p, c->packed_tokens,
                        static_cast<const __half *>(c->buf.v_tail), c->tail_tokens,
                        c->cfg.tail_capacity, H, Gq, out);
     KV_HIP_CHECK(hipGetLastError());

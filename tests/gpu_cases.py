@@ -39,8 +39,8 @@ def oracle_cache(K, V, k_rel=0.1, v_rel=0.2, pack_size=16):
     """Compress the packed prefix of K and V with the oracle.  K, V: numpy fp16 [B, L, H, D]."""
     L = K.shape[1]
     n_packed = L // 64 * 64
-    ck = oracle.compress(np.ascontiguousarray(K[:, :n_packed]), k_rel, pack_size) if n_packed else None
-    cv = oracle.compress(np.ascontiguousarray(V[:, :n_packed]), v_rel, pack_size) if n_packed else None
+    ck = oracle.compress_k(np.ascontiguousarray(K[:, :n_packed]), k_rel, pack_size) if n_packed else None
+    cv = oracle.compress_v(np.ascontiguousarray(V[:, :n_packed]), v_rel, pack_size) if n_packed else None
     return n_packed, ck, cv
 
 
@@ -177,7 +177,7 @@ def run_case(B, H, Hq, L, seed, pieces=None, check_bytes=True, sm_scale=None, de
 
     if repack and L >= 64:
         n_full = L // 64 * 64
-        order = oracle.v_median_order(oracle.compress(np.ascontiguousarray(Vn[:, :n_full]), v_rel, pack_size).codes)
+        order = oracle.v_median_order(oracle.compress_v(np.ascontiguousarray(Vn[:, :n_full]), v_rel, pack_size).codes)
         Kn = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_full:]], axis=1)
         Vn = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_full:]], axis=1)
         mt = ((max_tokens or max(L, 64)) + 63) // 64 * 64

@@ -68,7 +68,7 @@ def test_two_caches_share_a_pool_by_the_stated_placement_rule():
         pk = 16 if who == 0 else 8
         for t, (x, rel) in enumerate(((K, 0.1), (V, 0.2))):
             # chunk sizes depend on the appended blocks alone: compress just those with the oracle
-            c = oracle.compress(np.ascontiguousarray(x.numpy()[:, lo:hi]), rel, pk)
+            c = (oracle.compress_v if t else oracle.compress_k)(np.ascontiguousarray(x.numpy()[:, lo:hi]), rel, pk)
             sizes = np.diff(c.offsets16.astype(np.int64)).tolist()
             # the library compresses at most 65536 chunks per round; these calls are far below
             placed = model.place(tensors[who][t], sizes)
@@ -114,7 +114,7 @@ def test_two_caches_share_a_pool_by_the_stated_placement_rule():
     caches[0].kv_compress_append(K[:, :64 * 5].contiguous().cuda(), V[:, :64 * 5].contiguous().cuda())
     torch.cuda.synchronize()
     for t, (name, x, rel) in enumerate((("k", K, 0.1), ("v", V, 0.2))):
-        c = oracle.compress(np.ascontiguousarray(x.numpy()[:, :64 * 5]), rel, 16)
+        c = (oracle.compress_v if t else oracle.compress_k)(np.ascontiguousarray(x.numpy()[:, :64 * 5]), rel, 16)
         placed = model.place(tensors[0][t], np.diff(c.offsets16.astype(np.int64)).tolist())
         assert _chunk_pairs(caches[0], name, 5 * B * H) == placed, name
     n_packed, ck, cv = gpu_cases.oracle_cache(K.numpy()[:, :64 * 5], V.numpy()[:, :64 * 5])
@@ -139,7 +139,7 @@ def test_exhausted_pool_drops_the_call_and_keeps_its_pages():
         cache.kv_compress_append(K[:, lo:hi].contiguous().cuda(), V[:, lo:hi].contiguous().cuda())
         ok = {}
         for name, t, x, rel in (("k", kt, K, 0.1), ("v", vt, V, 0.2)):
-            c = oracle.compress(np.ascontiguousarray(x.numpy()[:, lo:hi]), rel)
+            c = (oracle.compress_k if name == "k" else oracle.compress_v)(np.ascontiguousarray(x.numpy()[:, lo:hi]), rel)
             ok[name] = model.place(t, np.diff(c.offsets16.astype(np.int64)).tolist()) is not None
             if ok[name] and dropped_at is None:
                 kept[name] = hi
@@ -226,7 +226,7 @@ def test_bulk_append_placement_equals_the_rule():
     for n in calls:
         cache.kv_compress_append(K[:, lo:lo + n].contiguous().cuda(), V[:, lo:lo + n].contiguous().cuda())
         for t, (x, rel) in enumerate(((K, 0.1), (V, 0.2))):
-            c = oracle.compress(np.ascontiguousarray(x.numpy()[:, lo:lo + n]), rel)
+            c = (oracle.compress_v if t else oracle.compress_k)(np.ascontiguousarray(x.numpy()[:, lo:lo + n]), rel)
             placed = model.place(tensors[t], np.diff(c.offsets16.astype(np.int64)).tolist())
             assert placed is not None
             expected[t].extend(placed)

@@ -240,13 +240,13 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     for n in (pieces or [L]):
         cache.kv_compress_append(K[:, pos:pos + n].contiguous().cuda(), V[:, pos:pos + n].contiguous().cuda())
         pos += n
-    cv0 = oracle.compress(np.ascontiguousarray(Vn[:, :n_packed]), v_rel, pack_size)
+    cv0 = oracle.compress_v(np.ascontiguousarray(Vn[:, :n_packed]), v_rel, pack_size)
     order = oracle.v_median_order(cv0.codes)
     assert len(np.unique(order[:, :64])) == 64 and not np.array_equal(order[0, :64], np.arange(64))
     Kp = np.concatenate([oracle.apply_order(Kn, order), Kn[:, n_packed:]], axis=1)
     Vp = np.concatenate([oracle.apply_order(Vn, order), Vn[:, n_packed:]], axis=1)
-    ck = oracle.compress(np.ascontiguousarray(Kp[:, :n_packed]), k_rel, pack_size)
-    cv = oracle.compress(np.ascontiguousarray(Vp[:, :n_packed]), v_rel, pack_size)
+    ck = oracle.compress_k(np.ascontiguousarray(Kp[:, :n_packed]), k_rel, pack_size)
+    cv = oracle.compress_v(np.ascontiguousarray(Vp[:, :n_packed]), v_rel, pack_size)
     (gpu_cases.check_paged_state if paged else gpu_cases.check_packed_state)(cache, n_packed, ck, cv, B, H)
     max_tokens = cache.tensors["token_order"].numel() // B
     got_order = cache.tensors["token_order"].view(B, max_tokens)[:, :n_packed].cpu().numpy()
@@ -379,7 +379,7 @@ def test_non_finite_inputs_keep_the_format_valid(kw):
         arena = cache.tensors[name + "_arena"][:index[-1] * 16].cpu().numpy()
         for c in range(n_chunks):
             buf = arena[index[c] * 16:index[c + 1] * 16]
-            codes, widths, mins = chunk_reader.read_chunk_wide(buf) if qmax > 15 else chunk_reader.read_chunk(buf, pk)
+            codes, widths, mins = chunk_reader.read_chunk_wide(buf) if qmax > 15 else chunk_reader.read_chunk(buf, pk, contiguous=(name == "k"))
             assert codes.min() >= 0 and codes.max() <= qmax and widths.max() <= (8 if qmax > 15 else 4)
     scores = cache.kv_k_matvec(q.cuda(), 0.1)
     cache.kv_softmax(scores)

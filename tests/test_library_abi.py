@@ -52,9 +52,9 @@ def test_query_sizes_and_config_checks():
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
     for g in range(1, 9):                                          # every group size up to 8
         assert L.kv_query_sizes(C.byref(binding.make_config(1, 4, 4 * g, 4096)), 0.0, C.byref(out)) == 0
-    for g in (9, 12, 16, 24, 64):                                  # split into s groups of g / s <= 8 heads
+    for g in (9, 11, 12, 16, 24, 64):                              # split into s <= 16 groups of g / s <= 4 heads
         assert L.kv_query_sizes(C.byref(binding.make_config(1, 2, 2 * g, 4096)), 0.0, C.byref(out)) == 0
-    for g in (11, 13, 17, 65, 128):                                # no such split
+    for g in (17, 19, 65, 128):                                    # no such split
         assert L.kv_query_sizes(C.byref(binding.make_config(1, 2, 2 * g, 4096)), 0.0, C.byref(out)) == -2
     bad = binding.make_config(0, 1, 1, 64)
     assert L.kv_query_sizes(C.byref(bad), 0.0, C.byref(out)) == -1
