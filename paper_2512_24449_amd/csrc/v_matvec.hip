@@ -323,6 +323,14 @@ int v_splits_for(int n_blocks, int streams) {
 
 // partial: [splits][B * H_q][V_PART_STRIDE] floats for the split sums; max_split_rows: how many
 // such rows it can take (the split count is lowered to fit).
+// Workgroups of 256 threads of `kernel` that fit one compute unit (registers, LDS); 1 if the
+// runtime cannot tell.
+int resident_workgroups(const void *kernel) {
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 256, 0) != hipSuccess || n < 1) n = 1;
+    return n;
+}
+
 // Workgroups for the flat work list of `total` chunks: one round of resident workgroups (per_cu
 // of them fit a compute unit), never less than one block per wave, at most 62 per stream (the
 // combine kernels take up to 64 row sets per stream).
@@ -373,9 +381,15 @@ static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p,
     if (n_blocks > 0 && planes) {
         // row sets: one per (workgroup, stream it touches), G rows each
         if (max_split_rows / G <= int64_t(B) * Hs) return KV_ERR_CAPACITY;
-        plan.n_groups = flat_groups_for(plan.total, B * Hs, 4, max_split_rows / G);
-#define PACKKV_LAUNCH_V(g) hipLaunchKernelGGL((v_matvec_kernel<g, false>), dim3(plan.n_groups), dim3(256), 0, s, a, plan)
-#define PACKKV_LAUNCH_VH(g) hipLaunchKernelGGL((v_matvec_kernel<g, true>), dim3(plan.n_groups), dim3(256), 0, s, a, plan)
+        // one round of resident workgroups: how many fit a compute unit depends on the instance
+#define PACKKV_LAUNCH_VX(g, high)                                                                          \
+    {                                                                                                      \
+        static const int per_cu = resident_workgroups(reinterpret_cast<const void *>(v_matvec_kernel<g, high>)); \
+        plan.n_groups = flat_groups_for(plan.total, B * Hs, per_cu, max_split_rows / G);                    \
+        hipLaunchKernelGGL((v_matvec_kernel<g, high>), dim3(plan.n_groups), dim3(256), 0, s, a, plan);      \
+    }
+#define PACKKV_LAUNCH_V(g) PACKKV_LAUNCH_VX(g, false)
+#define PACKKV_LAUNCH_VH(g) PACKKV_LAUNCH_VX(g, true)
         if (c->qmax_v > 7) {
             PACKKV_DISPATCH_GROUP4(G, PACKKV_LAUNCH_VH)
         } else {
@@ -383,6 +397,7 @@ static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p,
         }
 #undef PACKKV_LAUNCH_VH
 #undef PACKKV_LAUNCH_V
+#undef PACKKV_LAUNCH_VX
     } else if (n_blocks > 0) {
         n_splits = int(std::min<int64_t>(v_splits_for(n_blocks, B * Hs), max_split_rows / rows));
         a.blocks_per_split = (n_blocks + n_splits - 1) / n_splits;

@@ -179,29 +179,21 @@ __device__ inline void v_planes_chunk(const uint8_t *lds_all, int cur, const uin
 // and the block scale was taken one above the unit.
 constexpr float V_PLANES_OUT_SCALE = 512.0f;  // 2 * 2^9 / 2
 
+template <int N_SHIFT>
+__device__ inline float row_shl0(float v) {   // lane i <- lane i + N_SHIFT of its row of 16, 0 past the row's end
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x100 + N_SHIFT, 0xF, 0xF, true));
+}
+
 // Writes this wave's sums as red[g][0..127] (outputs) and red[g][128] (the token-minimum term).
+// The digits of a head sit in neighbouring columns (lanes of a row): the first of them collects
+// the others in a fixed order.
 template <int G>
 __device__ inline void v_planes_store(const VPlaneState<G> &st, float (*red)[D + 4], int lane) {
     constexpr int NP = v_pieces<G>();
     const int rg = lane >> 4, col = lane & 15;
     const int head = col / NP, piece = col % NP;
     const float place = head < G ? V_PLANES_OUT_SCALE * float(1u << (4 * piece)) : 0.0f;
-    // columns of one head are neighbours but do not fill a power-of-two group of lanes: the sums
-    // go through LDS, one float per (channel, column)
-#pragma unroll
-    for (int g = 0; g < G; ++g)
-        for (int d = lane; d < D; d += 64) red[g][d] = 0.0f;
-    wave_lds_fence();
-    for (int k = 0; k < NP; ++k) {
-        // in round k the lanes holding digit k add their column in: a fixed order
-        if (piece == k && head < G) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-#pragma unroll
-                for (int r = 0; r < 4; ++r) red[head][8 * (4 * rg + r) + j] += st.acc[j][r] * place;
-        }
-        wave_lds_fence();
-    }
+    // pack-minimum term first: lanes 0..15 cover every channel of every head
 #pragma unroll
     for (int g = 0; g < G; ++g) {
 #pragma unroll
@@ -209,12 +201,35 @@ __device__ inline void v_planes_store(const VPlaneState<G> &st, float (*red)[D +
             float v = st.macc[g][j];
             v += __shfl_xor(v, 16);
             v += __shfl_xor(v, 32);
-            if (lane < 16) red[g][8 * lane + j] += v;
+            if (lane < 16) red[g][8 * lane + j] = v;
         }
         float s = st.pm[g];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) s += __shfl_xor(s, o);
         if (lane == 0) red[g][D] = s;
+    }
+    wave_lds_fence();
+    const bool first = piece == 0 && head < G;
+    float *row = red[first ? head : 0] + 32 * rg;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        // four sums at a time keep the register count of the main loop
+        float sum[4], cur[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const float v = st.acc[j][r] * place;
+            float t = v + row_shl0<1>(v);
+            t += row_shl0<2>(v);
+            t += row_shl0<3>(v);
+            if constexpr (NP == 5) t += row_shl0<4>(v);
+            sum[r] = t;
+        }
+        if (first) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) cur[r] = row[8 * r + j];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) row[8 * r + j] = cur[r] + sum[r];
+        }
     }
 }
 
