@@ -147,11 +147,14 @@ def pack_chunk_wide(q_chunk):
     return buf[:size].copy(), w, m
 
 
-def pack_chunk(q_chunk, pack_size=K, contiguous=False):
+ORDERS = {"group": 0, "channel": 1}
+
+
+def pack_chunk(q_chunk, pack_size=K, order="group", contiguous=False):
     """q_chunk: uint8 [64, 128] -> (bytes uint8 [size], widths [packs], mins [packs]), packs =
     (64 / pack_size) * 128, widths and mins indexed [token_group*128 + channel].  Packs of 16 use
-    the plane layout (the V cache); contiguous=True packs them in the contiguous-pack layout
-    instead (the K cache; also the layout of the packs of 8)."""
+    the plane layout with the given pack list order ("group" or "channel"); contiguous=True
+    packs them in the contiguous-pack layout instead (the layout of the packs of 8)."""
     q_chunk = np.ascontiguousarray(q_chunk, dtype=np.uint8)
     assert q_chunk.shape == (N, D) and pack_size in (8, 16)
     packs = N // pack_size * D
@@ -159,8 +162,9 @@ def pack_chunk(q_chunk, pack_size=K, contiguous=False):
     w = np.empty(packs, np.uint8)
     m = np.empty(packs, np.uint8)
     if pack_size == 16 and not contiguous:
-        size = lib().orc_pack_chunk_planes(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m))
+        size = lib().orc_pack_chunk_planes(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), ORDERS[order])
     else:
+        assert order == "group"
         size = lib().orc_pack_chunk_k(_p(q_chunk), C.c_int64(D), _p(buf), _p(w), _p(m), pack_size)
     return buf[:size].copy(), w, m
 
@@ -185,11 +189,11 @@ class Compressed:
         return (self.meta >> 16).astype(np.uint16)
 
 
-def compress(x, rel, pack_size=K, contiguous=False) -> Compressed:
+def compress(x, rel, pack_size=K, order="group") -> Compressed:
     """x: fp16 [B, T, H, D] with T a multiple of 64 -> Compressed (packs of pack_size tokens).
-    Scales finer than 1/15 (codes above 15) give wide chunks and need pack_size 8.  contiguous:
-    bit order of the chunks with packs of 16 tokens (False: planes, the V cache; True:
-    contiguous packs, the K cache; see compress_k / compress_v)."""
+    Scales finer than 1/15 (codes above 15) give wide chunks and need pack_size 8.  order: pack
+    list of the chunks with packs of 16 tokens ("group" or "channel"; the cache keeps V
+    group-major and K channel-major)."""
     x = _u16(x)
     B, T, H, Dd = x.shape
     assert Dd == D and T % N == 0 and pack_size in (8, 16)
@@ -205,19 +209,19 @@ def compress(x, rel, pack_size=K, contiguous=False) -> Compressed:
     size = lib().orc_compress_k(_p(x), B, T, H, Dd, C.c_int64(T * H * Dd), C.c_int64(H * Dd),
                                 C.c_float(rel), _p(arena), C.c_int64(cap), _p(offsets), _p(meta),
                                 _p(codes), _p(widths), _p(mins), pack_size,
-                                1 if (contiguous and pack_size == 16) else 0)
+                                ORDERS[order] if pack_size == 16 else 0)
     assert size >= 0, size
     return Compressed(arena[:size].copy(), offsets, meta, codes, widths, mins)
 
 
 def compress_k(x, rel, pack_size=K) -> Compressed:
-    """The K cache: packs of 16 in the contiguous-pack layout."""
-    return compress(x, rel, pack_size, contiguous=True)
+    """The K cache: chunks with packs of 16 list their packs channel-major."""
+    return compress(x, rel, pack_size, order="channel")
 
 
 def compress_v(x, rel, pack_size=K) -> Compressed:
-    """The V cache: packs of 16 in the plane layout."""
-    return compress(x, rel, pack_size, contiguous=False)
+    """The V cache: chunks with packs of 16 list their packs group-major."""
+    return compress(x, rel, pack_size, order="group")
 
 
 def v_median_order(v_codes):

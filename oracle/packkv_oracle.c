@@ -34,11 +34,10 @@
  *     channel], then the packs in the same order, each `width` bytes
  *     little-endian with the code of token i at bits [i*width, (i+1)*width),
  *     zero padded to 16 bytes;
- *   - chunk bytes, packs of 16: 512 header bytes indexed [token_group*128 +
- *     channel], then exactly 16*width bits per pack (Sec. III-B.3), zero padded
- *     to 16 bytes, in one of two bit orders: contiguous (orc_pack_chunk_k, the K
- *     cache: pack after pack, token i at bits [i*width, (i+1)*width)) or planes
- *     (orc_pack_chunk_planes, the V cache: two-bit planes and a one-bit plane);
+ *   - chunk bytes, packs of 16 (orc_pack_chunk_planes): 512 header bytes, then
+ *     every pack's 16*width bits as two-bit planes and a one-bit plane (a fixed
+ *     order of exactly 16*width bits per pack, Sec. III-B.3), zero padded to 16
+ *     bytes; the packs of a chunk are listed group-major or channel-major;
  *   - repacking (V-median and greedy orders): see the comments of
  *     orc_v_median_order and orc_greedy_order; the median and tie conventions
  *     are "parity unpinned" readings (any order is a valid cache).
@@ -207,8 +206,9 @@ int orc_width(int range)
 
 /*
  * Pack one chunk in the contiguous-pack layout: the 64 x 128 codes of one (batch,
- * kv-head, block), packs of k tokens (k = 8: the layout of packs of 8 tokens; k = 16:
- * the layout of the K cache with packs of 16).  q points at code (token 0, channel 0); consecutive
+ * kv-head, block), packs of k tokens (k = 8 is the layout of packs of 8 tokens; k = 16
+ * in this layout is kept as a second, plainer statement of the same packs that the
+ * tests compare the plane layout's sizes and metadata with).  q points at code (token 0, channel 0); consecutive
  * tokens are `token_stride` apart.  Writes the chunk bytes (header, payload,
  * zero padding to 16 bytes) and, when not NULL, the logical per-pack widths and
  * minimums [(64/k)*128].  Returns the chunk size in bytes (a multiple of 16).
@@ -288,7 +288,9 @@ int orc_pack_chunk_wide(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
  * ceil(log2(range+1)) and 16 codes of w bits (Sec. III-B.3) -- and that lengths and
  * minimums come first in the block (Sec. III-C); the order of the 16*w bits is a
  * choice of this build:
- *   pack list     pack p = g*128 + d (g = token group of 16 tokens, d = channel)
+ *   pack list     order 0 (group-major):   pack p = g*128 + d
+ *                 order 1 (channel-major): pack p = d*4 + g
+ *                 (g = token group of 16 tokens, d = channel)
  *   bytes [0,512) header, byte p = (w << 4) | min of pack p
  *   region E      for p = 0..511 in turn: if w >= 2 one little-endian 32-bit word
  *                 with the low two bits (c & 3) of the 16 codes, and if w == 4 a
@@ -300,15 +302,16 @@ int orc_pack_chunk_wide(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
  *                 4*(i & 3) + (i >> 2)
  *   zero padding to a multiple of 16 bytes
  * so a pack takes 0, 16, 32, 48 or 64 bits for w = 0..4.  widths / mins (optional)
- * receive the per-pack values indexed [g*128 + d].  Returns the chunk size in bytes.
+ * receive the logical per-pack values indexed [g*128 + d] whatever the order.
+ * Returns the chunk size in bytes.
  */
 int orc_pack_chunk_planes(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
-                          uint8_t *widths, uint8_t *mins)
+                          uint8_t *widths, uint8_t *mins, int order)
 {
     int w_of[ORC_PACKS], lo_of[ORC_PACKS], g_of[ORC_PACKS], d_of[ORC_PACKS];
     for (int p = 0; p < ORC_PACKS; ++p) {
-        int g = p / ORC_D;
-        int d = p % ORC_D;
+        int g = order ? p % ORC_GROUPS : p / ORC_D;
+        int d = order ? p / ORC_GROUPS : p % ORC_D;
         int lo = 255, hi = 0;
         for (int i = 0; i < ORC_K; ++i) {
             int v = q[(int64_t)(g * ORC_K + i) * token_stride + d];
@@ -351,11 +354,11 @@ int orc_pack_chunk_planes(const uint8_t *q, int64_t token_stride, uint8_t *bytes
     return pos;
 }
 
-/* Packs of 16 tokens, plane layout. */
+/* Packs of 16 tokens, group-major pack list. */
 int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
                    uint8_t *widths, uint8_t *mins)
 {
-    return orc_pack_chunk_planes(q, token_stride, bytes, widths, mins);
+    return orc_pack_chunk_planes(q, token_stride, bytes, widths, mins, 0);
 }
 
 /*
@@ -365,18 +368,18 @@ int orc_pack_chunk(const uint8_t *q, int64_t token_stride, uint8_t *bytes,
  * chunk c in 16-byte units, offsets16[nchunks] the end of the arena.
  * meta[b*T + t] = scale16 | min16 << 16.  q_out (optional) receives the codes,
  * widths_out / mins_out (optional) the per-pack values [nchunks][(64/k)*128],
- * indexed [token_group*128 + channel].  contiguous: bit order of chunks with packs
- * of 16 (0 planes, the V cache; 1 contiguous, the K cache).
+ * indexed [token_group*128 + channel].  order: pack list of the chunks with packs
+ * of 16 (0 group-major, 1 channel-major; see orc_pack_chunk_planes).
  * Returns the arena size in bytes, or -1 if it would exceed arena_cap.
  */
 int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
                        int64_t batch_stride, int64_t token_stride, float rel,
                        uint8_t *arena, int64_t arena_cap, uint32_t *offsets16,
                        uint32_t *meta, uint8_t *q_out, uint8_t *widths_out,
-                       uint8_t *mins_out, int k, int contiguous)
+                       uint8_t *mins_out, int k, int order)
 {
     if (D != ORC_D || T % ORC_N || (k != 8 && k != 16)) return -2;
-    if (contiguous != 0 && contiguous != 1) return -2;
+    if (order != 0 && (order != 1 || k != 16)) return -2;  /* the pack list order exists for packs of 16 */
     int wide = orc_qmax(rel) > 15;  /* codes do not fit the 4-bit minimum of the one-byte metadata */
     if (wide && (k != 8 || orc_qmax(rel) > 255)) return -2;
     int packs = ORC_N / k * ORC_D;
@@ -400,7 +403,7 @@ int64_t orc_compress_k(const uint16_t *x, int B, int T, int H, int D,
                 uint8_t *wo = widths_out ? widths_out + c * packs : NULL;
                 uint8_t *mo = mins_out ? mins_out + c * packs : NULL;
                 int sz = wide ? orc_pack_chunk_wide(q0, (int64_t)H * D, tmp, wo, mo)
-                         : k == 16 && !contiguous ? orc_pack_chunk_planes(q0, (int64_t)H * D, tmp, wo, mo)
+                         : k == 16 ? orc_pack_chunk_planes(q0, (int64_t)H * D, tmp, wo, mo, order)
                                    : orc_pack_chunk_k(q0, (int64_t)H * D, tmp, wo, mo, k);
                 if (pos + sz > arena_cap) { rc = -1; break; }
                 memcpy(arena + pos, tmp, (size_t)sz);

@@ -264,14 +264,14 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         job.first_token = c->packed_tokens;
         job.first_chunk = c->packed_tokens / N * B * H;
         job.order = nullptr;
-        job.planes = true;
+        job.pack_order = 0;
         job.bf16 = bf16;
         CompressJob kjob = job, vjob = job;
         kjob.src = ksrc + int64_t(done) * N * job.token_stride;
         kjob.rel = c->cfg.k_rel_scale;
         kjob.qmax = c->qmax_k;
         kjob.wide = c->wide_k;
-        kjob.planes = false;
+        kjob.pack_order = 1;  // K chunks list their packs channel-major (what the K kernel's lanes own)
         kjob.arena = static_cast<uint8_t *>(c->buf.k_arena);
         kjob.arena_cap16 = c->sizes.k_arena / 16;
         kjob.index = static_cast<uint32_t *>(c->buf.k_index);

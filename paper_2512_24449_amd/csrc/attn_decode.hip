@@ -19,7 +19,7 @@
 // handles the raw fp16 tail.  No floating-point atomics: bitwise reproducible.
 #include <algorithm>
 
-#include "k_chunk.h"
+#include "k_planes.h"
 #include "pack8.h"
 #include "v_chunk.h"
 #include "v_planes.h"
@@ -171,21 +171,20 @@ __device__ inline void attn_store_partial(const AArgs &a, const State &st, const
 // HIGH: the V codes of the cache may need four bits (a plane H exists).
 template <int G, bool HIGH>
 __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
-    // per wave: buffer 0 holds the K chunk, buffer 1 the V chunk of the block in flight; after
-    // the main loop the same memory holds the cross-wave reduction array red[4][G][D + 4]
+    // per wave: buffer 0 holds the K chunk (and then its tiles, k_planes.h), buffer 1 the V chunk of
+    // the block in flight; after the main loop the same memory holds the cross-wave reduction array
+    // red[4][G][D + 4]
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
     constexpr int VB = vb_bytes<G>();
     __shared__ __attribute__((aligned(16))) uint8_t vb_all[4 * VB];  // digit staging of the V phase
-    __shared__ uint4 table[PACK_TABLE_ENTRIES];                      // K chunks: contiguous bit fields
-    __shared__ uint4 vtable[PLANE_TABLE_ENTRIES];                    // V chunks: plane layout
+    __shared__ uint4 ktable[5];                                      // K chunks: plane layout, channel-major
+    __shared__ uint4 vtable[PLANE_TABLE_ENTRIES];                    // V chunks: plane layout, group-major
     __shared__ uint32_t vhighs[PLANE_TABLE_ENTRIES];
     static_assert(sizeof(float) * 4 * G * (D + 4) <= 4 * 2 * CHUNK_LDS, "reduction array must fit");
+    static_assert(K_TILES_BYTES <= CHUNK_LDS && CHUNK_LDS % 16 == 0, "the K tiles are built in the K buffer");
     float(*red)[G][D + 4] = reinterpret_cast<float(*)[G][D + 4]>(lds_all);
-    if constexpr (G == 1)
-        build_pair_table(reinterpret_cast<uint2 *>(table));
-    else
-        build_pack_table(table, 0, fold_min<G>());
     for (int i = threadIdx.x; i < 4 * VB / 4; i += 256) reinterpret_cast<uint32_t *>(vb_all)[i] = 0;
+    build_k_plane_table(ktable);
     build_plane_table(vtable, vhighs);
 
     const int lane = threadIdx.x & 63;
@@ -193,23 +192,12 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
     const int split = blockIdx.x;
     const int bh = blockIdx.y;
     const int h = bh % a.H, b = bh / a.H;
-    const int row = lane >> 4, col = lane & 15;
+    const int col = lane & 15;
     const int kbuf = wave * 2 * CHUNK_LDS, vbuf = kbuf + CHUNK_LDS;
     const int64_t head0 = int64_t(b) * a.H * G + h * G;
 
-    KQueryFma kq1;
-    KQueryMfma<G == 1 ? 2 : G> kqg;  // the unused form costs nothing
-    float qsum[G];
-    if constexpr (G == 1) {
-        kq1.load(a.q + head0 * D, lane);
-        qsum[0] = kq1.qsum;
-    } else {
-        kqg.load(a.q + head0 * D, lane);
-        // the sum over all 128 channels is the same in every lane: scalar registers
-#pragma unroll
-        for (int g = 0; g < G; ++g)
-            qsum[g] = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(kqg.qsum[g])));
-    }
+    KQueryPlanes<G> kq;
+    kq.load(a.q + head0 * D, lane);
     uint8_t *vb = vb_all + wave * VB;
     VPlaneState<G> st;
     st.clear();
@@ -244,40 +232,17 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
 
             float s[G];  // scores of token `lane` in log2 units
             if (valid) {
-                const uint2 hdr = *reinterpret_cast<const uint2 *>(lds_all + kbuf + lane * 8);
-                LanePacks lp;
-                lp.init(hdr.x, hdr.y, kbuf + HEADER);
                 float u[G];
-                if constexpr (G == 1) {
-                    u[0] = k_chunk_fma(lds_all, reinterpret_cast<const uint2 *>(table), lp, kq1, lane);
-                } else {
-                    float4_t acc[4];
-                    float ms_row[G];
-                    k_chunk_mfma<G>(lds_all, table, lp, kqg, acc, ms_row);
-                    // lane (r, n) holds four consecutive tokens of heads 4r..4r+3: through LDS to lane = token
-                    // the digit staging of the V phase is idle now; its last row (zeros) stays untouched
-                    static_assert(VB - 64 >= int(sizeof(float)) * G * N, "score tile must fit the digit staging");
-                    float(*sc)[N] = reinterpret_cast<float(*)[N]>(vb);
-                    const int tb = k_mfma_token_base(col);
-#pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        if (4 * row + x < G)
-                            *reinterpret_cast<float4 *>(&sc[4 * row + x][tb]) =
-                                make_float4(acc[0][x], acc[1][x], acc[2][x], acc[3][x]);
-                    wave_lds_fence();
-#pragma unroll
-                    for (int g = 0; g < G; ++g) u[g] = fmaf(sc[g][lane], K_MFMA_OUT_SCALE, ms_row[g]);
-                    wave_lds_fence();
-                }
+                k_planes_chunk<G>(lds_all, kbuf, ktable, lds_all + kbuf, kq, u, []() {});
                 const float kscale = __half2float(__ushort_as_half(uint16_t(kmt & 0xFFFFu)));
                 const float kmn = __half2float(__ushort_as_half(uint16_t(kmt >> 16)));
 #pragma unroll
-                for (int g = 0; g < G; ++g) s[g] = a.sm_log2 * fmaf(kscale, u[g], kmn * qsum[g]);
+                for (int g = 0; g < G; ++g) s[g] = a.sm_log2 * fmaf(kscale, u[g], kmn * kq.qsum[g]);
 
                 attn_raise_reference<G>(s, m_ref, l_lane, st, col);
             }
             wait_chunk_landed();  // V chunk of this block
-            lds_reads_returned();  // the K chunk has been read completely before the next one overwrites it
+            lds_reads_returned();  // the K tiles have been read completely before the next chunk overwrites them
             if (it + 1 < n_it)
                 chunk_issue_lds(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
             if (!valid) continue;

@@ -68,6 +68,11 @@ struct FlatPlan {
     __host__ __device__ int group_of(int64_t f) const { return int(((f + 1) * n_groups - 1) / total); }
 };
 
+// Workgroups of 256 threads of `kernel` that fit one compute unit; workgroups for a flat work
+// list of `total` chunks, at most `most` (v_matvec.hip).
+int resident_workgroups(const void *kernel);
+int flat_groups_for(int64_t total, int per_cu, int64_t most);
+
 inline size_t v_partial_bytes(int batch, int n_q_heads) {
     return size_t(V_SPLITS_MAX) * batch * n_q_heads * V_PART_STRIDE * sizeof(float);
 }
@@ -266,7 +271,7 @@ struct CompressJob {
     uint32_t *page_list;      // paged arena: [0] pages held, [1] 16-byte units used in the newest, [2..] page numbers
     int64_t max_pages;        // page numbers the list has room for
     const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
-    bool planes;              // packs of 16: plane layout (V) instead of the contiguous bit fields (K)
+    int pack_order;           // packs of 16 (plane layout): 0 group-major pack list (V), 1 channel-major (K)
 };
 
 int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s);

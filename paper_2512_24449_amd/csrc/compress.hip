@@ -804,16 +804,14 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     if (n_chunks <= 0 || n_chunks > MAX_NEW_CHUNKS) return KV_ERR_ARG;
     uint8_t *ws = static_cast<uint8_t *>(c->buf.workspace);
     uint32_t *sizes16 = reinterpret_cast<uint32_t *>(ws + WS_SIZES);
-    const bool planes = !job.wide && c->cfg.pack_size == 16 && job.planes;
-    auto sizes_kernel = job.wide ? chunk_kernel<false, 8, true>
-                                 : (c->cfg.pack_size == 8 ? chunk_kernel<false, 8> : chunk_kernel<false, 16>);
-    auto write_kernel = job.wide ? chunk_kernel<true, 8, true>
-                                 : (c->cfg.pack_size == 8 ? chunk_kernel<true, 8> : chunk_kernel<true, 16>);
+    const bool planes = !job.wide && c->cfg.pack_size == 16;
+    auto sizes_kernel = job.wide ? chunk_kernel<false, 8, true> : chunk_kernel<false, 8>;
+    auto write_kernel = job.wide ? chunk_kernel<true, 8, true> : chunk_kernel<true, 8>;
     if (planes)
         hipLaunchKernelGGL(chunk16_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
                            job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                            job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16, 0);
+                           job.order, job.bf16, job.pack_order);
     else
         hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                            job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
@@ -829,7 +827,7 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
         hipLaunchKernelGGL(chunk16_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
                            job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
                            job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16, 0);
+                           job.order, job.bf16, job.pack_order);
     else
         hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
                            job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,

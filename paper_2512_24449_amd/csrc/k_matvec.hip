@@ -20,6 +20,7 @@
 #include <algorithm>
 
 #include "k_chunk.h"
+#include "k_planes.h"
 #include "pack8.h"
 
 namespace packkv {
@@ -378,6 +379,87 @@ __global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
     }
 }
 
+// Packs of 16 tokens, plane layout (k_planes.h), G <= 4 heads per kv-head.  The chunks of all
+// streams form one work list cut into equal ranges, one per workgroup (FlatPlan); the four waves
+// of a workgroup take every fourth block of its range.  A wave keeps ONE chunk buffer and its
+// tiles: the planes of a chunk are copied to the tiles in the first part of its decode, and the
+// next chunk streams into the buffer during the rest (the products, the score exchange, the
+// stores), so five workgroups fit a compute unit and their waves hide one another's waits.  The
+// token metadata of a chunk travels the same way as the chunk (one dword per lane, global memory
+// -> LDS, behind the chunk in its buffer).  Workgroups past the plan's take the raw fp16 tail.
+template <int G>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k_planes_kernel(KArgs a, FlatPlan plan) {
+    constexpr int SIDE = CHUNK_MAX + LDS_TAIL_PAD;  // metadata row behind the chunk
+    constexpr int BUF = SIDE + 256;
+    static_assert(BUF % 16 == 0, "buffers are 16-byte aligned");
+    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * BUF];
+    __shared__ __attribute__((aligned(16))) uint8_t tiles_all[4 * K_TILES_BYTES];
+    __shared__ uint4 table[5];
+    build_k_plane_table(table);
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int grp = blockIdx.x;
+    if (grp >= plan.n_groups) {
+        const int bh = (grp - plan.n_groups) * 4 + wave;
+        if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
+        return;
+    }
+    const int cur = wave * BUF;
+    uint8_t *tiles = tiles_all + wave * K_TILES_BYTES;
+    const int64_t range_end = plan.begin(grp + 1);
+
+    for (int64_t f = plan.begin(grp); f < range_end;) {
+        const int stream = int(f / plan.n_blocks);
+        const int blk_begin = int(f - int64_t(stream) * plan.n_blocks);
+        const int blk_end = int(min<int64_t>(plan.n_blocks, blk_begin + (range_end - f)));
+        f += blk_end - blk_begin;
+        const int h = stream % a.H, b = stream / a.H;
+        const uint32_t *meta = a.meta + b * a.meta_stride;
+        const int64_t head0 = int64_t(stream) * G;
+        KQueryPlanes<G> kq;
+        kq.load(a.q + head0 * D, lane);
+
+        auto issue = [&](const IndexBatch &ib, int it, int blk) {
+            uint8_t *buf = lds_all + cur;
+            row_issue_lds(meta + int64_t(blk) * N, buf + SIDE, lane);
+            chunk_issue_lds(a.arena, ib.start16(it), ib.end16(it), buf, lane);
+        };
+
+        for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+            IndexBatch ib;
+            ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
+            const int n_it = min(64, (blk_end - first + 3) / 4);
+            wait_chunk_landed();  // the index words and the query (the only loads the compiler sees)
+            issue(ib, 0, first);
+            for (int it = 0; it < n_it; ++it) {
+                const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
+                wait_chunk_landed();  // chunk it with its metadata row (and the score stores before it)
+                const int64_t tok = int64_t(first + 4 * it) * N + lane;
+                const uint32_t mt = *reinterpret_cast<const uint32_t *>(lds_all + cur + SIDE + 4 * lane);
+                auto refill = [&]() {
+                    if (it + 1 < n_it) issue(ib, it + 1, first + 4 * (it + 1));
+                };
+                if (!valid) {  // block dropped by an arena overflow: defined output
+                    lds_reads_returned();
+                    refill();
+#pragma unroll
+                    for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                    continue;
+                }
+                float u[G];
+                k_planes_chunk<G>(lds_all, cur, table, tiles, kq, u, refill);
+                const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+                const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+#pragma unroll
+                for (int g = 0; g < G; ++g)
+                    a.scores[(head0 + g) * a.ld + tok] = a.sm_scale * fmaf(scale, u[g], mn * kq.qsum[g]);
+            }
+            wait_chunk_landed();
+        }
+    }
+}
+
 template <int G>
 __global__ __launch_bounds__(256) void k8_matvec_kernel(KArgs a) {
     __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK8_LDS + LDS_TAIL_PAD];
@@ -458,7 +540,18 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     } else if (c->cfg.pack_size == 8) {
         PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_K8)
     } else {
-        PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_K)
+        FlatPlan plan;
+        plan.n_blocks = a.n_blocks;
+        plan.total = int64_t(a.n_blocks) * streams;
+        // one round of resident workgroups, never less than one block per wave
+#define PACKKV_LAUNCH_KP(g)                                                                                   \
+    {                                                                                                         \
+        static const int per_cu = resident_workgroups(reinterpret_cast<const void *>(k_planes_kernel<g>));    \
+        plan.n_groups = plan.total > 0 ? flat_groups_for(plan.total, per_cu, int64_t(1) << 30) : 0;  \
+        hipLaunchKernelGGL(k_planes_kernel<g>, dim3(plan.n_groups + tail_groups), dim3(256), 0, s, a, plan); \
+    }
+        PACKKV_DISPATCH_GROUP4(c->group, PACKKV_LAUNCH_KP)
+#undef PACKKV_LAUNCH_KP
     }
 #undef PACKKV_LAUNCH_KW
 #undef PACKKV_LAUNCH_K8

@@ -332,9 +332,8 @@ int resident_workgroups(const void *kernel) {
 }
 
 // Workgroups for the flat work list of `total` chunks: one round of resident workgroups (per_cu
-// of them fit a compute unit), never less than one block per wave, at most 62 per stream (the
-// combine kernels take up to 64 row sets per stream).
-int flat_groups_for(int64_t total, int streams, int per_cu, int64_t max_row_sets) {
+// of them fit a compute unit), never less than one block per wave, at most `most`.
+int flat_groups_for(int64_t total, int per_cu, int64_t most) {
     static int n_cu = 0;
     if (n_cu == 0) {
         int dev = 0, v = 0;
@@ -346,8 +345,7 @@ int flat_groups_for(int64_t total, int streams, int per_cu, int64_t max_row_sets
     }
     int64_t w = int64_t(n_cu) * per_cu;
     w = std::min<int64_t>(w, (total + 3) / 4);
-    w = std::min<int64_t>(w, int64_t(62) * streams);
-    w = std::min<int64_t>(w, max_row_sets - streams);
+    w = std::min<int64_t>(w, most);
     return int(std::max<int64_t>(w, 1));
 }
 
@@ -381,11 +379,13 @@ static int launch_v_matvec_into(const kv_cache *c, const float *p, int64_t ld_p,
     if (n_blocks > 0 && planes) {
         // row sets: one per (workgroup, stream it touches), G rows each
         if (max_split_rows / G <= int64_t(B) * Hs) return KV_ERR_CAPACITY;
-        // one round of resident workgroups: how many fit a compute unit depends on the instance
+        // one round of resident workgroups: how many fit a compute unit depends on the instance; at
+        // most 62 per stream (the combine kernel takes up to 64 row sets per stream)
+        const int64_t most_groups = std::min<int64_t>(int64_t(62) * B * Hs, max_split_rows / G - int64_t(B) * Hs);
 #define PACKKV_LAUNCH_VX(g, high)                                                                          \
     {                                                                                                      \
         static const int per_cu = resident_workgroups(reinterpret_cast<const void *>(v_matvec_kernel<g, high>)); \
-        plan.n_groups = flat_groups_for(plan.total, B * Hs, per_cu, max_split_rows / G);                    \
+        plan.n_groups = flat_groups_for(plan.total, per_cu, most_groups);                                 \
         hipLaunchKernelGGL((v_matvec_kernel<g, high>), dim3(plan.n_groups), dim3(256), 0, s, a, plan);      \
     }
 #define PACKKV_LAUNCH_V(g) PACKKV_LAUNCH_VX(g, false)

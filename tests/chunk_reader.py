@@ -1,14 +1,14 @@
 """An independent reader of the packed chunk formats, written from the format
 descriptions alone (not from the oracle's packer, not from the HIP kernels).
 
-Contiguous-pack layout (packs of 8 tokens; K chunks with packs of 16): (64/k)*128 header bytes, byte
+Contiguous-pack layout (packs of 8 tokens): (64/k)*128 header bytes, byte
 [g*128 + d] = (width << 4) | min for the pack of token group g (k tokens) and
 channel d; then the pack payloads in the same order, k*width/8 bytes each,
 little-endian, token i at bits [i*width, (i+1)*width); zero padding up to a
 multiple of 16 bytes.
 
-Plane layout (V chunks with packs of 16 tokens): 512 header bytes, pack p = g*128 + d;
-region E: one
+Plane layout (packs of 16 tokens): 512 header bytes in pack-list order
+(group-major: pack p = g*128 + d; channel-major: p = d*4 + g); region E: one
 32-bit word per pack of width >= 2 (the low two bits of its codes) directly
 followed, for width 4, by a second word (the high two bits), packs in list
 order; region O: one 16-bit word per pack of odd width (the top bit of its
@@ -22,11 +22,12 @@ D, N, K = 128, 64, 16
 PACKS = (N // K) * D
 
 
-def read_chunk_planes(buf):
+def read_chunk_planes(buf, order="group"):
     """Plane layout, packs of 16 -> (codes [64,128], widths [512], mins [512]), the last two
     indexed [g*128 + d]."""
     buf = np.asarray(buf, dtype=np.uint8)
-    where = [divmod(p, D) for p in range(PACKS)]
+    assert order in ("group", "channel")
+    where = [divmod(p, D) if order == "group" else (p % 4, p // 4) for p in range(PACKS)]
     widths = np.zeros(PACKS, np.int64)
     mins = np.zeros(PACKS, np.int64)
     codes = np.zeros((N, D), np.int64)
@@ -58,11 +59,11 @@ def read_chunk_planes(buf):
     return codes, widths, mins
 
 
-def read_chunk(buf, k=K, contiguous=False):
+def read_chunk(buf, k=K, order="group", contiguous=False):
     """buf: uint8 array holding exactly one chunk -> (codes [64,128], widths [packs], mins [packs]).
     Packs of 16 are read in the plane layout unless contiguous is set."""
     if k == 16 and not contiguous:
-        return read_chunk_planes(buf)
+        return read_chunk_planes(buf, order)
     buf = np.asarray(buf, dtype=np.uint8)
     packs = (N // k) * D
     widths = (buf[:packs] >> 4).astype(np.int64)
@@ -105,7 +106,7 @@ def read_chunk_wide(buf):
     return codes, widths, mins
 
 
-def read_arena(arena, offsets16, B, T, H, k=K, wide=False, contiguous=False):
+def read_arena(arena, offsets16, B, T, H, k=K, wide=False, order="group"):
     """Decode every chunk of an arena -> codes int64 [B, T, H, 128]."""
     out = np.zeros((B, T, H, D), np.int64)
     c = 0
@@ -113,7 +114,7 @@ def read_arena(arena, offsets16, B, T, H, k=K, wide=False, contiguous=False):
         for b in range(B):
             for h in range(H):
                 lo, hi = int(offsets16[c]) * 16, int(offsets16[c + 1]) * 16
-                codes, _, _ = read_chunk_wide(arena[lo:hi]) if wide else read_chunk(arena[lo:hi], k, contiguous)
+                codes, _, _ = read_chunk_wide(arena[lo:hi]) if wide else read_chunk(arena[lo:hi], k, order)
                 out[b, blk * N:(blk + 1) * N, h, :] = codes
                 c += 1
     return out

@@ -379,7 +379,7 @@ def test_non_finite_inputs_keep_the_format_valid(kw):
         arena = cache.tensors[name + "_arena"][:index[-1] * 16].cpu().numpy()
         for c in range(n_chunks):
             buf = arena[index[c] * 16:index[c + 1] * 16]
-            codes, widths, mins = chunk_reader.read_chunk_wide(buf) if qmax > 15 else chunk_reader.read_chunk(buf, pk, contiguous=(name == "k"))
+            codes, widths, mins = chunk_reader.read_chunk_wide(buf) if qmax > 15 else chunk_reader.read_chunk(buf, pk, "channel" if name == "k" else "group")
             assert codes.min() >= 0 and codes.max() <= qmax and widths.max() <= (8 if qmax > 15 else 4)
     scores = cache.kv_k_matvec(q.cuda(), 0.1)
     cache.kv_softmax(scores)

@@ -132,12 +132,13 @@ def test_pack_chunk_against_independent_reader(orc, seed, k):
     assert buf.size == (64 // k * 128 + k // 8 * int(widths.sum()) + 15) // 16 * 16
 
 
+@pytest.mark.parametrize("order", ["group", "channel"])
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
-def test_plane_layout_of_packs_of_16(orc, seed):
-    """The plane layout (V chunks) stores the same packs as the contiguous-pack layout (K chunks):
-    same widths and minimums, same size (exactly 16 * width bits per pack, Sec. III-B.3), same
-    codes through the independent reader; all five widths and the odd/even plane combinations
-    occur."""
+def test_plane_layout_of_packs_of_16(orc, seed, order):
+    """The plane layout stores the same packs as the contiguous-pack layout: same widths and
+    minimums, same size (exactly 16 * width bits per pack, Sec. III-B.3), same codes through
+    the independent reader, whatever the pack list order; all five widths and the odd/even
+    plane combinations occur."""
     rng = np.random.default_rng(100 + seed)
     q = rng.integers(0, 11, size=(64, 128)).astype(np.uint8)
     q[:, 3] = 7                                  # width 0
@@ -146,7 +147,7 @@ def test_plane_layout_of_packs_of_16(orc, seed):
     q[:, 70:90] = rng.integers(1, 9, size=(64, 20))     # width 3
     if seed == 3:
         q[:] = rng.integers(0, 16, size=(64, 128))      # every pack 4 bits wide: the largest chunk
-    buf, widths, mins = orc.pack_chunk(q, 16)
+    buf, widths, mins = orc.pack_chunk(q, 16, order)
     ref, w_ref, m_ref = orc.pack_chunk(q, 16, contiguous=True)
     assert buf.size == ref.size == (512 + 2 * int(widths.sum()) + 15) // 16 * 16
     assert np.array_equal(widths, w_ref) and np.array_equal(mins, m_ref)
@@ -154,14 +155,17 @@ def test_plane_layout_of_packs_of_16(orc, seed):
         assert set(np.unique(widths)) == {0, 1, 2, 3, 4}
     else:
         assert buf.size == orc.CHUNK_MAX
-    codes, w2, m2 = chunk_reader.read_chunk(buf, 16)
+    codes, w2, m2 = chunk_reader.read_chunk(buf, 16, order)
     assert np.array_equal(codes, q) and np.array_equal(w2, widths) and np.array_equal(m2, mins)
     codes_c, _, _ = chunk_reader.read_chunk(ref, 16, contiguous=True)
     assert np.array_equal(codes_c, q)
-    # both layouts share the header: byte [g*128 + d] = (width << 4) | minimum
+    # the header lists the packs in the stated order
     hdr = buf[:512].astype(np.int64)
-    assert np.array_equal(hdr >> 4, widths) and np.array_equal(hdr & 15, mins)
-    assert np.array_equal(buf[:512], ref[:512])
+    g, d = (np.arange(512) // 128, np.arange(512) % 128) if order == "group" else (np.arange(512) % 4, np.arange(512) // 4)
+    assert np.array_equal(hdr >> 4, widths[g * 128 + d]) and np.array_equal(hdr & 15, mins[g * 128 + d])
+    # the two pack list orders hold the same bits in a different sequence
+    other, _, _ = orc.pack_chunk(q, 16, "channel" if order == "group" else "group")
+    assert other.size == buf.size and np.array_equal(np.sort(other[:512]), np.sort(buf[:512]))
 
 
 def test_plane_layout_bit_positions(orc):
@@ -171,20 +175,18 @@ def test_plane_layout_bit_positions(orc):
         at = 4 * i if i < 8 else 4 * (i - 8) + 2
         for code, w in ((15, 4), (5, 3), (2, 2), (1, 1)):
             q = np.zeros((64, 128), np.uint8)
-            q[i, 0] = code          # pack (group 0, channel 0): the first pack
-            buf, widths, _ = orc.pack_chunk(q, 16)
-            assert widths[0] == w and buf[0] == w << 4
-            payload = buf[512:]
-            if w >= 2:
-                assert int.from_bytes(bytes(payload[:4]), "little") == (code & 3) << at
-            if w == 4:
-                assert int.from_bytes(bytes(payload[4:8]), "little") == (code >> 2) << at
-            if w % 2:
-                o = 4 * (w // 2)
-                assert int.from_bytes(bytes(payload[o:o + 2]), "little") == 1 << (4 * (i % 4) + i // 4)
-            # the contiguous layout of the same chunk: token i at bits [i*w, (i+1)*w) of the pack
-            ref, _, _ = orc.pack_chunk(q, 16, contiguous=True)
-            assert int.from_bytes(bytes(ref[512:512 + 2 * w]), "little") == code << (i * w)
+            q[i, 0] = code          # pack (group 0, channel 0) = first pack in both orders
+            for order in ("group", "channel"):
+                buf, widths, _ = orc.pack_chunk(q, 16, order)
+                assert widths[0] == w and buf[0] == w << 4
+                payload = buf[512:]
+                if w >= 2:
+                    assert int.from_bytes(bytes(payload[:4]), "little") == (code & 3) << at
+                if w == 4:
+                    assert int.from_bytes(bytes(payload[4:8]), "little") == (code >> 2) << at
+                if w % 2:
+                    o = 4 * (w // 2)
+                    assert int.from_bytes(bytes(payload[o:o + 2]), "little") == 1 << (4 * (i % 4) + i // 4)
 
 
 @pytest.mark.parametrize("seed,top", [(0, 255), (1, 25), (2, 16)])
@@ -256,11 +258,11 @@ def test_compress_round_trip_and_size_formula(orc, B, T, H, rel, seed, k):
     assert np.array_equal(chunk_reader.read_arena(c.arena, c.offsets16, B, T, H, k), c.codes)
     # the codes themselves do not depend on the pack size
     assert np.array_equal(c.codes, orc.compress(K, rel).codes)
-    if k == 16:   # nor on the bit order inside the chunks, which also leaves every chunk's size alone
-        cc = orc.compress_k(K, rel, 16)
+    if k == 16:   # nor on the pack list order, which also leaves every chunk's size alone
+        cc = orc.compress(K, rel, 16, order="channel")
         assert np.array_equal(cc.offsets16, c.offsets16) and np.array_equal(cc.meta, c.meta)
         assert np.array_equal(cc.widths, c.widths) and np.array_equal(cc.mins, c.mins)
-        assert np.array_equal(chunk_reader.read_arena(cc.arena, cc.offsets16, B, T, H, 16, contiguous=True), c.codes)
+        assert np.array_equal(chunk_reader.read_arena(cc.arena, cc.offsets16, B, T, H, 16, order="channel"), c.codes)
     # bits per element = mean width + 8/k (pack byte) + padding; token meta adds 32/(H*D)
     sizes = np.diff(c.offsets16.astype(np.int64)) * 16
     expect = (header + per_bit * c.widths.astype(np.int64).sum(1) + 15) // 16 * 16
