@@ -1,6 +1,6 @@
 // Fused decode attention over the packed cache: Att(q, K, V) = softmax(sm_scale * K q)^T V
 // (definition in PackKV Sec. III-B.3) in one pass, with the per-chunk K and V work of
-// Sec. III-C.1 / III-C.2 (k_chunk.h, v_chunk.h) and an online softmax in between, so the
+// Sec. III-C.1 / III-C.2 (k_planes.h, v_planes.h; pack8.h) and an online softmax in between, so the
 // fp32 scores and probabilities never travel through HBM.
 //
 // A wave walks blocks of one (batch, kv-head) stream.  Per block it unpacks the K chunk
@@ -9,7 +9,7 @@
 // chunk of the same block with them.  m_ref is only raised when some score exceeds it by
 // more than 8 (in log2 units): then the exact wave maximum becomes the new reference and
 // all running sums are rescaled once.  Weights therefore stay below 2^8, inside the range
-// the fp16 hi/lo split of the V operand represents, and a reference below the true
+// the V operand's weight split represents, and a reference below the true
 // maximum cancels in the final division.  The wave holds one K and one V chunk buffer:
 // the V chunk streams in while K is unpacked, the next K chunk while V is unpacked.
 //

@@ -168,9 +168,9 @@ __device__ inline int block_exclusive_scan(int v, int *total) {
     return base + inc - v;
 }
 
-// One workgroup per new chunk; packs of PK tokens (16, or 8: Sec. IV-B): the chunk has
-// 64/PK token groups of 128 packs, thread tau owns packs tau + 256k (token group (tau >> 7) + 2k,
-// channel tau & 127).  A pack takes PK*w/8 payload bytes.  WIDE (codes above 15, packs of 8): the
+// One workgroup per new chunk; packs of PK = 8 tokens (Sec. IV-B; packs of 16 have their own
+// kernel below): the chunk has 64/PK token groups of 128 packs, thread tau owns packs tau + 256k
+// (token group (tau >> 7) + 2k, channel tau & 127).  A pack takes PK*w/8 payload bytes.  WIDE (codes above 15, packs of 8): the
 // header is a width byte per pack followed by a minimum byte per pack, widths go up to 8.
 template <bool WRITE, int PK, bool WIDE = false>
 __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ src,
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
                                                     int index_words,
                                                     uint8_t *__restrict__ arena,
                                                     const uint8_t *__restrict__ order, bool bf16) {
-    static_assert(!WIDE || PK == 8, "wide chunks have packs of 8 tokens");
+    static_assert(PK == 8, "contiguous packs are packs of 8 tokens");
     constexpr int NPACKS = N / PK * D;
     constexpr int HDR = WIDE ? 2 * NPACKS : NPACKS;  // header bytes
     constexpr int PER = N / PK * D / 256;  // packs per thread
@@ -249,13 +249,8 @@ __global__ __launch_bounds__(256) void chunk_kernel(const __half *__restrict__ s
         } else {
             dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
         }
-        if constexpr (PK == 16) {
-            uint16_t *out = reinterpret_cast<uint16_t *>(dst + HDR + off[k]);
-            for (int j = 0; j < pb[k].w; ++j) out[j] = uint16_t(pb[k].bits >> (16 * j));
-        } else {
-            uint8_t *out = dst + HDR + off[k];
-            for (int j = 0; j < pb[k].w; ++j) out[j] = uint8_t(pb[k].bits >> (8 * j));
-        }
+        uint8_t *out = dst + HDR + off[k];
+        for (int j = 0; j < pb[k].w; ++j) out[j] = uint8_t(pb[k].bits >> (8 * j));
     }
     if (tau < padded - HDR - payload) dst[HDR + payload + tau] = 0;
 }

@@ -1,34 +1,23 @@
-// Fused K path (PackKV Sec. III-C.1): scores = sm_scale * Khat q, streaming the
-// packed K cache once and unpacking in registers.
+// Fused K path (PackKV Sec. III-C.1): scores = sm_scale * Khat q, streaming the packed K cache
+// once and decoding it on chip.
 //
-// The paper walks a 32-lane warp over K rows and reduces with a warp sum.
-// Here a 64-lane wave owns whole chunks (64 tokens x 128 channels): lane l
-// owns token group g = l/16 and channels 8*(l%16)..+7 (unpack.h); the per-chunk
-// arithmetic (pairwise dot-product form for one query head per kv-head, matrix-core
-// form for grouped queries) is in k_chunk.h; chunks with packs of 8 tokens and wide
-// chunks have their own kernels here and their helpers in pack8.h.  De-quantization
-// is folded in:
+// The paper walks a 32-lane warp over K rows and reduces with a warp sum.  Here a 64-lane wave
+// owns whole chunks (64 tokens x 128 channels).  Chunks with packs of 16 tokens (plane layout)
+// are turned in LDS and contracted on the matrix cores for all query heads of the kv-head at
+// once (k_planes.h); chunks with packs of 8 tokens and wide chunks have their own kernels here
+// and their helpers in pack8.h.  De-quantization is folded in:
 //   score_t = sm_scale * (scale_t * (sum_d q_d code[t,d] + sum_d q_d m[g,d])
 //                         + min_t * sum_d q_d)
-// so the pack minimums cost a few instructions per chunk and (scale_t, min_t) one
-// FMA per token.
-// A workgroup of four waves walks a contiguous range of blocks of one
-// (batch, kv-head) stream; every wave double-buffers whole chunks in LDS with
-// direct global->LDS transfers, so the next chunk is in flight while the
-// current one is unpacked; the raw fp16 tail is handled by extra workgroups of
-// the same launch (one launch covers everything, Sec. III-B.4).
+// so the pack minimums cost a few instructions per chunk and (scale_t, min_t) one FMA per token.
+// Whole chunks travel global memory -> LDS directly, the next one while the current one is
+// decoded; the raw fp16 tail is handled by extra workgroups of the same launch (one launch covers
+// everything, Sec. III-B.4).
 #include <algorithm>
 
-#include "k_chunk.h"
 #include "k_planes.h"
 #include "pack8.h"
 
 namespace packkv {
-
-// In the K kernel alone, folding the pack minimum into the codes pays from eight heads on
-// (at four it costs 4 % here, while it wins in the V and fused kernels).
-template <int G>
-constexpr bool K_FOLD = G >= 8;
 
 struct KArgs {
     const uint8_t *arena;
@@ -50,159 +39,6 @@ struct KArgs {
     int n_tail, tail_cap;
     float sm_scale;
 };
-
-// lds0: the workgroup's chunk buffers; this wave owns the two buffers at byte
-// offsets buf_base and buf_base + CHUNK_LDS.  One query head per kv-head.
-__device__ inline void k_stream_fma(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
-                                    int lane, uint8_t *lds0, int buf_base, const uint2 *table) {
-    const int h = bh % a.H, b = bh / a.H;
-    const int64_t head = int64_t(b) * a.H + h;
-    KQueryFma kq;
-    kq.load(a.q + head * D, lane);
-
-    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
-        IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
-        const int n_it = min(64, (blk_end - first + 3) / 4);
-        vmem_order_fence();
-        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
-        vmem_order_fence();
-        uint32_t mt_next = a.meta[b * a.meta_stride + int64_t(first) * N + lane];
-        for (int it = 0; it < n_it; ++it) {
-            const int cur = buf_base + (it & 1) * CHUNK_LDS;
-            const int64_t tok = int64_t(first + 4 * it) * N + lane;  // this lane's token after the reduction
-            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
-            // issued after this chunk's transfers, and allowed to stay in flight: the metadata
-            // load and, from the second iteration on, the previous iteration's score store
-            if (it == 0)
-                wait_chunk_landed_except<1>();
-            else
-                wait_chunk_landed_except<2>();
-            uint32_t mt = mt_next;
-            consume_here(mt);
-            // the next chunk streams into the other buffer while this one is unpacked
-            if (it + 1 < n_it) {
-                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
-                                lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
-                vmem_order_fence();
-                mt_next = a.meta[b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane];
-            }
-            if (!valid) {  // block dropped by an arena overflow: defined output
-                a.scores[head * a.ld + tok] = 0.0f;  // one store, as on the regular path: the count holds
-                continue;
-            }
-            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
-            LanePacks lp;
-            lp.init(hdr.x, hdr.y, cur + HEADER);
-            const float u = k_chunk_fma(lds0, table, lp, kq, lane);
-            const float scale = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
-            const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
-            a.scores[head * a.ld + tok] = a.sm_scale * fmaf(scale, u, mn * kq.qsum);
-        }
-        wait_chunk_landed();  // nothing may still be streaming into LDS when the buffers are reused
-    }
-}
-
-// Grouped queries: the matrix-core form; lane n < 16 of the rows that hold heads stores four
-// consecutive tokens per head.
-template <int G>
-__device__ inline void k_stream_mfma(const KArgs &a, int bh, int blk_begin, int blk_end, int wave,
-                                     int lane, uint8_t *lds0, int buf_base, const uint4 *table) {
-    const int h = bh % a.H, b = bh / a.H;
-    const int row = lane >> 4, col = lane & 15;
-    const int64_t head0 = int64_t(b) * a.H * G + h * G;
-    KQueryMfma<G, K_FOLD<G>> kq;
-    kq.load(a.q + head0 * D, lane);
-    // this lane's four output tokens inside a block, the heads it holds, where its
-    // token group's pack-minimum sums come from
-    const int tok_base = k_mfma_token_base(col);
-    const int src_lane = 16 * (col >> 2);
-    float qs[4];
-#pragma unroll
-    for (int x = 0; x < 4; ++x) {
-        qs[x] = x < G ? kq.qsum[x] : 0.0f;
-        if (G > 4 && row == 1) qs[x] = kq.qsum[(4 + x) % G];
-    }
-    const bool writer = 4 * row < G;
-
-    for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
-        IndexBatch ib;
-        ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
-        const int n_it = min(64, (blk_end - first + 3) / 4);
-        vmem_order_fence();
-        chunk_issue_lds(a.arena, ib.start16(0), ib.end16(0), lds0 + buf_base, lane);
-        vmem_order_fence();
-        const uint32_t *meta = a.meta + b * a.meta_stride + tok_base;
-        uint4 mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first) * N);
-        for (int it = 0; it < n_it; ++it) {
-            const int cur = buf_base + (it & 1) * CHUNK_LDS;
-            const int64_t tok = int64_t(first + 4 * it) * N + tok_base;
-            const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
-            // issued after this chunk's transfers, and allowed to stay in flight: the metadata
-            // load and, from the second iteration on, the previous iteration's score stores (one
-            // instruction per head register, also for a dropped block)
-            if (it == 0)
-                wait_chunk_landed_except<1>();
-            else
-                wait_chunk_landed_except<1 + (G < 4 ? G : 4)>();
-            uint4 mt = mt_next;
-            consume_here(mt.x), consume_here(mt.y), consume_here(mt.z), consume_here(mt.w);
-            // the next chunk streams into the other buffer while this one is unpacked
-            if (it + 1 < n_it) {
-                chunk_issue_lds(a.arena, ib.start16(it + 1), ib.end16(it + 1),
-                                lds0 + buf_base + ((it + 1) & 1) * CHUNK_LDS, lane);
-                vmem_order_fence();
-                mt_next = *reinterpret_cast<const uint4 *>(meta + int64_t(first + 4 * (it + 1)) * N);
-            }
-            if (!valid) {  // block dropped by an arena overflow: defined output
-                if (writer) {
-#pragma unroll
-                    for (int x = 0; x < 4; ++x)
-                        if (4 * row + x < G)
-                            *reinterpret_cast<float4_u *>(a.scores + (head0 + 4 * row + x) * a.ld + tok) =
-                                float4_u{0.0f, 0.0f, 0.0f, 0.0f};
-                }
-                wait_chunk_landed();  // rare path: keep the next wait's count independent of it
-                continue;
-            }
-            const uint2 hdr = *reinterpret_cast<const uint2 *>(lds0 + cur + lane * 8);
-            LanePacks lp;
-            lp.init(hdr.x, hdr.y, cur + HEADER);
-            float4_t acc[4];  // [token offset 0..3] x [head register]
-            float ms_row[G];
-            k_chunk_mfma<G, K_FOLD<G>>(lds0, table, lp, kq, acc, ms_row);
-
-            // pack-minimum term of this lane's token group, per head register
-            float ms[4] = {0.0f, 0.0f, 0.0f, 0.0f};
-#pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const float v = K_FOLD<G> ? 0.0f : __shfl(ms_row[g], src_lane);
-                if (g < 4) {
-                    if (G <= 4 || row == 0) ms[g] = v;
-                } else if (row == 1) {
-                    ms[g - 4] = v;
-                }
-            }
-            if (writer) {
-                const uint32_t mtw[4] = {mt.x, mt.y, mt.z, mt.w};
-#pragma unroll
-                for (int x = 0; x < 4; ++x) {
-                    if (4 * row + x < G) {
-                        float4_u o;
-#pragma unroll
-                        for (int t = 0; t < 4; ++t) {
-                            const float scale = __half2float(__ushort_as_half(uint16_t(mtw[t] & 0xFFFFu)));
-                            const float mn = __half2float(__ushort_as_half(uint16_t(mtw[t] >> 16)));
-                            o[t] = a.sm_scale * fmaf(scale, acc[t][x] * K_MFMA_OUT_SCALE + ms[x], mn * qs[x]);
-                        }
-                        *reinterpret_cast<float4_u *>(a.scores + (head0 + 4 * row + x) * a.ld + tok) = o;
-                    }
-                }
-            }
-        }
-        wait_chunk_landed();  // nothing may still be streaming into LDS when the buffers are reused
-    }
-}
 
 // Packs of 8 tokens (Sec. IV-B), any group size: every chunk is decoded as two halves of 32
 // tokens (pack8.h).  After the two reductions lane (r, i) holds token 32 (i & 1) + 8 r + (i >> 1)
@@ -347,36 +183,6 @@ __device__ inline void k_tail(const KArgs &a, int bh, int lane) {
 #pragma unroll
     for (int g = 0; g < G; ++g)
         a.scores[(int64_t(b) * a.H * G + h * G + g) * a.ld + a.packed_tokens + lane] = a.sm_scale * acc[g];
-}
-
-template <int G>
-__global__ __launch_bounds__(256) void k_matvec_kernel(KArgs a) {
-    __shared__ __attribute__((aligned(16))) uint8_t lds_all[4 * 2 * CHUNK_LDS + LDS_TAIL_PAD];
-    __shared__ uint4 table[PACK_TABLE_ENTRIES];
-    if constexpr (G == 1)
-        build_pair_table(reinterpret_cast<uint2 *>(table));
-    else
-        build_pack_table(table, 0, K_FOLD<G>);
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int grp = blockIdx.x;
-    if (grp < a.n_stream_groups) {
-        const int bh = grp / a.groups_per_stream;
-        const int part = grp % a.groups_per_stream;
-        const int blk_begin = part * a.blocks_per_group;
-        const int blk_end = min(blk_begin + a.blocks_per_group, a.n_blocks);
-        // one query head per kv-head: pairwise dot products cost fewer issue slots than the two
-        // matrix products and need fewer registers; with grouped queries the unpack is shared
-        // by the G heads only in the matrix-core form
-        if constexpr (G == 1)
-            k_stream_fma(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS,
-                         reinterpret_cast<const uint2 *>(table));
-        else
-            k_stream_mfma<G>(a, bh, blk_begin, blk_end, wave, lane, lds_all, wave * 2 * CHUNK_LDS, table);
-    } else {
-        const int bh = (grp - a.n_stream_groups) * 4 + wave;
-        if (bh < a.B * a.H) k_tail<G>(a, bh, lane);
-    }
 }
 
 // Packs of 16 tokens, plane layout (k_planes.h), G <= 4 heads per kv-head.  The chunks of all
@@ -534,7 +340,6 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     if (grid == 0) return KV_OK;
 #define PACKKV_LAUNCH_KW(g) hipLaunchKernelGGL(kw_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
 #define PACKKV_LAUNCH_K8(g) hipLaunchKernelGGL(k8_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
-#define PACKKV_LAUNCH_K(g) hipLaunchKernelGGL(k_matvec_kernel<g>, dim3(grid), dim3(256), 0, s, a)
     if (c->wide_k) {
         PACKKV_DISPATCH_GROUP(c->group, PACKKV_LAUNCH_KW)
     } else if (c->cfg.pack_size == 8) {
@@ -555,7 +360,6 @@ int launch_k_matvec(const kv_cache *c, const __half *q, float sm_scale, float *s
     }
 #undef PACKKV_LAUNCH_KW
 #undef PACKKV_LAUNCH_K8
-#undef PACKKV_LAUNCH_K
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

@@ -10,7 +10,7 @@
 // only the pack decode itself differs: 8 codes in at most 32 bits, two 16-bit fields.
 #pragma once
 
-#include "k_chunk.h"
+#include "k_dot.h"
 #include "unpack.h"
 #include "v_chunk.h"
 

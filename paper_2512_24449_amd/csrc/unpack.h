@@ -1,27 +1,20 @@
-// Device helpers shared by the fused K and V kernels (gfx950, wave64):
-// DPP wave scan and row reductions, chunk prologue (header -> per-pack LDS
-// positions, payload staging) and the register unpack of one pack into
-// fp16 pairs.
+// Device helpers shared by the fused K, V and attention kernels (gfx950, wave64): DPP wave scan
+// and row reductions, the index batch of a wave, direct global -> LDS transfers of whole chunks
+// and of metadata rows with their counted waits, and the pack tables of the kernels for packs of
+// 8 tokens and wide chunks (pack8.h).  The decode of chunks with packs of 16 tokens (plane
+// layout) is in planes.h, k_planes.h and v_planes.h.
 //
-// Lane-to-pack mapping used by both kernels: lane l of the wave that owns a
-// chunk reads header bytes 8l..8l+7, i.e. it owns token group g = l/16
-// (tokens 16g..16g+15) and channels 8*(l%16)..+7; its eight packs are
-// contiguous in the payload.
-//
-// Unpack: the codes of a pack never become fp32 one by one.  Aligned LDS reads
-// and funnel shifts fetch tokens 0..7 and 8..15; byte permutes build two words
-// whose low/high 16-bit halves hold tokens (m, m+8) at equal bit offsets, and
-// a rotate + mask per token pair leaves each code in the low bits of a 16-bit
-// half.  Read as fp16 that bit pattern is the subnormal code * 2^-24 -- exact,
-// no conversion instruction -- ready for an fp16 dot-product instruction or an fp16 MFMA; the
-// factor 2^24 is applied once per output.
+// In the paths of pack8.h the codes of a pack never become fp32 one by one: the unpack leaves each
+// code in the low bits of a 16-bit half, which read as fp16 is the subnormal code * 2^-24 --
+// exact, no conversion instruction -- ready for an fp16 dot-product instruction or an fp16 MFMA;
+// the factor 2^24 is applied once per output.
 #pragma once
 
 #include "common.h"
 
 namespace packkv {
 
-// A pack read may touch up to 12 bytes past the end of a chunk buffer.
+// A pack read may touch a few bytes past the end of a chunk buffer (at most 12).
 constexpr int LDS_TAIL_PAD = 16;
 constexpr float CODE_SCALE = 16777216.0f;  // 2^24: fp16 subnormal unit^-1
 // The matrix cores align the products of one instruction to the largest nominal exponent
@@ -78,7 +71,7 @@ template <int G>
 constexpr bool fold_min() { return G >= 4; }
 
 // Built once per workgroup, followed by a workgroup barrier.  lift: bit position of a code
-// inside its 16-bit half after expand_pack<lift> (0 or CODE_LIFT).  fold: the last field is
+// inside its 16-bit half after the unpack (0 or CODE_LIFT).  fold: the last field is
 // the pack minimum as a bit pattern for both halves (to be added to the unpacked words)
 // instead of float(min).
 __device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = false) {
@@ -92,7 +85,7 @@ __device__ inline void build_pack_table(uint4 *table, int lift = 0, bool fold = 
     __syncthreads();
 }
 
-// Pack table of the single-head K path, which unpacks two packs side by side: eight bytes
+// Pack table of the K paths that unpack two packs side by side (pack8.h): eight bytes
 // per entry (half the LDS traffic and bank conflicts of the 16-byte form), every field placed
 // where its consumer reads it without a shift:
 //   x: 4w in bits 0..4 (a bit-field offset/width as it stands), w in byte 1, the w-bit code
@@ -119,35 +112,6 @@ __device__ inline uint32_t byte_prefix_sums(uint32_t x) {
     asm("v_lshl_add_u32 %0, %1, 16, %1" : "=v"(x) : "v"(y));
     return x;
 }
-
-// Per-lane view of a chunk header and of where its eight packs sit in LDS.
-struct LanePacks {
-    uint32_t hlo, hhi;  // eight header bytes, pack j in byte j
-    uint32_t plo, phi;  // byte j = 2 * (w_0 + .. + w_j): payload bytes up to and including pack j
-    int start;          // LDS byte address of pack 0
-
-    // lds_base: LDS byte address of this wave's payload region
-    __device__ inline void init(uint32_t lo, uint32_t hi, int lds_base) {
-        hlo = lo;
-        hhi = hi;
-        uint32_t wl = (lo >> 3) & 0x1E1E1E1Eu, wh = (hi >> 3) & 0x1E1E1E1Eu;  // 2 * width per byte
-        wl = byte_prefix_sums(wl);
-        wh = byte_prefix_sums(wh);
-        const uint32_t tl = wl >> 24;
-        wh += tl | (tl << 8) | (tl << 16) | (tl << 24);
-        plo = wl;
-        phi = wh;
-        const int bytes = int(wh >> 24);
-        start = wave_inclusive_scan(bytes) - bytes + lds_base;
-    }
-    __device__ inline uint32_t header_byte(int j) const { return ((j < 4 ? hlo : hhi) >> (8 * (j & 3))) & 0xFFu; }
-    // LDS byte address of pack j
-    __device__ inline int pos(int j) const {
-        if (j == 0) return start;
-        const int k = j - 1;
-        return start + int(((k < 4 ? plo : phi) >> (8 * (k & 3))) & 0xFFu);
-    }
-};
 
 // Chunk offsets of up to 64 blocks of one wave, one block per lane: lane i holds
 // the index words of block first + stride*i of stream (b, h).  Read once per 64
@@ -294,44 +258,6 @@ __device__ inline void wave_lds_fence() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// The raw LDS words of one pack and its width-dependent constants.
-struct PackRaw {
-    uint32_t d0, d1, d2;  // aligned dwords covering the pack's 64-bit window
-    uint32_t sh;          // low 2 bits: byte offset of the pack inside d0
-    uint4 k;              // pack table entry
-};
-
-// lds0: start of the workgroup's payload array; pos: byte address inside it
-// (2-byte aligned).  Aligned dword reads plus byte funnel shifts: misaligned LDS
-// reads, although legal on gfx950, were measured several times slower.
-__device__ inline PackRaw fetch_pack(const uint8_t *lds0, const uint4 *table, int pos, uint32_t hb) {
-    PackRaw r;
-    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
-    r.d0 = pp[0];
-    r.d1 = pp[1];
-    r.d2 = pp[2];
-    r.sh = uint32_t(pos);
-    r.k = table[hb];
-    return r;
-}
-
-// The same with an entry of the pair table.
-struct PackRawPair {
-    uint32_t d0, d1, d2, sh;
-    uint2 k;
-};
-
-__device__ inline PackRawPair fetch_pack_pair(const uint8_t *lds0, const uint2 *table, int pos, uint32_t hb) {
-    PackRawPair r;
-    const uint32_t *pp = reinterpret_cast<const uint32_t *>(lds0 + (pos & ~3));
-    r.d0 = pp[0];
-    r.d1 = pp[1];
-    r.d2 = pp[2];
-    r.sh = uint32_t(pos);
-    r.k = table[hb];
-    return r;
-}
-
 // x >> (byte 1 of amount): the sub-dword operand select reads the byte in place, which saves
 // the instruction that would extract it (the compiler does not form this by itself).
 __device__ inline uint32_t shr_by_byte1(uint32_t x, uint32_t amount) {
@@ -340,33 +266,6 @@ __device__ inline uint32_t shr_by_byte1(uint32_t x, uint32_t amount) {
         : "=v"(y)
         : "v"(amount), "v"(x));
     return y;
-}
-
-// Unpack into eight fp16-pair words: P[m] = tokens (m, m+8) of the group; each
-// 16-bit half is the bit pattern of fp16(code * 2^(LIFT-24)); the table must have been
-// built with the same lift.
-template <int LIFT = 0, bool FOLD = false>
-__device__ inline void expand_pack(const PackRaw &r, uint32_t (&P)[8]) {
-    const uint32_t A = __builtin_amdgcn_alignbyte(r.d1, r.d0, r.sh);   // pack bits [0, 32): tokens 0..7
-    const uint32_t hi_ = __builtin_amdgcn_alignbyte(r.d2, r.d1, r.sh); // pack bits [32, 64)
-    const uint32_t R = uint32_t(((uint64_t(hi_) << 32) | A) >> r.k.z);  // bits [8w, 8w+32): tokens 8..15
-    const uint32_t w = r.k.y, M = r.k.x;  // the rotates read the low five bits of w only
-    uint32_t Z0 = __builtin_amdgcn_perm(R, A, 0x05040100u);  // tokens 0..3 | 8..11
-    // tokens 4..7 | 12..15: both words shifted right by 4w, taken straight from byte 1 of the table field
-    uint32_t Z1 = __builtin_amdgcn_perm(shr_by_byte1(R, r.k.y), shr_by_byte1(A, r.k.y), 0x05040100u);
-    if (LIFT) {  // rotate left: the codes of both halves move up together, the mask picks them there
-        Z0 = __builtin_amdgcn_alignbit(Z0, Z0, 32 - LIFT);
-        Z1 = __builtin_amdgcn_alignbit(Z1, Z1, 32 - LIFT);
-    }
-#pragma unroll
-    for (int m = 0; m < 4; ++m) {
-        P[m] = (Z0 & M) + (FOLD ? r.k.w : 0u);  // FOLD: code + pack minimum (table built with fold)
-        P[4 + m] = (Z1 & M) + (FOLD ? r.k.w : 0u);
-        if (m < 3) {
-            Z0 = __builtin_amdgcn_alignbit(Z0, Z0, w);
-            Z1 = __builtin_amdgcn_alignbit(Z1, Z1, w);
-        }
-    }
 }
 
 __device__ inline float half_lo(uint32_t p) { return float(__builtin_bit_cast(_Float16, uint16_t(p & 0xFFFFu))); }

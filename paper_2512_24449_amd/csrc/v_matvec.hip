@@ -1,20 +1,14 @@
-// Fused V path (PackKV Sec. III-C.2): out = p^T Vhat, streaming the packed V
-// cache once and unpacking in registers.
+// Fused V path (PackKV Sec. III-C.2): out = p^T Vhat, streaming the packed V cache once and
+// decoding it on chip.
 //
-// The paper gives each thread one pack (a dot-product segment along ctx_len)
-// and combines segments with fp32 atomic adds.  Here the contraction runs
-// along the pack direction, so it maps onto the matrix cores without any
-// transposition: for pack slot jj the wave issues
-//     C_jj[channel row i][column] += A[i][k] * B[k][column]      (16x16x32 fp16 MFMA)
-// where row i is lane%16 (channel 8i+jj), the 32 k-slots are 8 tokens of each
-// of the 4 token groups (lane/16), A holds the unpacked codes exactly as
-// unpack_pairs leaves them (fp16 code * 2^-24) and B holds the weights
-// w_t = p_t * scale_t split into fp16 hi and lo*2^11 parts, one column pair per
-// query head (so fp32-accurate weights cost no extra MFMA and G query heads of
-// a GQA group share one unpack).  Accumulation is fp32 inside the MFMA, in a
-// fixed order: the context axis is split over workgroups whose partial sums
-// are combined by a second small kernel -- no atomics, bitwise reproducible.
-// De-quantization is folded in:
+// The paper gives each thread one pack (a dot-product segment along ctx_len) and combines
+// segments with fp32 atomic adds.  Here the contraction runs along the pack direction, so it maps
+// onto the matrix cores without any transposition: the planes of a pack are FP4 operands as they
+// are stored (v_planes.h; packs of 8 tokens and wide chunks: fp16 operands, pack8.h), the
+// softmax weights times the token scales are the other operand, and the G query heads of a group
+// share one decode.  Accumulation is fp32 inside the matrix instruction, in a fixed order: the
+// context axis is split over workgroups whose partial sums are combined by a second small kernel
+// -- no atomics, bitwise reproducible.  De-quantization is folded in:
 //   out_d = sum_t w_t code[t,d] + sum_g m[g,d] sum_{t in g} w_t + sum_t p_t min_t
 #include <algorithm>
 #include <mutex>
