@@ -30,11 +30,39 @@ DEFAULT_WORKLOAD = "llama2_30b_32k_b8"
 ROTATE_BYTES = 1.1e9             # working set to rotate over so reads come from HBM, not the 256 MB LLC
 
 
-# Wave64 issue slots per 64x128 chunk with one query head per kv-head, the binding resource of
-# these kernels (measured constants of profiles/issue_counters_*.txt; an MFMA counts as 2 slots:
-# about 8 cycles of the port when mixed with vector work).  Peak = 256 CUs x 4 SIMDs x 2.4 GHz /
-# 4 cycles per instruction = 614.4 G wave-instructions/s.
-ISSUE_SLOTS_PER_CHUNK = {"k": 344, "v": 303 + 16}
+# The GPU raises its clock over the first tenths of a second of sustained work (measured: the same
+# kernel takes 20 % longer in the first milliseconds after an idle phase).  Every timed loop below is
+# therefore preceded by an untimed run of the same kernels for this long, before the W warmup steps.
+CLOCK_RAMP_S = 0.5
+DOM_KERNEL = {"k": "k_planes_kernel<1>", "v": "v_matvec_kernel<1, false>"}   # names in the profiles
+
+
+def stored_profile_numbers(workload, dom):
+    """Per-launch figures that come from committed rocprofv3 summaries, not from this run:
+    (HBM bytes per launch or None, vector instructions per chunk or None, the files read)."""
+    traffic = slots = None
+    files = []
+    path = os.path.join(ROOT, "profiles", "hbm_traffic_%s.txt" % workload)
+    if os.path.exists(path):
+        for ln in open(path):
+            f = ln.split()
+            if ln.startswith(DOM_KERNEL[dom]) and len(f) >= 4:
+                try:
+                    traffic = int((float(f[-2]) + float(f[-1])) * 1e6)   # fetch_MB + write_MB
+                    files.append("profiles/" + os.path.basename(path))
+                except ValueError:
+                    pass
+    path = os.path.join(ROOT, "profiles", "issue_counters_%s.txt" % workload)
+    if os.path.exists(path):
+        for ln in open(path):
+            if ln.startswith(DOM_KERNEL[dom]):
+                rest = ln[len(DOM_KERNEL[dom]):].split()
+                try:
+                    slots = float(rest[0])                               # VALU/chunk (MFMAs included)
+                    files.append("profiles/" + os.path.basename(path))
+                except (ValueError, IndexError):
+                    pass
+    return traffic, slots, files
 
 
 def parse_args():
@@ -115,7 +143,18 @@ def algorithmic_bytes(st, w, tokens):
     return k, v
 
 
-def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2), paged=False):
+def ramp_clocks(torch, once, seconds):
+    """Untimed: repeat once(i) until `seconds` of wall time have passed (the queue is drained every 50 calls)."""
+    t0, i = time.perf_counter(), 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(50):
+            once(i)
+            i += 1
+        torch.cuda.synchronize()
+
+
+def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2), paged=False,
+               ramp_s=CLOCK_RAMP_S):
     """Timed decode steps over rotating replicas; returns a dict of measurements."""
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
@@ -154,6 +193,12 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
             e3.record()
             v_ev.append((e2, e3))
 
+    def ramp_once(i):   # the decode kernels of a step without the append
+        c = reps.caches[i % R]
+        c.kv_k_matvec(q, sm_scale, scores, stream=st_raw)
+        c.kv_v_matvec(c.kv_softmax(scores, stream=st_raw), out, stream=st_raw)
+
+    ramp_clocks(torch, ramp_once, ramp_s)
     for i in range(warmup):
         step(i, False)
     torch.cuda.synchronize()
@@ -178,6 +223,8 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
             e1.record()
             a_ev.append((e0, e1))
 
+    ramp_clocks(torch, lambda i: reps.caches[i % R].kv_decode_attention(q, sm_scale, attn_out, stream=st_raw),
+                ramp_s / 2)
     for i in range(warmup):
         fused_step(i, False)
     torch.cuda.synchronize()
@@ -218,7 +265,7 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
     return res
 
 
-def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth):
+def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth, ramp_s=CLOCK_RAMP_S):
     """The uncompressed fp16 GEMV companions at the same shapes (head-major cache)."""
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
@@ -235,6 +282,12 @@ def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth):
     p = torch.softmax(scores, dim=-1)
     k_ev, v_ev, mm_ev = [], [], []
     st_raw = torch.cuda.current_stream().cuda_stream
+
+    def ramp_once(i):
+        binding.kv_fp16_k_matvec(Ks[i % R], q, 128 ** -0.5, H, scores, stream=st_raw)
+        binding.kv_fp16_v_matvec(Vs[i % R], p, out, ws, stream=st_raw)
+
+    ramp_clocks(torch, ramp_once, ramp_s)
     for i in range(warmup + steps):
         e0, e1 = _event_pair(torch)
         e2, e3 = _event_pair(torch)
@@ -265,15 +318,15 @@ def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth):
     # streaming-read ceiling over >= 2 GB
     big = Ks[0] if nbytes >= 2e9 else torch.empty(int(2.2e9), dtype=torch.uint8, device=K.device).zero_()
     chk = torch.zeros(1, dtype=torch.int32, device=K.device)
-    for _ in range(3):
-        binding.kv_stream_read(big, chk)
+    ramp_clocks(torch, lambda i: binding.kv_stream_read(big, chk, stream=st_raw), ramp_s)
     e0, e1 = _event_pair(torch)
     e0.record()
-    for _ in range(5):
-        binding.kv_stream_read(big, chk)
+    for _ in range(8):           # one kernel launch each, nothing else in the timed region
+        binding.kv_stream_read(big, chk, stream=st_raw)
     e1.record()
     torch.cuda.synchronize()
-    res["stream_read_gbps"] = big.numel() * big.element_size() * 5 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    res["stream_read_gbps"] = big.numel() * big.element_size() * 8 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    res["stream_read_bytes"] = int(big.numel() * big.element_size())
     return res
 
 
@@ -451,20 +504,9 @@ def run_repack(w, torch, binding, synth):
     return res
 
 
-def cpu_baseline(w, synth, torch):
-    """The oracle as it stands on the host cores, on a bounded sample of the workload."""
-    import numpy as np
-    import oracle
-    # sized for roughly 10-30 s of host work (compression is single-threaded)
-    L = min(w.tokens // 64 * 64, max(64, (200_000_000 // (w.n_kv_heads * 128)) // 64 * 64))
-    B = 1
-    K, V, q = synth.make_kv(B, L, w.n_kv_heads, w.n_q_heads, 7)
-    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
-    t0 = time.perf_counter()
-    ck = oracle.compress_k(Kn, 0.1)
-    cv = oracle.compress_v(Vn, 0.2)
-    compress_s = time.perf_counter() - t0
-    reps, step_s = 10, 0.0
+def _oracle_step_seconds(oracle, np, ck, cv, Kn, Vn, qn, L, reps):
+    """Mean time of the oracle's K product + V product over an already compressed cache."""
+    step_s = 0.0
     for _ in range(reps):
         t1 = time.perf_counter()
         s = oracle.k_scores(ck.codes, Kn, ck.meta, L, qn, 128 ** -0.5)
@@ -474,13 +516,49 @@ def cpu_baseline(w, synth, torch):
         oracle.v_out(cv.codes, Vn, cv.meta, L, p)
         t4 = time.perf_counter()
         step_s += ((t2 - t1) + (t4 - t3)) / reps
+    return step_s
+
+
+def cpu_baseline(w, synth, torch):
+    """The oracle as it stands on the host cores: a bounded sample of the headline workload (all
+    threads, and one thread beside it), and the three smaller benchmark configurations in full."""
+    import numpy as np
+    import oracle
+    n_threads = oracle.threads()
+    # sized for roughly 10-20 s of host work (compression is single-threaded)
+    L = min(w.tokens // 64 * 64, max(64, (80_000_000 // (w.n_kv_heads * 128)) // 64 * 64))
+    K, V, q = synth.make_kv(1, L, w.n_kv_heads, w.n_q_heads, 7)
+    Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
+    t0 = time.perf_counter()
+    ck = oracle.compress_k(Kn, 0.1)
+    cv = oracle.compress_v(Vn, 0.2)
+    compress_s = time.perf_counter() - t0
+    step_s = _oracle_step_seconds(oracle, np, ck, cv, Kn, Vn, qn, L, 3)
+    oracle.set_threads(1)
+    step1_s = _oracle_step_seconds(oracle, np, ck, cv, Kn, Vn, qn, L, 1)
+    oracle.set_threads(n_threads)
+    nbytes = ck.arena.size + cv.arena.size
+    configs = {}
+    for idx in (0, 1, 2):           # the smaller configurations, whole
+        sw = synth.workload(idx)
+        Ls = sw.tokens // 64 * 64
+        Ks, Vs, qs = synth.make_kv(sw.batch, Ls, sw.n_kv_heads, sw.n_q_heads, 7)
+        Ksn, Vsn, qsn = Ks.numpy(), Vs.numpy(), qs.numpy()
+        t0 = time.perf_counter()
+        cks, cvs = oracle.compress_k(Ksn, 0.1), oracle.compress_v(Vsn, 0.2)
+        cs = time.perf_counter() - t0
+        ss = _oracle_step_seconds(oracle, np, cks, cvs, Ksn, Vsn, qsn, Ls, 2)
+        configs[sw.name] = {"value": (cks.arena.size + cvs.arena.size) / ss / 1e9, "unit": "GB/s",
+                            "matvec_s": ss, "compress_s": cs, "tokens": Ls, "batch": sw.batch}
     # same unit as the headline: compressed bytes consumed by one decode step / its time
-    return {"value": (ck.arena.size + cv.arena.size) / step_s / 1e9, "unit": "GB/s", "cores": oracle.threads(),
+    return {"value": nbytes / step_s / 1e9, "unit": "GB/s", "cores": n_threads,
             "kind": "oracle",
             "sample": "1 batch element x %d tokens x %d kv heads of %s: oracle K and V matvec over the "
-                      "packed cache, %.2f s per step (mean of %d); oracle compression of the same tokens took "
-                      "%.1f s on one core" % (L, w.n_kv_heads, w.name, step_s, reps, compress_s),
-            "compress_s": compress_s, "matvec_s": step_s}
+                      "packed cache, %.2f s per step (mean of 3, %d threads); oracle compression of the same "
+                      "tokens took %.1f s on one core" % (L, w.n_kv_heads, w.name, step_s, n_threads, compress_s),
+            "single_thread": {"value": nbytes / step1_s / 1e9, "unit": "GB/s", "cores": 1, "matvec_s": step1_s},
+            "compress_s": compress_s, "matvec_s": step_s,
+            "other_configs_in_full": configs}
 
 
 def main():
@@ -534,12 +612,7 @@ def main():
     dom = "k" if packed["k_ms"] >= packed["v_ms"] else "v"
     alg = packed[dom + "_alg_bytes"]
     achieved = alg / (packed[dom + "_ms"] * 1e-3) / 1e9
-    traffic = None
-    tf = os.path.join(ROOT, "paper_2512_24449_amd", "measured_traffic.json")
-    if os.path.exists(tf):
-        t = json.load(open(tf)).get(w.name, {}).get(dom)
-        if t:
-            traffic = t
+    traffic, slots_per_chunk, stored_files = stored_profile_numbers(w.name, dom) if w.n_q_heads == w.n_kv_heads else (None, None, [])
     n_chunks = w.tokens // 64 * w.batch * w.n_kv_heads
     line = {
         "metric": "fused K/V decompress-GEMV GB/s (compressed)",
@@ -553,11 +626,10 @@ def main():
         "pct_hbm_peak": round(100.0 * packed["value_gbps"] / HBM_PEAK_GBPS, 2),
         "roofline": {"bound": "hbm", "kernel": "kv_%s_matvec" % dom, "achieved": round(achieved, 2),
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBPS, 4),
-                     "traffic": traffic, "algorithmic_bytes_per_launch": alg,
+                     "traffic": traffic, "traffic_source": ("stored: " + ", ".join(f for f in stored_files if "hbm" in f)) if traffic else None,
+                     "algorithmic_bytes_per_launch": alg,
                      "avg_launch_ms": round(packed[dom + "_ms"], 5)},
-        # the binding resource of these kernels: vector issue slots.  Wave64 instructions per chunk are
-        # the measured constants of profiles/issue_counters_*.txt (an MFMA counted as 2 slots: about
-        # 8 cycles of the port when mixed with vector work); peak = 256 CUs x 4 SIMDs x 2.4 GHz / 4 cycles per instruction.
+        "clock_ramp_s": CLOCK_RAMP_S,
         "kernels": {
             "kv_k_matvec": {"ms": round(packed["k_ms"], 5), "compressed_gbps": round(packed["k_gbps_compressed"], 1),
                             "pct_hbm_peak": round(packed["k_gbps_compressed"] / 80.0, 2),
@@ -572,6 +644,7 @@ def main():
                       "speedup_k": round(fp16["k_ms"] / packed["k_ms"], 3),
                       "speedup_v": round(fp16["v_ms"] / packed["v_ms"], 3)},
         "stream_read_gbps": round(fp16["stream_read_gbps"], 1),
+        "stream_read_bytes": fp16["stream_read_bytes"],
         "pct_of_stream_read": {"kv_k_matvec": round(100.0 * packed["k_gbps_compressed"] / fp16["stream_read_gbps"], 2),
                                "kv_v_matvec": round(100.0 * packed["v_gbps_compressed"] / fp16["stream_read_gbps"], 2)},
         "fused_decode_attention": {"ms": round(packed["attn_ms"], 5),
@@ -579,11 +652,15 @@ def main():
                                    "compressed_gbps": round((packed["k_bytes"] + packed["v_bytes"]) /
                                                             (packed["attn_ms"] * 1e-3) / 1e9, 1)},
     }
-    if w.n_q_heads == w.n_kv_heads:   # the per-chunk constants below were measured for one query head per kv-head
-        slots = n_chunks * ISSUE_SLOTS_PER_CHUNK[dom] / (packed[dom + "_ms"] * 1e-3)
+    if slots_per_chunk:
+        # second view of the same kernel: vector issue slots.  Wave64 instructions per chunk come from the
+        # committed counter summary (stored, not measured by this run); peak = 256 CUs x 4 SIMDs x 2.4 GHz /
+        # 4 cycles per instruction = 614.4 G wave-instructions/s.
+        slots = n_chunks * slots_per_chunk / (packed[dom + "_ms"] * 1e-3)
         line["roofline_alu"] = {"bound": "alu", "kernel": "kv_%s_matvec" % dom, "achieved": round(slots / 1e9, 1),
                                 "peak": 614.4, "unit": "G wave-instructions/s", "frac": round(slots / 614.4e9, 4),
-                                "slots_per_chunk": ISSUE_SLOTS_PER_CHUNK[dom]}
+                                "slots_per_chunk": slots_per_chunk,
+                                "slots_source": "stored: " + ", ".join(f for f in stored_files if "issue" in f)}
     if packed8 is not None:
         line["pack_size_8"] = {"k_ms": round(packed8["k_ms"], 5), "v_ms": round(packed8["v_ms"], 5),
                                "attn_ms": round(packed8["attn_ms"], 5),

@@ -139,6 +139,11 @@ typedef struct {
     int64_t index_bytes;   /* per tensor                                          */
     int64_t token_meta_bytes; /* per tensor                                       */
     int32_t overflow;      /* sticky: an append did not fit into an arena         */
+    /* what the chunk bytes of each tensor consist of (chunks dropped by an overflow
+     * count nothing): pack metadata (the header bytes), payload (exactly
+     * pack_size * width bits per pack) and the zero padding up to 16 bytes       */
+    int64_t k_header_bytes, k_payload_bytes, k_padding_bytes;
+    int64_t v_header_bytes, v_payload_bytes, v_padding_bytes;
 } kv_stats_t;
 
 /*
@@ -336,9 +341,11 @@ int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_p, float *o
                      int32_t n_kv_heads, int32_t n_q_heads, int64_t tokens, void *workspace,
                      void *hip_stream);
 size_t kv_fp16_v_workspace_bytes(int32_t batch, int32_t n_q_heads);
-/* Streaming-read ceiling: sums `bytes` (multiple of 16) of device memory into
- * checksum[0] (device uint32, overwritten).  Used to measure achievable HBM
- * read bandwidth next to the 8 TB/s peak. */
+/* Streaming-read ceiling: reads `bytes` (multiple of 16) of device memory with
+ * sixteen independent 16-byte loads per thread and xors every word into
+ * checksum[0] (device uint32; accumulated, the caller clears it): one kernel
+ * launch and nothing else.  Used to measure achievable HBM read bandwidth next
+ * to the 8 TB/s peak. */
 int kv_stream_read(const void *src, size_t bytes, uint32_t *checksum, void *hip_stream);
 
 #ifdef __cplusplus

@@ -46,7 +46,9 @@ class kv_stats_t(C.Structure):
     _fields_ = [("tokens", C.c_int64), ("packed_tokens", C.c_int64), ("tail_tokens", C.c_int64),
                 ("n_chunks", C.c_int64), ("k_bytes", C.c_int64), ("v_bytes", C.c_int64),
                 ("index_bytes", C.c_int64), ("token_meta_bytes", C.c_int64),
-                ("overflow", C.c_int32)]
+                ("overflow", C.c_int32),
+                ("k_header_bytes", C.c_int64), ("k_payload_bytes", C.c_int64), ("k_padding_bytes", C.c_int64),
+                ("v_header_bytes", C.c_int64), ("v_payload_bytes", C.c_int64), ("v_padding_bytes", C.c_int64)]
 
 
 EXPORTS = ("kv_query_sizes", "kv_cache_create", "kv_cache_destroy", "kv_compress_append", "kv_compress_append_bf16",

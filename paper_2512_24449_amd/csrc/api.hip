@@ -396,6 +396,43 @@ extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale,
                                    static_cast<hipStream_t>(hip_stream));
 }
 
+namespace packkv {
+// Sums, over the chunks of one tensor, the chunk bytes and the payload bytes their headers
+// announce: one wave per chunk, widths read from the header (high nibble of a pack byte, or a
+// width byte per pack in wide chunks).  sums[0] += chunks present, [1] += chunk bytes,
+// [2] += payload bytes.
+__global__ __launch_bounds__(256) void chunk_bytes_kernel(const uint8_t *__restrict__ arena,
+                                                          const uint32_t *__restrict__ index, int index_words,
+                                                          int64_t n_chunks, int width_bytes, bool nibble,
+                                                          int bytes_per_width, unsigned long long *sums) {
+    const int lane = threadIdx.x & 63;
+    const int64_t wave0 = (int64_t(blockIdx.x) * blockDim.x + threadIdx.x) >> 6;
+    const int64_t n_waves = (int64_t(gridDim.x) * blockDim.x) >> 6;
+    unsigned long long present = 0, bytes = 0, payload = 0;
+    for (int64_t c = wave0; c < n_chunks; c += n_waves) {
+        const uint32_t o0 = index[c * index_words], o1 = index[c * index_words + 1];
+        if (o1 == o0) continue;  // dropped
+        const uint8_t *hdr = arena + size_t(o0) * 16;
+        int wsum = 0;
+        for (int i = lane * 4; i < width_bytes; i += 256) {
+            const uint32_t w4 = *reinterpret_cast<const uint32_t *>(hdr + i);
+            const uint32_t w = nibble ? (w4 >> 4) & 0x0F0F0F0Fu : w4;
+            wsum += int((w & 0xFF) + ((w >> 8) & 0xFF) + ((w >> 16) & 0xFF) + (w >> 24));
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) wsum += __shfl_xor(wsum, o);
+        present += 1;
+        bytes += (unsigned long long)(o1 - o0) * 16;
+        payload += (unsigned long long)wsum * bytes_per_width;
+    }
+    if (lane == 0 && present) {
+        atomicAdd(&sums[0], present);
+        atomicAdd(&sums[1], bytes);
+        atomicAdd(&sums[2], payload);
+    }
+}
+}  // namespace packkv
+
 extern "C" int kv_cache_stats(kv_cache_t *c, kv_stats_t *out, void *hip_stream) {
     if (!c || !out) return KV_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
@@ -419,6 +456,34 @@ extern "C" int kv_cache_stats(kv_cache_t *c, kv_stats_t *out, void *hip_stream) 
     out->index_bytes = c->pool ? n_chunks * 8 : (n_chunks + 1) * 4;
     out->token_meta_bytes = int64_t(c->cfg.batch) * c->packed_tokens * 4;
     out->overflow = (status[ST_OVERFLOW_K] || status[ST_OVERFLOW_V]) ? 1 : 0;
+    if (n_chunks > 0) {
+        // byte split of the chunks: six 64-bit sums in the status area (words 16..27)
+        unsigned long long *sums = reinterpret_cast<unsigned long long *>(
+            static_cast<uint8_t *>(c->buf.workspace) + WS_STATUS + 64);
+        unsigned long long host[6];
+        KV_HIP_CHECK(hipMemsetAsync(sums, 0, sizeof(host), s));
+        const int grid = int(std::min<int64_t>((n_chunks + 3) / 4, 4096));
+        for (int t = 0; t < 2; ++t) {
+            const bool wide = t ? c->wide_v : c->wide_k;
+            const int packs = N / c->cfg.pack_size * D;
+            hipLaunchKernelGGL(chunk_bytes_kernel, dim3(grid), dim3(256), 0, s,
+                               static_cast<const uint8_t *>(t ? c->buf.v_arena : c->buf.k_arena),
+                               static_cast<const uint32_t *>(t ? c->buf.v_index : c->buf.k_index), c->index_words,
+                               n_chunks, packs, !wide, c->cfg.pack_size / 8, sums + 3 * t);
+        }
+        KV_HIP_CHECK(hipGetLastError());
+        KV_HIP_CHECK(hipMemcpyAsync(host, sums, sizeof(host), hipMemcpyDeviceToHost, s));
+        KV_HIP_CHECK(hipStreamSynchronize(s));
+        for (int t = 0; t < 2; ++t) {
+            const bool wide = t ? c->wide_v : c->wide_k;
+            const int64_t header = int64_t(host[3 * t]) * chunk_header_bytes(c->cfg.pack_size, wide);
+            const int64_t payload = int64_t(host[3 * t + 2]);
+            const int64_t padding = int64_t(host[3 * t + 1]) - header - payload;
+            (t ? out->v_header_bytes : out->k_header_bytes) = header;
+            (t ? out->v_payload_bytes : out->k_payload_bytes) = payload;
+            (t ? out->v_padding_bytes : out->k_padding_bytes) = padding;
+        }
+    }
     return KV_OK;
 }
 

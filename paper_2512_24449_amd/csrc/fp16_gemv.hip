@@ -143,26 +143,30 @@ __global__ __launch_bounds__(256) void fp16_v_reduce_kernel(const float *__restr
     if (threadIdx.x < D) out[int64_t(blockIdx.x) * D + threadIdx.x] = acc;
 }
 
-// Grid-stride 16-byte reads, xor-folded so the loads cannot be dropped.
+// Streaming read: every thread keeps sixteen independent 16-byte loads in flight (a workgroup
+// reads 64 KiB per round, 4 KiB per load instruction), xor-folded so the loads cannot be dropped.
 __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restrict__ src, size_t n16,
                                                           uint32_t *__restrict__ checksum) {
+    constexpr int DEPTH = 16;
     uint32_t acc = 0;
-    const size_t stride = size_t(gridDim.x) * blockDim.x;
-    size_t i = size_t(blockIdx.x) * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        uint4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
-        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    const size_t tile = size_t(DEPTH) * 256;
+    const size_t n_tiles = n16 / tile;
+    for (size_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
+        const uint4 *p = src + t * tile + threadIdx.x;
+        uint4 v[DEPTH];
+#pragma unroll
+        for (int k = 0; k < DEPTH; ++k) v[k] = p[k * 256];
+#pragma unroll
+        for (int k = 0; k < DEPTH; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }
-    for (; i < n16; i += stride) {
-        uint4 a = src[i];
+    for (size_t i = n_tiles * tile + size_t(blockIdx.x) * 256 + threadIdx.x; i < n16; i += size_t(gridDim.x) * 256) {
+        const uint4 a = src[i];
         acc ^= a.x ^ a.y ^ a.z ^ a.w;
     }
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o);
     if ((threadIdx.x & 63) == 0 && acc != 0) atomicXor(checksum, acc);
 }
-
-__global__ void zero_word_kernel(uint32_t *w) { *w = 0; }
 
 }  // namespace packkv
 
@@ -229,10 +233,10 @@ extern "C" int kv_fp16_v_matvec(const void *v_cache, const float *p, int64_t ld_
 extern "C" int kv_stream_read(const void *src, size_t bytes, uint32_t *checksum, void *hip_stream) {
     if (!src || !checksum || bytes % 16) return KV_ERR_ARG;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    hipLaunchKernelGGL(zero_word_kernel, dim3(1), dim3(1), 0, s, checksum);
     const size_t n16 = bytes / 16;
+    // one launch, nothing else: persistent workgroups, eight per compute unit
     size_t blocks = (n16 + 256 * 16 - 1) / (256 * 16);
-    if (blocks > 256 * 32) blocks = 256 * 32;
+    if (blocks > 256 * 8) blocks = 256 * 8;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, s,
                        static_cast<const uint4 *>(src), n16, checksum);

@@ -75,6 +75,14 @@ def check_packed_state(cache, n_packed, ck, cv, B, H):
             raise AssertionError("%s arena differs first at byte %d of %d" % (name, first, nbytes))
         meta = cache.view(name + "_token_meta", torch.int32).view(B, max_tokens)[:, :n_packed]
         assert np.array_equal(meta.cpu().numpy().view(np.uint32), c.meta), name + " token meta"
+        # the byte split of the statistics: pack metadata, exactly pack_size * width bits per pack, padding
+        packs = c.widths.shape[1]
+        wide = int(c.widths.max()) > 4 or int(c.mins.max()) > 15
+        header = n_chunks * packs * (2 if wide else 1)
+        payload = int(c.widths.astype(np.int64).sum()) * (64 * 128 // packs // 8)
+        got = (getattr(st, name + "_header_bytes"), getattr(st, name + "_payload_bytes"), getattr(st, name + "_padding_bytes"))
+        if not wide or packs == 1024:
+            assert got == (header, payload, nbytes - header - payload), (name, got, header, payload, nbytes)
     return st
 
 
