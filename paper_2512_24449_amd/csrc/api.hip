@@ -26,6 +26,12 @@ int head_split_for(int g, int pack_size) {
     return 0;
 }
 
+// Capacity of an arena in the 16-byte units of the 32-bit index words: what lies beyond the last
+// addressable unit of a larger buffer stays unused.
+uint32_t arena_units(size_t bytes) {
+    return uint32_t(std::min<size_t>(bytes / 16, 0xFFFFFFFFu));
+}
+
 int check_config(const kv_config_t *c) {
     if (!c) return KV_ERR_ARG;
     if (c->batch < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->max_tokens < 1) return KV_ERR_ARG;
@@ -273,7 +279,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         kjob.wide = c->wide_k;
         kjob.pack_order = 1;  // K chunks list their packs channel-major (what the K kernel's lanes own)
         kjob.arena = static_cast<uint8_t *>(c->buf.k_arena);
-        kjob.arena_cap16 = c->sizes.k_arena / 16;
+        kjob.arena_cap16 = arena_units(c->sizes.k_arena);
         kjob.index = static_cast<uint32_t *>(c->buf.k_index);
         kjob.meta = static_cast<uint32_t *>(c->buf.k_token_meta);
         kjob.status = status + ST_OVERFLOW_K;
@@ -284,7 +290,7 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
         vjob.qmax = c->qmax_v;
         vjob.wide = c->wide_v;
         vjob.arena = static_cast<uint8_t *>(c->buf.v_arena);
-        vjob.arena_cap16 = c->sizes.v_arena / 16;
+        vjob.arena_cap16 = arena_units(c->sizes.v_arena);
         vjob.index = static_cast<uint32_t *>(c->buf.v_index);
         vjob.meta = static_cast<uint32_t *>(c->buf.v_token_meta);
         vjob.status = status + ST_OVERFLOW_V;
@@ -391,6 +397,7 @@ extern "C" int kv_v_matvec_noalloc(kv_cache_t *c, const float *p, int64_t ld_p, 
 extern "C" int kv_decode_attention(kv_cache_t *c, const void *q, float sm_scale, float *out,
                                    void *hip_stream) {
     if (!c || !q || !out || !(sm_scale == sm_scale)) return KV_ERR_ARG;
+    if (reinterpret_cast<uintptr_t>(q) & 15u) return KV_ERR_ARG;
     if (c->packed_tokens + c->tail_tokens < 1) return KV_ERR_ARG;  // softmax over nothing
     return launch_decode_attention(c, static_cast<const __half *>(q), sm_scale, out,
                                    static_cast<hipStream_t>(hip_stream));

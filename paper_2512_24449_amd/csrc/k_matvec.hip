@@ -80,9 +80,9 @@ __device__ inline void k8_stream(const KArgs &a, int bh, int blk_begin, int blk_
                 vmem_order_fence();
                 mt_next = meta[int64_t(first + 4 * (it + 1)) * N];
             }
-            if (!valid) {  // block dropped by an arena overflow: defined output
+            if (!valid) {  // block dropped by an arena overflow: no softmax weight
 #pragma unroll
-                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = -INFINITY;
                 wait_chunk_landed();  // rare path: keep the next wait's count independent of it
                 continue;
             }
@@ -129,9 +129,9 @@ __device__ inline void kw_stream(const KArgs &a, int bh, int blk_begin, int blk_
             chunk_issue_lds<CHUNKW_MAX, HEADERW>(a.arena, ib.start16(it), ib.end16(it), lds0 + buf, lane);
             const uint32_t mt = meta[int64_t(first + 4 * it) * N];
             wait_chunk_landed();
-            if (!valid) {  // block dropped by an arena overflow: defined output
+            if (!valid) {  // block dropped by an arena overflow: no softmax weight
 #pragma unroll
-                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = -INFINITY;
                 continue;
             }
             float u0[G], u1[G];
@@ -246,11 +246,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
                 auto refill = [&]() {
                     if (it + 1 < n_it) issue(ib, it + 1, first + 4 * (it + 1));
                 };
-                if (!valid) {  // block dropped by an arena overflow: defined output
+                if (!valid) {  // block dropped by an arena overflow: no softmax weight
                     lds_reads_returned();
                     refill();
 #pragma unroll
-                    for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = 0.0f;
+                    for (int g = 0; g < G; ++g) a.scores[(head0 + g) * a.ld + tok] = -INFINITY;
                     continue;
                 }
                 float u[G];

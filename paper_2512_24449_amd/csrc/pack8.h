@@ -17,6 +17,7 @@
 namespace packkv {
 
 constexpr int CHUNK8_LDS = CHUNK8_MAX;
+constexpr float V8_WEIGHT_MAX = 32752.0f;  // largest weight p_t * scale_t the fp16 hi/lo split of the V paths here carries
 constexpr int DPP_ROW_HALF_MIRROR = 0x141;  // lane i <- lane 7 - i of its half row
 
 // Per-lane view of the header of one half and of where its eight packs sit in LDS.
@@ -197,7 +198,10 @@ __device__ inline void v8_chunk(const uint8_t *lds_all, int cur, const uint4 *ta
     float wsum[2][G];  // per half: sum of the weights of this lane's token group (8 tokens)
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const float w = pt[g] * scale;
+        // the fp16 split holds weights below 2^15 (hi rounds toward zero, the residual times 2^11 stays
+        // finite); a larger product -- a token range in the thousands times a weight near 2^8 -- is
+        // clamped there instead of turning into infinities
+        const float w = fminf(pt[g] * scale, V8_WEIGHT_MAX);
         st.pm[g] = fmaf(pt[g], mn, st.pm[g]);
         const _Float16 hi = __builtin_bit_cast(
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));
@@ -377,7 +381,10 @@ __device__ inline void vw_chunk(const uint8_t *lds_all, int cur, const uint4 *vt
     float wsum[2][G];
 #pragma unroll
     for (int g = 0; g < G; ++g) {
-        const float w = pt[g] * scale;
+        // the fp16 split holds weights below 2^15 (hi rounds toward zero, the residual times 2^11 stays
+        // finite); a larger product -- a token range in the thousands times a weight near 2^8 -- is
+        // clamped there instead of turning into infinities
+        const float w = fminf(pt[g] * scale, V8_WEIGHT_MAX);
         st.pm[g] = fmaf(pt[g], mn, st.pm[g]);
         const _Float16 hi = __builtin_bit_cast(
             _Float16, uint16_t(__builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(w, 0.0f)) & 0xFFFFu));

@@ -31,6 +31,11 @@ __device__ inline float block_reduce(float v, bool is_max, float *lds) {
 }
 
 // NREG > 0: thread t holds elements t, t + 1024, ... (NREG of them) in registers.
+// Scores of -inf (blocks dropped by an arena overflow) get weight 0; a row that holds nothing else
+// comes out as zeros.
+__device__ inline float finite_max(float mx) { return mx == -INFINITY ? 0.0f : mx; }
+__device__ inline float safe_inverse(float sum) { return sum > 0.0f ? 1.0f / sum : 0.0f; }
+
 // NREG == 0: rows of any length, three passes over memory.
 template <int NREG>
 __global__ __launch_bounds__(SMX_THREADS) void softmax_kernel(float *__restrict__ s, int64_t ld,
@@ -47,7 +52,7 @@ __global__ __launch_bounds__(SMX_THREADS) void softmax_kernel(float *__restrict_
             x[k] = i < tokens ? row[i] : -INFINITY;
             mx = fmaxf(mx, x[k]);
         }
-        mx = block_reduce(mx, true, lds);
+        mx = finite_max(block_reduce(mx, true, lds));
         float sum = 0.0f;
 #pragma unroll
         for (int k = 0; k < NREG; ++k) {
@@ -55,7 +60,7 @@ __global__ __launch_bounds__(SMX_THREADS) void softmax_kernel(float *__restrict_
             sum += x[k];
         }
         sum = block_reduce(sum, false, lds);
-        const float inv = 1.0f / sum;
+        const float inv = safe_inverse(sum);
 #pragma unroll
         for (int k = 0; k < NREG; ++k) {
             const int64_t i = int64_t(k) * SMX_THREADS + threadIdx.x;
@@ -64,11 +69,11 @@ __global__ __launch_bounds__(SMX_THREADS) void softmax_kernel(float *__restrict_
     } else {
         float mx = -INFINITY;
         for (int64_t i = threadIdx.x; i < tokens; i += SMX_THREADS) mx = fmaxf(mx, row[i]);
-        mx = block_reduce(mx, true, lds);
+        mx = finite_max(block_reduce(mx, true, lds));
         float sum = 0.0f;
         for (int64_t i = threadIdx.x; i < tokens; i += SMX_THREADS) sum += exp2f((row[i] - mx) * LOG2E);
         sum = block_reduce(sum, false, lds);
-        const float inv = 1.0f / sum;
+        const float inv = safe_inverse(sum);
         for (int64_t i = threadIdx.x; i < tokens; i += SMX_THREADS)
             row[i] = exp2f((row[i] - mx) * LOG2E) * inv;
     }
@@ -87,8 +92,9 @@ __global__ __launch_bounds__(SMX_THREADS) void softmax_stats_kernel(const float 
     float mx = -INFINITY;
     for (int64_t i = lo + threadIdx.x; i < hi; i += SMX_THREADS) mx = fmaxf(mx, row[i]);
     mx = block_reduce(mx, true, lds);
+    const float ref = finite_max(mx);
     float sum = 0.0f;
-    for (int64_t i = lo + threadIdx.x; i < hi; i += SMX_THREADS) sum += exp2f((row[i] - mx) * LOG2E);
+    for (int64_t i = lo + threadIdx.x; i < hi; i += SMX_THREADS) sum += exp2f((row[i] - ref) * LOG2E);
     sum = block_reduce(sum, false, lds);
     if (threadIdx.x == 0) stats[int64_t(blockIdx.y) * gridDim.x + blockIdx.x] = make_float2(mx, sum);
 }
@@ -101,9 +107,10 @@ __global__ __launch_bounds__(SMX_THREADS) void softmax_apply_kernel(float *__res
     const float2 *st = stats + int64_t(blockIdx.y) * gridDim.x;
     float mx = -INFINITY;
     for (unsigned k = 0; k < gridDim.x; ++k) mx = fmaxf(mx, st[k].x);
+    mx = finite_max(mx);
     float sum = 0.0f;
     for (unsigned k = 0; k < gridDim.x; ++k) sum += st[k].y * exp2f((st[k].x - mx) * LOG2E);
-    const float inv = 1.0f / sum;
+    const float inv = safe_inverse(sum);
     const int64_t lo = int64_t(blockIdx.x) * seg, hi = lo + seg < tokens ? lo + seg : tokens;
     for (int64_t i = lo + threadIdx.x; i < hi; i += SMX_THREADS) row[i] = exp2f((row[i] - mx) * LOG2E) * inv;
 }

@@ -110,10 +110,12 @@ def _check_batch_element_rel(cache, K, V, q, scores, p, out, b, sm_scale, n_pack
 
 
 def test_growing_cache_decode_steps():
-    """Benchmark configuration 4 (growing cache): start at 131072 tokens, append one token per
-    decode step with a flush every 64 tokens; compare at a step with a part-filled tail and at the end."""
+    """Benchmark configuration 4 (growing cache) in full: start at 131072 tokens, append one token per
+    decode step for all its 1024 steps (16 tail flushes); every appended block's bytes and the outputs
+    of a batch element are compared with the oracle at a step with a part-filled tail and at the end."""
     w = synth.workload(4)
-    steps = 130
+    steps = w.decode_steps
+    assert steps == 1024
     K, V, q = synth.make_kv(w.batch, w.tokens + steps, w.n_kv_heads, w.n_q_heads, 4, device="cuda:0")
     L0 = w.tokens
     cache = binding.PackedKVCache(w.batch, w.n_kv_heads, w.n_q_heads, L0 + steps)

@@ -181,6 +181,27 @@ def test_degenerate_inputs():
     K[1, 5, 0, 0] = -60000.0
     V = (rng.standard_normal((2, 64, 2, 128)) * 1e-3).astype(np.float16)
     _special_case(K, V, 4)
+    # V tokens with a range around 4000 (scale above 256 at rel 0.2) under peaked attention: weights of
+    # the fused path reach 2^8 * scale, far above the fp16 range
+    V = (rng.standard_normal((1, 192, 2, 128)) * 3).astype(np.float16)
+    V[0, 7::16] = (rng.uniform(-2000, 2000, size=(12, 2, 128))).astype(np.float16)
+    K = (rng.standard_normal((1, 192, 2, 128))).astype(np.float16)
+    q = synth.make_kv(1, 64, 2, 4, 98)[2]
+    K[0, 7, :, :] = (q[0, ::2].numpy().astype(np.float32) * 3).astype(np.float16)   # token 7 takes most of the weight
+    st, ck, cv = _special_case(K, V, 4)
+    cache = binding.PackedKVCache(1, 2, 4, 192)
+    cache.kv_compress_append(torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    attn = cache.kv_decode_attention(q.cuda(), 1.0).cpu().numpy()
+    kc, km = gpu_cases.full_codes(ck, K.shape, 192)
+    vc, vm = gpu_cases.full_codes(cv, V.shape, 192)
+    assert np.isfinite(attn).all()
+    assert_close_vectors(attn, oracle.attention(kc, K, km, vc, V, vm, 192, q.numpy(), 1.0), "fused attention, V range 4000")
+    cache.close()
+    # the same tokens through packs of 8: the fp16 weight split clamps such weights, the result stays finite
+    c8 = binding.PackedKVCache(1, 2, 4, 192, pack_size=8)
+    c8.kv_compress_append(torch.from_numpy(K).cuda(), torch.from_numpy(V).cuda())
+    assert torch.isfinite(c8.kv_decode_attention(q.cuda(), 1.0)).all()
+    c8.close()
 
 
 @pytest.mark.parametrize("Hq,pack_size,k_rel", [(2, 16, 0.1), (4, 16, 0.1), (2, 8, 0.1), (8, 8, 0.1), (4, 8, 0.05)])
@@ -212,7 +233,19 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_re
     kept = st.k_bytes and int(np.searchsorted(ck.offsets16.astype(np.int64) * 16, st.k_bytes, "right") - 1) // (B * H)
     assert 1 <= kept < 4
     assert_close_vectors(scores[:, :, :kept * 64].cpu().numpy(), s_ref[:, :, :kept * 64], "kept blocks")
-    assert (scores[:, :, kept * 64:] == 0).all(), "dropped blocks read as zeros"
+    assert torch.isinf(scores[:, :, kept * 64:]).all() and (scores[:, :, kept * 64:] < 0).all(), \
+        "dropped blocks score -inf"
+    # the dropped blocks carry no softmax weight, so the three-step path and the fused path agree
+    # (the V arena holds every block here: only K overflowed)
+    p = cache.kv_softmax(scores.clone())
+    assert (p[:, :, kept * 64:] == 0).all() and torch.isfinite(p).all()
+    out3 = cache.kv_v_matvec(p)
+    fused = cache.kv_decode_attention(q.cuda(), 1.0)
+    torch.cuda.synchronize()
+    assert_close_vectors(out3.cpu().numpy(), fused.cpu().numpy().astype(np.float64), "three-step vs fused after an overflow")
+    # a row of nothing but dropped blocks comes out as zeros
+    none = torch.full_like(scores, float("-inf"))
+    assert (cache.kv_softmax(none) == 0).all()
 
 
 @pytest.mark.parametrize("paged", [False, True])
@@ -320,6 +353,9 @@ def test_host_argument_errors():
     q = torch.zeros(1, 2, 128, dtype=torch.float16, device="cuda")
     s = torch.zeros(1, 2, 32, dtype=torch.float32, device="cuda")
     assert L.kv_k_matvec(cache.handle, q.data_ptr(), 1.0, s.data_ptr(), 32, None) == -1   # ld < tokens
+    s64 = torch.zeros(1, 2, 64, dtype=torch.float32, device="cuda")
+    assert L.kv_k_matvec(cache.handle, q.data_ptr() + 2, 1.0, s64.data_ptr(), 64, None) == -1        # q not 16-byte aligned
+    assert L.kv_decode_attention(cache.handle, q.data_ptr() + 2, 1.0, o0.data_ptr(), None) == -1  # the same
     assert L.kv_v_matvec(cache.handle, s.data_ptr(), 32, s.data_ptr(), None) == -1
     with pytest.raises(binding.PackKVError):
         cache.kv_compress_append(torch.zeros(1, 65, 2, 128, dtype=torch.float16, device="cuda"),

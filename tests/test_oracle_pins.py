@@ -272,16 +272,16 @@ def test_compress_round_trip_and_size_formula(orc, B, T, H, rel, seed, k):
     assert np.isclose(bits, c.widths.mean() + 8 / k + pad_bits / K.size)
 
 
-def _fixed_width_tensor(b, g_heads, T=64, seed=0):
-    """Values on an exact grid so that every pack needs exactly b bits."""
+def _fixed_width_tensor(b, g_heads, T=64, seed=0, pack=16):
+    """Values on an exact grid so that every pack (of `pack` tokens) needs exactly b bits."""
     rng = np.random.default_rng(seed)
     qmax = 2 ** b - 1
     codes = rng.integers(0, qmax + 1, size=(1, T, g_heads, 128))
     t = np.arange(T)[:, None]
     d = np.arange(128)[None, :]
     # in every pack one token holds 0 and the next holds qmax; every token holds both
-    codes[0][np.broadcast_to((t % 16 == d % 16)[:, None, :], codes[0].shape)] = 0
-    codes[0][np.broadcast_to((t % 16 == (d + 1) % 16)[:, None, :], codes[0].shape)] = qmax
+    codes[0][np.broadcast_to((t % pack == d % pack)[:, None, :], codes[0].shape)] = 0
+    codes[0][np.broadcast_to((t % pack == (d + 1) % pack)[:, None, :], codes[0].shape)] = qmax
     x = (codes - 4).astype(np.float16)
     return x, codes, 1.0 / qmax
 
@@ -291,19 +291,29 @@ def test_fixed_width_special_case_reproduces_printed_ratios(orc):
     paper's token-wise ratios 16g/(bg+32) (Table of V ratios, Sec. IV-D.2)."""
     rows = [l.split() for l in open(os.path.join(GOLD, "paper_closed_form_cr.txt"))
             if l.strip() and not l.startswith("#")]
-    assert len(rows) == 11
+    assert len(rows) == 15
+    seen = set()
     for bits, g, printed, _model in rows:
         b, g, printed = int(bits), int(g), float(printed)
-        x, codes, rel = _fixed_width_tensor(b, g // 128)
-        c = orc.compress(x, rel)
+        seen.add(printed)
+        if g < 128:
+            # groups of 64 values (the comparison system's channel-wise quantization): the token-wise
+            # quantizer has no such group, so only the closed form itself is checked
+            assert round(16 * g / (b * g + 32), 2) == printed, (b, g, printed)
+            continue
+        # five bits need codes up to 31: the wide layout, packs of 8 tokens, two header bytes per pack
+        pack, header = (16, 512) if b <= 4 else (8, 2048)
+        x, codes, rel = _fixed_width_tensor(b, g // 128, pack=pack)
+        c = orc.compress(x, rel, pack)
         assert np.array_equal(c.codes, codes), "grid data quantizes to its own indices"
         assert (c.widths == b).all()
-        payload = c.arena.size - 512 * c.widths.shape[0]
+        payload = c.arena.size - header * c.widths.shape[0]
         assert payload * 8 == b * x.size
         token_meta = c.meta.size * 4
         cr = x.size * 2 / (payload + token_meta)
         assert np.isclose(cr, 16 * g / (b * g + 32))
         assert round(cr, 2) == printed, (b, g, cr, printed)
+    assert {3.20, 6.40, 4.57, 3.56} <= seen
 
 
 def test_paper_arithmetic_examples():
