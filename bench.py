@@ -72,6 +72,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default=DEFAULT_WORKLOAD)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--ramp-s", type=float, default=None,
+                    help="seconds of untimed work before every timed loop (default %.1f; profile runs use less)" % CLOCK_RAMP_S)
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known bytes, for scaling rocprofv3 byte counters)")
     ap.add_argument("--no-side-workloads", action="store_true",
@@ -154,8 +156,9 @@ def ramp_clocks(torch, once, seconds):
 
 
 def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, rel=(0.1, 0.2), paged=False,
-               ramp_s=CLOCK_RAMP_S):
+               ramp_s=None):
     """Timed decode steps over rotating replicas; returns a dict of measurements."""
+    ramp_s = CLOCK_RAMP_S if ramp_s is None else ramp_s
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
     total = steps + warmup
@@ -265,8 +268,9 @@ def run_packed(w, K, V, q, steps, warmup, torch, binding, synth, pack_size=16, r
     return res
 
 
-def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth, ramp_s=CLOCK_RAMP_S):
+def run_fp16(w, K, V, q, steps, warmup, torch, binding, synth, ramp_s=None):
     """The uncompressed fp16 GEMV companions at the same shapes (head-major cache)."""
+    ramp_s = CLOCK_RAMP_S if ramp_s is None else ramp_s
     B, H, Hq = w.batch, w.n_kv_heads, w.n_q_heads
     L = K.shape[1]
     Kh = K.permute(0, 2, 1, 3).contiguous()
@@ -563,6 +567,9 @@ def cpu_baseline(w, synth, torch):
 
 def main():
     args = parse_args()
+    global CLOCK_RAMP_S
+    if args.ramp_s is not None:
+        CLOCK_RAMP_S = max(0.0, args.ramp_s)
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the path shards over (batch, kv-head) "
               "without exchange); --gpus %d is not supported" % args.gpus, file=sys.stderr)

@@ -3,8 +3,8 @@
  *
  * A KV cache that is token-wise quantized and bit-packed in independent
  * 64-token blocks (PackKV, arXiv 2512.24449, Sec. III), an append-side
- * compressor, and two fused kernels that stream the packed cache from HBM,
- * unpack codes in registers and compute q.K^T and p.V without ever writing
+ * compressor, and fused kernels that stream the packed cache from HBM,
+ * decode it on chip and compute q.K^T and p.V without ever writing
  * decompressed data back (Sec. III-C).
  *
  * Conventions for every entry point
@@ -23,15 +23,25 @@
  * Cache layout (Sec. II-A): tokens arrive as fp16 [batch][n][n_kv_heads][128].
  * Packed format (Sec. III-B.3, III-B.4, III-C): one chunk per
  * (block of 64 tokens, batch, kv-head), chunk index c = (block*B + b)*H + h,
- * chunks stored back to back in c order in one arena per tensor:
- *     bytes [0,512)   header, byte [g*128 + d] = (width << 4) | min of the
- *                     pack holding tokens 16g..16g+15 of channel d
- *     then            the 512 packs in the same order, 2*width bytes each,
- *                     little-endian, token i of the group at bits
- *                     [i*width, (i+1)*width)
+ * chunks stored back to back in c order in one arena per tensor.  A pack is the
+ * 16 codes of one channel d in one token group g (tokens 16g..16g+15) with their
+ * minimum subtracted: `width` = ceil(log2(range + 1)) bits per code, 0..4.  The
+ * default layout (packs of 16 tokens) stores exactly 16*width bits per pack as
+ * bit planes, which the decode kernels feed to the matrix cores as they are:
+ *     pack list       V chunks: pack p = g*128 + d (group-major)
+ *                     K chunks: pack p = d*4 + g   (channel-major)
+ *     bytes [0,512)   header, byte p = (width << 4) | min of pack p
+ *     region E        for p = 0..511 in turn: if width >= 2 a 32-bit word L with
+ *                     the low two bits of the 16 codes, and if width == 4 a
+ *                     second word H with their high two bits; in both, token i
+ *                     of the group sits at bits [4i, 4i+2) for i < 8 and at
+ *                     [4(i-8)+2, 4(i-8)+4) for i >= 8
+ *     region O        for p = 0..511 in turn: if width is odd a 16-bit word T
+ *                     with the top bit (bit width-1) of the 16 codes, token i
+ *                     at bit 4*(i%4) + i/4
  *     then            zero padding to a multiple of 16 bytes
- * (the default layout, packs of 16 tokens; see kv_config_t for packs of 8 tokens
- * and for the wide layout that fine quantization scales use).
+ * (all words little-endian; see kv_config_t for packs of 8 tokens and for the
+ * wide layout that fine quantization scales use, which keep contiguous packs).
  * index[c] (uint32) is the chunk start in 16-byte units, index[n_chunks] the
  * arena end.  token_meta[b*max_tokens + t] (uint32) = scale_fp16 | min_fp16<<16
  * (Sec. III-B.2: one scale and minimum per token over all kv-heads).
@@ -85,10 +95,10 @@ typedef struct kv_page_pool kv_page_pool_t; /* the same: pages shared by paged c
 typedef struct {
     int32_t batch;         /* B >= 1                                              */
     int32_t n_kv_heads;    /* H_kv >= 1                                           */
-    int32_t n_q_heads;     /* H_q, a multiple of H_kv; H_q / H_kv from 1 to 8, or a
-                              product s * g with s, g <= 8 (12, 16, 24, 64 ...): such a
-                              group runs as s groups of g heads over the same kv-head;
-                              B * H_kv * s at most 65535                          */
+    int32_t n_q_heads;     /* H_q, a multiple of H_kv; H_q / H_kv from 1 to 4 (packs of 16;
+                              1 to 8 with packs of 8), or a product s * g with s <= 16 and g
+                              in that range (8, 12, 16, 64 ...): such a group runs as s groups
+                              of g heads over the same kv-head; B * H_kv * s at most 65535 */
     int32_t head_dim;      /* must be 128                                         */
     int32_t block_tokens;  /* must be 64                                          */
     int32_t pack_size;     /* 16 or 8                                             */
@@ -175,8 +185,14 @@ int kv_cache_destroy(kv_cache_t *cache);
  * arenas as one chunk per (batch, kv-head); the tail then empties.  Several
  * full blocks in one call are compressed straight from k_new/v_new.
  * Errors: KV_ERR_CAPACITY if tokens + n_new > max_tokens (nothing is done).
- * An arena that is too small is detected on the device: the block is dropped,
- * a sticky overflow flag is set and later reads of that block return zeros.
+ * An arena that is too small is detected on the device: the block is dropped
+ * from that tensor and a sticky overflow flag is set.  Rule for dropped blocks:
+ * kv_k_matvec scores the tokens of a block missing from K as -infinity, so
+ * kv_softmax gives them weight 0 (a row of nothing else comes out as zeros);
+ * kv_v_matvec adds nothing for a block missing from V; kv_decode_attention
+ * leaves a block out when either tensor dropped it.  The three-step path and
+ * the fused path therefore agree whenever no block is missing from V alone.
+ * An arena larger than 2^32 * 16 bytes is used up to that size only.
  */
 int kv_compress_append(kv_cache_t *cache, const void *k_new, const void *v_new, int32_t n_new,
                        void *hip_stream);
@@ -196,7 +212,10 @@ int kv_compress_append_bf16(kv_cache_t *cache, const void *k_new, const void *v_
  * q[b][hq][d] * Khat[b][t][hq / G][d] for every cached token t, where Khat is
  * scale_t*code + min_t for packed tokens and the raw fp16 value for tail
  * tokens.  q: device fp16 [B][H_q][128]; scores: device fp32 [B][H_q][ld_scores],
- * ld_scores >= tokens.  fp32 accumulation.  One launch covers all chunks.
+ * ld_scores >= tokens (q 16-byte aligned).  fp32 accumulation.  One launch covers
+ * all chunks.  With packs of 16 the products run on the matrix cores: the codes
+ * enter exactly, q as three 4-bit pieces per value (a head's values below 2^-12
+ * of its largest magnitude lose their low bits), sums in fp32.
  */
 int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores, int64_t ld_scores,
                 void *hip_stream);
@@ -207,6 +226,11 @@ int kv_k_matvec(kv_cache_t *cache, const void *q, float sm_scale, float *scores,
  * out: device fp32 [B][H_q][128].  fp32 accumulation in a fixed order (no
  * floating-point atomics): the result is bitwise reproducible.  Uses the
  * workspace for per-split partial sums; calls on one cache must not overlap.
+ * With packs of 16 the products run on the matrix cores: the codes enter
+ * exactly, the weights p_t * scale_t of a block rounded to 20 bits (16 with four
+ * query heads per kv-head) below the block's largest weight of that head, and
+ * the same rounded weights multiply the codes, the pack minimums and the token
+ * minimums.  p must be non-negative.
  */
 int kv_v_matvec(kv_cache_t *cache, const float *p, int64_t ld_p, float *out, void *hip_stream);
 
@@ -249,8 +273,8 @@ int kv_softmax(kv_cache_t *cache, float *scores, int64_t ld_scores, void *hip_st
  * [B][H_q][128].  Equivalent to kv_k_matvec -> softmax -> kv_v_matvec up to
  * fp32 rounding.  Fixed-order fp32 accumulation, bitwise reproducible.  Uses the
  * workspace for per-split partial results; calls on one cache must not overlap.
- * KV_ERR_ARG on an empty cache.  Blocks dropped by an arena overflow are left out
- * of the softmax.
+ * KV_ERR_ARG on an empty cache or if q is not 16-byte aligned.  Blocks dropped by
+ * an arena overflow (in either tensor) are left out of the softmax.
  */
 int kv_decode_attention(kv_cache_t *cache, const void *q, float sm_scale, float *out, void *hip_stream);
 

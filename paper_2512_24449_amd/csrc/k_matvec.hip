@@ -224,20 +224,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
         const uint32_t *meta = a.meta + b * a.meta_stride;
         const int64_t head0 = int64_t(stream) * G;
         KQueryPlanes<G> kq;
-        kq.load(a.q + head0 * D, lane);
+        kq.fetch(a.q + head0 * D, lane);
 
         auto issue = [&](const IndexBatch &ib, int it, int blk) {
             uint8_t *buf = lds_all + cur;
             row_issue_lds(meta + int64_t(blk) * N, buf + SIDE, lane);
             chunk_issue_lds(a.arena, ib.start16(it), ib.end16(it), buf, lane);
         };
-
-        for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
-            IndexBatch ib;
+        // index words of up to 64 blocks of this wave, then the first chunk of the batch
+        auto start_batch = [&](IndexBatch &ib, int first) {
+            if (first >= blk_end) return;
             ib.load(a.index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
-            const int n_it = min(64, (blk_end - first + 3) / 4);
             wait_chunk_landed();  // the index words and the query (the only loads the compiler sees)
             issue(ib, 0, first);
+        };
+
+        IndexBatch ib;
+        start_batch(ib, blk_begin + wave);
+        kq.build(lane);  // the query operand is built while the first chunk is on its way
+        for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
+            const int n_it = min(64, (blk_end - first + 3) / 4);
             for (int it = 0; it < n_it; ++it) {
                 const bool valid = ib.end16(it) - ib.start16(it) >= uint32_t(HEADER / 16);
                 wait_chunk_landed();  // chunk it with its metadata row (and the score stores before it)
@@ -262,6 +268,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
                     a.scores[(head0 + g) * a.ld + tok] = a.sm_scale * fmaf(scale, u[g], mn * kq.qsum[g]);
             }
             wait_chunk_landed();
+            start_batch(ib, first + 4 * 64);
         }
     }
 }

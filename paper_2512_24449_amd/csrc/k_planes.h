@@ -63,23 +63,41 @@ struct KQueryPlanes {
     int scale_a;    // E8M0 block scale of this lane's row
     float qsum[G];  // sum_d q[head][d], the same in every lane
 
-    // q_group: the G query heads of the kv-head, [G][128] fp16
-    __device__ inline void load(const __half *q_group, int lane) {
+    uint4 raw[4];   // fetch() -> build(): this lane's 32 query values as loaded
+
+    // Issues the loads of this lane's part of q_group (the G query heads of the kv-head, [G][128]
+    // fp16); build() turns them into the operand.  Kept apart so that a caller can start a chunk
+    // transfer between the two and pay one memory latency for both.
+    __device__ inline void fetch(const __half *q_group, int lane) {
         const int m = lane & 15, kb = lane >> 4;
+        const int head = m >> 2;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            raw[2 * half] = raw[2 * half + 1] = make_uint4(0, 0, 0, 0);
+            if (head < G) {
+                // bytes 16 half .. 16 half + 15 are k-group kg = 4 half + kb: the (kg & 1)-th read of row group kg / 2
+                const int kg = 4 * half + kb;
+                const __half *src = q_group + head * D + k_read_channel(kg >> 1, kg & 1, 0);
+                raw[2 * half] = *reinterpret_cast<const uint4 *>(src);
+                raw[2 * half + 1] = *reinterpret_cast<const uint4 *>(src + 8);
+            }
+        }
+    }
+
+    __device__ inline void load(const __half *q_group, int lane) {
+        fetch(q_group, lane);
+        build(lane);
+    }
+
+    __device__ inline void build(int lane) {
+        const int m = lane & 15;
         const int head = m >> 2, piece = m & 3;
         const bool used = head < G && piece < 3;
         float x[32];
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
-            uint4 raw[2] = {make_uint4(0, 0, 0, 0), make_uint4(0, 0, 0, 0)};
-            if (head < G) {
-                // bytes 16 half .. 16 half + 15 are k-group kg = 4 half + kb: the (kg & 1)-th read of row group kg / 2
-                const int kg = 4 * half + kb;
-                const __half *src = q_group + head * D + k_read_channel(kg >> 1, kg & 1, 0);
-                raw[0] = *reinterpret_cast<const uint4 *>(src);
-                raw[1] = *reinterpret_cast<const uint4 *>(src + 8);
-            }
-            const uint32_t w[8] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w, raw[1].x, raw[1].y, raw[1].z, raw[1].w};
+            const uint32_t w[8] = {raw[2 * half].x, raw[2 * half].y, raw[2 * half].z, raw[2 * half].w,
+                                   raw[2 * half + 1].x, raw[2 * half + 1].y, raw[2 * half + 1].z, raw[2 * half + 1].w};
 #pragma unroll
             for (int k = 0; k < 8; ++k) {
                 x[16 * half + 2 * k] = half_lo(w[k]);
