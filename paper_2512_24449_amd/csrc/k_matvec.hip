@@ -241,7 +241,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
 
         IndexBatch ib;
         start_batch(ib, blk_begin + wave);
-        kq.build(lane);  // the query operand is built while the first chunk is on its way
+        // the query operand is built while the first chunk is on its way, a quarter per wave (the tiles
+        // of the workgroup are idle between two segments and carry the exchange)
+        kq.build_shared(lane, wave, reinterpret_cast<uint32_t *>(tiles_all));
         for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
             const int n_it = min(64, (blk_end - first + 3) / 4);
             for (int it = 0; it < n_it; ++it) {

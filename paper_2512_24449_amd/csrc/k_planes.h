@@ -89,41 +89,16 @@ struct KQueryPlanes {
         build(lane);
     }
 
-    __device__ inline void build(int lane) {
-        const int m = lane & 15;
-        const int head = m >> 2, piece = m & 3;
-        const bool used = head < G && piece < 3;
-        float x[32];
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            const uint32_t w[8] = {raw[2 * half].x, raw[2 * half].y, raw[2 * half].z, raw[2 * half].w,
-                                   raw[2 * half + 1].x, raw[2 * half + 1].y, raw[2 * half + 1].z, raw[2 * half + 1].w};
-#pragma unroll
-            for (int k = 0; k < 8; ++k) {
-                x[16 * half + 2 * k] = half_lo(w[k]);
-                x[16 * half + 2 * k + 1] = half_hi(w[k]);
-            }
-        }
-        // the four lanes of a row (kb = 0..3) cover the 128 channels of its head
-        float s = 0.0f, big = 0.0f;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-            s += x[k];
-            big = fmaxf(big, fabsf(x[k]));
-        }
-        s += __shfl_xor(s, 16);
-        s += __shfl_xor(s, 32);
-        big = fmaxf(big, __shfl_xor(big, 16));
-        big = fmaxf(big, __shfl_xor(big, 32));
-        // e: biased exponent of the largest |q| of the head (fp16 inputs: 103 .. 142, or 0 for a zero head)
-        int e = int(__float_as_uint(big) >> 23);
-        if (e == 0) e = 127;
-        const float down = __uint_as_float(uint32_t(254 - e) << 23);  // 2^-(e - 127): |x * down| < 2
-        uint32_t bytes[8];
+    // The pieces of the value pairs first .. first + count - 1 (of this lane's 16 pairs), as FP8
+    // byte pairs in out[pair / 2] (even pair: low half).  down: 2^-(e - 127).
+    __device__ inline void pieces(int first, int count, int piece, float down, uint32_t (&out)[8]) const {
+        const uint32_t w[16] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w, raw[1].x, raw[1].y, raw[1].z, raw[1].w,
+                                raw[2].x, raw[2].y, raw[2].z, raw[2].w, raw[3].x, raw[3].y, raw[3].z, raw[3].w};
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
+            if (k < first || k >= first + count) continue;
             // two values at a time: piece p is the FP8 rounding of what the pieces before it left, times 16^p
-            float r0 = x[2 * k] * down, r1 = x[2 * k + 1] * down;
+            float r0 = half_lo(w[k]) * down, r1 = half_hi(w[k]) * down;
             uint32_t pk = 0;
 #pragma unroll
             for (int p = 0; p < 3; ++p) {
@@ -133,17 +108,79 @@ struct KQueryPlanes {
                 r1 = (r1 - __builtin_amdgcn_cvt_f32_fp8(int(c), 1)) * 16.0f;
             }
             if (k & 1)
-                bytes[k >> 1] |= pk << 16;
+                out[k >> 1] |= pk << 16;
             else
-                bytes[k >> 1] = pk;
+                out[k >> 1] = pk;
         }
+    }
+
+    // Exponent of the head's largest |q| and the sums: what every wave needs of all 32 values.
+    // Returns e, the biased exponent of the largest |q| of the head (fp16 inputs: 103 .. 142; 127 for a zero head).
+    __device__ inline int scan_values() {
+        typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+        const uint32_t w[16] = {raw[0].x, raw[0].y, raw[0].z, raw[0].w, raw[1].x, raw[1].y, raw[1].z, raw[1].w,
+                                raw[2].x, raw[2].y, raw[2].z, raw[2].w, raw[3].x, raw[3].y, raw[3].z, raw[3].w};
+        h2 big2 = {_Float16(0.0f), _Float16(0.0f)};
+        const h2 ones = {_Float16(1.0f), _Float16(1.0f)};
+        float s = 0.0f;
 #pragma unroll
-        for (int k = 0; k < 8; ++k) a[k] = used ? int(bytes[k]) : 0;
-        scale_a = used ? e - 4 * piece : E8M0_ONE;
+        for (int k = 0; k < 16; ++k) {
+            big2 = __builtin_elementwise_max(big2, __builtin_bit_cast(h2, w[k] & 0x7FFF7FFFu));
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(h2, w[k]), ones, s, false);  // exact products, fp32 sum
+        }
+        float big = fmaxf(float(big2[0]), float(big2[1]));
+        // the four lanes of a row (kb = 0..3) cover the 128 channels of its head
+        s += __shfl_xor(s, 16);
+        s += __shfl_xor(s, 32);
+        big = fmaxf(big, __shfl_xor(big, 16));
+        big = fmaxf(big, __shfl_xor(big, 32));
         // the sum of head g sits in the lanes of its rows
 #pragma unroll
         for (int g = 0; g < G; ++g)
             qsum[g] = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(s), 4 * g));
+        const int e = int(__float_as_uint(big) >> 23);
+        return e == 0 ? 127 : e;
+    }
+
+    __device__ inline void build(int lane) {
+        const int m = lane & 15;
+        const int head = m >> 2, piece = m & 3;
+        const bool used = head < G && piece < 3;
+        const int e = scan_values();
+        uint32_t bytes[8];
+        pieces(0, 16, piece, __uint_as_float(uint32_t(254 - e) << 23), bytes);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a[k] = used ? int(bytes[k]) : 0;
+        scale_a = used ? e - 4 * piece : E8M0_ONE;
+    }
+
+    // The same with the piece arithmetic shared by the four waves of a workgroup that all need the
+    // operand of one stream: wave w converts the value pairs 4w .. 4w + 3 of every lane and the
+    // waves exchange the bytes through `share` (workgroup-shared LDS, 64 x 8 dwords, free for the
+    // duration of the call).  Contains workgroup barriers: every wave of the workgroup must call it.
+    __device__ inline void build_shared(int lane, int wave, uint32_t *share) {
+        const int m = lane & 15;
+        const int head = m >> 2, piece = m & 3;
+        const bool used = head < G && piece < 3;
+        const int e = scan_values();
+        const float down = __uint_as_float(uint32_t(254 - e) << 23);
+        uint32_t bytes[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        if (wave == 0) pieces(0, 4, piece, down, bytes);
+        if (wave == 1) pieces(4, 4, piece, down, bytes);
+        if (wave == 2) pieces(8, 4, piece, down, bytes);
+        if (wave == 3) pieces(12, 4, piece, down, bytes);
+        __syncthreads();  // `share` is free: every wave has left what used it before
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            if (wave == q) *reinterpret_cast<uint2 *>(share + lane * 8 + 2 * q) = make_uint2(bytes[2 * q], bytes[2 * q + 1]);
+        __syncthreads();
+        const uint4 lo = *reinterpret_cast<const uint4 *>(share + lane * 8);
+        const uint4 hi = *reinterpret_cast<const uint4 *>(share + lane * 8 + 4);
+        const uint32_t all[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+#pragma unroll
+        for (int k = 0; k < 8; ++k) a[k] = used ? int(all[k]) : 0;
+        scale_a = used ? e - 4 * piece : E8M0_ONE;
+        __syncthreads();  // read by every wave: `share` may be reused
     }
 };
 
