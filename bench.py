@@ -472,7 +472,10 @@ def run_compress(w, K, V, torch, binding):
     return {"prompt_ms": round(ms, 3), "fp16_input_gbps": round(in_bytes / (ms * 1e-3) / 1e9, 1),
             "pct_hbm_peak_on_input": round(100.0 * in_bytes / (ms * 1e-3) / 8e12, 2),
             "tail_flush_ms": round(flush_ms, 4),
-            "note": "quantizes every value twice (sizes pass, write pass): bound by that arithmetic, not by HBM"}
+            "hbm_bytes_per_input_byte": "about 2.85: the input is read twice (token minimum and maximum, then "
+                                        "quantization), the packed bytes are written to a staging slot, read back "
+                                        "and written to their place",
+            "note": "staged path, every value quantized once; bound by HBM traffic"}
 
 
 def run_repack(w, torch, binding, synth):

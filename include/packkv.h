@@ -115,7 +115,8 @@ typedef struct {
     size_t k_index, v_index;           /* uint32 [max_chunks + 1]                 */
     size_t k_token_meta, v_token_meta; /* uint32 [B][max_tokens]                  */
     size_t k_tail, v_tail;             /* fp16 [B][tail_capacity][H_kv][128]      */
-    size_t workspace;                  /* status words, chunk sizes, V partials   */
+    size_t workspace;                  /* status words, chunk sizes, V partials, and (packs of
+                                          16) the compressor's staging area: at most 75 MB */
     size_t token_order;                /* uint8 [B][max_tokens]; 0 without repacking */
     size_t k_pages, v_pages;           /* paged caches only: uint32 page lists; else 0 */
 } kv_sizes_t;

@@ -95,6 +95,8 @@ extern "C" int kv_query_sizes(const kv_config_t *cfg, double bits_per_element_bu
     out->k_tail = out->v_tail =
         round256(size_t(cfg->batch) * cfg->tail_capacity * cfg->n_kv_heads * D * 2);
     out->workspace = round256(WS_VPART + v_partial_bytes(cfg->batch, cfg->n_q_heads));
+    if (cfg->pack_size == 16)  // staging area of the compressor behind the rest
+        out->workspace += round256(size_t(stage_chunks_for(cfg->batch, cfg->n_kv_heads)) * chunk_max_bytes(16));
     out->token_order = cfg->repack ? round256(size_t(cfg->batch) * max_tokens) : 0;
     out->k_pages = out->v_pages = 0;
     return KV_OK;
@@ -196,6 +198,9 @@ int create_cache(const kv_config_t *cfg, kv_page_pool *pool, const kv_buffers_t 
     c->wide_v = c->qmax_v > 15;
     c->packed_tokens = 0;
     c->tail_tokens = 0;
+    c->fill_bound16[0] = c->fill_bound16[1] = 0;
+    c->stage_offset = round256(WS_VPART + v_partial_bytes(cfg->batch, cfg->n_q_heads));
+    c->stage_chunks = stage_chunks_for(cfg->batch, cfg->n_kv_heads);
     c->pool = pool;
     c->index_words = pool ? 2 : 1;
     c->max_pages_k = c->max_pages_v = 0;
@@ -237,6 +242,7 @@ extern "C" int kv_cache_release(kv_cache_t *c, void *hip_stream) {
     if ((rc = launch_init(c, s))) return rc;  // status words, index[0]; the page lists are empty already
     c->packed_tokens = 0;
     c->tail_tokens = 0;
+    c->fill_bound16[0] = c->fill_bound16[1] = 0;
     return KV_OK;
 }
 
@@ -304,8 +310,12 @@ int compress_blocks(kv_cache *c, const __half *ksrc, const __half *vsrc, int64_t
             if ((rc = launch_v_median_order(c, vjob, kjob.meta, order, s))) return rc;
             kjob.order = vjob.order = order;
         }
+        kjob.fill_bound16 = c->fill_bound16[0];
+        vjob.fill_bound16 = c->fill_bound16[1];
         if ((rc = launch_pack(c, kjob, s))) return rc;
         if ((rc = launch_pack(c, vjob, s))) return rc;
+        c->fill_bound16[0] += uint64_t(nb) * B * H * (chunk_max_bytes(c->cfg.pack_size, c->wide_k) / 16);
+        c->fill_bound16[1] += uint64_t(nb) * B * H * (chunk_max_bytes(c->cfg.pack_size, c->wide_v) / 16);
         c->packed_tokens += int64_t(nb) * N;
         done += nb;
     }

@@ -73,6 +73,14 @@ struct FlatPlan {
 int resident_workgroups(const void *kernel);
 int flat_groups_for(int64_t total, int per_cu, int64_t most);
 
+// Staging area of the compressor (packs of 16): chunks it holds, each in a slot of the largest
+// chunk's size.  64 blocks of the cache at a time, within 256 .. 16384 chunks (1.2 .. 75 MB):
+// large enough to fill the chip, small enough to stay in the last-level cache until it is read back.
+inline int stage_chunks_for(int batch, int n_kv_heads) {
+    const int64_t want = int64_t(batch) * n_kv_heads * 64;
+    return int(want < 256 ? 256 : want > 16384 ? 16384 : want);
+}
+
 inline size_t v_partial_bytes(int batch, int n_q_heads) {
     return size_t(V_SPLITS_MAX) * batch * n_q_heads * V_PART_STRIDE * sizeof(float);
 }
@@ -200,6 +208,26 @@ struct kv_page_pool {
     int64_t n_pages;
 };
 
+// Staged compression of packs of 16 (compress.hip).  A round whose chunks fit the arena even at
+// their largest takes the staged path; the test runs on the device, where the fill level is.
+struct StagedRound {
+    int64_t first_chunk;   // first chunk of the whole round
+    uint32_t worst16;      // chunks of the round times the largest chunk, in 16-byte units; 0: two-pass only
+    uint64_t arena_cap16;
+};
+
+// A staged part: chunks in their slots, to be copied to the arena once the part's scan has set
+// their index words.
+struct StagedPart {
+    const uint8_t *staging;   // slot i holds chunk first_chunk + i
+    const uint32_t *index;
+    int64_t first_chunk;      // absolute chunk number
+    int n;
+    uint8_t *arena;
+    StagedRound round;        // of the part's tensor
+};
+
+
 struct kv_cache {
     kv_config_t cfg;
     kv_buffers_t buf;
@@ -212,6 +240,9 @@ struct kv_cache {
     bool wide_k, wide_v;    // codes above 15: wide chunk layout for that tensor
     int64_t packed_tokens;  // per batch element
     int32_t tail_tokens;
+    size_t stage_offset;    // staging area of the compressor inside the workspace (packs of 16; else unused)
+    int stage_chunks;       // chunks it holds
+    uint64_t fill_bound16[2];  // K, V: upper bound of the arena's fill level, every chunk so far at its largest
     // paged arena: both tensors live in the pool's pages (buf.k_arena = buf.v_arena = pool->pages),
     // the index has a (start, end) pair per chunk, buf.k_pages / buf.v_pages list the pages held
     kv_page_pool *pool;     // null: chunks back to back in the cache's own arenas
@@ -272,6 +303,7 @@ struct CompressJob {
     int64_t max_pages;        // page numbers the list has room for
     const uint8_t *order;     // [B][max_tokens] source position of each storage slot inside its block, or null
     int pack_order;           // packs of 16 (plane layout): 0 group-major pack list (V), 1 channel-major (K)
+    uint64_t fill_bound16;    // the arena holds at most this much before the round (every chunk so far at its largest)
 };
 
 int launch_token_params(const kv_cache *c, const CompressJob &job, hipStream_t s);

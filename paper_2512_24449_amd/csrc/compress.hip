@@ -5,13 +5,19 @@
 //                  H*128 values -> fp16 scale = rel*(max-min), fp16 min
 //   v_median_key, block_order   (V-median repacking only) sort key per token,
 //                  order of the 64 tokens of a block, metadata into storage order
-//   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
+// then, packs of 16 in a contiguous arena whose free space takes even the largest chunks
+// (staged path, the input is quantized once):
+//   stage          resident workgroups, a chunk at a time each: quantize, build the chunk's
+//                  bytes in LDS, store them in a fixed slot of the staging area, and its size
 //   scan_offsets   one workgroup: prefix sum of the new chunk sizes -> index
-//   place_chunks   (paged arena instead of scan_offsets) one workgroup: chunk positions inside
-//                  pages taken from a shared pool -> index of (start, end) pairs
+//   compact        one wave per chunk: staged bytes to their place in the arena
+// else (two-pass path: packs of 8, paged arenas, a nearly full arena):
+//   chunk_sizes    one workgroup per chunk: quantize, per-pack width -> bytes
+//   scan_offsets / place_chunks (paged arena) one workgroup: chunk positions -> index; paged:
+//                  inside pages taken from a shared pool, index of (start, end) pairs
 //   pack_chunks    one workgroup per chunk: quantize again and write header +
-//                  payload at its final place (no staging copy, no atomics, so
-//                  the arena bytes are a pure function of the input)
+//                  payload at its final place
+// No atomics in either path: the arena bytes are a pure function of the input.
 #include <algorithm>
 
 #include "common.h"
@@ -21,8 +27,7 @@ namespace packkv {
 // Eight consecutive input values as fp16.  fp16 inputs pass as they are; bf16 inputs are rounded
 // to fp16 (to nearest even; exact for every value in fp16's normal range, fp16 having the longer
 // significand) -- from there on the path does not know the input type.
-__device__ inline uint4 load8_as_fp16(const __half *p, bool bf16) {
-    uint4 raw = *reinterpret_cast<const uint4 *>(p);
+__device__ inline uint4 as_fp16(uint4 raw, bool bf16) {
     if (bf16) {
         uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
@@ -34,6 +39,9 @@ __device__ inline uint4 load8_as_fp16(const __half *p, bool bf16) {
         raw = make_uint4(w[0], w[1], w[2], w[3]);
     }
     return raw;
+}
+__device__ inline uint4 load8_as_fp16(const __half *p, bool bf16) {
+    return as_fp16(*reinterpret_cast<const uint4 *>(p), bf16);
 }
 
 // ---------------------------------------------------------------------------
@@ -265,53 +273,243 @@ struct PlaneBits {
     int w, m;
 };
 
-__device__ inline PlaneBits make_planes(const __half *tile, int g, int d, const float4 *sm, int qmax) {
-    int q[PACK];
-    int lo = 255, hi = 0;
-#pragma unroll
-    for (int i = 0; i < PACK; ++i) {
-        const float4 t = sm[g * PACK + i];
-        const int v = quantize_value(__half2float(tile[(g * PACK + i) * D + d]), t.x, t.y, t.z, qmax);
-        q[i] = v;
-        lo = min(lo, v);
-        hi = max(hi, v);
-    }
+// n0, n1: the 16 codes of a pack as nibbles (tokens 0..7, 8..15); lo, hi: their minimum and maximum.
+__device__ inline PlaneBits planes_from_nibbles(uint32_t n0, uint32_t n1, int lo, int hi) {
     PlaneBits pb;
     const int range = hi - lo;
     pb.w = range == 0 ? 0 : 32 - __clz(range);
     pb.m = lo;
-    pb.low = pb.high = pb.top = 0;
+    // codes minus the pack minimum: no nibble borrows (every code is at least the minimum)
+    n0 -= uint32_t(lo) * 0x11111111u;
+    n1 -= uint32_t(lo) * 0x11111111u;
+    // planes of two-bit fields: token i at bits [4i, 4i+2) for i < 8, at [4(i-8)+2, 4(i-8)+4) for i >= 8
+    pb.low = (n0 & 0x33333333u) | ((n1 & 0x33333333u) << 2);
+    pb.high = ((n0 >> 2) & 0x33333333u) | (n1 & 0xCCCCCCCCu);
+    // top bit of every code, token i at bit 4 (i % 4) + i / 4
     const int top_bit = pb.w > 0 ? pb.w - 1 : 0;
-#pragma unroll
-    for (int i = 0; i < PACK; ++i) {
-        const uint32_t c = uint32_t(q[i] - lo);
-        const int at = i < 8 ? 4 * i : 4 * (i - 8) + 2;
-        pb.low |= (c & 3u) << at;
-        pb.high |= (c >> 2) << at;
-        pb.top |= ((c >> top_bit) & 1u) << (4 * (i & 3) + (i >> 2));
-    }
+    const uint32_t t0 = (n0 >> top_bit) & 0x11111111u, t1 = (n1 >> top_bit) & 0x11111111u;
+    pb.top = (t0 & 0xFFFFu) | ((t0 >> 16) << 1) | ((t1 & 0xFFFFu) << 2) | ((t1 >> 16) << 3);
     return pb;
 }
 
-template <bool WRITE>
-__global__ __launch_bounds__(256) void chunk16_kernel(const __half *__restrict__ src,
-                                                      int64_t batch_stride, int64_t token_stride,
-                                                      int B, int H, int qmax,
-                                                      const uint32_t *__restrict__ meta,
-                                                      int64_t meta_stride, int64_t first_token,
-                                                      int64_t first_chunk,
-                                                      uint32_t *__restrict__ sizes16,
-                                                      const uint32_t *__restrict__ index,
-                                                      int index_words,
-                                                      uint8_t *__restrict__ arena,
-                                                      const uint8_t *__restrict__ order, bool bf16,
-                                                      int pack_order) {
-    const int cl = blockIdx.x;  // chunk within this round: (blk*B + b)*H + h
-    const int h = cl % H;
-    const int b = (cl / H) % B;
-    const int blk = cl / (H * B);
-    const int tau = threadIdx.x;
+// Code tile of a chunk in LDS: channel d has a row of 16 words (and one word of padding, which
+// spreads the rows over the banks); word 4g + q of it holds four codes of token group g, one per
+// byte: q = 0: tokens 0, 2, 4, 6; q = 1: tokens 1, 3, 5, 7; q = 2: tokens 8, 10, 12, 14; q = 3:
+// tokens 9, 11, 13, 15.  So word 0 | word 1 << 4 is the nibble string of tokens 0..7 and
+// word 2 | word 3 << 4 that of tokens 8..15 (codes of packs of 16 are below 16).
+constexpr int CODE_ROW_WORDS = 17;
+constexpr int CODE_TILE_WORDS = D * CODE_ROW_WORDS;
+typedef unsigned short pk_u16 __attribute__((ext_vector_type(2)));
 
+__device__ inline PlaneBits planes_from_codes(const uint32_t *words) {
+    const uint32_t w0 = words[0], w1 = words[1], w2 = words[2], w3 = words[3];
+    // minimum and maximum of the 16 bytes, two 16-bit lanes at a time
+    constexpr uint32_t EVEN = 0x00FF00FFu;
+    const uint32_t v[8] = {w0 & EVEN, (w0 >> 8) & EVEN, w1 & EVEN, (w1 >> 8) & EVEN,
+                           w2 & EVEN, (w2 >> 8) & EVEN, w3 & EVEN, (w3 >> 8) & EVEN};
+    pk_u16 mn = __builtin_bit_cast(pk_u16, v[0]), mx = mn;
+#pragma unroll
+    for (int i = 1; i < 8; ++i) {
+        mn = __builtin_elementwise_min(mn, __builtin_bit_cast(pk_u16, v[i]));
+        mx = __builtin_elementwise_max(mx, __builtin_bit_cast(pk_u16, v[i]));
+    }
+    const int lo = min(int(mn.x), int(mn.y)), hi = max(int(mx.x), int(mx.y));
+    return planes_from_nibbles(w0 | (w1 << 4), w2 | (w3 << 4), lo, hi);
+}
+
+// One chunk of packs of 16 in a workgroup's registers: thread tau holds packs 2 tau and 2 tau + 1
+// of the pack list; off: the bytes of the packs before them in region E (low half) and region O
+// (high half).
+struct PlaneChunk {
+    PlaneBits pb[2];
+    int off;
+    int e_bytes, o_bytes, padded;
+};
+
+// What a thread loads of a chunk: eight channels (8 * (tau % 16) ...) of the four tokens that
+// share a word of the code tile (word tau / 16 of each of those channels), and the tokens' metadata.
+struct ChunkInput {
+    uint4 raw[4];
+    uint32_t mt[4];
+};
+
+struct ChunkSource {
+    const __half *src;
+    int64_t batch_stride, token_stride;
+    int B, H, qmax;
+    uint64_t magic_h, magic_hb;  // floor(2^32 / H) + 1, floor(2^32 / (H * B)) + 1
+    const uint32_t *meta;
+    int64_t meta_stride, first_token;
+    const uint8_t *order;
+    bool bf16;
+    int pack_order;
+};
+
+// Chunk cl of the round is (blk*B + b)*H + h.  cl is the same for the whole workgroup, so the
+// quotients are scalar work: x / d = (x * (floor(2^32 / d) + 1)) >> 32 for x * d < 2^32
+// (cl < 2^16 here, H * B <= 2^16).
+struct ChunkCoord {
+    int h, b, blk;
+};
+__device__ inline ChunkCoord chunk_coord(const ChunkSource &cs, int cl) {
+    const uint32_t c = uint32_t(__builtin_amdgcn_readfirstlane(cl));
+    const uint32_t by_h = uint32_t((uint64_t(c) * cs.magic_h) >> 32);
+    const uint32_t blk = uint32_t((uint64_t(c) * cs.magic_hb) >> 32);
+    ChunkCoord k;
+    k.h = int(c - by_h * uint32_t(cs.H));
+    k.b = int(by_h - blk * uint32_t(cs.B));
+    k.blk = int(blk);
+    return k;
+}
+
+// Where chunk cl of the round ((blk*B + b)*H + h) finds the four tokens of thread tau: rows
+// row0 + 2i of the block in storage order, at the source positions the token order gives.
+struct ChunkRows {
+    int src_row[4];
+};
+__device__ inline int chunk_row0() {
+    const int word = threadIdx.x >> 4;  // word = 4g + q
+    return 16 * (word >> 2) + 8 * ((word >> 1) & 1) + (word & 1);
+}
+__device__ inline ChunkRows load_chunk_rows(const ChunkSource &cs, int cl) {
+    const ChunkCoord k = chunk_coord(cs, cl);
+    const int b = k.b, blk = k.blk;
+    const int row0 = chunk_row0();
+    ChunkRows r;
+    if (cs.order) {
+        const uint8_t *ord = cs.order + b * cs.meta_stride + cs.first_token + int64_t(blk) * N;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.src_row[i] = ord[row0 + 2 * i];
+    } else {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r.src_row[i] = row0 + 2 * i;
+    }
+    return r;
+}
+
+// Issues the loads of chunk cl.
+__device__ inline ChunkInput load_chunk_input(const ChunkSource &cs, int cl, const ChunkRows &rows) {
+    const ChunkCoord k = chunk_coord(cs, cl);
+    const int h = k.h, b = k.b, blk = k.blk;
+    const int cg = threadIdx.x & 15;
+    const int row0 = chunk_row0();
+    const __half *x_blk = cs.src + b * cs.batch_stride + int64_t(blk) * N * cs.token_stride + h * D + cg * 8;
+    const uint32_t *meta_blk = cs.meta + b * cs.meta_stride + cs.first_token + int64_t(blk) * N;
+    ChunkInput in;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        in.raw[i] = *reinterpret_cast<const uint4 *>(x_blk + rows.src_row[i] * cs.token_stride);  // converted where it is used
+        in.mt[i] = meta_blk[row0 + 2 * i];
+    }
+    return in;
+}
+
+// The eight values of one token a thread holds, quantized (Sec. III-B.2: clamp(rint(fl((x - mn) / s)),
+// 0, qmax), the quotient rounded to fp32 as an IEEE divide does) into byte `slot` of out[0..7];
+// qmax < 16.  Fast path: q = (x - mn) * r with r = 1 / s to within an ulp, rounded to the nearest
+// integer (ties to even) and clamped to 0 .. 255 by the conversion that also places the byte.
+// q lies within 2^-22 relative of the rounded quotient (an ulp for r, half for the product, half
+// for the quotient's own rounding): within 2^-16 for quotients below 64, and from 64 on both sides
+// are clamped to qmax anyway.  So unless q is within 2^-15 of a rounding tie k + 1/2, it rounds as
+// the quotient does.  `clear` collects how far the eight values stay from a tie; the rare token
+// with a value near one takes the divide for all eight.
+constexpr float TIE_GUARD = 1.0f / 32768.0f;
+
+__device__ inline void quantize_token8(uint4 values, uint32_t mt, int qmax, int slot, uint32_t *out) {
+    const float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
+    const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
+    const float r = s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;  // s = 0: every code is 0
+    const float top = float(qmax);
+    const __half *x = reinterpret_cast<const __half *>(&values);
+    float clear = 1.0f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+        const float q = (__half2float(x[j]) - mn) * r;
+        clear = fminf(clear, fabsf(__builtin_amdgcn_fractf(q) - 0.5f));
+        out[j] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(q, top), uint32_t(slot), out[j]);
+    }
+    if (clear < TIE_GUARD) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float q = s != 0.0f ? (__half2float(x[j]) - mn) / s : 0.0f;  // IEEE fp32 divide
+            out[j] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(q, top), uint32_t(slot), out[j]);
+        }
+    }
+}
+
+// Quantizes a chunk and lays out its regions.  Every value is quantized by the thread that loaded
+// it, with its token's scale and minimum, so the code tile is written a word at a time.
+// Ends behind a barrier that all threads pass after their last read of the tile.
+__device__ inline PlaneChunk make_plane_chunk(const ChunkSource &cs, const ChunkInput &in, uint32_t *codes) {
+    const int tau = threadIdx.x;
+    {
+        const int cg = tau & 15, word = tau >> 4;
+        uint32_t out[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) quantize_token8(as_fp16(in.raw[i], cs.bf16), in.mt[i], cs.qmax, i, out);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) codes[(cg * 8 + j) * CODE_ROW_WORDS + word] = out[j];
+    }
+    __syncthreads();
+    PlaneChunk c;
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int p = 2 * tau + k;
+        const int g = cs.pack_order ? (p & 3) : (p >> 7);
+        const int d = cs.pack_order ? (p >> 2) : (p & 127);
+        c.pb[k] = planes_from_codes(codes + d * CODE_ROW_WORDS + 4 * g);
+    }
+    // one scan carries both regions: E bytes in the low half, O bytes in the high half
+    int total;
+    const int w0 = c.pb[0].w, w1 = c.pb[1].w;
+    c.off = block_exclusive_scan(4 * ((w0 >> 1) + (w1 >> 1)) + ((2 * ((w0 & 1) + (w1 & 1))) << 16), &total);
+    c.e_bytes = total & 0xFFFF;
+    c.o_bytes = total >> 16;
+    c.padded = (HEADER + c.e_bytes + c.o_bytes + 15) & ~15;
+    return c;
+}
+
+__device__ inline void write_plane_chunk(const PlaneChunk &c, uint8_t *__restrict__ dst) {
+    const int tau = threadIdx.x;
+    const int w0 = c.pb[0].w, w1 = c.pb[1].w;
+    reinterpret_cast<uint16_t *>(dst)[tau] = uint16_t(((w0 << 4) | c.pb[0].m) | (((w1 << 4) | c.pb[1].m) << 8));
+    uint32_t *e = reinterpret_cast<uint32_t *>(dst + HEADER + (c.off & 0xFFFF));
+    if (w0 >= 2) e[0] = c.pb[0].low;
+    if (w0 == 4) e[1] = c.pb[0].high;
+    e += w0 >> 1;
+    if (w1 >= 2) e[0] = c.pb[1].low;
+    if (w1 == 4) e[1] = c.pb[1].high;
+    uint16_t *o = reinterpret_cast<uint16_t *>(dst + HEADER + c.e_bytes + (c.off >> 16));
+    if (w0 & 1) o[0] = uint16_t(c.pb[0].top);
+    o += w0 & 1;
+    if (w1 & 1) o[0] = uint16_t(c.pb[1].top);
+    if (tau < c.padded - HEADER - c.e_bytes - c.o_bytes) dst[HEADER + c.e_bytes + c.o_bytes + tau] = 0;
+}
+
+// Staged path, packs of 16, contiguous arena: the input is quantized once.
+//   stage     one workgroup per chunk: quantize, build the chunk's bytes in LDS, store them in a
+//             slot of CHUNK_MAX bytes of the staging area in the workspace, and the chunk's size
+//   scan_offsets   as in the two-pass path
+//   compact   one wave per chunk: copy the staged bytes to their place in the arena
+// A chunk's place depends on the sizes of all chunks before it, so some second step is needed;
+// this one re-reads the compressed bytes (a fraction of the input, and still in the last-level
+// cache: the staging area is a few tens of MB) instead of the input.  A round is cut into parts
+// that fit the staging area.  The path runs when even the largest chunks fit the arena (worst16 =
+// chunks of the round times the largest chunk, checked on the device, where the fill level is), so
+// no part can overflow and a round keeps or drops its chunks as a whole; otherwise its kernels
+// return at once and the two-pass kernels do the round, and the other way round.
+__device__ inline bool staged_round(const StagedRound &r, const uint32_t *index) {
+    return r.worst16 != 0 && uint64_t(index[r.first_chunk]) + r.worst16 <= r.arena_cap16;
+}
+
+// Two-pass path, packs of 16: WRITE false = sizes only, true = bytes at the offsets of the index.
+template <bool WRITE>
+__global__ __launch_bounds__(256) void chunk16_kernel(ChunkSource cs, int64_t first_chunk,
+                                                      uint32_t *__restrict__ sizes16,
+                                                      const uint32_t *__restrict__ index, int index_words,
+                                                      uint8_t *__restrict__ arena, StagedRound round) {
+    if (staged_round(round, index)) return;  // the staged path writes this round
+    const int cl = blockIdx.x;
     uint8_t *dst = nullptr;
     if (WRITE) {
         const int64_t e = (first_chunk + cl) * index_words;
@@ -319,92 +517,146 @@ __global__ __launch_bounds__(256) void chunk16_kernel(const __half *__restrict__
         if (o1 == o0) return;  // dropped: the arena was full
         dst = arena + size_t(o0) * 16;
     }
-
-    __shared__ __attribute__((aligned(16))) __half tile[N * D];
-    __shared__ float4 sm[N];
-    if (tau < N) sm[tau] = token_scale_min(meta[b * meta_stride + first_token + int64_t(blk) * N + tau]);
-    {
-        const __half *x_blk = src + b * batch_stride + int64_t(blk) * N * token_stride + h * D;
-        const uint8_t *ord = order ? order + b * meta_stride + first_token + int64_t(blk) * N : nullptr;
-#pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int row = pass * 16 + (tau >> 4), c8 = (tau & 15) * 8;
-            const int src_row = ord ? ord[row] : row;
-            *reinterpret_cast<uint4 *>(tile + row * D + c8) = load8_as_fp16(x_blk + src_row * token_stride + c8, bf16);
-        }
-    }
-    __syncthreads();
-
-    PlaneBits pb[2];
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        const int p = tau + 256 * k;
-        const int g = pack_order ? (p & 3) : (p >> 7);
-        const int d = pack_order ? (p >> 2) : (p & 127);
-        pb[k] = make_planes(tile, g, d, sm, qmax);
-    }
-    // one scan per pack-list half carries both regions: E bytes in the low half, O bytes in the high half
-    int off[2];
-    int run = 0;
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        int total;
-        off[k] = run + block_exclusive_scan(4 * (pb[k].w >> 1) + ((2 * (pb[k].w & 1)) << 16), &total);
-        run += total;
-    }
-    const int e_bytes = run & 0xFFFF, o_bytes = run >> 16;
-    const int padded = (HEADER + e_bytes + o_bytes + 15) & ~15;
-
+    __shared__ uint32_t codes[CODE_TILE_WORDS];
+    const PlaneChunk c = make_plane_chunk(cs, load_chunk_input(cs, cl, load_chunk_rows(cs, cl)), codes);
     if (!WRITE) {
-        if (tau == 0) sizes16[cl] = uint32_t(padded >> 4);
+        if (threadIdx.x == 0) sizes16[cl] = uint32_t(c.padded >> 4);
         return;
     }
-#pragma unroll
-    for (int k = 0; k < 2; ++k) {
-        dst[tau + 256 * k] = uint8_t((pb[k].w << 4) | pb[k].m);
-        uint32_t *e = reinterpret_cast<uint32_t *>(dst + HEADER + (off[k] & 0xFFFF));
-        if (pb[k].w >= 2) e[0] = pb[k].low;
-        if (pb[k].w == 4) e[1] = pb[k].high;
-        if (pb[k].w & 1)
-            *reinterpret_cast<uint16_t *>(dst + HEADER + e_bytes + (off[k] >> 16)) = uint16_t(pb[k].top);
+    write_plane_chunk(c, dst);
+}
+
+// Chunks part_first .. part_first + n - 1 of the round, chunk part_first + i into slot i.  A
+// workgroup takes every gridDim.x-th chunk and has the loads of its next one in flight while it
+// works on the current one.
+__global__ __launch_bounds__(256) void chunk16_stage_kernel(ChunkSource cs, const uint32_t *__restrict__ index,
+                                                            int part_first, int n,
+                                                            uint32_t *__restrict__ sizes16,
+                                                            uint8_t *__restrict__ staging, StagedRound round) {
+    if (!staged_round(round, index)) return;
+    // the chunk's bytes are put together in the memory of the code tile (8704 bytes, a chunk has at most 4608)
+    __shared__ __attribute__((aligned(16))) uint32_t codes[CODE_TILE_WORDS];
+    static_assert(CODE_TILE_WORDS * 4 >= CHUNK_MAX, "the chunk image lives in the code tile");
+    static_assert(CHUNK_MAX <= 2 * 256 * 16, "two 16-byte units per thread move a chunk");
+    const int tau = threadIdx.x;
+    const int stride = int(gridDim.x);
+    int cl = blockIdx.x;
+    if (cl >= n) return;
+    // The loads of the next chunk and the token order of the one after it are always issued (of
+    // the last chunk again where there is no next one): the count of loads in flight is then the
+    // same on every path, and the waits of the current chunk do not wait for them.
+    ChunkInput in = load_chunk_input(cs, part_first + cl, load_chunk_rows(cs, part_first + cl));
+    ChunkRows rows_next = load_chunk_rows(cs, part_first + min(cl + stride, n - 1));
+    for (;;) {
+        const int next = cl + stride;
+        const ChunkInput in_next = load_chunk_input(cs, part_first + min(next, n - 1), rows_next);
+        rows_next = load_chunk_rows(cs, part_first + min(next + stride, n - 1));
+        const PlaneChunk c = make_plane_chunk(cs, in, codes);
+        write_plane_chunk(c, reinterpret_cast<uint8_t *>(codes));
+        __syncthreads();
+        if (tau == 0) sizes16[cl] = uint32_t(c.padded >> 4);
+        const uint4 *image = reinterpret_cast<const uint4 *>(codes);
+        uint4 *slot = reinterpret_cast<uint4 *>(staging + size_t(cl) * CHUNK_MAX);
+        const int n16 = c.padded >> 4;
+        if (tau < n16) slot[tau] = image[tau];
+        if (tau + 256 < n16) slot[tau + 256] = image[tau + 256];
+        if (next >= n) break;
+        __syncthreads();  // the image is read: the next code tile may take its place
+        in = in_next;
+        cl = next;
     }
-    if (tau < padded - HEADER - e_bytes - o_bytes) dst[HEADER + e_bytes + o_bytes + tau] = 0;
+}
+
+// One wave per chunk of a staged part (its index words are set: the part's scan has run): staged
+// bytes to their place.
+__global__ __launch_bounds__(256) void chunk16_compact_kernel(StagedPart waiting) {
+    if (!staged_round(waiting.round, waiting.index)) return;
+    const int lane = threadIdx.x & 63;
+    const int cl = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (cl >= waiting.n) return;
+    const uint32_t start = waiting.index[waiting.first_chunk + cl], end = waiting.index[waiting.first_chunk + cl + 1];
+    const int n16 = int(end - start);
+    const uint4 *from = reinterpret_cast<const uint4 *>(waiting.staging + size_t(cl) * CHUNK_MAX);
+    uint4 *to = reinterpret_cast<uint4 *>(waiting.arena + size_t(start) * 16);
+    constexpr int STEPS = (CHUNK_MAX / 16 + 63) / 64;
+    uint4 v[STEPS];
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
+        if (lane + 64 * i < n16) v[i] = from[lane + 64 * i];
+#pragma unroll
+    for (int i = 0; i < STEPS; ++i)
+        if (lane + 64 * i < n16) to[lane + 64 * i] = v[i];
 }
 
 // Single workgroup: index[first+i+1] = index[first] + sum_{j<=i} sizes16[j].
 // If the new chunks do not fit, all of them get size 0 and the flag is set.
+// Wave w owns a run of `per` consecutive sizes (a multiple of 256) and walks it 256 at a time,
+// four per lane, so loads and stores of a wave cover consecutive memory.
 __global__ __launch_bounds__(1024) void scan_offsets_kernel(const uint32_t *__restrict__ sizes16,
                                                             int n, uint32_t *__restrict__ index,
                                                             int64_t first_chunk,
                                                             uint64_t arena_cap16,
-                                                            uint32_t *__restrict__ status) {
+                                                            uint32_t *__restrict__ status,
+                                                            StagedRound round, bool staged_part) {
     __shared__ uint32_t wsum[16];
-    __shared__ uint32_t total_s;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int per = (n + 1023) / 1024;
-    const int lo = min(tid * per, n), hi = min(lo + per, n);
-    uint32_t local = 0;
-    for (int i = lo; i < hi; ++i) local += sizes16[i];
-    uint32_t inc = local;
+    const int per = ((n + 15) / 16 + 255) & ~255;
+    const int lo = min(wave * per, n), hi = min(lo + per, n);
+    // sizes lo + 256 r + 4 lane .. + 3 (sizes16 is 256-byte aligned and its area a multiple of 16 bytes)
+    auto load4 = [&](int r) {
+        const int i = lo + 256 * r + 4 * lane;
+        uint4 q = i < hi ? *reinterpret_cast<const uint4 *>(sizes16 + i) : make_uint4(0, 0, 0, 0);
+        if (i + 1 >= hi) q.y = 0;
+        if (i + 2 >= hi) q.z = 0;
+        if (i + 3 >= hi) q.w = 0;
+        return q;
+    };
+    const int rounds = (hi - lo + 255) / 256;
+    // the first four rounds (all of them for up to 16384 chunks) go out at once and stay in registers
+    uint4 held[4];
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-        uint32_t v = __shfl_up(inc, o);
-        if (lane >= o) inc += v;
-    }
-    if (lane == 63) wsum[wave] = inc;
-    __syncthreads();
-    uint32_t base = 0;
-    for (int k = 0; k < wave; ++k) base += wsum[k];
-    if (tid == 1023) total_s = base + inc;
-    __syncthreads();
+    for (int r = 0; r < 4; ++r) held[r] = load4(r);
     const uint32_t start = index[first_chunk];
-    const bool fits = uint64_t(start) + total_s <= arena_cap16;
-    if (!fits && tid == 0) status[0] = 1;
-    uint32_t run = start + base + inc - local;
-    for (int i = lo; i < hi; ++i) {
-        run += sizes16[i];
-        index[first_chunk + i + 1] = fits ? run : start;
+    uint32_t local = 0;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) local += held[r].x + held[r].y + held[r].z + held[r].w;
+    for (int r = 4; r < rounds; ++r) {
+        const uint4 q = load4(r);
+        local += q.x + q.y + q.z + q.w;
     }
+    // serves a part of a staged round (staged_part) or a whole two-pass round: whichever path runs
+    if (staged_round(round, index) != staged_part) return;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) local += __shfl_xor(local, o);
+    if (lane == 0) wsum[wave] = local;
+    __syncthreads();
+    uint32_t run = start, total = 0;
+    for (int k = 0; k < 16; ++k) {
+        if (k < wave) run += wsum[k];
+        total += wsum[k];
+    }
+    const bool fits = uint64_t(start) + total <= arena_cap16;
+    if (!fits && tid == 0) status[0] = 1;
+    auto place = [&](int r, uint4 q) {
+        const uint32_t mine = q.x + q.y + q.z + q.w;
+        uint32_t inc = mine;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t v = __shfl_up(inc, o);
+            if (lane >= o) inc += v;
+        }
+        const int i = lo + 256 * r + 4 * lane;
+        uint32_t at = run + inc - mine;
+        const uint32_t ends[4] = {at + q.x, at + q.x + q.y, at + q.x + q.y + q.z, at + mine};
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            if (i + k < hi) index[first_chunk + i + k + 1] = fits ? ends[k] : start;
+        run += __shfl(inc, 63);
+    };
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+        if (r < rounds) place(r, held[r]);
+    for (int r = 4; r < rounds; ++r) place(r, load4(r));
 }
 
 // Paged arena: places the n new chunks of one tensor (sizes16: their sizes in 16-byte units;
@@ -802,32 +1054,78 @@ int launch_pack(const kv_cache *c, const CompressJob &job, hipStream_t s) {
     const bool planes = !job.wide && c->cfg.pack_size == 16;
     auto sizes_kernel = job.wide ? chunk_kernel<false, 8, true> : chunk_kernel<false, 8>;
     auto write_kernel = job.wide ? chunk_kernel<true, 8, true> : chunk_kernel<true, 8>;
-    if (planes)
-        hipLaunchKernelGGL(chunk16_kernel<false>, dim3(n_chunks), dim3(256), 0, s, job.src,
-                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16, job.pack_order);
-    else
-        hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
-                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16);
-    if (c->pool)
-        hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
-                           job.first_chunk, job.page_list, job.max_pages, c->pool->state, job.status);
-    else
-        hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
-                           job.index, job.first_chunk, job.arena_cap16, job.status);
-    if (planes)
-        hipLaunchKernelGGL(chunk16_kernel<true>, dim3(n_chunks), dim3(256), 0, s, job.src,
-                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16, job.pack_order);
-    else
-        hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
-                           job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
-                           job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
-                           job.order, job.bf16);
+    // packs of 16, contiguous arena: the staged path when even the largest chunks fit (decided on
+    // the device, where the fill level is); the kernels of the other path return at once.  The
+    // host knows an upper bound of the fill level: where that already says "fits", the two-pass
+    // kernels are not launched at all.
+    ChunkSource cs;
+    cs.src = job.src;
+    cs.batch_stride = job.batch_stride;
+    cs.token_stride = job.token_stride;
+    cs.B = B;
+    cs.H = H;
+    cs.qmax = job.qmax;
+    cs.magic_h = (uint64_t(1) << 32) / uint64_t(H) + 1;
+    cs.magic_hb = (uint64_t(1) << 32) / (uint64_t(H) * uint64_t(B)) + 1;
+    cs.meta = job.meta;
+    cs.meta_stride = c->max_tokens;
+    cs.first_token = job.first_token;
+    cs.order = job.order;
+    cs.bf16 = job.bf16;
+    cs.pack_order = job.pack_order;
+    StagedRound round;
+    round.first_chunk = job.first_chunk;
+    round.worst16 = 0;
+    round.arena_cap16 = job.arena_cap16;
+    bool two_pass = true;
+    // (a small round is bound by its launches, not by reading the input twice: two passes, three kernels)
+    constexpr int STAGED_MIN_CHUNKS = 1024;
+    if (planes && !c->pool && n_chunks >= STAGED_MIN_CHUNKS) {
+        round.worst16 = uint32_t(n_chunks) * uint32_t(CHUNK_MAX / 16);
+        two_pass = job.fill_bound16 + round.worst16 > job.arena_cap16;
+        uint8_t *staging = ws + c->stage_offset;
+        for (int part = 0; part < n_chunks; part += c->stage_chunks) {
+            const int n = std::min(c->stage_chunks, n_chunks - part);
+            static const int per_cu = resident_workgroups(reinterpret_cast<const void *>(chunk16_stage_kernel));
+            const int groups = flat_groups_for(int64_t(n) * 4, per_cu, n);  // all resident, at most one per chunk
+            hipLaunchKernelGGL(chunk16_stage_kernel, dim3(groups), dim3(256), 0, s, cs, job.index, part, n,
+                               sizes16, staging, round);
+            hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n, job.index,
+                               job.first_chunk + part, job.arena_cap16, job.status, round, true);
+            StagedPart staged;
+            staged.staging = staging;
+            staged.index = job.index;
+            staged.first_chunk = job.first_chunk + part;
+            staged.n = n;
+            staged.arena = job.arena;
+            staged.round = round;
+            hipLaunchKernelGGL(chunk16_compact_kernel, dim3((n + 3) / 4), dim3(256), 0, s, staged);
+        }
+    }
+    if (two_pass) {
+        if (planes)
+            hipLaunchKernelGGL(chunk16_kernel<false>, dim3(n_chunks), dim3(256), 0, s, cs, job.first_chunk,
+                               sizes16, job.index, c->index_words, job.arena, round);
+        else
+            hipLaunchKernelGGL(sizes_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
+                               job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                               job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                               job.order, job.bf16);
+        if (c->pool)
+            hipLaunchKernelGGL(place_chunks_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks, job.index,
+                               job.first_chunk, job.page_list, job.max_pages, c->pool->state, job.status);
+        else
+            hipLaunchKernelGGL(scan_offsets_kernel, dim3(1), dim3(1024), 0, s, sizes16, n_chunks,
+                               job.index, job.first_chunk, job.arena_cap16, job.status, round, false);
+        if (planes)
+            hipLaunchKernelGGL(chunk16_kernel<true>, dim3(n_chunks), dim3(256), 0, s, cs, job.first_chunk,
+                               sizes16, job.index, c->index_words, job.arena, round);
+        else
+            hipLaunchKernelGGL(write_kernel, dim3(n_chunks), dim3(256), 0, s, job.src,
+                               job.batch_stride, job.token_stride, B, H, job.qmax, job.meta, c->max_tokens,
+                               job.first_token, job.first_chunk, sizes16, job.index, c->index_words, job.arena,
+                               job.order, job.bf16);
+    }
     KV_HIP_CHECK(hipGetLastError());
     return KV_OK;
 }

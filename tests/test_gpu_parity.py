@@ -115,6 +115,57 @@ def test_incremental_appends_equal_bulk_compression():
     gpu_cases.run_case(1, 1, 1, 130, 22, pieces=[1] * 130)
 
 
+def test_compressor_takes_each_of_its_paths_and_writes_the_same_bytes():
+    """Packs of 16, contiguous arena: a round is staged in parts (quantized once) when even its
+    largest chunks fit what is left of the arena, else sized and written in two passes; the host
+    skips the two-pass kernels where its own bound already says "fits" (and rounds below 1024
+    chunks always take two passes).  Three appends into an arena sized for 2.85 bits per element
+    meet all three cases, and the state stays the oracle's bit for bit."""
+    B, H, Hq, blocks = 2, 4, 8, [150, 130, 128]   # 1200, 1040, 1024 chunks; the staging area holds 512
+    L = 64 * sum(blocks)
+    K, V, q = synth.make_kv(B, L, H, Hq, 77)
+    cache = binding.PackedKVCache(B, H, Hq, L, k_rel_scale=0.2, v_rel_scale=0.2, bits_per_element_budget=2.85)
+    n_packed, ck, cv = gpu_cases.oracle_cache(K.numpy(), V.numpy(), 0.2, 0.2)
+    # which path each append takes, from the oracle's chunk sizes (288 units of 16 bytes: the largest chunk)
+    seen = set()
+    for c, cap16 in ((ck, cache.sizes.k_arena // 16), (cv, cache.sizes.v_arena // 16)):
+        done = bound = 0
+        for nb in blocks:
+            n = nb * B * H
+            host_sure = bound + n * 288 <= cap16
+            staged = int(c.offsets16[done]) + n * 288 <= cap16
+            assert int(c.offsets16[done + n]) <= cap16, "no append of this test overflows"
+            seen.add((host_sure, staged))
+            bound, done = bound + n * 288, done + n
+    assert seen == {(True, True), (False, True), (False, False)}
+    pos = 0
+    for nb in blocks:
+        cache.kv_compress_append(K[:, pos:pos + 64 * nb].contiguous().cuda(), V[:, pos:pos + 64 * nb].contiguous().cuda())
+        pos += 64 * nb
+    gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
+    cache.close()
+
+
+def test_rounding_ties_of_the_quantizer_follow_the_divide():
+    """Quotients (x - min) / scale that are exactly k + 1/2 (scale 1, values on the half-integers)
+    round to even, as rint of the IEEE quotient does; the compressor's reciprocal shortcut has to
+    notice them.  Bit-exact bytes, both pack sizes."""
+    B, H, Hq, L = 1, 2, 2, 256
+    gen = torch.Generator().manual_seed(4242)
+    for pack_size in (16, 8):
+        halves = torch.randint(0, 21, (B, L, H, 128), generator=gen).to(torch.float32) / 2  # 0, 0.5, ..., 10
+        halves[:, :, 0, 0] = 0.0
+        halves[:, :, 0, 1] = 10.0      # every token: minimum 0, range 10, scale 0.1 * 10 -> 1 in fp16
+        K = (halves - 3.0).to(torch.float16)   # a minimum that is not zero
+        V = halves.flip(1).contiguous().to(torch.float16)
+        cache = binding.PackedKVCache(B, H, Hq, L, k_rel_scale=0.1, v_rel_scale=0.1, pack_size=pack_size)
+        cache.kv_compress_append(K.cuda(), V.cuda())
+        n_packed, ck, cv = gpu_cases.oracle_cache(K.numpy(), V.numpy(), 0.1, 0.1, pack_size)
+        assert int(ck.codes.max()) == 10 and (ck.codes[:, :, 0, 2:] % 2 == 0).mean() > 0.7, "ties went to even"
+        gpu_cases.check_packed_state(cache, n_packed, ck, cv, B, H)
+        cache.close()
+
+
 def test_decode_kernels_on_oracle_packed_bytes():
     """Feed the fused kernels a cache written by the oracle (restore path):
     isolates the decode kernels from the GPU compressor."""
