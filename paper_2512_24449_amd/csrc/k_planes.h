@@ -207,20 +207,11 @@ __device__ inline void k_planes_chunk(const uint8_t *lds_all, int cur, const uin
     uint32_t lo[8], hi[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-#ifdef EXP2
-        const uint32_t *e = reinterpret_cast<const uint32_t *>(lds_all + cur + HEADER + (j * 64 + lane) * 8 + (lp.e0 == 12345 ? 4 : 0));
-        const uint32_t T = *reinterpret_cast<const uint16_t *>(lds_all + cur + HEADER + (j * 64 + lane) * 2 + (lp.o0 == 12345 ? 4 : 0));
-#else
         const uint32_t *e = reinterpret_cast<const uint32_t *>(lds_all + lp.e_pos(j));
         const uint32_t T = *reinterpret_cast<const uint16_t *>(lds_all + lp.o_pos(j));
-#endif
         const uint32_t L = e[0], H = e[1];
         const uint32_t w16 = ((j < 4 ? wsel_lo : wsel_hi) >> (8 * (j & 3))) & 0xFFu;
-#ifdef EXP1
-        const uint4 k = make_uint4(w16 ? ~0u : 0u, ~0u, 0x55555555u, 0x55555555u);
-#else
         const uint4 k = *reinterpret_cast<const uint4 *>(reinterpret_cast<const uint8_t *>(table) + w16);
-#endif
         // the bit of token t = 4r + s sits at 4s + r of T; in y the tokens 0..7 sit at bit 4n and the
         // tokens 8..15 at bit 4n + 2 (n = token % 8): bit 0 of the two-bit fields of a plane word
         const uint32_t y = T | (T << 15);
