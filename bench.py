@@ -472,9 +472,9 @@ def run_compress(w, K, V, torch, binding):
     return {"prompt_ms": round(ms, 3), "fp16_input_gbps": round(in_bytes / (ms * 1e-3) / 1e9, 1),
             "pct_hbm_peak_on_input": round(100.0 * in_bytes / (ms * 1e-3) / 8e12, 2),
             "tail_flush_ms": round(flush_ms, 4),
-            "hbm_bytes_per_input_byte": "about 2.85: the input is read twice (token minimum and maximum, then "
-                                        "quantization), the packed bytes are written to a staging slot, read back "
-                                        "and written to their place",
+            "hbm_bytes_per_input_byte": "about 2.5 (stored: profiles/hbm_traffic_llama2_30b_32k_b8.txt): the input is "
+                                        "read twice (token minimum and maximum, then quantization), the packed bytes "
+                                        "are written to a staging slot, read back and written to their place",
             "note": "staged path, every value quantized once; bound by HBM traffic"}
 
 
