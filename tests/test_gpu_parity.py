@@ -303,6 +303,7 @@ def test_arena_overflow_sets_sticky_flag_and_drops_the_block(Hq, pack_size, k_re
 @pytest.mark.parametrize("B,H,Hq,L,pieces,pack_size,k_rel,v_rel", [
     (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 16, 0.1, 0.2),   # blocks from bulk appends and from tail flushes
     (1, 52, 52, 128, None, 16, 0.1, 0.2),                        # wide token vectors (6656 values per median)
+    (2, 4, 8, 150 * 64, None, 16, 0.1, 0.2),                     # 1200 chunks in one call: the staged compressor, in three parts
     (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8, 0.1, 0.2),    # the same with packs of 8 tokens
     (2, 3, 6, 3 * 64 + 21, [70, 64, 1, 57, 21], 8, 0.1, 1 / 40), # medians of codes up to 40 (wide V chunks)
     (1, 52, 52, 128, None, 8, 1 / 255, 1 / 255),                 # both tensors wide, codes up to 255
@@ -317,7 +318,8 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     V = (torch.rand(V.shape, generator=torch.Generator().manual_seed(72)) ** lean).to(torch.float16)
     Kn, Vn, qn = K.numpy(), V.numpy(), q.numpy()
     n_packed = L // 64 * 64
-    pool = binding.PagePool(40) if paged else None   # the same through a paged arena
+    n_pages = max(40, L // 64 * B * H * 2 * 4608 // binding.PAGE_BYTES + 8)
+    pool = binding.PagePool(n_pages) if paged else None   # the same through a paged arena
     cache = binding.PackedKVCache(B, H, Hq, L, repack=binding.REPACK_V_MEDIAN, pack_size=pack_size,
                                   k_rel_scale=k_rel, v_rel_scale=v_rel, pool=pool)
     pos = 0
@@ -355,7 +357,7 @@ def test_v_median_repacking_matches_oracle(B, H, Hq, L, pieces, pack_size, k_rel
     assert_close_vectors(attn.cpu().numpy(), a_orig, "attention, arrival order")
     cache.close()
     if paged:
-        assert pool.kv_page_pool_free_pages() == 40
+        assert pool.kv_page_pool_free_pages() == n_pages
         pool.close()
 
 
@@ -477,13 +479,16 @@ def test_non_finite_inputs_keep_the_format_valid(kw):
 
 
 @pytest.mark.parametrize("kw", [dict(), dict(pack_size=8, k_rel_scale=0.05, v_rel_scale=1 / 255),
-                                dict(repack=binding.REPACK_V_MEDIAN)])
+                                dict(repack=binding.REPACK_V_MEDIAN), dict(big=True)])
 def test_bf16_inputs_enter_as_their_fp16_roundings(kw):
     """kv_compress_append_bf16: packed bytes, index, token metadata, raw tail and every result are
     bitwise those of kv_compress_append on the inputs rounded to fp16 -- and those are compared
     with the oracle.  The values include magnitudes below fp16's normal range (rounded in its
-    subnormal grid) and bf16 values that fp16 holds exactly."""
-    B, H, Hq, L = 2, 3, 6, 64 * 5 + 23
+    subnormal grid) and bf16 values that fp16 holds exactly.  big: one append of 1120 chunks per
+    tensor, which takes the staged compressor."""
+    kw = dict(kw)
+    big = kw.pop("big", False)
+    B, H, Hq, L = (2, 4, 8, 64 * 140 + 23) if big else (2, 3, 6, 64 * 5 + 23)
     g = torch.Generator().manual_seed(808)
     K = torch.randn(B, L, H, 128, generator=g)
     V = torch.randn(B, L, H, 128, generator=g) * 0.3
@@ -493,7 +498,7 @@ def test_bf16_inputs_enter_as_their_fp16_roundings(kw):
     Kh, Vh = Kb.to(torch.float16), Vb.to(torch.float16)
     assert not torch.equal(Kh.float(), Kb.float()), "some values are meant to round"
     q = torch.randn(B, Hq, 128, generator=g).to(torch.float16)
-    pieces = [70, 64, 1, 190, 18]
+    pieces = [64 * 140, 23] if big else [70, 64, 1, 190, 18]
     caches = []
     for Kx, Vx in ((Kb, Vb), (Kh, Vh)):
         cache = binding.PackedKVCache(B, H, Hq, L, **kw)
