@@ -150,8 +150,28 @@ constexpr int CHUNK_LDS = CHUNK_MAX;
 // the s_nop is the wait state between writing M0 and the transfer that reads it.
 #pragma clang diagnostic push
 #pragma clang diagnostic ignored "-Winline-asm"  // M0 is a reserved register; naming it as clobbered is the point
-// MAXB: buffer bytes = largest chunk; HDR: header bytes, the smallest valid chunk.
-template <int MAXB = CHUNK_MAX, int HDR = HEADER>
+// MAXB: buffer bytes = largest chunk; HDR: header bytes, the smallest valid chunk.  STREAM: the
+// transfers carry the non-temporal hint -- a chunk is read once, and without the hint it pushes
+// out of the caches what the kernel reads again or what the kernel before it has just written
+// (the weights of the V product).
+#define PACKKV_CHUNK_TRANSFERS(POLICY)                                                                                  \
+    for (int k = 0; k < (MAXB + 1023) / 1024; ++k) {                                                                    \
+        if (k * 1024 < size && ((k + 1) * 1024 <= MAXB || k * 1024 + lane * 16 < MAXB)) {                               \
+            const int off = lane * 16;                                                                                  \
+            const int lim = last - k * 1024;                                                                            \
+            const int voff = off < lim ? off : lim;                                                                     \
+            if (k == 0) asm volatile("global_load_lds_dwordx4 %0, %1" POLICY : : "v"(voff), "s"(chunk) : "memory", "m0"); \
+            if (k == 1) asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" POLICY : : "v"(voff), "s"(chunk) : "memory", "m0"); \
+            if (k == 2) asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" POLICY : : "v"(voff), "s"(chunk) : "memory", "m0"); \
+            if (k == 3) asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" POLICY : : "v"(voff), "s"(chunk) : "memory", "m0"); \
+            if (k >= 4)                                                                                                 \
+                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" POLICY                       \
+                             :                                                                                          \
+                             : "s"(lds + k * 1024), "v"(voff), "s"(chunk + k * 1024)                                    \
+                             : "memory", "m0");                                                                         \
+        }                                                                                                               \
+    }
+template <int MAXB = CHUNK_MAX, int HDR = HEADER, bool STREAM = false>
 __device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
                                        uint8_t *buf, int lane) {
     const int size = int(o1 - o0) * 16;
@@ -163,24 +183,15 @@ __device__ inline void chunk_issue_lds(const uint8_t *__restrict__ arena, uint32
     // and the LDS address alike.  Nothing between these statements touches M0 (no LDS-DMA
     // builtin, no indexed register access, no message).
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0" : : "s"(lds) : "memory", "m0");
+    if constexpr (STREAM) {
 #pragma unroll
-    for (int k = 0; k < (MAXB + 1023) / 1024; ++k) {
-        if (k * 1024 < size && ((k + 1) * 1024 <= MAXB || k * 1024 + lane * 16 < MAXB)) {
-            const int off = lane * 16;
-            const int lim = last - k * 1024;
-            const int voff = off < lim ? off : lim;
-            if (k == 0) asm volatile("global_load_lds_dwordx4 %0, %1" : : "v"(voff), "s"(chunk) : "memory", "m0");
-            if (k == 1) asm volatile("global_load_lds_dwordx4 %0, %1 offset:1024" : : "v"(voff), "s"(chunk) : "memory", "m0");
-            if (k == 2) asm volatile("global_load_lds_dwordx4 %0, %1 offset:2048" : : "v"(voff), "s"(chunk) : "memory", "m0");
-            if (k == 3) asm volatile("global_load_lds_dwordx4 %0, %1 offset:3072" : : "v"(voff), "s"(chunk) : "memory", "m0");
-            if (k >= 4)
-                asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
-                             :
-                             : "s"(lds + k * 1024), "v"(voff), "s"(chunk + k * 1024)
-                             : "memory", "m0");
-        }
+        PACKKV_CHUNK_TRANSFERS(" nt")
+    } else {
+#pragma unroll
+        PACKKV_CHUNK_TRANSFERS("")
     }
 }
+#undef PACKKV_CHUNK_TRANSFERS
 #pragma clang diagnostic pop
 
 // All outstanding global->LDS transfers (and other vector memory operations) of
@@ -201,12 +212,12 @@ __device__ inline void vmem_order_fence() { asm volatile("" ::: "memory"); }
 // transfer, with the number of transfer instructions it issued as the result (wave-uniform; 0 for
 // a dropped block), which the caller needs to count the vector memory operations that may stay in
 // flight at its next wait.
-template <int MAXB = CHUNK_MAX, int HDR = HEADER>
+template <int MAXB = CHUNK_MAX, int HDR = HEADER, bool STREAM = false>
 __device__ inline int chunk_issue_lds_counted(const uint8_t *__restrict__ arena, uint32_t o0, uint32_t o1,
                                               uint8_t *buf, int lane) {
     const int size = int(o1 - o0) * 16;
     if (size < HDR) return 0;
-    chunk_issue_lds<MAXB, HDR>(arena, o0, o1, buf, lane);
+    chunk_issue_lds<MAXB, HDR, STREAM>(arena, o0, o1, buf, lane);
     const int slices = (size + 1023) >> 10;
     constexpr int MOST = (MAXB + 1023) / 1024;
     return slices < MOST ? slices : MOST;

@@ -86,13 +86,14 @@ __global__ __launch_bounds__(256) void v_matvec_kernel(VArgs a, FlatPlan plan) {
         st.clear();
 
         // everything chunk `blk` needs, into buffer `slot`: 1 + G row transfers, then the chunk
-        // itself; returns the number of transfer instructions of the chunk
+        // itself (with the streaming hint: the weights, which the softmax kernel has just written,
+        // then stay in the caches); returns the number of transfer instructions of the chunk
         auto issue = [&](const IndexBatch &ib, int it, int blk, int slot) -> int {
             uint8_t *buf = lds_all + buf_base + slot * BUF;
             row_issue_lds(meta + int64_t(blk) * N, buf + SIDE, lane);
 #pragma unroll
             for (int g = 0; g < G; ++g) row_issue_lds(prow + g * a.ld + int64_t(blk) * N, buf + SIDE + 256 * (1 + g), lane);
-            return chunk_issue_lds_counted<CHUNK_BYTES>(a.arena, ib.start16(it), ib.end16(it), buf, lane);
+            return chunk_issue_lds_counted<CHUNK_BYTES, HEADER, true>(a.arena, ib.start16(it), ib.end16(it), buf, lane);
         };
 
         for (int first = blk_begin + wave; first < blk_end; first += 4 * 64) {
