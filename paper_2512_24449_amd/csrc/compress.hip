@@ -40,8 +40,12 @@ __device__ inline uint4 as_fp16(uint4 raw, bool bf16) {
     }
     return raw;
 }
+// (The input is read once per kernel and is larger than the caches: the non-temporal hint keeps it
+// from pushing out what is read again, the staged chunks for one.)
 __device__ inline uint4 load8_as_fp16(const __half *p, bool bf16) {
-    return as_fp16(*reinterpret_cast<const uint4 *>(p), bf16);
+    typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
+    const u32x4n v = __builtin_nontemporal_load(reinterpret_cast<const u32x4n *>(p));
+    return as_fp16(make_uint4(v.x, v.y, v.z, v.w), bf16);
 }
 
 // ---------------------------------------------------------------------------
