@@ -212,7 +212,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
         ik.load(a.k_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         iv.load(a.v_index, a.index_words, first, 4, blk_end, a.B, a.H / a.dup, b, h / a.dup, lane);
         const int n_it = min(64, (blk_end - first + 3) / 4);
-        chunk_issue_lds(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
+        chunk_issue_lds<CHUNK_MAX, HEADER, true>(a.k_arena, ik.start16(0), ik.end16(0), lds_all + kbuf, lane);
         const int64_t tok0 = b * a.meta_stride + int64_t(first) * N + lane;
         uint32_t kmt_next = a.k_meta[tok0], vmt_next = a.v_meta[tok0];
         for (int it = 0; it < n_it; ++it) {
@@ -223,7 +223,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
             uint32_t kmt = kmt_next, vmt = vmt_next;
             consume_here(kmt), consume_here(vmt);
             lds_reads_returned();  // the previous V chunk has been read completely
-            chunk_issue_lds(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
+            chunk_issue_lds<CHUNK_MAX, HEADER, true>(a.v_arena, iv.start16(it), iv.end16(it), lds_all + vbuf, lane);
             if (it + 1 < n_it) {
                 const int64_t tok = b * a.meta_stride + int64_t(first + 4 * (it + 1)) * N + lane;
                 kmt_next = a.k_meta[tok];
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AArgs a) {
             wait_chunk_landed();  // V chunk of this block
             lds_reads_returned();  // the K tiles have been read completely before the next chunk overwrites them
             if (it + 1 < n_it)
-                chunk_issue_lds(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
+                chunk_issue_lds<CHUNK_MAX, HEADER, true>(a.k_arena, ik.start16(it + 1), ik.end16(it + 1), lds_all + kbuf, lane);
             if (!valid) continue;
             float pt[G];
 #pragma unroll

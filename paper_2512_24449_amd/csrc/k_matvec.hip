@@ -229,7 +229,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5))) void k
         auto issue = [&](const IndexBatch &ib, int it, int blk) {
             uint8_t *buf = lds_all + cur;
             row_issue_lds(meta + int64_t(blk) * N, buf + SIDE, lane);
-            chunk_issue_lds(a.arena, ib.start16(it), ib.end16(it), buf, lane);
+            chunk_issue_lds<CHUNK_MAX, HEADER, true>(a.arena, ib.start16(it), ib.end16(it), buf, lane);
         };
         // index words of up to 64 blocks of this wave, then the first chunk of the batch
         auto start_batch = [&](IndexBatch &ib, int first) {

@@ -152,8 +152,8 @@ constexpr int CHUNK_LDS = CHUNK_MAX;
 #pragma clang diagnostic ignored "-Winline-asm"  // M0 is a reserved register; naming it as clobbered is the point
 // MAXB: buffer bytes = largest chunk; HDR: header bytes, the smallest valid chunk.  STREAM: the
 // transfers carry the non-temporal hint -- a chunk is read once, and without the hint it pushes
-// out of the caches what the kernel reads again or what the kernel before it has just written
-// (the weights of the V product).
+// out of the caches what the kernel reads again, what the kernel before it has just written (the
+// weights of the V product) and what the kernel after it reads first (the scores of the K product).
 #define PACKKV_CHUNK_TRANSFERS(POLICY)                                                                                  \
     for (int k = 0; k < (MAXB + 1023) / 1024; ++k) {                                                                    \
         if (k * 1024 < size && ((k + 1) * 1024 <= MAXB || k * 1024 + lane * 16 < MAXB)) {                               \
