@@ -9,6 +9,14 @@
 
 namespace packkv {
 
+// 16 bytes that are read once: with the non-temporal hint, as the packed kernels read their chunks.
+__device__ inline uint4 load16_stream(const void *p) {
+    typedef uint32_t u32x4n __attribute__((ext_vector_type(4)));
+    const u32x4n v = __builtin_nontemporal_load(static_cast<const u32x4n *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
 // K: one wave per 64 consecutive tokens of one (b, h).  Per step the wave reads
@@ -43,7 +51,7 @@ __global__ __launch_bounds__(256) void fp16_k_kernel(const __half *__restrict__ 
 #pragma unroll
     for (int it = 0; it < 16; ++it) {
         const int64_t t = t0 + 4 * it + row;
-        raw[it] = t < L ? *reinterpret_cast<const uint4 *>(base + (4 * it + row) * D + ch0)
+        raw[it] = t < L ? load16_stream(base + (4 * it + row) * D + ch0)
                         : make_uint4(0, 0, 0, 0);
     }
     float acc[G][16];
@@ -99,7 +107,7 @@ __global__ __launch_bounds__(256) void fp16_v_kernel(const __half *__restrict__ 
 #pragma unroll
         for (int it = 0; it < 16; ++it) {
             const int64_t t = t0 + 4 * it + row;
-            raw[it] = t < t_end ? *reinterpret_cast<const uint4 *>(vc + (bh * L + t) * D + ch0)
+            raw[it] = t < t_end ? load16_stream(vc + (bh * L + t) * D + ch0)
                                 : make_uint4(0, 0, 0, 0);
         }
 #pragma unroll
@@ -155,7 +163,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const uint4 *__restric
         const uint4 *p = src + t * tile + threadIdx.x;
         uint4 v[DEPTH];
 #pragma unroll
-        for (int k = 0; k < DEPTH; ++k) v[k] = p[k * 256];
+        for (int k = 0; k < DEPTH; ++k) v[k] = load16_stream(p + k * 256);
 #pragma unroll
         for (int k = 0; k < DEPTH; ++k) acc ^= v[k].x ^ v[k].y ^ v[k].z ^ v[k].w;
     }
