@@ -411,7 +411,8 @@ __device__ inline ChunkInput load_chunk_input(const ChunkSource &cs, int cl, con
 // The eight values of one token a thread holds, quantized (Sec. III-B.2: clamp(rint(fl((x - mn) / s)),
 // 0, qmax), the quotient rounded to fp32 as an IEEE divide does) into byte `slot` of out[0..7];
 // qmax < 16.  Fast path: q = (x - mn) * r with r = 1 / s to within an ulp, rounded to the nearest
-// integer (ties to even) and clamped to 0 .. 255 by the conversion that also places the byte.
+// integer (ties to even) and clamped to 0 .. 255 by the conversion that also places the byte; a token
+// with a quotient that could round above qmax takes the slow path, which clamps.
 // q lies within 2^-22 relative of the rounded quotient (an ulp for r, half for the product, half
 // for the quotient's own rounding): within 2^-16 for quotients below 64, and from 64 on both sides
 // are clamped to qmax anyway.  So unless q is within 2^-15 of a rounding tie k + 1/2, it rounds as
@@ -419,24 +420,44 @@ __device__ inline ChunkInput load_chunk_input(const ChunkSource &cs, int cl, con
 // with a value near one takes the divide for all eight.
 constexpr float TIE_GUARD = 1.0f / 32768.0f;
 
+// x - mn in fp32 for the low (HI = false) or high half of a word of two fp16 values: the mixed-
+// precision fused multiply-add x * 1 + (-mn) rounds the exact difference once, as the conversion
+// to fp32 (exact) followed by the subtraction does, and saves the conversion.
+template <bool HI>
+__device__ inline float half_minus(uint32_t two_halves, float neg_mn) {
+    float a;
+    if (HI)
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(a) : "v"(two_halves), "v"(neg_mn));
+    else
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[1,0,0]" : "=v"(a) : "v"(two_halves), "v"(neg_mn));
+    return a;
+}
+
 __device__ inline void quantize_token8(uint4 values, uint32_t mt, int qmax, int slot, uint32_t *out) {
     const float s = __half2float(__ushort_as_half(uint16_t(mt & 0xFFFFu)));
     const float mn = __half2float(__ushort_as_half(uint16_t(mt >> 16)));
     const float r = s != 0.0f ? __builtin_amdgcn_rcpf(s) : 0.0f;  // s = 0: every code is 0
     const float top = float(qmax);
-    const __half *x = reinterpret_cast<const __half *>(&values);
-    float clear = 1.0f;
+    const uint32_t w[4] = {values.x, values.y, values.z, values.w};
+    float clear = 1.0f, most = 0.0f;
+    float q[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
-        const float q = (__half2float(x[j]) - mn) * r;
-        clear = fminf(clear, fabsf(__builtin_amdgcn_fractf(q) - 0.5f));
-        out[j] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(q, top), uint32_t(slot), out[j]);
+        const float a = (j & 1) ? half_minus<true>(w[j >> 1], -mn) : half_minus<false>(w[j >> 1], -mn);
+        q[j] = a * r;
+        clear = fminf(clear, fabsf(__builtin_amdgcn_fractf(q[j]) - 0.5f));
+        most = fmaxf(most, q[j]);
+        out[j] = __builtin_amdgcn_cvt_pk_u8_f32(q[j], uint32_t(slot), out[j]);  // rounds to nearest even, 0 .. 255
     }
-    if (clear < TIE_GUARD) {
+    // rare: a value near a rounding tie (the divide decides), or one that rounds above qmax (the
+    // scale is an fp16 rounding of rel * range, so the largest quotient can pass qmax + 1/2; an
+    // infinite quotient lands here too, and a NaN converts to code 0)
+    if (clear < TIE_GUARD || most >= top + 0.5f - TIE_GUARD) {
+        const __half *x = reinterpret_cast<const __half *>(&values);
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
-            const float q = s != 0.0f ? (__half2float(x[j]) - mn) / s : 0.0f;  // IEEE fp32 divide
-            out[j] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(q, top), uint32_t(slot), out[j]);
+            const float qd = s != 0.0f ? (__half2float(x[j]) - mn) / s : 0.0f;  // IEEE fp32 divide
+            out[j] = __builtin_amdgcn_cvt_pk_u8_f32(fminf(qd, top), uint32_t(slot), out[j]);
         }
     }
 }

@@ -51,8 +51,8 @@ def test_reciprocal_rule_gives_the_codes_of_the_divide():
 
 
 def _codes16(x, mn, s, qmax, ulp_off):
-    """The rule of packs of 16: q = fl(a * r), r = 1 / s up to an ulp; near a tie the divide; round to
-    nearest even after the clamp from above (the conversion saturates below 0)."""
+    """The rule of packs of 16: q = fl(a * r), r = 1 / s up to an ulp, rounded to nearest even; near a
+    tie, or where q could round above qmax, the divide with the clamp."""
     x, mn, s = x.astype(np.float32), mn.astype(np.float32), s.astype(np.float32)
     a = (x - mn).astype(np.float32)
     quotient = (a / s).astype(np.float32)
@@ -61,9 +61,13 @@ def _codes16(x, mn, s, qmax, ulp_off):
     r = (r.view(np.int32) + ulp_off).view(np.float32)          # the hardware reciprocal: within one ulp
     q = (a * r).astype(np.float32)
     frac = (q - np.floor(q)).astype(np.float32)
-    near_tie = np.abs((frac - np.float32(0.5)).astype(np.float32)) < np.float32(2.0 ** -15)
-    q = np.where(near_tie, quotient, q)
-    fast = np.clip(np.rint(np.minimum(q, qmax)), 0, 255)
+    guard = np.float32(2.0 ** -15)
+    near_tie = np.abs((frac - np.float32(0.5)).astype(np.float32)) < guard
+    # a quotient that could round above qmax also takes the divide, which clamps; the fast path
+    # rounds to nearest even and saturates at 0 and 255 only
+    too_big = q >= (qmax.astype(np.float32) + np.float32(0.5) - guard).astype(np.float32)
+    slow = near_tie | too_big
+    fast = np.where(slow, np.clip(np.rint(np.minimum(quotient, qmax)), 0, 255), np.clip(np.rint(q), 0, 255))
     return exact, fast, int(near_tie.sum())
 
 
